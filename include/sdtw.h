@@ -1,0 +1,168 @@
+/*
+ * sdtw.h - C boundary of the MI355X (gfx950) Soft-DTW library.
+ *
+ * What is computed (paper: "SoftDTW-CUDA-Torch"):
+ *   forward   R[i,j] = d(x_i,y_j) + softmin_gamma(R[i-1,j-1], R[i-1,j], R[i,j-1]),
+ *             R[0,0]=0, R[i,0]=R[0,j]=+inf, value = R[N,M]              (Sec. 2, Eq. 1-3)
+ *   cost      d(x_i,y_j) = ||x_i||^2 - 2<x_i,y_j> + ||y_j||^2            (Sec. 4.3, Eq. 8)
+ *   backward  E[i,j] = dR[N,M]/dd[i,j] by the reverse DP carried in log space
+ *             (Sec. 2 "Backward pass", Sec. 4.2), then
+ *             dx_i = 2 (x_i sum_j E_ij - sum_j E_ij y_j), dy_j alike    (Sec. 4.3)
+ *   modes     unfused: the B x N x M cost tensor is materialised once;
+ *             fused:   the cost is recomputed per tile inside the DP kernels and the
+ *                      cost tensor is never stored                       (Sec. 4.3)
+ *   barycenter step: loss = sum_k sdtw(z, X_k), dz = sum_k d/dz, Adam    (Sec. 4.4)
+ *
+ * Conventions for every entry point
+ *   - All tensor arguments are DEVICE pointers to row-major, contiguous float32 memory
+ *     owned by the caller, 16-byte aligned.  Descriptors and scalar out-parameters are
+ *     HOST pointers.  Inputs are never modified; outputs are overwritten, not accumulated.
+ *   - The library allocates no device memory.  Temporary storage is the caller's
+ *     `workspace` (device, 256-byte aligned) of at least sdtw_workspace_bytes() bytes.  The
+ *     forward call leaves its DP table there for the backward call of the same descriptor.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue
+ *     work on it and return without waiting, except where stated.
+ *   - Return value: an sdtw_status.  Argument errors are detected on the host before any
+ *     device work is enqueued.  Conditions only the device can see (a backward call on a
+ *     workspace whose forward was run for another descriptor; an inter-workgroup wait that
+ *     gave up) are recorded in the workspace and read with sdtw_workspace_status().
+ *   - No call throws, aborts or prints.
+ *   - Two calls that use the same workspace must be ordered (same stream, or synchronised by
+ *     the caller).
+ */
+#ifndef SDTW_H
+#define SDTW_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum sdtw_status {
+    SDTW_OK = 0,
+    SDTW_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, gamma not finite or <= 0, bad mode */
+    SDTW_ERR_WORKSPACE = 2,   /* workspace missing, misaligned or smaller than required */
+    SDTW_ERR_UNSUPPORTED = 3, /* bandwidth != 0 (Algorithm 1 names it, the paper never defines it) */
+    SDTW_ERR_STATE = 4,       /* device: backward on a workspace not filled by a matching forward */
+    SDTW_ERR_HIP = 5,         /* a HIP runtime call failed (launch, copy) */
+    SDTW_ERR_TIMEOUT = 6      /* device: a band gave up waiting for the band it depends on */
+} sdtw_status;
+
+enum { SDTW_UNFUSED = 0, SDTW_FUSED = 1 };
+
+/* What sdtw_debug_export copies out of a workspace. */
+enum { SDTW_EXPORT_COST = 0, SDTW_EXPORT_R = 1, SDTW_EXPORT_E = 2 };
+
+/* One batch of B independent pairs (x_b, y_b); every pair has the same N, M, D. */
+typedef struct sdtw_desc {
+    int32_t B, N, M, D;     /* all >= 1 */
+    float gamma;            /* > 0, finite */
+    int32_t mode;           /* SDTW_UNFUSED or SDTW_FUSED */
+    int64_t x_batch_stride; /* elements between consecutive x sequences: N*D, or 0 = one x shared */
+    int64_t y_batch_stride; /* elements between consecutive y sequences: M*D, or 0 = one y shared */
+    int32_t bandwidth;      /* reserved, must be 0 (no band constraint, as in the paper's Sec. 5) */
+    uint32_t flags;         /* reserved, must be 0 */
+} sdtw_desc;
+
+/* One barycenter step: K sequences X_k [Lx,D] against the current barycenter z [Lz,D]. */
+typedef struct sdtw_bary_desc {
+    int32_t K, Lz, Lx, D;   /* all >= 1 */
+    float gamma;            /* > 0, finite */
+    int32_t mode;           /* SDTW_UNFUSED or SDTW_FUSED */
+    float lr, beta1, beta2, eps; /* Adam: lr > 0, 0 <= beta < 1, eps > 0 */
+    int32_t step;           /* 1-based index of this step (bias correction) */
+    uint32_t flags;         /* reserved, must be 0 */
+} sdtw_bary_desc;
+
+int sdtw_version(void);
+const char *sdtw_status_string(int status);
+
+/* Bytes of workspace the descriptor needs; 0 if the descriptor is invalid.  Host only. */
+size_t sdtw_workspace_bytes(const sdtw_desc *desc);
+
+/*
+ * Forward (Sec. 2 Eq. 1-3; Sec. 4.1 removes the length cap; Sec. 4.3 defines the modes).
+ *   x [B,N,D] (or [N,D] with x_batch_stride 0), y [B,M,D]: device, read only.
+ *   value [B]: device, out; value[b] = R[N,M] of pair b (float32; the table itself is
+ *              carried in float64 inside the workspace).
+ * Leaves the DP table (and, unfused, the cost tensor) in `workspace` for sdtw_backward.
+ */
+int sdtw_forward(const sdtw_desc *desc, const float *x, const float *y, float *value,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Backward (Sec. 2 "Backward pass", Sec. 4.2 log-space recurrence, Sec. 4.3 gradient formulas).
+ * Must follow sdtw_forward with the same descriptor, x, y and workspace.
+ *   grad_value [B]: device, upstream dL/dvalue per pair, or NULL for ones.
+ *   dx [B,N,D], dy [B,M,D]: device, out; either may be NULL if not wanted.  With
+ *        x_batch_stride 0 dx still has one [N,D] slab per pair (the caller sums them).
+ *   E_out [B,N,M]: device, out, optional (NULL): the alignment matrix E.
+ */
+int sdtw_backward(const sdtw_desc *desc, const float *x, const float *y, const float *grad_value,
+                  float *dx, float *dy, float *E_out, void *workspace, size_t workspace_bytes,
+                  void *stream);
+
+/* Bytes of workspace for sdtw_barycenter_step; 0 if the descriptor is invalid.  Host only. */
+size_t sdtw_barycenter_workspace_bytes(const sdtw_bary_desc *desc);
+
+/*
+ * One barycenter step (Sec. 4.4): loss = sum_k sdtw_gamma(z, X_k); dz = sum_k d sdtw/dz
+ * (summed over k in index order); then Adam with bias correction:
+ *   m = beta1 m + (1-beta1) dz;  v = beta2 v + (1-beta2) dz^2;
+ *   z -= lr * (m/(1-beta1^step)) / (sqrt(v/(1-beta2^step)) + eps).
+ *   z [Lz,D]: device, in/out.  X [K,Lx,D]: device, read only.
+ *   adam_m, adam_v [Lz,D]: device, in/out, caller-owned optimiser state (zeros before step 1).
+ *   loss [1]: device, out.  dz_out [Lz,D]: device, out, optional (NULL).
+ */
+int sdtw_barycenter_step(const sdtw_bary_desc *desc, float *z, const float *X, float *adam_m,
+                         float *adam_v, float *loss, float *dz_out, void *workspace,
+                         size_t workspace_bytes, void *stream);
+
+/*
+ * Reads the device-side status word of a workspace: waits for `stream`, copies 4 bytes to the
+ * host.  *device_status receives SDTW_OK, SDTW_ERR_STATE or SDTW_ERR_TIMEOUT.  When a backward
+ * call found SDTW_ERR_STATE its dx, dy and E outputs are filled with NaN.
+ */
+int sdtw_workspace_status(const void *workspace, size_t workspace_bytes, void *stream,
+                          int32_t *device_status);
+
+/*
+ * Test hook: copies an intermediate out of a workspace as a plain row-major tensor.
+ *   SDTW_EXPORT_COST: out = float32 [B,N,M], the cost tensor d (unfused mode, after forward)
+ *   SDTW_EXPORT_R:    out = float64 [B,N,M], the DP table R[1..N,1..M] (after forward)
+ *   SDTW_EXPORT_E:    out = float32 [B,N,M], the alignment matrix (after backward)
+ * `out` is a device pointer with room for B*N*M elements of that type.
+ */
+int sdtw_debug_export(const sdtw_desc *desc, const void *workspace, size_t workspace_bytes,
+                      int what, void *out, void *stream);
+
+/*
+ * Test hook: runs the two cross-lane shifts the DP kernels rely on, on lane numbers.
+ * out [128] int32, device: out[t] = lane t-1 (lane 0: -1), out[64+t] = lane t+1 (lane 63: -2).
+ */
+int sdtw_debug_lane_shift(int32_t *out, void *stream);
+
+/*
+ * Test hook: number of polls after which a band that waits for its neighbouring band gives up
+ * and records SDTW_ERR_TIMEOUT (default 2^23, several seconds).  Process-wide; host only.
+ */
+int sdtw_debug_set_spin_limit(uint32_t polls);
+
+/*
+ * Benchmark hook: per-kernel timing.  sdtw_debug_profile(1) makes every later call bracket each
+ * of its kernel launches with two HIP events on the caller's stream (this creates events, so it
+ * is not for latency-critical callers); sdtw_debug_profile(0) switches it off and drops what was
+ * recorded.  sdtw_debug_profile_read waits for the recorded events, writes up to max_entries
+ * durations in milliseconds to ms (host) and the kernel labels, ';'-separated in launch order, to
+ * names (host, names_bytes long), sets *count and clears the record.  Process-wide; not
+ * thread-safe.
+ */
+int sdtw_debug_profile(int enable);
+int sdtw_debug_profile_read(char *names, size_t names_bytes, float *ms, int max_entries, int *count);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SDTW_H */

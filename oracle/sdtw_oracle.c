@@ -133,28 +133,45 @@ void sdtw_oracle_backward(const double *d, const double *R, int N, int M, double
             E[(size_t)(i - 1) * M + (j - 1)] = exp(Ebar[i * W + j]);
 }
 
-/* dx[i,:] = g * 2 (x_i sum_j E_ij - sum_j E_ij y_j); dy[j,:] = g * 2 (y_j sum_i E_ij - sum_i E_ij x_i). */
+/* dx[i,:] = g * 2 (x_i sum_j E_ij - sum_j E_ij y_j); dy[j,:] = g * 2 (y_j sum_i E_ij - sum_i E_ij x_i).
+ * Every sum runs over its index in increasing order; the feature loop is innermost only so that
+ * memory is walked along rows (the terms of each sum and their order are those of the formula). */
 void sdtw_oracle_input_grads(const float *x, const float *y, const double *E, int N, int M, int D,
                              double g, double *dx, double *dy)
 {
+    double *acc = (double *)malloc((size_t)(N > M ? N : M) * D * sizeof(double));
+    double *marg = (double *)malloc((size_t)(N > M ? N : M) * sizeof(double));
+    if (!acc || !marg) { free(acc); free(marg); return; }
+    /* dx: for each i, sum over j */
     for (int i = 0; i < N; ++i) {
         double rs = 0.0;
-        for (int j = 0; j < M; ++j) rs += E[(size_t)i * M + j];
-        for (int k = 0; k < D; ++k) {
-            double acc = 0.0;
-            for (int j = 0; j < M; ++j) acc += E[(size_t)i * M + j] * (double)y[(size_t)j * D + k];
-            dx[(size_t)i * D + k] = g * 2.0 * ((double)x[(size_t)i * D + k] * rs - acc);
+        double *a = acc + (size_t)i * D;
+        for (int k = 0; k < D; ++k) a[k] = 0.0;
+        for (int j = 0; j < M; ++j) {
+            const double e = E[(size_t)i * M + j];
+            rs += e;
+            for (int k = 0; k < D; ++k) a[k] += e * (double)y[(size_t)j * D + k];
         }
+        for (int k = 0; k < D; ++k)
+            dx[(size_t)i * D + k] = g * 2.0 * ((double)x[(size_t)i * D + k] * rs - a[k]);
     }
+    /* dy: for each j, sum over i (i is the outer loop, so each j still receives its terms in order of i) */
     for (int j = 0; j < M; ++j) {
-        double cs = 0.0;
-        for (int i = 0; i < N; ++i) cs += E[(size_t)i * M + j];
-        for (int k = 0; k < D; ++k) {
-            double acc = 0.0;
-            for (int i = 0; i < N; ++i) acc += E[(size_t)i * M + j] * (double)x[(size_t)i * D + k];
-            dy[(size_t)j * D + k] = g * 2.0 * ((double)y[(size_t)j * D + k] * cs - acc);
-        }
+        marg[j] = 0.0;
+        for (int k = 0; k < D; ++k) acc[(size_t)j * D + k] = 0.0;
     }
+    for (int i = 0; i < N; ++i)
+        for (int j = 0; j < M; ++j) {
+            const double e = E[(size_t)i * M + j];
+            double *a = acc + (size_t)j * D;
+            marg[j] += e;
+            for (int k = 0; k < D; ++k) a[k] += e * (double)x[(size_t)i * D + k];
+        }
+    for (int j = 0; j < M; ++j)
+        for (int k = 0; k < D; ++k)
+            dy[(size_t)j * D + k] = g * 2.0 * ((double)y[(size_t)j * D + k] * marg[j] - acc[(size_t)j * D + k]);
+    free(acc);
+    free(marg);
 }
 
 /* One pair, start to end.  Any of R_out ((N+2)(M+2)), E_out (N*M), dx, dy, d_out (N*M)

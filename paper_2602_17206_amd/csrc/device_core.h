@@ -1,0 +1,122 @@
+// Device-side building blocks: cross-lane shifts, the soft-minimum, the 32x32 cost block.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "layout.h"
+
+namespace sdtw {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// ---------------------------------------------------------------------------------------------
+// Cross-lane shifts over the 64 lanes of a wavefront (DPP wave_shr:1 / wave_shl:1).
+// result[t] = v[t-1]; lane 0 keeps `fill`.
+__device__ __forceinline__ int lane_shr1_i32(int v, int fill)
+{
+    return __builtin_amdgcn_update_dpp(fill, v, 0x138, 0xf, 0xf, false);
+}
+// result[t] = v[t+1]; lane 63 keeps `fill`.
+__device__ __forceinline__ int lane_shl1_i32(int v, int fill)
+{
+    return __builtin_amdgcn_update_dpp(fill, v, 0x130, 0xf, 0xf, false);
+}
+__device__ __forceinline__ double lane_shr1(double v, double fill)
+{
+    int lo = lane_shr1_i32(__double2loint(v), __double2loint(fill));
+    int hi = lane_shr1_i32(__double2hiint(v), __double2hiint(fill));
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double lane_shl1(double v, double fill)
+{
+    int lo = lane_shl1_i32(__double2loint(v), __double2loint(fill));
+    int hi = lane_shl1_i32(__double2hiint(v), __double2hiint(fill));
+    return __hiloint2double(hi, lo);
+}
+// value of lane `src` (compile-time constant after unrolling) broadcast to the wavefront
+__device__ __forceinline__ double read_lane(double v, int src)
+{
+    int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
+    int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
+    return __hiloint2double(hi, lo);
+}
+
+// ---------------------------------------------------------------------------------------------
+// softmin_gamma(a,b,c) = -gamma log(e^{-a/gamma}+e^{-b/gamma}+e^{-c/gamma})     (Sec. 2, Eq. 2)
+// evaluated as  m - gamma ln2 * log2(1 + 2^{-(med-m) c2} + 2^{-(max-m) c2}),  c2 = log2(e)/gamma,
+// i.e. the max-shifted log-sum-exp of Sec. 4.2 with the shift equal to the minimum.
+// The table values (a,b,c,m) are float64 so that differences of neighbours keep an absolute
+// accuracy far below gamma however large R grows; the exponentials and the logarithm see only
+// those differences and run in float32 on the hardware's exp2/log2 units.
+// +inf arguments (cells outside the grid) contribute 2^{-inf} = 0.  If all three are +inf the
+// result is NaN; callers discard it (such a cell is outside the grid).
+__device__ __forceinline__ double softmin3(double a, double b, double c, float c2, float gamma_ln2)
+{
+    const double m = fmin(fmin(a, b), c);
+    const float fa = (float)(a - m), fb = (float)(b - m), fc = (float)(c - m);
+    const float mx = __builtin_fmaxf(__builtin_fmaxf(fa, fb), fc);
+    const float md = __builtin_amdgcn_fmed3f(fa, fb, fc);
+    const float S = 1.0f + __builtin_amdgcn_exp2f(-md * c2) + __builtin_amdgcn_exp2f(-mx * c2);
+    return m - (double)(gamma_ln2 * __builtin_amdgcn_logf(S));
+}
+
+// ---------------------------------------------------------------------------------------------
+// One 32x32 block of inner products <x_r, y_c> on the fp32 matrix cores
+// (v_mfma_f32_32x32x2_f32).  Lane l supplies row r = l&31 of both operands; lanes 0-31 and 32-63
+// split every group of 8 feature indices into its lower and upper 4, so one float4 load per
+// operand feeds four MFMAs.  xrow / yrow point at this lane's rows (already clamped in range).
+// Result layout (hardware): acc[i] belongs to row 8*(i/4) + 4*(l>>5) + (i&3), column l&31.
+__device__ __forceinline__ floatx16 dot_block_32x32(const float *__restrict__ xrow,
+                                                    const float *__restrict__ yrow, int D, bool vec,
+                                                    int lane)
+{
+    floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const int h4 = (lane >> 5) * 4;
+    if (vec) {
+#pragma unroll 4
+        for (int k0 = 0; k0 < D; k0 += 8) {
+            const float4 a = *reinterpret_cast<const float4 *>(xrow + k0 + h4);
+            const float4 b = *reinterpret_cast<const float4 *>(yrow + k0 + h4);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
+        }
+    } else {
+        for (int k0 = 0; k0 < D; k0 += 8) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int k = k0 + h4 + c;
+                const float a = (k < D) ? xrow[k] : 0.f;
+                const float b = (k < D) ? yrow[k] : 0.f;
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+            }
+        }
+    }
+    return acc;
+}
+
+__device__ __forceinline__ int acc_row(int i, int lane) { return 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3); }
+
+// Squared-Euclidean cost block through the norm expansion (Sec. 4.3, Eq. 8):
+//   d = ||x_i||^2 - 2 <x_i,y_j> + ||y_j||^2, clamped at 0 (rounding can push it below).
+// Rows i0.., columns j0.. of pair data (xb, yb, xnb, ynb); rows/columns outside the grid are
+// computed from clamped indices and must be ignored by the caller.
+__device__ __forceinline__ void cost_block(const Params &p, const float *__restrict__ xb,
+                                           const float *__restrict__ yb,
+                                           const float *__restrict__ xnb,
+                                           const float *__restrict__ ynb, int i0, int j0, int lane,
+                                           float (&out)[16])
+{
+    const int r = lane & 31;
+    const int xi = min(i0 + r, p.N - 1), yj = min(j0 + r, p.M - 1);
+    const floatx16 acc = dot_block_32x32(xb + (size_t)xi * p.D, yb + (size_t)yj * p.D, p.D,
+                                         p.vec_xy != 0, lane);
+    const float ynv = ynb[yj];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int row = min(i0 + acc_row(i, lane), p.N - 1);
+        out[i] = fmaxf(xnb[row] + ynv - 2.0f * acc[i], 0.0f);
+    }
+}
+
+}  // namespace sdtw

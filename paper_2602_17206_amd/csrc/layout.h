@@ -1,0 +1,102 @@
+// Workspace layout and kernel parameter blocks shared by the host entry points and the kernels.
+//
+// The DP works on row bands of 64 rows (one row per wavefront lane).  A band sweeps the columns
+// in "steps": at step s lane t owns cell (row0+t, s-t), so all 64 cells of a step lie on one
+// anti-diagonal (Sec. 4.1: cells of an anti-diagonal are independent).  Steps are grouped in
+// macro-steps of 32 because the cost arrives in 32x32 blocks.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+namespace sdtw {
+
+constexpr int kBandRows = 64;    // rows per band == lanes per wavefront
+constexpr int kBlk = 32;         // edge of a cost block (one 32x32 MFMA tile)
+constexpr int kLdsStride = 36;   // floats per LDS block row: 16-byte aligned rows, odd (stride-1)
+constexpr uint64_t kSentinel = 0xFFFFFFFFFFFFFFFFull;  // "not written yet" in boundary rows
+constexpr uint32_t kMagic = 0x53445457u;               // 'SDTW'
+constexpr int kGuardBytes = 512;  // slack before/after regions that are read with clamped indices
+
+// First 256 bytes of a workspace (device memory).
+struct Header {
+    uint32_t magic;
+    int32_t B, N, M, D, mode;
+    uint32_t gamma_bits;
+    int32_t forward_done;  // set by the forward call, checked by the backward call
+    int32_t status;        // device-side sdtw_status (0, STATE, TIMEOUT)
+    int32_t abort_backward;
+    uint32_t fwd_ticket;   // next band task of the forward sweep
+    uint32_t bwd_ticket;   // next band task of the backward sweep
+    uint32_t pad[52];
+};
+static_assert(sizeof(Header) == 256, "header is 256 bytes");
+
+struct Layout {
+    int32_t B, N, M, D, mode;
+    int32_t nbands;   // ceil(N/64)
+    int32_t nmacro;   // macro-steps per band sweep: ceil((M+63)/32)
+    int32_t nrb, ncb; // 32x32 block rows / columns: ceil(N/32), ceil(M/32)
+    int64_t xn_count, yn_count;  // number of norm entries (1 sequence when the batch stride is 0)
+    size_t off_hdr, off_rfinal, off_xn, off_yn, off_brow, off_R, off_cost, off_E, off_nz, total;
+};
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// steps per band sweep (multiple of 32, >= M+63)
+inline int64_t steps_of(const Layout &L) { return (int64_t)L.nmacro * kBlk; }
+
+inline Layout make_layout(int32_t B, int32_t N, int32_t M, int32_t D, int32_t mode, bool x_shared,
+                          bool y_shared)
+{
+    Layout L{};
+    L.B = B; L.N = N; L.M = M; L.D = D; L.mode = mode;
+    L.nbands = (N + kBandRows - 1) / kBandRows;
+    L.nmacro = (M + kBandRows - 1 + kBlk - 1) / kBlk;
+    L.nrb = (N + kBlk - 1) / kBlk;
+    L.ncb = (M + kBlk - 1) / kBlk;
+    L.xn_count = (int64_t)(x_shared ? 1 : B) * N;
+    L.yn_count = (int64_t)(y_shared ? 1 : B) * M;
+    size_t o = 0;
+    L.off_hdr = o;      o += sizeof(Header);
+    L.off_rfinal = o;   o = align_up(o + (size_t)B * sizeof(double), 256);
+    L.off_xn = o;       o = align_up(o + (size_t)L.xn_count * sizeof(float), 256);
+    L.off_yn = o;       o = align_up(o + (size_t)L.yn_count * sizeof(float), 256);
+    // boundary rows: one row of M float64 per (pair, band)
+    L.off_brow = o;     o = align_up(o + (size_t)B * L.nbands * (size_t)M * sizeof(double), 256);
+    // DP table in step-major order: [B][nbands][steps][64] float64
+    L.off_R = o;        o = align_up(o + (size_t)B * L.nbands * (size_t)steps_of(L) * kBandRows * sizeof(double), 256);
+    o += kGuardBytes;
+    L.off_cost = o;
+    if (mode == 0) o = align_up(o + (size_t)B * N * (size_t)M * sizeof(float), 256);
+    o += kGuardBytes;
+    L.off_E = o;        o = align_up(o + (size_t)B * N * (size_t)M * sizeof(float), 256);
+    o += kGuardBytes;
+    L.off_nz = o;       o = align_up(o + (size_t)B * L.nrb * (size_t)L.ncb, 256);
+    L.total = o;
+    return L;
+}
+
+// Everything a kernel needs; passed by value.
+struct Params {
+    int32_t B, N, M, D, mode;
+    int32_t nbands, nmacro, nrb, ncb;
+    float gamma;
+    float inv_gamma_log2e;  // log2(e)/gamma
+    float gamma_ln2;        // gamma*ln(2)
+    int64_t x_stride, y_stride;    // batch strides of x, y (elements)
+    int64_t xn_stride, yn_stride;  // batch strides of the norm vectors (0 when shared)
+    int32_t vec_xy;                // 1: D%8==0 and x,y 16-byte aligned -> float4 operand loads
+    int32_t vec_m;                 // 1: M%4==0 -> float4 loads/stores of cost and E rows
+    uint32_t spin_limit;           // polls before a band gives up waiting
+    const float *x, *y;
+    Header *hdr;
+    double *rfinal;
+    float *xn, *yn;
+    unsigned long long *brow;
+    double *R;
+    float *cost;
+    float *E;
+    unsigned char *nz;
+};
+
+}  // namespace sdtw

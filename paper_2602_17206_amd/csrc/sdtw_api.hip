@@ -1,0 +1,363 @@
+// C entry points of the Soft-DTW library (declared in include/sdtw.h): argument checks,
+// workspace carving and kernel launches.  No device memory is allocated here.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/sdtw.h"
+#include "kernels.h"
+#include "layout.h"
+
+namespace {
+
+using namespace sdtw;
+
+uint32_t g_spin_limit = 1u << 23;  // ~10 s of polling before a band gives up
+
+// Optional per-kernel timing (test/benchmark hook): when switched on, every kernel launch of the
+// library is bracketed by two HIP events on the caller's stream.
+struct ProfEntry { const char *name; hipEvent_t a, b; };
+bool g_profile = false;
+std::vector<ProfEntry> g_prof;
+
+struct ProfScope {
+    hipStream_t st;
+    bool on;
+    ProfScope(const char *name, hipStream_t s) : st(s), on(g_profile)
+    {
+        if (!on) return;
+        ProfEntry e{name, nullptr, nullptr};
+        if (hipEventCreate(&e.a) != hipSuccess || hipEventCreate(&e.b) != hipSuccess) { on = false; return; }
+        (void)hipEventRecord(e.a, st);
+        g_prof.push_back(e);
+    }
+    ~ProfScope() { if (on) (void)hipEventRecord(g_prof.back().b, st); }
+};
+
+bool desc_ok(const sdtw_desc *d, int *why)
+{
+    *why = SDTW_ERR_INVALID_ARG;
+    if (!d) return false;
+    if (d->B < 1 || d->N < 1 || d->M < 1 || d->D < 1) return false;
+    if (d->B > 32767) return false;
+    if (!(d->gamma > 0.0f) || !std::isfinite(d->gamma)) return false;
+    if (d->mode != SDTW_UNFUSED && d->mode != SDTW_FUSED) return false;
+    if (d->flags != 0) return false;
+    if (d->x_batch_stride != 0 && d->x_batch_stride != (int64_t)d->N * d->D) return false;
+    if (d->y_batch_stride != 0 && d->y_batch_stride != (int64_t)d->M * d->D) return false;
+    if ((int64_t)d->M + 128 > 0x3FFFFFFF || (int64_t)d->N + 128 > 0x3FFFFFFF) return false;
+    if (d->bandwidth != 0) { *why = SDTW_ERR_UNSUPPORTED; return false; }
+    *why = SDTW_OK;
+    return true;
+}
+
+Layout layout_of(const sdtw_desc *d)
+{
+    return make_layout(d->B, d->N, d->M, d->D, d->mode, d->x_batch_stride == 0, d->y_batch_stride == 0);
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+Params make_params(const sdtw_desc *d, const Layout &L, const float *x, const float *y, void *ws)
+{
+    Params p{};
+    char *base = static_cast<char *>(ws);
+    p.B = d->B; p.N = d->N; p.M = d->M; p.D = d->D; p.mode = d->mode;
+    p.nbands = L.nbands; p.nmacro = L.nmacro; p.nrb = L.nrb; p.ncb = L.ncb;
+    p.gamma = d->gamma;
+    p.inv_gamma_log2e = (float)(1.4426950408889634 / (double)d->gamma);
+    p.gamma_ln2 = (float)(0.6931471805599453 * (double)d->gamma);
+    p.x_stride = d->x_batch_stride; p.y_stride = d->y_batch_stride;
+    p.xn_stride = d->x_batch_stride == 0 ? 0 : d->N;
+    p.yn_stride = d->y_batch_stride == 0 ? 0 : d->M;
+    p.vec_xy = (d->D % 8 == 0) && aligned16(x) && aligned16(y) && (d->x_batch_stride % 4 == 0) &&
+               (d->y_batch_stride % 4 == 0);
+    p.vec_m = (d->M % 4 == 0);
+    p.spin_limit = g_spin_limit;
+    p.x = x; p.y = y;
+    p.hdr = reinterpret_cast<Header *>(base + L.off_hdr);
+    p.rfinal = reinterpret_cast<double *>(base + L.off_rfinal);
+    p.xn = reinterpret_cast<float *>(base + L.off_xn);
+    p.yn = reinterpret_cast<float *>(base + L.off_yn);
+    p.brow = reinterpret_cast<unsigned long long *>(base + L.off_brow);
+    p.R = reinterpret_cast<double *>(base + L.off_R);
+    p.cost = reinterpret_cast<float *>(base + L.off_cost);
+    p.E = reinterpret_cast<float *>(base + L.off_E);
+    p.nz = reinterpret_cast<unsigned char *>(base + L.off_nz);
+    return p;
+}
+
+int check_ws(const void *ws, size_t bytes, size_t need)
+{
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) != 0 || bytes < need) return SDTW_ERR_WORKSPACE;
+    return SDTW_OK;
+}
+
+inline int hip_ok() { return hipGetLastError() == hipSuccess ? SDTW_OK : SDTW_ERR_HIP; }
+
+unsigned fill_grid(size_t n) { size_t g = (n + 255) / 256; return (unsigned)(g < 1 ? 1 : (g > 4096 ? 4096 : g)); }
+
+void fill_boundary(const Params &p, hipStream_t st)
+{
+    const size_t n = (size_t)p.B * p.nbands * p.M;
+    fill_u64_kernel<<<fill_grid(n), 256, 0, st>>>(p.brow, n, kSentinel);
+}
+
+int forward_impl(const sdtw_desc *d, const float *x, const float *y, float *value, void *ws, hipStream_t st)
+{
+    const Layout L = layout_of(d);
+    const Params p = make_params(d, L, x, y, ws);
+    { ProfScope ps("forward_begin", st); forward_begin_kernel<<<1, 64, 0, st>>>(p); }
+    { ProfScope ps("fill_boundary", st); fill_boundary(p, st); }
+    { ProfScope ps("row_sqnorm", st);
+    row_sqnorm_kernel<<<(unsigned)std::min<int64_t>((L.xn_count + 3) / 4, 65535), 256, 0, st>>>(x, p.xn, L.xn_count, d->D);
+    row_sqnorm_kernel<<<(unsigned)std::min<int64_t>((L.yn_count + 3) / 4, 65535), 256, 0, st>>>(y, p.yn, L.yn_count, d->D);
+    }
+    const unsigned tasks = (unsigned)d->B * (unsigned)L.nbands;
+    if (d->mode == SDTW_UNFUSED) {
+        dim3 g((d->M + 63) / 64, (d->N + 63) / 64, d->B);
+        { ProfScope ps("cost_tensor", st); cost_tensor_kernel<<<g, 256, 0, st>>>(p); }
+        { ProfScope ps("forward_dp_unfused", st); forward_dp_kernel<false><<<tasks, 64, 0, st>>>(p, value); }
+    } else {
+        ProfScope ps("forward_dp_fused", st);
+        forward_dp_kernel<true><<<tasks, 64, 0, st>>>(p, value);
+    }
+    return hip_ok();
+}
+
+int backward_impl(const sdtw_desc *d, const float *x, const float *y, const float *grad_value, float *dx,
+                  float *dy, float *E_out, void *ws, hipStream_t st)
+{
+    const Layout L = layout_of(d);
+    const Params p = make_params(d, L, x, y, ws);
+    { ProfScope ps("backward_begin", st); backward_begin_kernel<<<1, 64, 0, st>>>(p); }
+    { ProfScope ps("fill_boundary", st); fill_boundary(p, st); }
+    const unsigned tasks = (unsigned)d->B * (unsigned)L.nbands;
+    if (d->mode == SDTW_UNFUSED) {
+        ProfScope ps("backward_dp_unfused", st);
+        backward_dp_kernel<false><<<tasks, 64, 0, st>>>(p);
+    } else {
+        ProfScope ps("backward_dp_fused", st);
+        backward_dp_kernel<true><<<tasks, 64, 0, st>>>(p);
+    }
+    if (dx || dy) {
+        const int P = std::max(dx ? d->N : 0, dy ? d->M : 0);
+        dim3 g((P + 63) / 64, (d->D + 63) / 64, 2 * d->B);
+        ProfScope ps("input_grad", st);
+        input_grad_kernel<<<g, 256, 0, st>>>(p, grad_value, dx, dy);
+    }
+    if (E_out) {
+        const size_t n = (size_t)d->B * d->N * d->M;
+        export_E_kernel<<<fill_grid(n), 256, 0, st>>>(p, E_out);
+    }
+    return hip_ok();
+}
+
+bool bary_ok(const sdtw_bary_desc *d)
+{
+    if (!d) return false;
+    if (d->K < 1 || d->Lz < 1 || d->Lx < 1 || d->D < 1 || d->step < 1 || d->K > 32767) return false;
+    if (!(d->gamma > 0.0f) || !std::isfinite(d->gamma)) return false;
+    if (d->mode != SDTW_UNFUSED && d->mode != SDTW_FUSED) return false;
+    if (!(d->lr > 0.0f) || !std::isfinite(d->lr)) return false;
+    if (!(d->beta1 >= 0.0f && d->beta1 < 1.0f) || !(d->beta2 >= 0.0f && d->beta2 < 1.0f)) return false;
+    if (!(d->eps > 0.0f) || !std::isfinite(d->eps)) return false;
+    if (d->flags != 0) return false;
+    return true;
+}
+
+sdtw_desc bary_pair_desc(const sdtw_bary_desc *d)
+{
+    sdtw_desc s{};
+    s.B = d->K; s.N = d->Lz; s.M = d->Lx; s.D = d->D;
+    s.gamma = d->gamma; s.mode = d->mode;
+    s.x_batch_stride = 0;
+    s.y_batch_stride = (int64_t)d->Lx * d->D;
+    s.bandwidth = 0; s.flags = 0;
+    return s;
+}
+
+struct BaryLayout { size_t off_values, off_dx, off_pair_ws, total; };
+
+BaryLayout bary_layout(const sdtw_bary_desc *d)
+{
+    BaryLayout L{};
+    size_t o = 0;
+    // the pair workspace comes first so that its header (status word) sits at offset 0
+    L.off_pair_ws = o;
+    const sdtw_desc s = bary_pair_desc(d);
+    o = align_up(o + layout_of(&s).total, 256);
+    L.off_values = o; o = align_up(o + (size_t)d->K * sizeof(float), 256);
+    L.off_dx = o;     o = align_up(o + (size_t)d->K * d->Lz * (size_t)d->D * sizeof(float), 256);
+    L.total = o;
+    return L;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sdtw_version(void) { return 100; }
+
+const char *sdtw_status_string(int status)
+{
+    switch (status) {
+        case SDTW_OK: return "ok";
+        case SDTW_ERR_INVALID_ARG: return "invalid argument";
+        case SDTW_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case SDTW_ERR_UNSUPPORTED: return "unsupported option (bandwidth must be 0)";
+        case SDTW_ERR_STATE: return "backward called on a workspace without a matching forward";
+        case SDTW_ERR_HIP: return "HIP runtime error";
+        case SDTW_ERR_TIMEOUT: return "a band gave up waiting for its neighbour";
+        default: return "unknown status";
+    }
+}
+
+size_t sdtw_workspace_bytes(const sdtw_desc *desc)
+{
+    int why;
+    if (!desc_ok(desc, &why)) return 0;
+    return layout_of(desc).total;
+}
+
+int sdtw_forward(const sdtw_desc *desc, const float *x, const float *y, float *value, void *workspace,
+                 size_t workspace_bytes, void *stream)
+{
+    int why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!x || !y || !value) return SDTW_ERR_INVALID_ARG;
+    if (int rc = check_ws(workspace, workspace_bytes, layout_of(desc).total)) return rc;
+    return forward_impl(desc, x, y, value, workspace, static_cast<hipStream_t>(stream));
+}
+
+int sdtw_backward(const sdtw_desc *desc, const float *x, const float *y, const float *grad_value, float *dx,
+                  float *dy, float *E_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!x || !y) return SDTW_ERR_INVALID_ARG;
+    if (int rc = check_ws(workspace, workspace_bytes, layout_of(desc).total)) return rc;
+    return backward_impl(desc, x, y, grad_value, dx, dy, E_out, workspace, static_cast<hipStream_t>(stream));
+}
+
+size_t sdtw_barycenter_workspace_bytes(const sdtw_bary_desc *desc)
+{
+    if (!bary_ok(desc)) return 0;
+    return bary_layout(desc).total;
+}
+
+int sdtw_barycenter_step(const sdtw_bary_desc *desc, float *z, const float *X, float *adam_m, float *adam_v,
+                         float *loss, float *dz_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!bary_ok(desc)) return SDTW_ERR_INVALID_ARG;
+    if (!z || !X || !adam_m || !adam_v || !loss) return SDTW_ERR_INVALID_ARG;
+    const BaryLayout BL = bary_layout(desc);
+    if (int rc = check_ws(workspace, workspace_bytes, BL.total)) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *base = static_cast<char *>(workspace);
+    float *values = reinterpret_cast<float *>(base + BL.off_values);
+    float *dxk = reinterpret_cast<float *>(base + BL.off_dx);
+    void *pair_ws = base + BL.off_pair_ws;
+    const sdtw_desc s = bary_pair_desc(desc);
+    if (int rc = forward_impl(&s, z, X, values, pair_ws, st)) return rc;
+    if (int rc = backward_impl(&s, z, X, nullptr, dxk, nullptr, nullptr, pair_ws, st)) return rc;
+    AdamParams a{};
+    a.K = desc->K;
+    a.n = (int64_t)desc->Lz * desc->D;
+    a.lr = desc->lr; a.beta1 = desc->beta1; a.beta2 = desc->beta2; a.eps = desc->eps;
+    a.corr1 = (float)(1.0 - std::pow((double)desc->beta1, (double)desc->step));
+    a.corr2 = (float)(1.0 - std::pow((double)desc->beta2, (double)desc->step));
+    {
+        ProfScope ps("barycenter_update", st);
+        barycenter_update_kernel<<<(unsigned)((a.n + 255) / 256), 256, 0, st>>>(a, dxk, values, z, adam_m, adam_v, loss, dz_out);
+    }
+    return hip_ok();
+}
+
+int sdtw_workspace_status(const void *workspace, size_t workspace_bytes, void *stream, int32_t *device_status)
+{
+    if (!device_status) return SDTW_ERR_INVALID_ARG;
+    if (int rc = check_ws(workspace, workspace_bytes, sizeof(Header))) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Header h;
+    if (hipMemcpyAsync(&h, workspace, sizeof(Header), hipMemcpyDeviceToHost, st) != hipSuccess) return SDTW_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return SDTW_ERR_HIP;
+    *device_status = (h.magic == kMagic) ? h.status : SDTW_ERR_STATE;
+    return SDTW_OK;
+}
+
+int sdtw_debug_export(const sdtw_desc *desc, const void *workspace, size_t workspace_bytes, int what, void *out,
+                      void *stream)
+{
+    int why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!out) return SDTW_ERR_INVALID_ARG;
+    const Layout L = layout_of(desc);
+    if (int rc = check_ws(workspace, workspace_bytes, L.total)) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const Params p = make_params(desc, L, nullptr, nullptr, const_cast<void *>(workspace));
+    const size_t n = (size_t)desc->B * desc->N * desc->M;
+    switch (what) {
+        case SDTW_EXPORT_COST:
+            if (desc->mode != SDTW_UNFUSED) return SDTW_ERR_INVALID_ARG;
+            if (hipMemcpyAsync(out, p.cost, n * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) return SDTW_ERR_HIP;
+            return SDTW_OK;
+        case SDTW_EXPORT_R:
+            export_R_kernel<<<fill_grid(n), 256, 0, st>>>(p, static_cast<double *>(out));
+            return hip_ok();
+        case SDTW_EXPORT_E:
+            export_E_kernel<<<fill_grid(n), 256, 0, st>>>(p, static_cast<float *>(out));
+            return hip_ok();
+        default:
+            return SDTW_ERR_INVALID_ARG;
+    }
+}
+
+int sdtw_debug_lane_shift(int32_t *out, void *stream)
+{
+    if (!out) return SDTW_ERR_INVALID_ARG;
+    lane_shift_probe_kernel<<<1, 64, 0, static_cast<hipStream_t>(stream)>>>(out);
+    return hip_ok();
+}
+
+int sdtw_debug_set_spin_limit(uint32_t polls)
+{
+    g_spin_limit = polls;
+    return SDTW_OK;
+}
+
+int sdtw_debug_profile(int enable)
+{
+    for (ProfEntry &e : g_prof) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+    g_prof.clear();
+    g_profile = enable != 0;
+    return SDTW_OK;
+}
+
+int sdtw_debug_profile_read(char *names, size_t names_bytes, float *ms, int max_entries, int *count)
+{
+    if (!names || !ms || !count || max_entries < 0) return SDTW_ERR_INVALID_ARG;
+    std::string joined;
+    int n = 0;
+    for (ProfEntry &e : g_prof) {
+        if (n >= max_entries) break;
+        if (hipEventSynchronize(e.b) != hipSuccess) return SDTW_ERR_HIP;
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, e.a, e.b) != hipSuccess) return SDTW_ERR_HIP;
+        ms[n++] = t;
+        joined += e.name;
+        joined += ';';
+    }
+    if (joined.size() + 1 > names_bytes) return SDTW_ERR_INVALID_ARG;
+    std::memcpy(names, joined.c_str(), joined.size() + 1);
+    *count = n;
+    for (ProfEntry &e : g_prof) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+    g_prof.clear();
+    return SDTW_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,347 @@
+"""Parity of the HIP path against the float64 CPU oracle, element by element, through the C-ABI.
+
+Bars (stated by the benchmark spec for fp32 I/O): |value - oracle| <= 1e-4 * max(|oracle|, 1) per pair;
+max|dx - oracle| <= 1e-3 * max|oracle dx| per pair (dy alike).  E is compared with an absolute
+tolerance since its entries lie in [0, 1].
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2602_17206_amd as pkg
+from paper_2602_17206_amd import binding, workloads
+
+pytestmark = pytest.mark.gpu
+
+VALUE_RTOL = 1e-4
+GRAD_RTOL = 1e-3
+E_ATOL = 2e-4
+MODES = {"unfused": pkg.UNFUSED, "fused": pkg.FUSED}
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def to_dev(a):
+    import torch
+
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def run_gpu(x, y, gamma, mode, grad_value=None, want_E=True):
+    import torch
+
+    xd, yd = to_dev(x), to_dev(y)
+    value, desc, ws = pkg.sdtw_forward(xd, yd, gamma, mode)
+    gv = to_dev(grad_value.astype(np.float32)) if grad_value is not None else None
+    dx, dy, E = pkg.sdtw_backward(desc, xd, yd, ws, grad_value=gv, want_E=want_E)
+    torch.cuda.synchronize()
+    assert binding.workspace_status(ws) == 0
+    out = {"value": value.cpu().numpy().astype(np.float64), "dx": dx.cpu().numpy().astype(np.float64),
+           "dy": dy.cpu().numpy().astype(np.float64), "desc": desc, "ws": ws}
+    if want_E:
+        out["E"] = E.cpu().numpy().astype(np.float64)
+    return out
+
+
+def check_against(ref, got, pairs=None, what=""):
+    """ref: oracle dict over `pairs` (indices into the GPU batch), got: GPU dict over the batch."""
+    B = ref["value"].shape[0]
+    pairs = list(range(B)) if pairs is None else pairs
+    for r, b in enumerate(pairs):
+        v, w = got["value"][b], ref["value"][r]
+        assert abs(v - w) <= VALUE_RTOL * max(abs(w), 1.0), "%s value pair %d: %r vs %r" % (what, b, v, w)
+        for key in ("dx", "dy"):
+            g, o = got[key][b], ref[key][r]
+            scale = max(np.abs(o).max(), 1e-30)
+            err = np.abs(g - o).max() / scale
+            assert err <= GRAD_RTOL, "%s %s pair %d: rel err %.3e" % (what, key, b, err)
+        if "E" in ref and "E" in got:
+            err = np.abs(got["E"][b] - ref["E"][r]).max()
+            assert err <= E_ATOL, "%s E pair %d: abs err %.3e" % (what, b, err)
+
+
+# ------------------------------------------------------------------------------- hardware facts
+def test_lane_shifts_behave_as_the_kernels_assume():
+    out = binding.debug_lane_shift().cpu().numpy()
+    np.testing.assert_array_equal(out[:64], np.concatenate([[-1], np.arange(63)]))
+    np.testing.assert_array_equal(out[64:], np.concatenate([np.arange(1, 64), [-2]]))
+
+
+# ------------------------------------------------------------------------------- intermediates
+@pytest.mark.parametrize("B,N,M,D", [(2, 64, 64, 8), (3, 70, 45, 5), (2, 33, 130, 128), (1, 1, 1, 1)])
+def test_unfused_cost_tensor(B, N, M, D):
+    import torch
+
+    say("cost tensor B=%d N=%d M=%d D=%d" % (B, N, M, D))
+    x, y = workloads.normal_pairs(100 + N, B, N, M, D)
+    xd, yd = to_dev(x), to_dev(y)
+    _, desc, ws = pkg.sdtw_forward(xd, yd, 1.0, pkg.UNFUSED)
+    d = binding.debug_export(desc, ws, binding.EXPORT_COST).cpu().numpy().astype(np.float64)
+    torch.cuda.synchronize()
+    ref = ((x[:, :, None, :].astype(np.float64) - y[:, None, :, :].astype(np.float64)) ** 2).sum(-1)
+    for b in range(B):
+        np.testing.assert_allclose(d[b], oracle.pair_tables(x[b], y[b], 1.0)["d"], rtol=0, atol=2e-5 * max(ref.max(), 1))
+    np.testing.assert_allclose(d, ref, rtol=0, atol=2e-5 * max(ref.max(), 1))
+
+
+@pytest.mark.parametrize("mode", ["unfused", "fused"])
+@pytest.mark.parametrize("N,M,D,gamma", [(64, 64, 8, 1.0), (100, 77, 16, 0.1), (130, 31, 3, 0.5)])
+def test_full_R_table(mode, N, M, D, gamma):
+    import torch
+
+    say("R table %s N=%d M=%d D=%d gamma=%g" % (mode, N, M, D, gamma))
+    x, y = workloads.normal_pairs(200 + N, 2, N, M, D)
+    xd, yd = to_dev(x), to_dev(y)
+    value, desc, ws = pkg.sdtw_forward(xd, yd, gamma, MODES[mode])
+    R = binding.debug_export(desc, ws, binding.EXPORT_R).cpu().numpy()
+    torch.cuda.synchronize()
+    for b in range(2):
+        ref = oracle.pair_tables(x[b], y[b], gamma)["R"][1:N + 1, 1:M + 1]
+        np.testing.assert_allclose(R[b], ref, rtol=1e-5, atol=1e-4)
+        assert abs(value[b].item() - ref[-1, -1]) <= VALUE_RTOL * max(abs(ref[-1, -1]), 1)
+
+
+# ------------------------------------------------------------------------------- end to end, small
+SHAPES = [
+    # B, N, M, D, gamma
+    (4, 64, 64, 8, 1.0),       # config 1 shape
+    (1, 1, 1, 4, 1.0),         # single cell
+    (2, 1, 9, 3, 0.5),         # single row
+    (2, 9, 1, 3, 0.5),         # single column
+    (2, 2, 2, 2, 0.3),
+    (3, 63, 33, 5, 0.1),       # ragged in both directions, odd D
+    (3, 65, 31, 8, 0.1),
+    (2, 64, 32, 12, 1.0),
+    (2, 96, 160, 16, 0.1),     # N != M, several bands and macro-steps
+    (2, 200, 129, 24, 0.01),   # small gamma, ragged tail in the last band and the last block
+    (1, 257, 70, 128, 0.1),
+]
+
+
+@pytest.mark.parametrize("mode", ["unfused", "fused"])
+@pytest.mark.parametrize("B,N,M,D,gamma", SHAPES)
+def test_value_E_and_gradients(mode, B, N, M, D, gamma):
+    say("parity %s B=%d N=%d M=%d D=%d gamma=%g" % (mode, B, N, M, D, gamma))
+    x, y = workloads.normal_pairs(300 + 7 * N + M, B, N, M, D)
+    ref = oracle.batch(x, y, gamma, want_E=True)
+    got = run_gpu(x, y, gamma, MODES[mode])
+    check_against(ref, got, what="%s %s" % (mode, (B, N, M, D, gamma)))
+    E = got["E"]
+    assert np.all(np.isfinite(E)) and E.min() >= 0.0 and E.max() <= 1.0 + 1e-5
+    np.testing.assert_allclose(E[:, -1, -1], 1.0, atol=1e-6)
+    np.testing.assert_allclose(E[:, 0, 0], 1.0, atol=1e-4)
+
+
+def test_config1_tiny_oracle_case():
+    wl = workloads.pair_workload("c1_tiny")
+    say("config 1")
+    ref = oracle.batch(wl.x, wl.y, wl.gamma, want_E=True)
+    got = run_gpu(wl.x, wl.y, wl.gamma, pkg.UNFUSED)
+    check_against(ref, got, what="c1")
+
+
+@pytest.mark.parametrize("mode", ["unfused", "fused"])
+def test_zero_cost_gives_delannoy_table(mode):
+    # data-free check at a size spanning bands: R[i,j] = -gamma log Del(i-1,j-1)
+    import torch
+
+    N, M, gamma = 150, 90, 1.0
+    say("delannoy %s" % mode)
+    x = np.full((1, N, 4), 0.5, dtype=np.float32)
+    y = np.full((1, M, 4), 0.5, dtype=np.float32)
+    value, desc, ws = pkg.sdtw_forward(to_dev(x), to_dev(y), gamma, MODES[mode])
+    R = binding.debug_export(desc, ws, binding.EXPORT_R).cpu().numpy()[0]
+    torch.cuda.synchronize()
+    logdel = np.zeros((N, M))
+    for i in range(1, N):
+        for j in range(1, M):
+            logdel[i, j] = np.logaddexp(np.logaddexp(logdel[i - 1, j], logdel[i, j - 1]), logdel[i - 1, j - 1])
+    np.testing.assert_allclose(R, -gamma * logdel, rtol=1e-5, atol=1e-4)
+
+
+@pytest.mark.parametrize("mode", ["unfused", "fused"])
+def test_upstream_gradient_and_shared_x(mode):
+    say("grad_value / shared x %s" % mode)
+    B, N, M, D, gamma = 3, 70, 50, 6, 0.2
+    x, y = workloads.normal_pairs(77, B, N, M, D)
+    gv = np.array([1.0, -2.0, 0.25])
+    ref = oracle.batch(x, y, gamma, grad_value=gv)
+    got = run_gpu(x, y, gamma, MODES[mode], grad_value=gv, want_E=False)
+    check_against(ref, got, what="grad_value")
+    ref = oracle.batch(x[0], y, gamma)
+    got = run_gpu(x[0], y, gamma, MODES[mode], want_E=False)
+    check_against(ref, got, what="shared x")
+
+
+def test_fused_equals_unfused_to_rounding():
+    x, y = workloads.normal_pairs(5, 4, 120, 140, 32)
+    a = run_gpu(x, y, 0.1, pkg.UNFUSED)
+    b = run_gpu(x, y, 0.1, pkg.FUSED)
+    np.testing.assert_allclose(a["value"], b["value"], rtol=1e-6)
+    np.testing.assert_allclose(a["E"], b["E"], atol=1e-5)
+    np.testing.assert_allclose(a["dx"], b["dx"], atol=1e-4 * np.abs(a["dx"]).max())
+
+
+def test_symmetry():
+    x, y = workloads.normal_pairs(6, 2, 90, 75, 8)
+    a = run_gpu(x, y, 0.5, pkg.FUSED)
+    b = run_gpu(y, x, 0.5, pkg.FUSED)
+    np.testing.assert_allclose(a["value"], b["value"], rtol=1e-6)
+    np.testing.assert_allclose(a["E"], np.swapaxes(b["E"], 1, 2), atol=1e-5)
+    np.testing.assert_allclose(a["dx"], b["dy"], atol=1e-4 * np.abs(a["dx"]).max())
+
+
+# ------------------------------------------------------------------------------- device-side errors
+def test_backward_without_forward_is_refused_on_the_device():
+    import torch
+
+    x, y = workloads.normal_pairs(8, 2, 40, 40, 4)
+    xd, yd = to_dev(x), to_dev(y)
+    desc = binding.make_desc(2, 40, 40, 4, 1.0, pkg.FUSED)
+    ws = binding.Workspace(pkg.sdtw_workspace_bytes(desc))
+    ws.buffer.zero_()
+    dx, dy, E = pkg.sdtw_backward(desc, xd, yd, ws, want_E=True)
+    torch.cuda.synchronize()
+    assert binding.workspace_status(ws) == binding.STATUS_STATE
+    assert torch.isnan(dx).all() and torch.isnan(dy).all() and torch.isnan(E).all()
+    # a forward for another descriptor does not make it valid either
+    pkg.sdtw_forward(xd, yd, 0.5, pkg.FUSED, workspace=ws)
+    dx, dy, _ = pkg.sdtw_backward(desc, xd, yd, ws)
+    torch.cuda.synchronize()
+    assert binding.workspace_status(ws) == binding.STATUS_STATE and torch.isnan(dx).all()
+    # the matching forward does
+    _, d2, _ = pkg.sdtw_forward(xd, yd, 1.0, pkg.FUSED, workspace=ws)
+    dx, dy, _ = pkg.sdtw_backward(d2, xd, yd, ws)
+    torch.cuda.synchronize()
+    assert binding.workspace_status(ws) == 0 and torch.isfinite(dx).all()
+
+
+def test_a_band_that_cannot_wait_gives_up_instead_of_hanging():
+    import torch
+
+    x, y = workloads.normal_pairs(9, 8, 512, 512, 8)
+    xd, yd = to_dev(x), to_dev(y)
+    binding.debug_set_spin_limit(0)
+    try:
+        value, desc, ws = pkg.sdtw_forward(xd, yd, 1.0, pkg.FUSED)
+        torch.cuda.synchronize()
+        status = binding.workspace_status(ws)
+    finally:
+        binding.debug_set_spin_limit(1 << 23)
+    # either every band happened to find its neighbour ready, or the timeout was recorded;
+    # in both cases every kernel has exited
+    assert status in (0, binding.STATUS_TIMEOUT)
+    value, desc, ws = pkg.sdtw_forward(xd, yd, 1.0, pkg.FUSED)
+    torch.cuda.synchronize()
+    assert binding.workspace_status(ws) == 0
+    ref = oracle.batch(x[:2], y[:2], 1.0, backward=False)
+    np.testing.assert_allclose(value[:2].cpu().numpy(), ref["value"], rtol=VALUE_RTOL)
+
+
+# ------------------------------------------------------------------------------- benchmark configurations
+@pytest.mark.parametrize("mode", ["unfused", "fused"])
+def test_config2_full(mode):
+    wl = workloads.pair_workload("c2_b32_l256")
+    say("config 2 %s" % mode)
+    ref = oracle.batch(wl.x, wl.y, wl.gamma)
+    got = run_gpu(wl.x, wl.y, wl.gamma, MODES[mode], want_E=False)
+    check_against(ref, got, what="c2 " + mode)
+
+
+@pytest.mark.parametrize("mode", ["unfused", "fused"])
+def test_config3_full_size_sampled_pairs(mode):
+    wl = workloads.pair_workload("c3_b32_l1024_walk")
+    say("config 3 %s" % mode)
+    pairs = [0, 13, 31]
+    ref = oracle.batch(wl.x[pairs], wl.y[pairs], wl.gamma)
+    got = run_gpu(wl.x, wl.y, wl.gamma, MODES[mode], want_E=False)
+    check_against(ref, got, pairs=pairs, what="c3 " + mode)
+    assert np.all(np.isfinite(got["dx"])) and np.all(np.isfinite(got["dy"]))
+
+
+def test_config4_full_size_sampled_pairs():
+    import torch
+
+    wl = workloads.pair_workload("c4_b32_l8192")
+    say("config 4 fused: GPU")
+    xd, yd = to_dev(wl.x), to_dev(wl.y)
+    value, desc, ws = pkg.sdtw_forward(xd, yd, wl.gamma, pkg.FUSED)
+    dx, dy, _ = pkg.sdtw_backward(desc, xd, yd, ws)
+    torch.cuda.synchronize()
+    assert binding.workspace_status(ws) == 0
+    got = {"value": value.cpu().numpy().astype(np.float64), "dx": dx.cpu().numpy().astype(np.float64),
+           "dy": dy.cpu().numpy().astype(np.float64)}
+    assert np.all(np.isfinite(got["value"])) and np.all(np.isfinite(got["dx"])) and np.all(np.isfinite(got["dy"]))
+    # E summed over a row is at least 1 and dx_i = 2 sum_j E_ij (x_i - y_j): translation invariance
+    tot = got["dx"].sum(axis=1) + got["dy"].sum(axis=1)
+    assert np.abs(tot).max() <= 2e-2 * np.abs(got["dx"]).max()
+    del ws
+    torch.cuda.empty_cache()
+    pairs = [3, 28]
+    say("config 4 fused: oracle on pairs %s" % pairs)
+    ref = oracle.batch(wl.x[pairs], wl.y[pairs], wl.gamma, nthreads=2)
+    check_against(ref, got, pairs=pairs, what="c4")
+
+
+# ------------------------------------------------------------------------------- barycenter
+@pytest.mark.parametrize("mode", ["unfused", "fused"])
+def test_barycenter_steps_teacher_forced(mode):
+    import torch
+
+    bw = workloads.barycenter_workload(K=8, L=96, D=6, seed=5)
+    say("barycenter %s" % mode)
+    lr, b1, b2, eps, gamma = 0.05, 0.9, 0.999, 1e-8, 1.0
+    z = to_dev(bw.z0.copy())
+    X = to_dev(bw.X)
+    m = torch.zeros_like(z)
+    v = torch.zeros_like(z)
+    ws = None
+    for step in (1, 2, 3):
+        z_in = z.cpu().numpy()
+        m_in, v_in = m.cpu().numpy().astype(np.float64), v.cpu().numpy().astype(np.float64)
+        loss, dz, ws = pkg.sdtw_barycenter_step(z, X, m, v, gamma, step, lr, b1, b2, eps, MODES[mode],
+                                                workspace=ws, want_dz=True)
+        torch.cuda.synchronize()
+        zo = z_in.astype(np.float64)
+        lo, dzo = oracle.barycenter_step(zo, bw.X, gamma, lr, b1, b2, eps, step, m_in, v_in)
+        assert abs(loss.item() - lo) <= VALUE_RTOL * max(abs(lo), 1.0)
+        g = dz.cpu().numpy().astype(np.float64)
+        assert np.abs(g - dzo).max() <= GRAD_RTOL * np.abs(dzo).max()
+        np.testing.assert_allclose(m.cpu().numpy(), m_in, rtol=2e-3, atol=2e-3 * np.abs(m_in).max())
+        # the update itself, given the library's own gradient (Adam divides by |g| where g ~ 0,
+        # so the comparison through the oracle's gradient would amplify rounding there)
+        mm = m.cpu().numpy().astype(np.float64)
+        vv = v.cpu().numpy().astype(np.float64)
+        expect = z_in.astype(np.float64) - lr * (mm / (1 - b1 ** step)) / (np.sqrt(vv / (1 - b2 ** step)) + eps)
+        np.testing.assert_allclose(z.cpu().numpy(), expect, rtol=1e-5, atol=1e-6)
+
+
+def test_config5_barycenter_loss_decreases_and_first_step_matches():
+    import torch
+
+    bw = workloads.barycenter_workload()
+    say("config 5")
+    z = to_dev(bw.z0.copy())
+    X = to_dev(bw.X)
+    m = torch.zeros_like(z)
+    v = torch.zeros_like(z)
+    z_np = bw.z0.astype(np.float64)
+    lo, dzo = oracle.barycenter_step(z_np, bw.X, bw.gamma, bw.lr, 0.9, 0.999, 1e-8, 1,
+                                     np.zeros_like(z_np), np.zeros_like(z_np))
+    ws = None
+    losses = []
+    for step in range(1, 11):
+        loss, dz, ws = pkg.sdtw_barycenter_step(z, X, m, v, bw.gamma, step, bw.lr, workspace=ws, want_dz=(step == 1))
+        if step == 1:
+            torch.cuda.synchronize()
+            assert abs(loss.item() - lo) <= VALUE_RTOL * max(abs(lo), 1.0)
+            assert np.abs(dz.cpu().numpy() - dzo).max() <= GRAD_RTOL * np.abs(dzo).max()
+        losses.append(loss.item())
+    torch.cuda.synchronize()
+    assert binding.workspace_status(ws) == 0
+    assert losses[-1] < losses[0]
