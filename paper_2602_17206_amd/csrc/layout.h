@@ -12,7 +12,6 @@ namespace sdtw {
 
 constexpr int kBandRows = 64;    // rows per band == lanes per wavefront
 constexpr int kBlk = 32;         // edge of a cost block (one 32x32 MFMA tile)
-constexpr int kLdsStride = 36;   // floats per LDS block row: 16-byte aligned rows, odd (stride-1)
 constexpr uint64_t kSentinel = 0xFFFFFFFFFFFFFFFFull;  // "not written yet" in boundary rows
 constexpr uint32_t kMagic = 0x53445457u;               // 'SDTW'
 constexpr int kGuardBytes = 512;  // slack before/after regions that are read with clamped indices
@@ -86,6 +85,7 @@ struct Params {
     int64_t x_stride, y_stride;    // batch strides of x, y (elements)
     int64_t xn_stride, yn_stride;  // batch strides of the norm vectors (0 when shared)
     int32_t vec_xy;                // 1: D%8==0 and x,y 16-byte aligned -> float4 operand loads
+    int32_t vec_d4;                // 1: D%4==0 and x,y 16-byte aligned -> float4 loads of register operands
     int32_t vec_m;                 // 1: M%4==0 -> float4 loads/stores of cost and E rows
     uint32_t spin_limit;           // polls before a band gives up waiting
     const float *x, *y;

@@ -10,6 +10,7 @@
 
 #include "../../include/sdtw.h"
 #include "kernels.h"
+#include "dp_kernels.h"
 #include "layout.h"
 
 namespace {
@@ -76,6 +77,8 @@ Params make_params(const sdtw_desc *d, const Layout &L, const float *x, const fl
     p.yn_stride = d->y_batch_stride == 0 ? 0 : d->M;
     p.vec_xy = (d->D % 8 == 0) && aligned16(x) && aligned16(y) && (d->x_batch_stride % 4 == 0) &&
                (d->y_batch_stride % 4 == 0);
+    p.vec_d4 = (d->D % 4 == 0) && aligned16(x) && aligned16(y) && (d->x_batch_stride % 4 == 0) &&
+               (d->y_batch_stride % 4 == 0);
     p.vec_m = (d->M % 4 == 0);
     p.spin_limit = g_spin_limit;
     p.x = x; p.y = y;
@@ -89,6 +92,18 @@ Params make_params(const sdtw_desc *d, const Layout &L, const float *x, const fl
     p.E = reinterpret_cast<float *>(base + L.off_E);
     p.nz = reinterpret_cast<unsigned char *>(base + L.off_nz);
     return p;
+}
+
+// Fused DP kernel variant: number of 8-feature chunks of the MFMA operands kept in registers
+// (D <= 8, 16, 32, 64, 128), or 0 for the generic kernel that reads x and y per block.
+int fused_variant(int D)
+{
+    if (D <= 8) return 1;
+    if (D <= 16) return 2;
+    if (D <= 32) return 4;
+    if (D <= 64) return 8;
+    if (D <= 128) return 16;
+    return 0;
 }
 
 int check_ws(const void *ws, size_t bytes, size_t need)
@@ -121,10 +136,17 @@ int forward_impl(const sdtw_desc *d, const float *x, const float *y, float *valu
     if (d->mode == SDTW_UNFUSED) {
         dim3 g((d->M + 63) / 64, (d->N + 63) / 64, d->B);
         { ProfScope ps("cost_tensor", st); cost_tensor_kernel<<<g, 256, 0, st>>>(p); }
-        { ProfScope ps("forward_dp_unfused", st); forward_dp_kernel<false><<<tasks, 64, 0, st>>>(p, value); }
+        { ProfScope ps("forward_dp_unfused", st); forward_dp_kernel<-1><<<tasks, 64, 0, st>>>(p, value); }
     } else {
         ProfScope ps("forward_dp_fused", st);
-        forward_dp_kernel<true><<<tasks, 64, 0, st>>>(p, value);
+        switch (fused_variant(d->D)) {
+            case 1: forward_dp_kernel<1><<<tasks, 64, 0, st>>>(p, value); break;
+            case 2: forward_dp_kernel<2><<<tasks, 64, 0, st>>>(p, value); break;
+            case 4: forward_dp_kernel<4><<<tasks, 64, 0, st>>>(p, value); break;
+            case 8: forward_dp_kernel<8><<<tasks, 64, 0, st>>>(p, value); break;
+            case 16: forward_dp_kernel<16><<<tasks, 64, 0, st>>>(p, value); break;
+            default: forward_dp_kernel<0><<<tasks, 64, 0, st>>>(p, value); break;
+        }
     }
     return hip_ok();
 }
@@ -139,10 +161,17 @@ int backward_impl(const sdtw_desc *d, const float *x, const float *y, const floa
     const unsigned tasks = (unsigned)d->B * (unsigned)L.nbands;
     if (d->mode == SDTW_UNFUSED) {
         ProfScope ps("backward_dp_unfused", st);
-        backward_dp_kernel<false><<<tasks, 64, 0, st>>>(p);
+        backward_dp_kernel<-1><<<tasks, 64, 0, st>>>(p);
     } else {
         ProfScope ps("backward_dp_fused", st);
-        backward_dp_kernel<true><<<tasks, 64, 0, st>>>(p);
+        switch (fused_variant(d->D)) {
+            case 1: backward_dp_kernel<1><<<tasks, 64, 0, st>>>(p); break;
+            case 2: backward_dp_kernel<2><<<tasks, 64, 0, st>>>(p); break;
+            case 4: backward_dp_kernel<4><<<tasks, 64, 0, st>>>(p); break;
+            case 8: backward_dp_kernel<8><<<tasks, 64, 0, st>>>(p); break;
+            case 16: backward_dp_kernel<16><<<tasks, 64, 0, st>>>(p); break;
+            default: backward_dp_kernel<0><<<tasks, 64, 0, st>>>(p); break;
+        }
     }
     if (dx || dy) {
         const int P = std::max(dx ? d->N : 0, dy ? d->M : 0);
