@@ -1,10 +1,19 @@
 // Forward and backward DP kernels (the dependent anti-diagonal sweeps) for gfx950.
 //
-// Geometry.  A band is 64 consecutive rows of one pair; one wavefront owns it, lane t owning row
-// row0+t.  At step s lane t is at column j = s - t, so the 64 cells of a step lie on one
-// anti-diagonal and are independent (Sec. 4.1).  A cell's three neighbours are the lane's own
-// previous value, the adjacent lane's previous value (one DPP wave shift) and that same value one
-// step earlier, so the dependent chain never leaves the registers.  Steps come in macro-steps of 32.
+// Geometry.  A band is 64 consecutive rows of one pair; one wavefront (the band's CONSUMER) owns
+// it, lane t owning row row0+t.  At step s lane t is at column j = s - t, so the 64 cells of a step
+// lie on one anti-diagonal and are independent (Sec. 4.1).  A cell's three neighbours are the
+// lane's own previous value, the adjacent lane's previous value (one DPP wave shift) and that same
+// value one step earlier, so the dependent chain never leaves the registers.  Steps come in
+// macro-steps of 32.
+//
+// Workgroup.  512 threads = 8 wavefronts = 4 bands (the same band index of 4 consecutive pairs):
+// per band one consumer (the DP chain, pure VALU) and one PRODUCER that prepares the cost blocks
+// of the next macro-step in LDS - on the fp32 matrix cores in fused mode, by copying from the
+// stored cost tensor in unfused mode.  The matrix cores only run concurrently with VALU work of a
+// DIFFERENT wavefront on the same SIMD, so the roles are separate wavefronts and the two
+// wavefronts that share a SIMD are paired (elected at run time from the hardware SIMD id; any
+// pairing is correct, this one is fast).  One workgroup barrier per macro-step keeps them in step.
 //
 // Cells outside the N x M grid are not masked.  They are fed a huge finite cost (kBigCost) and the
 // table boundary is a huge finite value (kBig) instead of +inf: a cell whose three neighbours are
@@ -14,10 +23,10 @@
 // column M or below row N get finite garbage that no grid cell depends on.
 //
 // Cost values reach the lanes through an LDS ring indexed by STEP, not by column:
-// cell (band row t, column j) lives at ring[t][(j + t) mod 96].  At step s every lane reads
-// position s mod 96 of its own row, so the address of a step is a per-macro-step base plus an
-// immediate, and three phases of 32 steps are live at any time: the one being read and the two
-// being filled for later.  32x32 cost blocks are written into the ring with that skew applied.
+// cell (band row t, column j) lives at ring[t][(j + t) mod 128].  At step s every lane reads
+// position s mod 128 of its own row, so the address of a step is a per-macro-step base plus an
+// immediate.  Four phases of 32 steps exist: the one being read, the one still being flushed (E,
+// backward) and the two being filled for later.  32x32 cost blocks are written with that skew.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -26,9 +35,12 @@
 
 namespace sdtw {
 
-constexpr int kRingCols = 96;     // three phases of 32 steps
-constexpr int kRingStride = 97;   // floats per band row in LDS (odd: lanes hit distinct banks)
-constexpr double kBig = 1e300;    // stands for +inf in the DP tables
+constexpr int kRingCols = 128;     // four phases of 32 steps
+constexpr int kRingStride = 129;   // floats per band row in LDS (odd: lanes hit distinct banks)
+constexpr int kRingFloats = kBandRows * kRingStride;
+constexpr int kSlots = 4;          // bands per workgroup
+constexpr int kWgThreads = 2 * kSlots * 64;
+constexpr double kBig = 1e300;     // stands for +inf in the DP tables
 constexpr float kBigCost = 3.0e38f;  // cost of a cell outside the grid
 constexpr int kStatusTimeoutDp = 6;  // SDTW_ERR_TIMEOUT
 
@@ -39,17 +51,17 @@ __device__ __forceinline__ double min_f64(double a, double b)
     return r;
 }
 
-// softmin_gamma(a,b,c) split as  m - corr  with  m = min(a,b,c) (float64) and
-// corr = gamma ln(sum_k exp(-(v_k - m)/gamma)) (float32, >= 0).   (Sec. 2 Eq. 2; max-shift of Sec. 4.2)
-__device__ __forceinline__ void softmin3_parts(double a, double b, double c, float c2, float gamma_ln2,
-                                               double &m, float &corr)
+// softmin_gamma(a,b,c) = m - gamma ln2 * L  with  m = min(a,b,c) (float64) and
+// L = log2(sum_k 2^{-(v_k - m) c2}) in [0, log2 3] (float32), c2 = log2(e)/gamma.
+// (Sec. 2 Eq. 2, evaluated with the max-shift of Sec. 4.2; the term of the minimum is 2^0 = 1.)
+__device__ __forceinline__ void softmin3_parts(double a, double b, double c, float c2, double &m, float &L)
 {
     m = min_f64(min_f64(a, b), c);
     const float fa = (float)(a - m), fb = (float)(b - m), fc = (float)(c - m);
     const float mx = __builtin_fmaxf(__builtin_fmaxf(fa, fb), fc);
     const float md = __builtin_amdgcn_fmed3f(fa, fb, fc);
     const float S = 1.0f + __builtin_amdgcn_exp2f(-md * c2) + __builtin_amdgcn_exp2f(-mx * c2);
-    corr = gamma_ln2 * __builtin_amdgcn_logf(S);
+    L = __builtin_amdgcn_logf(S);
 }
 
 __device__ __forceinline__ float comp4(const float4 &v, int c)
@@ -57,119 +69,14 @@ __device__ __forceinline__ float comp4(const float4 &v, int c)
     return c == 0 ? v.x : (c == 1 ? v.y : (c == 2 ? v.z : v.w));
 }
 
-// MFMA operand of one 32-row block: lane (r = lane&31, h = lane>>5) keeps, for every group of 8
-// features, the 4 features 8c+4h .. 8c+4h+3 of row r.  Features >= D are zero.
-template <int KCH>
-__device__ __forceinline__ void load_operand(float4 (&dst)[KCH], const float *__restrict__ rowptr, int D,
-                                             int h4, bool vec, float scale)
-{
-#pragma unroll
-    for (int c = 0; c < KCH; ++c) {
-        const int k = 8 * c + h4;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (vec) {
-            if (k < D) v = *reinterpret_cast<const float4 *>(rowptr + k);
-        } else {
-            if (k + 0 < D) v.x = rowptr[k + 0];
-            if (k + 1 < D) v.y = rowptr[k + 1];
-            if (k + 2 < D) v.z = rowptr[k + 2];
-            if (k + 3 < D) v.w = rowptr[k + 3];
-        }
-        dst[c] = make_float4(v.x * scale, v.y * scale, v.z * scale, v.w * scale);
-    }
-}
-
-// One whole 32x32 cost block from register operands:  sum_k (-2 x_ik) y_jk + ||x_i||^2 * 1 + 1 * ||y_j||^2
-// (Sec. 4.3 Eq. 8 with the two norm terms fed through one extra MFMA).
-template <int KCH>
-__device__ __forceinline__ floatx16 block_from_regs(const float4 (&xa)[KCH], float ax, const float4 (&yb)[KCH],
-                                                    float by)
-{
-    floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int c = 0; c < KCH; ++c) {
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[c].x, yb[c].x, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[c].y, yb[c].y, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[c].z, yb[c].z, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[c].w, yb[c].w, acc, 0, 0, 0);
-    }
-    return __builtin_amdgcn_mfma_f32_32x32x2f32(ax, by, acc, 0, 0, 0);
-}
-
-// Writes a 32x32 cost block given in MFMA accumulator layout into the step-indexed ring.
-// Block rows are band rows 32*rb .., columns 32*cb ..; entries outside the grid become kBigCost.
-__device__ __forceinline__ void store_block_acc(float *ring, const floatx16 &acc, int rb, int cb, int row0, int N,
-                                                int M, int lane)
-{
-    const int h = lane >> 5, c = lane & 31;
-    int ph = (cb + rb) % 3;
-    if (ph < 0) ph += 3;
-    const unsigned sbase = (unsigned)ph * 32u + (unsigned)(c + 4 * h);
-    float *rowbase = ring + (32 * rb + 4 * h) * kRingStride;
-    const int i0 = row0 + 32 * rb, j0 = 32 * cb;
-    const bool inside = (i0 + 32 <= N) && (j0 >= 0) && (j0 + 32 <= M);
-    const bool col_ok = (unsigned)(j0 + c) < (unsigned)M;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int rr = 8 * (i >> 2) + (i & 3);  // + 4h = row inside the block
-        unsigned pos = sbase + (unsigned)rr;
-        pos = min(pos, pos - (unsigned)kRingCols);
-        float v = fmaxf(acc[i], 0.0f);
-        if (!inside) v = (col_ok && (i0 + 4 * h + rr < N)) ? v : kBigCost;
-        rowbase[rr * kRingStride + pos] = v;
-    }
-}
-
-// Unfused mode: the 32x32 block of the stored cost tensor as 4 float4 per lane
-// (lane -> row (lane>>3) + 8*it of the block, columns 4*(lane&7) ..), kBigCost outside the grid.
-__device__ __forceinline__ void load_cost_block(float4 (&v)[4], const float *__restrict__ cost_b, int rb, int cb,
-                                                int row0, int N, int M, bool vec_m, int lane)
-{
-    const int c4 = (lane & 7) * 4, j0 = 32 * cb;
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const int row = row0 + 32 * rb + (lane >> 3) + 8 * it;
-        const int col = j0 + c4;
-        float4 t = make_float4(kBigCost, kBigCost, kBigCost, kBigCost);
-        if (row < N && col >= 0) {
-            const float *q = cost_b + (size_t)row * M + col;
-            if (vec_m && col + 3 < M) {
-                t = *reinterpret_cast<const float4 *>(q);
-            } else {
-                if (col + 0 < M) t.x = q[0];
-                if (col + 1 < M) t.y = q[1];
-                if (col + 2 < M) t.z = q[2];
-                if (col + 3 < M) t.w = q[3];
-            }
-        }
-        v[it] = t;
-    }
-}
-
-__device__ __forceinline__ void store_cost_block(float *ring, const float4 (&v)[4], int rb, int cb, int lane)
-{
-    int ph = (cb + rb) % 3;
-    if (ph < 0) ph += 3;
-    const int c4 = (lane & 7) * 4;
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const int r = (lane >> 3) + 8 * it;
-        float *rowp = ring + (32 * rb + r) * kRingStride;
-        const unsigned base = (unsigned)ph * 32u + (unsigned)(c4 + r);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            unsigned pos = base + (unsigned)e;
-            pos = min(pos, pos - (unsigned)kRingCols);
-            rowp[pos] = comp4(v[it], e);
-        }
-    }
-}
-
-// Boundary values travel between bands through a buffer pre-filled with kSentinel; each value is
-// published with one 64-bit device-scope atomic store, so it validates itself (no flag, no fence).
-// `bits` holds what an earlier prefetch saw.  Polls until all needed lanes have a value; a band
-// gives up after p.spin_limit polls, records SDTW_ERR_TIMEOUT and never waits again; other bands
-// notice the recorded status and stop waiting too, so every kernel exits.
+// ---------------------------------------------------------------------------------------------
+// Boundary values between bands.  They travel through a buffer pre-filled with kSentinel; each
+// value is published with one 64-bit device-scope atomic store, so it validates itself (no flag,
+// no fence).  resolve_boundary polls until all needed lanes have a value (`bits` is what an
+// earlier prefetch saw); a band gives up after p.spin_limit polls, records SDTW_ERR_TIMEOUT and
+// never waits again; other bands notice the recorded status and stop waiting too, so every
+// kernel exits.
+// ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ double resolve_boundary(const Params &p, const unsigned long long *row, int jj, bool need,
                                                    int lane, bool &gave_up, unsigned long long bits)
 {
@@ -205,33 +112,98 @@ __device__ __forceinline__ void publish_boundary(unsigned long long *row, int j,
                        __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// How the cost blocks are made.
-//   KCH > 0 : fused, D <= 8*KCH: operands live in registers, MFMAs are interleaved with the DP steps
-//   KCH == 0: fused, any D: blocks are computed between macro-steps straight from x and y
-//   KCH < 0 : unfused: blocks are loaded from the stored cost tensor one macro-step ahead
-template <int KCH> struct CostRegs {
-    float4 xa[2][KCH > 0 ? KCH : 1];  // -2 * x rows of the two 32-row blocks
-    float ax[2];                      // lanes 0-31: ||x_r||^2, lanes 32-63: 1
-    float4 ya[KCH > 0 ? KCH : 1];     // y rows of the newer column block
-    float4 yb[KCH > 0 ? KCH : 1];     // y rows of the older column block
-    float bya, byb;                   // lanes 0-31: 1, lanes 32-63: ||y_c||^2
-};
-
-template <int KCH>
-__device__ __forceinline__ void load_y_block(const Params &p, const float *yb_ptr, const float *ynb, int cb, int lane,
-                                             float4 (&dst)[KCH > 0 ? KCH : 1], float &by)
+// ---------------------------------------------------------------------------------------------
+// Producer side: cost blocks into the ring.
+// ---------------------------------------------------------------------------------------------
+// MFMA operand chunk: lane (r = lane&31, h = lane>>5) keeps the 4 features 8c+4h .. 8c+4h+3 of its
+// row for chunk c (a group of 8 features).  Features >= D are zero.
+// Requires D % 4 == 0 and 16-byte aligned rows (the host picks the any-D kernel otherwise).
+__device__ __forceinline__ float4 load_chunk(const float *__restrict__ rowptr, int D, int c, int h4)
 {
-    if constexpr (KCH > 0) {
-        int col = 32 * cb + (lane & 31);
-        col = max(0, min(col, p.M - 1));
-        load_operand<KCH>(dst, yb_ptr + (size_t)col * p.D, p.D, (lane >> 5) * 4, p.vec_d4 != 0, 1.0f);
-        by = (lane >> 5) ? ynb[col] : 1.0f;
+    const int k = 8 * c + h4;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (k < D) v = *reinterpret_cast<const float4 *>(rowptr + k);
+    return v;
+}
+
+__device__ __forceinline__ floatx16 zero16()
+{
+    floatx16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    return z;
+}
+
+__device__ __forceinline__ floatx16 mfma4(floatx16 acc, const float4 &a, const float4 &b)
+{
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
+    return acc;
+}
+
+// Writes a 32x32 cost block given in MFMA accumulator layout (acc[i]: row 8*(i/4)+4*(lane>>5)+(i&3),
+// column lane&31) into the step-indexed ring.  Block rows are band rows 32*rb .., columns 32*cb ..;
+// entries outside the grid become kBigCost, negative round-off is clamped to 0.
+__device__ __forceinline__ void store_block_acc(float *ring, const floatx16 &acc, int rb, int cb, int row0, int N,
+                                                int M, int lane)
+{
+    const int h = lane >> 5, c = lane & 31;
+    const int sbase = 32 * (cb + rb) + c + 4 * h;
+    float *rowbase = ring + (32 * rb + 4 * h) * kRingStride;
+    const int i0 = row0 + 32 * rb, j0 = 32 * cb;
+    const bool inside = (i0 + 32 <= N) && (j0 >= 0) && (j0 + 32 <= M);
+    const bool col_ok = (unsigned)(j0 + c) < (unsigned)M;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int rr = 8 * (i >> 2) + (i & 3);  // + 4h = row inside the block
+        const int pos = (sbase + rr) & (kRingCols - 1);
+        float v = fmaxf(acc[i], 0.0f);
+        if (!inside) v = (col_ok && (i0 + 4 * h + rr < N)) ? v : kBigCost;
+        rowbase[rr * kRingStride + pos] = v;
     }
 }
 
-// Generic-D cost block between macro-steps (no register operands).
-__device__ __forceinline__ void sync_block_generic(const Params &p, int b, float *ring, int rb, int cb, int row0,
-                                                   int lane)
+// Unfused mode: the 32x32 block of the stored cost tensor as 4 float4 per lane
+// (lane -> row (lane>>3) + 8*it of the block, columns 4*(lane&7) ..), kBigCost outside the grid.
+__device__ __forceinline__ void load_cost_block(float4 (&v)[4], const float *__restrict__ cost_b, int rb, int cb,
+                                                int row0, int N, int M, bool vec_m, int lane)
+{
+    const int c4 = (lane & 7) * 4, j0 = 32 * cb;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int row = row0 + 32 * rb + (lane >> 3) + 8 * it;
+        const int col = j0 + c4;
+        float4 t = make_float4(kBigCost, kBigCost, kBigCost, kBigCost);
+        if (row < N && col >= 0) {
+            const float *q = cost_b + (size_t)row * M + col;
+            if (vec_m && col + 3 < M) {
+                t = *reinterpret_cast<const float4 *>(q);
+            } else {
+                if (col + 0 < M) t.x = q[0];
+                if (col + 1 < M) t.y = q[1];
+                if (col + 2 < M) t.z = q[2];
+                if (col + 3 < M) t.w = q[3];
+            }
+        }
+        v[it] = t;
+    }
+}
+
+__device__ __forceinline__ void store_cost_block(float *ring, const float4 (&v)[4], int rb, int cb, int lane)
+{
+    const int c4 = (lane & 7) * 4;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int r = (lane >> 3) + 8 * it;
+        float *rowp = ring + (32 * rb + r) * kRingStride;
+        const int base = 32 * (cb + rb) + c4 + r;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) rowp[(base + e) & (kRingCols - 1)] = comp4(v[it], e);
+    }
+}
+
+// Any-D cost block straight from x and y (fused mode when D > 128).
+__device__ __forceinline__ void generic_block(const Params &p, int b, float *ring, int rb, int cb, int row0, int lane)
 {
     float out[16];
     const int i0 = row0 + 32 * rb, j0 = 32 * cb;
@@ -240,160 +212,292 @@ __device__ __forceinline__ void sync_block_generic(const Params &p, int b, float
     floatx16 acc;
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = out[i];
-    // cost_block clamps row/column indices itself; entries outside the grid are replaced on store.
-    // When the block origin had to be clamped the whole block is outside the grid.
+    // when the block origin had to be clamped the whole block lies outside the grid
     const bool origin_ok = (i0 < p.N) && (j0 >= 0) && (j0 < p.M);
     store_block_acc(ring, acc, rb, cb, row0, origin_ok ? p.N : 0, p.M, lane);
 }
 
+// The two cost blocks a macro-step `sg` must prepare for the following one.
+//   forward  (DIR=+1): (lower rows, sg) then (upper rows, sg+1)
+//   backward (DIR=-1): (upper rows, sg-2) then (lower rows, sg-3)
+template <int DIR> __device__ __forceinline__ int blk_rb(int which) { return DIR > 0 ? 1 - which : which; }
+template <int DIR> __device__ __forceinline__ int blk_cb(int sg, int which)
+{
+    return DIR > 0 ? sg + which : sg - 2 - which;
+}
+
+// Register-operand MFMA producer for D <= 8*KCH (KCH = 1, 2, 4, 8, 16).
+// -2*x of the band's two 32-row blocks stays in registers for the whole sweep; y streams through
+// NBUF stage buffers of CPS chunks each, every buffer being reloaded right after its use with the
+// data of the stage NBUF stages later, so loads are in flight for thousands of cycles.
+template <int KCH, int DIR> struct MfmaProducer {
+    static constexpr int CPS = KCH >= 8 ? 2 : 1;         // chunks (8 MFMAs' worth of y) per stage
+    static constexpr int NQ = KCH / CPS;                 // stages per block
+    static constexpr int NST = 2 * NQ;                   // stages per macro-step
+    static constexpr int NBUF = KCH >= 8 ? 4 : NST;      // stage buffers
+
+    float4 xa[2][KCH];
+    float ax[2];  // lanes 0-31: ||x_r||^2, lanes 32-63: 1
+    float4 ybuf[NBUF][CPS];
+    float by0, by1;  // lanes 0-31: 1, lanes 32-63: ||y_c||^2, for the two blocks of the macro-step
+
+    __device__ __forceinline__ const float *yrow(const Params &p, const float *yb, int cb, int lane) const
+    {
+        int col = 32 * cb + (lane & 31);
+        col = max(0, min(col, p.M - 1));
+        return yb + (size_t)col * p.D;
+    }
+    __device__ __forceinline__ float ynorm(const Params &p, const float *ynb, int cb, int lane) const
+    {
+        int col = 32 * cb + (lane & 31);
+        col = max(0, min(col, p.M - 1));
+        const float v = ynb[col];
+        return (lane >> 5) ? v : 1.0f;
+    }
+    __device__ __forceinline__ void load_stage(const Params &p, const float *yb, int buf, int cb, int quarter,
+                                               int lane)
+    {
+        const float *r = yrow(p, yb, cb, lane);
+#pragma unroll
+        for (int c = 0; c < CPS; ++c)
+            ybuf[buf][c] = load_chunk(r, p.D, quarter * CPS + c, (lane >> 5) * 4);
+    }
+    __device__ __forceinline__ void init(const Params &p, const float *xb, const float *xnb, int row0, int lane)
+    {
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            const int row = min(row0 + 32 * rb + (lane & 31), p.N - 1);
+#pragma unroll
+            for (int c = 0; c < KCH; ++c) {
+                const float4 v = load_chunk(xb + (size_t)row * p.D, p.D, c, (lane >> 5) * 4);
+                xa[rb][c] = make_float4(-2.0f * v.x, -2.0f * v.y, -2.0f * v.z, -2.0f * v.w);
+            }
+            const float xn = xnb[row];
+            ax[rb] = (lane >> 5) ? 1.0f : xn;
+        }
+    }
+    // one whole block, loads included (start-up only)
+    __device__ __forceinline__ void block_now(const Params &p, const float *yb, const float *ynb, float *ring, int rb,
+                                              int cb, int row0, int lane)
+    {
+        const float *r = yrow(p, yb, cb, lane);
+        floatx16 acc = zero16();
+#pragma unroll
+        for (int c = 0; c < KCH; ++c)
+            acc = mfma4(acc, xa[rb][c], load_chunk(r, p.D, c, (lane >> 5) * 4));
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(ax[rb], ynorm(p, ynb, cb, lane), acc, 0, 0, 0);
+        store_block_acc(ring, acc, rb, cb, row0, p.N, p.M, lane);
+    }
+    // stage buffers and norms for the first macro-step `sg`
+    __device__ __forceinline__ void prime(const Params &p, const float *yb, const float *ynb, int sg, int lane)
+    {
+#pragma unroll
+        for (int q = 0; q < NBUF; ++q) load_stage(p, yb, q, blk_cb<DIR>(sg, q / NQ), q % NQ, lane);
+        by0 = ynorm(p, ynb, blk_cb<DIR>(sg, 0), lane);
+        by1 = ynorm(p, ynb, blk_cb<DIR>(sg, 1), lane);
+    }
+    // the two blocks of macro-step sg
+    __device__ __forceinline__ void run(const Params &p, const float *yb, const float *ynb, float *ring, int sg,
+                                        int row0, int lane)
+    {
+        const int sgn = sg + DIR;  // next macro-step
+        const float nby0 = ynorm(p, ynb, blk_cb<DIR>(sgn, 0), lane);
+        const float nby1 = ynorm(p, ynb, blk_cb<DIR>(sgn, 1), lane);
+        floatx16 acc = zero16();
+#pragma unroll
+        for (int q = 0; q < NST; ++q) {
+            const int which = q / NQ, quarter = q % NQ, buf = q % NBUF;
+            const int rb = blk_rb<DIR>(which);
+#pragma unroll
+            for (int c = 0; c < CPS; ++c) acc = mfma4(acc, xa[rb][quarter * CPS + c], ybuf[buf][c]);
+            // reload this buffer with the stage NBUF stages later (not earlier: registers are scarce)
+            __builtin_amdgcn_sched_barrier(0);
+            const int q2 = q + NBUF;
+            if (q2 < NST)
+                load_stage(p, yb, buf, blk_cb<DIR>(sg, q2 / NQ), q2 % NQ, lane);
+            else
+                load_stage(p, yb, buf, blk_cb<DIR>(sgn, (q2 - NST) / NQ), (q2 - NST) % NQ, lane);
+            if (quarter == NQ - 1) {
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(ax[rb], which == 0 ? by0 : by1, acc, 0, 0, 0);
+                store_block_acc(ring, acc, rb, blk_cb<DIR>(sg, which), row0, p.N, p.M, lane);
+                acc = zero16();
+            }
+        }
+        by0 = nby0;
+        by1 = nby1;
+    }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Workgroup bookkeeping shared by both kernels.
+// ---------------------------------------------------------------------------------------------
+struct WgShared {
+    float ring[kSlots][kRingFloats];
+    double edge_in[kSlots][kBlk];  // boundary values of the current macro-step, one per step
+    int simd_count[4];
+};
+
+// Pairs the two wavefronts that share a SIMD as consumer (0) and producer (1) of one band slot.
+// If the 8 wavefronts are not spread 2 per SIMD, falls back to wavefront w -> role w/4, slot w%4.
+__device__ __forceinline__ void elect_role(WgShared &sh, int lane, int w, int &producer, int &slot)
+{
+    if (threadIdx.x < 4) sh.simd_count[threadIdx.x] = 0;
+    __syncthreads();
+    const unsigned hwid = __builtin_amdgcn_s_getreg((1 << 11) | (4 << 6) | 4);  // HW_ID bits [5:4]: SIMD id
+    const int simd = (int)(hwid & 3u);
+    int idx = 0;
+    if (lane == 0) idx = atomicAdd(&sh.simd_count[simd], 1);
+    idx = __builtin_amdgcn_readfirstlane(idx);
+    __syncthreads();
+    const bool even = sh.simd_count[0] == 2 && sh.simd_count[1] == 2 && sh.simd_count[2] == 2 && sh.simd_count[3] == 2;
+    producer = __builtin_amdgcn_readfirstlane(even ? idx : (w >> 2));
+    slot = __builtin_amdgcn_readfirstlane(even ? simd : (w & 3));
+}
+
 // ---------------------------------------------------------------------------------------------
 // Forward DP (Sec. 2 Eq. 1-2 in the anti-diagonal order of Sec. 4.1).
-// Band tasks are handed out by an atomic ticket in band-major order: a band only ever waits for a
-// band with a smaller ticket, which is running or done, so the wait ends whatever order the
-// hardware starts workgroups in.  The table goes to HBM step-major, R[b][band][s][lane]: one
-// coalesced 512-byte store per step; the band's last row goes to the boundary buffer.
+// Workgroups take tickets in band-major order: a band only ever waits for a band with a smaller
+// ticket, which is running or done, so the wait ends whatever order the hardware starts
+// workgroups in.  The table goes to HBM step-major, R[b][band][s][lane]: one coalesced 512-byte
+// store per step; the band's last row goes to the boundary buffer.
+//   KCH > 0: fused, D <= 8*KCH (register operands);  KCH == 0: fused, any D;  KCH < 0: unfused.
 // ---------------------------------------------------------------------------------------------
 template <int KCH>
-__global__ __launch_bounds__(64) void forward_dp_kernel(Params p, float *__restrict__ value)
+__global__ __launch_bounds__(kWgThreads) void forward_dp_kernel(Params p, float *__restrict__ value)
 {
-    __shared__ float ring[kBandRows * kRingStride];
-    constexpr bool FUSED_REG = KCH > 0;
-    constexpr bool UNFUSED = KCH < 0;
-    constexpr int KR = KCH > 0 ? KCH : 1;
+    __shared__ WgShared sh;
+    __shared__ unsigned ticket_s;
+    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
-    const int lane = threadIdx.x;
-    unsigned ticket = 0;
-    if (lane == 0) ticket = atomicAdd(&p.hdr->fwd_ticket, 1u);
-    ticket = __builtin_amdgcn_readfirstlane(ticket);
-    const int k = ticket / (unsigned)p.B;
-    const int b = ticket - k * p.B;
-    if (k >= p.nbands) return;
+    if (threadIdx.x == 0) ticket_s = atomicAdd(&p.hdr->fwd_ticket, 1u);
+    for (int e = threadIdx.x; e < kSlots * kRingFloats; e += kWgThreads) (&sh.ring[0][0])[e] = kBigCost;
+    int producer, slot;
+    elect_role(sh, lane, w, producer, slot);  // contains two barriers: ticket_s and the rings are visible
+    const unsigned ticket = __builtin_amdgcn_readfirstlane(ticket_s);
+    const int ngroups = (p.B + kSlots - 1) / kSlots;
+    const int k = ticket / (unsigned)ngroups;
+    const int b = (ticket - k * ngroups) * kSlots + slot;
+    const bool live = (k < p.nbands) && (b < p.B);
 
     const int M = p.M, N = p.N;
     const int row0 = k * kBandRows;
-    const float c2 = p.inv_gamma_log2e, g2 = p.gamma_ln2;
-    const float *xb = p.x + b * p.x_stride, *yb_ptr = p.y + b * p.y_stride;
-    const float *xnb = p.xn + b * p.xn_stride, *ynb = p.yn + b * p.yn_stride;
-    const float *cost_b = UNFUSED ? p.cost + (size_t)b * N * M : nullptr;
+    float *ring = sh.ring[slot];
+    const int bb = live ? b : 0;
+    const float *xb = p.x + bb * p.x_stride, *yb = p.y + bb * p.y_stride;
+    const float *xnb = p.xn + bb * p.xn_stride, *ynb = p.yn + bb * p.yn_stride;
 
-    for (int e = lane; e < kBandRows * kRingStride; e += 64) ring[e] = kBigCost;
-
-    CostRegs<KCH> cr;
-    if constexpr (FUSED_REG) {
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-            const int row = min(row0 + 32 * rb + (lane & 31), N - 1);
-            load_operand<KR>(cr.xa[rb], xb + (size_t)row * p.D, p.D, (lane >> 5) * 4, p.vec_d4 != 0, -2.0f);
-            cr.ax[rb] = (lane >> 5) ? 1.0f : xnb[row];
+    if (producer) {
+        // ------------------------------------------------------------------ producer wavefront
+        if constexpr (KCH > 0) {
+            MfmaProducer<KCH, +1> mp;
+            if (live) {
+                mp.init(p, xb, xnb, row0, lane);
+                mp.block_now(p, yb, ynb, ring, 0, 0, row0, lane);  // (upper rows, column block 0)
+                mp.prime(p, yb, ynb, 0, lane);
+            }
+            __syncthreads();
+            for (int sg = 0; sg < p.nmacro; ++sg) {
+                if (live) mp.run(p, yb, ynb, ring, sg, row0, lane);
+                __syncthreads();
+            }
+        } else if constexpr (KCH == 0) {
+            if (live) generic_block(p, b, ring, 0, 0, row0, lane);
+            __syncthreads();
+            for (int sg = 0; sg < p.nmacro; ++sg) {
+                if (live) {
+                    generic_block(p, b, ring, 1, sg, row0, lane);
+                    generic_block(p, b, ring, 0, sg + 1, row0, lane);
+                }
+                __syncthreads();
+            }
+        } else {
+            const float *cost_b = p.cost + (size_t)bb * N * M;
+            float4 pre[2][4];
+            if (live) {
+                load_cost_block(pre[0], cost_b, 0, 0, row0, N, M, p.vec_m != 0, lane);
+                store_cost_block(ring, pre[0], 0, 0, lane);
+                load_cost_block(pre[0], cost_b, 1, 0, row0, N, M, p.vec_m != 0, lane);
+                load_cost_block(pre[1], cost_b, 0, 1, row0, N, M, p.vec_m != 0, lane);
+            }
+            __syncthreads();
+            for (int sg = 0; sg < p.nmacro; ++sg) {
+                if (live) {
+                    store_cost_block(ring, pre[0], 1, sg, lane);
+                    store_cost_block(ring, pre[1], 0, sg + 1, lane);
+                    load_cost_block(pre[0], cost_b, 1, sg + 1, row0, N, M, p.vec_m != 0, lane);
+                    load_cost_block(pre[1], cost_b, 0, sg + 2, row0, N, M, p.vec_m != 0, lane);
+                }
+                __syncthreads();
+            }
         }
-    }
-    __syncthreads();
-
-    // cost block (upper rows, column block 0) is needed by the very first macro-step
-    float4 pre[2][4];
-    if constexpr (FUSED_REG) {
-        load_y_block<KCH>(p, yb_ptr, ynb, 0, lane, cr.yb, cr.byb);
-        const floatx16 acc = block_from_regs<KR>(cr.xa[0], cr.ax[0], cr.yb, cr.byb);
-        store_block_acc(ring, acc, 0, 0, row0, N, M, lane);
-    } else if constexpr (UNFUSED) {
-        load_cost_block(pre[0], cost_b, 0, 0, row0, N, M, p.vec_m != 0, lane);
-        store_cost_block(ring, pre[0], 0, 0, lane);
-    } else {
-        sync_block_generic(p, b, ring, 0, 0, row0, lane);
+        return;
     }
 
+    // ---------------------------------------------------------------------- consumer wavefront
+    const float c2 = p.inv_gamma_log2e;
+    const double g2d = (double)p.gamma_ln2;
     bool gave_up = false;
     double left = kBig;                                  // R[i][j-1]
     double diag = (k == 0 && lane == 0) ? 0.0 : kBig;    // R[i-1][j-1]; R[0,0] = 0 in the paper's indexing
     double edge = kBig;                                  // collects lane 63's values of a macro-step
-    const unsigned long long *brow_in = p.brow + ((size_t)b * p.nbands + (k > 0 ? k - 1 : 0)) * M;
-    unsigned long long *brow_out = p.brow + ((size_t)b * p.nbands + k) * M;
-    double *Rw = p.R + ((size_t)b * p.nbands + k) * (size_t)p.nmacro * kBlk * kBandRows + lane;
-    const bool emit_bottom = (k + 1 < p.nbands);
+    const int kc = live ? k : 0;
+    const unsigned long long *brow_in = p.brow + ((size_t)bb * p.nbands + (kc > 0 ? kc - 1 : 0)) * M;
+    unsigned long long *brow_out = p.brow + ((size_t)bb * p.nbands + kc) * M;
+    double *Rk = p.R + ((size_t)bb * p.nbands + kc) * (size_t)p.nmacro * kBlk * kBandRows;
+    const bool has_above = live && k > 0;
+    const bool emit_bottom = live && (k + 1 < p.nbands);
     const float *my_ring = ring + lane * kRingStride;
+    double *top = sh.edge_in[slot];
 
-    // row above the band for macro-step 0: lane l < 32 holds column l
-    double topv = kBig;
-    if (k > 0) {
-        const bool need = lane < kBlk && lane < M;
-        topv = resolve_boundary(p, brow_in, lane, need, lane, gave_up, peek_boundary(brow_in, lane, need));
+    // row above the band for macro-step 0: lane l < 32 brings column l
+    {
+        double t0 = kBig;
+        if (has_above) {
+            const bool need = lane < kBlk && lane < M;
+            t0 = resolve_boundary(p, brow_in, lane, need, lane, gave_up, peek_boundary(brow_in, lane, need));
+        }
+        if (lane < kBlk) top[lane] = t0;
     }
     __syncthreads();
 
     for (int sg = 0; sg < p.nmacro; ++sg) {
-        // ---- prefetches for the next macro-step
-        unsigned long long nxt_bits = (unsigned long long)__double_as_longlong(kBig);
-        const int jn = (sg + 1) * kBlk + lane;
-        const bool need_n = (k > 0) && lane < kBlk && jn < M;
-        if (k > 0) nxt_bits = peek_boundary(brow_in, jn, need_n);
-        floatx16 acc0 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        floatx16 acc1 = acc0;
-        if constexpr (FUSED_REG) load_y_block<KCH>(p, yb_ptr, ynb, sg + 1, lane, cr.ya, cr.bya);
-        if constexpr (UNFUSED) {
-            load_cost_block(pre[0], cost_b, 1, sg, row0, N, M, p.vec_m != 0, lane);
-            load_cost_block(pre[1], cost_b, 0, sg + 1, row0, N, M, p.vec_m != 0, lane);
-        }
-        const float *rd = my_ring + (sg % 3) * kBlk;
-        double *Rs = Rw + (size_t)sg * kBlk * kBandRows;
-
-        // ---- 32 steps; the MFMAs of the two blocks the NEXT macro-step needs are spread over them:
-        //      first half: (lower rows, column block sg) with y block sg; second half: (upper rows, sg+1)
+        if (live) {
+            unsigned long long nxt_bits = (unsigned long long)__double_as_longlong(kBig);
+            const int jn = (sg + 1) * kBlk + lane;
+            const bool need_n = has_above && lane < kBlk && jn < M;
+            if (has_above) nxt_bits = peek_boundary(brow_in, jn, need_n);
+            const float *rd = my_ring + (sg & 3) * kBlk;
+            double *Rs = Rk + (size_t)sg * kBlk * kBandRows;
 #pragma unroll
-        for (int u = 0; u < kBlk; ++u) {
-            const double up = lane_shr1(left, topv);  // R[i-1][j]; lane 0 takes the row above the band
-            topv = lane_shl1(topv, topv);
-            const float dc = rd[u];
-            double m;
-            float corr;
-            softmin3_parts(diag, up, left, c2, g2, m, corr);
-            // all additions that build the table are float64: a float32 rounding of d - corr here
-            // would differ between the two sweeps and add up along the alignment path
-            const double cur = (m - (double)corr) + (double)dc;
-            Rs[u * kBandRows] = cur;
-            edge = lane_shl1(edge, cur);  // lane 63 keeps its own value, the others move down
-            diag = up;
-            left = cur;
-            if constexpr (FUSED_REG) {
-#pragma unroll
-                for (int mi = u * KR / 4; mi < (u + 1) * KR / 4; ++mi) {
-                    const int blk = mi / (4 * KR), c = (mi % (4 * KR)) / 4, e = mi % 4;
-                    if (blk == 0)
-                        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(comp4(cr.xa[1][c], e), comp4(cr.yb[c], e), acc0, 0, 0, 0);
-                    else
-                        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(comp4(cr.xa[0][c], e), comp4(cr.ya[c], e), acc1, 0, 0, 0);
-                }
-                if (u == 15) acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(cr.ax[1], cr.byb, acc0, 0, 0, 0);
-                if (u == 31) acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(cr.ax[0], cr.bya, acc1, 0, 0, 0);
+            for (int u = 0; u < kBlk; ++u) {
+                const double up = lane_shr1(left, top[u]);  // R[i-1][j]; lane 0 takes the row above the band
+                const float dc = rd[u];
+                double m;
+                float L;
+                softmin3_parts(diag, up, left, c2, m, L);
+                // every addition that builds the table is float64: a float32 rounding here would
+                // differ between the two sweeps and add up along the alignment path
+                const double cur = fma(-(double)L, g2d, m + (double)dc);
+                Rs[u * kBandRows + lane] = cur;
+                edge = lane_shl1(edge, cur);  // lane 63 keeps its own value, the others move down
+                diag = up;
+                left = cur;
             }
+            // last row of the band: lanes 32..63 hold columns 32*sg - 63 + (lane - 32)
+            if (emit_bottom && lane >= kBlk) {
+                const int j = sg * kBlk + lane - kBlk - (kBandRows - 1);
+                if (j >= 0 && j < M) publish_boundary(brow_out, j, edge);
+            }
+            double tn = kBig;
+            if (has_above) tn = resolve_boundary(p, brow_in, jn, need_n, lane, gave_up, nxt_bits);
+            if (lane < kBlk) top[lane] = tn;
         }
-
-        // ---- last row of the band: lanes 32..63 hold columns 32*sg - 63 + (lane - 32)
-        if (emit_bottom && lane >= kBlk) {
-            const int j = sg * kBlk + lane - kBlk - (kBandRows - 1);
-            if (j >= 0 && j < M) publish_boundary(brow_out, j, edge);
-        }
-        // ---- cost blocks for the next macro-step
-        if constexpr (FUSED_REG) {
-            store_block_acc(ring, acc0, 1, sg, row0, N, M, lane);
-            store_block_acc(ring, acc1, 0, sg + 1, row0, N, M, lane);
-#pragma unroll
-            for (int c = 0; c < KR; ++c) cr.yb[c] = cr.ya[c];
-            cr.byb = cr.bya;
-        } else if constexpr (UNFUSED) {
-            store_cost_block(ring, pre[0], 1, sg, lane);
-            store_cost_block(ring, pre[1], 0, sg + 1, lane);
-        } else {
-            sync_block_generic(p, b, ring, 1, sg, row0, lane);
-            sync_block_generic(p, b, ring, 0, sg + 1, row0, lane);
-        }
-        // ---- row above the band for the next macro-step
-        if (k > 0) topv = resolve_boundary(p, brow_in, jn, need_n, lane, gave_up, nxt_bits);
         __syncthreads();
     }
 
     // R[N,M] of the pair: cell (N-1, M-1) was stored at step M-1+lane by the lane that owns row N-1
-    if (row0 + lane == N - 1) {
-        const double r = Rw[(size_t)(M - 1 + lane) * kBandRows];
+    if (live && row0 + lane == N - 1) {
+        const double r = Rk[(size_t)(M - 1 + lane) * kBandRows + lane];
         p.rfinal[b] = r;
         value[b] = (float)r;
     }
@@ -421,8 +525,6 @@ __device__ __forceinline__ void flush_E_block(const Params &p, const float *ring
                                               unsigned char *__restrict__ nzb, int rb, int cb, int row0, int lane)
 {
     if (cb < 0 || cb >= p.ncb || row0 + 32 * rb >= p.N) return;
-    int ph = (cb + rb) % 3;
-    if (ph < 0) ph += 3;
     const int c4 = (lane & 7) * 4, j0 = cb * kBlk;
     bool any = false;
 #pragma unroll
@@ -430,14 +532,10 @@ __device__ __forceinline__ void flush_E_block(const Params &p, const float *ring
         const int r = (lane >> 3) + 8 * it;
         const int row = row0 + rb * 32 + r;
         const float *rowp = ring + (32 * rb + r) * kRingStride;
-        const unsigned base = (unsigned)ph * 32u + (unsigned)(c4 + r);
+        const int base = 32 * (cb + rb) + c4 + r;
         float v[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            unsigned pos = base + (unsigned)e;
-            pos = min(pos, pos - (unsigned)kRingCols);
-            v[e] = rowp[pos];
-        }
+        for (int e = 0; e < 4; ++e) v[e] = rowp[(base + e) & (kRingCols - 1)];
         if (row < p.N) {
             float *q = Eb + (size_t)row * p.M + j0 + c4;
             if (p.vec_m && j0 + c4 + 3 < p.M) {
@@ -455,174 +553,165 @@ __device__ __forceinline__ void flush_E_block(const Params &p, const float *ring
 }
 
 template <int KCH>
-__global__ __launch_bounds__(64) void backward_dp_kernel(Params p)
+__global__ __launch_bounds__(kWgThreads) void backward_dp_kernel(Params p)
 {
-    __shared__ float ring[kBandRows * kRingStride];
-    constexpr bool FUSED_REG = KCH > 0;
-    constexpr bool UNFUSED = KCH < 0;
-    constexpr int KR = KCH > 0 ? KCH : 1;
-
-    const int lane = threadIdx.x;
+    __shared__ WgShared sh;
+    __shared__ unsigned ticket_s;
+    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (p.hdr->abort_backward) return;
-    unsigned ticket = 0;
-    if (lane == 0) ticket = atomicAdd(&p.hdr->bwd_ticket, 1u);
-    ticket = __builtin_amdgcn_readfirstlane(ticket);
-    const int kk = ticket / (unsigned)p.B;
-    const int b = ticket - kk * p.B;
-    if (kk >= p.nbands) return;
+
+    if (threadIdx.x == 0) ticket_s = atomicAdd(&p.hdr->bwd_ticket, 1u);
+    for (int e = threadIdx.x; e < kSlots * kRingFloats; e += kWgThreads) (&sh.ring[0][0])[e] = kBigCost;
+    int producer, slot;
+    elect_role(sh, lane, w, producer, slot);
+    const unsigned ticket = __builtin_amdgcn_readfirstlane(ticket_s);
+    const int ngroups = (p.B + kSlots - 1) / kSlots;
+    const int kk = ticket / (unsigned)ngroups;
+    const int b = (ticket - kk * ngroups) * kSlots + slot;
     const int k = p.nbands - 1 - kk;
+    const bool live = (kk < p.nbands) && (b < p.B);
 
     const int M = p.M, N = p.N;
-    const int row0 = k * kBandRows;
-    const float c2 = p.inv_gamma_log2e, g2 = p.gamma_ln2;
-    const float *xb = p.x + b * p.x_stride, *yb_ptr = p.y + b * p.y_stride;
-    const float *xnb = p.xn + b * p.xn_stride, *ynb = p.yn + b * p.yn_stride;
-    const float *cost_b = UNFUSED ? p.cost + (size_t)b * N * M : nullptr;
-    float *Eb = p.E + (size_t)b * N * M;
-    unsigned char *nzb = p.nz + (size_t)b * p.nrb * p.ncb;
-
-    for (int e = lane; e < kBandRows * kRingStride; e += 64) ring[e] = kBigCost;
-
-    CostRegs<KCH> cr;
-    if constexpr (FUSED_REG) {
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-            const int row = min(row0 + 32 * rb + (lane & 31), N - 1);
-            load_operand<KR>(cr.xa[rb], xb + (size_t)row * p.D, p.D, (lane >> 5) * 4, p.vec_d4 != 0, -2.0f);
-            cr.ax[rb] = (lane >> 5) ? 1.0f : xnb[row];
-        }
-    }
-    __syncthreads();
-
-    // blocks the first macro-step reads: (upper rows, sg0-1), (lower rows, sg0-2) and (lower rows, sg0-1)
+    const int row0 = (live ? k : 0) * kBandRows;
+    float *ring = sh.ring[slot];
+    const int bb = live ? b : 0;
+    const float *xb = p.x + bb * p.x_stride, *yb = p.y + bb * p.y_stride;
+    const float *xnb = p.xn + bb * p.xn_stride, *ynb = p.yn + bb * p.yn_stride;
     const int sg0 = p.nmacro - 1;
-    float4 pre[2][4];
-    if constexpr (FUSED_REG) {
-        load_y_block<KCH>(p, yb_ptr, ynb, sg0 - 1, lane, cr.ya, cr.bya);
-        floatx16 acc = block_from_regs<KR>(cr.xa[0], cr.ax[0], cr.ya, cr.bya);
-        store_block_acc(ring, acc, 0, sg0 - 1, row0, N, M, lane);
-        acc = block_from_regs<KR>(cr.xa[1], cr.ax[1], cr.ya, cr.bya);
-        store_block_acc(ring, acc, 1, sg0 - 1, row0, N, M, lane);
-        load_y_block<KCH>(p, yb_ptr, ynb, sg0 - 2, lane, cr.yb, cr.byb);
-        acc = block_from_regs<KR>(cr.xa[1], cr.ax[1], cr.yb, cr.byb);
-        store_block_acc(ring, acc, 1, sg0 - 2, row0, N, M, lane);
-    } else if constexpr (UNFUSED) {
-        load_cost_block(pre[0], cost_b, 0, sg0 - 1, row0, N, M, p.vec_m != 0, lane);
-        store_cost_block(ring, pre[0], 0, sg0 - 1, lane);
-        load_cost_block(pre[0], cost_b, 1, sg0 - 1, row0, N, M, p.vec_m != 0, lane);
-        store_cost_block(ring, pre[0], 1, sg0 - 1, lane);
-        load_cost_block(pre[0], cost_b, 1, sg0 - 2, row0, N, M, p.vec_m != 0, lane);
-        store_cost_block(ring, pre[0], 1, sg0 - 2, lane);
-    } else {
-        sync_block_generic(p, b, ring, 0, sg0 - 1, row0, lane);
-        sync_block_generic(p, b, ring, 1, sg0 - 1, row0, lane);
-        sync_block_generic(p, b, ring, 1, sg0 - 2, row0, lane);
+
+    if (producer) {
+        // blocks the first macro-step reads: (upper rows, sg0-1), (lower rows, sg0-1), (lower rows, sg0-2)
+        if constexpr (KCH > 0) {
+            MfmaProducer<KCH, -1> mp;
+            if (live) {
+                mp.init(p, xb, xnb, row0, lane);
+                mp.block_now(p, yb, ynb, ring, 0, sg0 - 1, row0, lane);
+                mp.block_now(p, yb, ynb, ring, 1, sg0 - 1, row0, lane);
+                mp.block_now(p, yb, ynb, ring, 1, sg0 - 2, row0, lane);
+                mp.prime(p, yb, ynb, sg0, lane);
+            }
+            __syncthreads();
+            for (int sg = sg0; sg >= 0; --sg) {
+                if (live) mp.run(p, yb, ynb, ring, sg, row0, lane);
+                __syncthreads();
+            }
+        } else if constexpr (KCH == 0) {
+            if (live) {
+                generic_block(p, b, ring, 0, sg0 - 1, row0, lane);
+                generic_block(p, b, ring, 1, sg0 - 1, row0, lane);
+                generic_block(p, b, ring, 1, sg0 - 2, row0, lane);
+            }
+            __syncthreads();
+            for (int sg = sg0; sg >= 0; --sg) {
+                if (live) {
+                    generic_block(p, b, ring, 0, sg - 2, row0, lane);
+                    generic_block(p, b, ring, 1, sg - 3, row0, lane);
+                }
+                __syncthreads();
+            }
+        } else {
+            const float *cost_b = p.cost + (size_t)bb * N * M;
+            float4 pre[2][4];
+            if (live) {
+                load_cost_block(pre[0], cost_b, 0, sg0 - 1, row0, N, M, p.vec_m != 0, lane);
+                store_cost_block(ring, pre[0], 0, sg0 - 1, lane);
+                load_cost_block(pre[0], cost_b, 1, sg0 - 1, row0, N, M, p.vec_m != 0, lane);
+                store_cost_block(ring, pre[0], 1, sg0 - 1, lane);
+                load_cost_block(pre[0], cost_b, 1, sg0 - 2, row0, N, M, p.vec_m != 0, lane);
+                store_cost_block(ring, pre[0], 1, sg0 - 2, lane);
+                load_cost_block(pre[0], cost_b, 0, sg0 - 2, row0, N, M, p.vec_m != 0, lane);
+                load_cost_block(pre[1], cost_b, 1, sg0 - 3, row0, N, M, p.vec_m != 0, lane);
+            }
+            __syncthreads();
+            for (int sg = sg0; sg >= 0; --sg) {
+                if (live) {
+                    store_cost_block(ring, pre[0], 0, sg - 2, lane);
+                    store_cost_block(ring, pre[1], 1, sg - 3, lane);
+                    load_cost_block(pre[0], cost_b, 0, sg - 3, row0, N, M, p.vec_m != 0, lane);
+                    load_cost_block(pre[1], cost_b, 1, sg - 4, row0, N, M, p.vec_m != 0, lane);
+                }
+                __syncthreads();
+            }
+        }
+        return;
     }
 
+    // ---------------------------------------------------------------------- consumer wavefront
+    const float c2 = p.inv_gamma_log2e, g2 = p.gamma_ln2;
+    const double g2d = (double)p.gamma_ln2;
+    float *Eb = p.E + (size_t)bb * N * M;
+    unsigned char *nzb = p.nz + (size_t)bb * p.nrb * p.ncb;
     bool gave_up = false;
     double right = kBig;  // T[i][j+1]
     double diag = kBig;   // T[i+1][j+1]
     double edge = kBig;   // collects lane 0's values of a macro-step
     // step at which this lane meets the cell whose diagonal successor is T[N+1,M+1] = 0
-    const int s_corner = (row0 + lane == N - 1) ? (M - 1 + lane) : -1;
-    const double Rfin = p.rfinal[b];
-    const bool has_below = (k + 1 < p.nbands);
-    const unsigned long long *brow_in = p.brow + ((size_t)b * p.nbands + (has_below ? k + 1 : k)) * M;
-    unsigned long long *brow_out = p.brow + ((size_t)b * p.nbands + k) * M;
-    const double *Rw = p.R + ((size_t)b * p.nbands + k) * (size_t)p.nmacro * kBlk * kBandRows + lane;
+    const int s_corner = (live && row0 + lane == N - 1) ? (M - 1 + lane) : -1;
+    const double Rfin = live ? p.rfinal[b] : 0.0;
+    const int kc = live ? k : 0;
+    const bool has_below = live && (k + 1 < p.nbands);
+    const unsigned long long *brow_in = p.brow + ((size_t)bb * p.nbands + (has_below ? kc + 1 : kc)) * M;
+    unsigned long long *brow_out = p.brow + ((size_t)bb * p.nbands + kc) * M;
+    const double *Rk = p.R + ((size_t)bb * p.nbands + kc) * (size_t)p.nmacro * kBlk * kBandRows;
     float *my_ring = ring + lane * kRingStride;
+    double *bot = sh.edge_in[slot];
 
     // R of the first macro-step; afterwards each value is reloaded one macro-step ahead, right after use
     double Rq[kBlk];
 #pragma unroll
-    for (int u = 0; u < kBlk; ++u) Rq[u] = Rfin - Rw[((size_t)sg0 * kBlk + u) * kBandRows];
+    for (int u = 0; u < kBlk; ++u) Rq[u] = live ? Rfin - Rk[((size_t)sg0 * kBlk + u) * kBandRows + lane] : 0.0;
 
-    // row below the band for the first macro-step: lane l >= 32 holds column 32*sg - 63 + (l - 32)
-    double botv = kBig;
-    if (has_below) {
-        const int jj = sg0 * kBlk + lane - kBlk - (kBandRows - 1);
-        const bool need = lane >= kBlk && jj >= 0 && jj < M;
-        botv = resolve_boundary(p, brow_in, jj, need, lane, gave_up, peek_boundary(brow_in, jj, need));
+    // row below the band for the first macro-step: lane l >= 32 brings column 32*sg - 63 + (l - 32),
+    // which lane 63 meets at step u = l - 32
+    {
+        double b0 = kBig;
+        if (has_below) {
+            const int jj = sg0 * kBlk + lane - kBlk - (kBandRows - 1);
+            const bool need = lane >= kBlk && jj >= 0 && jj < M;
+            b0 = resolve_boundary(p, brow_in, jj, need, lane, gave_up, peek_boundary(brow_in, jj, need));
+        }
+        if (lane >= kBlk) bot[lane - kBlk] = b0;
     }
     __syncthreads();
 
     for (int sg = sg0; sg >= 0; --sg) {
-        unsigned long long nxt_bits = (unsigned long long)__double_as_longlong(kBig);
-        const int jn = (sg - 1) * kBlk + lane - kBlk - (kBandRows - 1);
-        const bool need_n = has_below && lane >= kBlk && jn >= 0 && jn < M;
-        if (has_below) nxt_bits = peek_boundary(brow_in, jn, need_n);
-        floatx16 acc0 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        floatx16 acc1 = acc0;
-        // this macro-step prepares (upper rows, sg-2) with y block sg-2 (held) and (lower rows, sg-3) with y block sg-3 (new)
-        if constexpr (FUSED_REG) {
+        if (live) {
+            unsigned long long nxt_bits = (unsigned long long)__double_as_longlong(kBig);
+            const int jn = (sg - 1) * kBlk + lane - kBlk - (kBandRows - 1);
+            const bool need_n = has_below && lane >= kBlk && jn >= 0 && jn < M;
+            if (has_below) nxt_bits = peek_boundary(brow_in, jn, need_n);
+            float *rd = my_ring + (sg & 3) * kBlk;
+            const double *Rn = Rk + (size_t)(sg > 0 ? sg - 1 : 0) * kBlk * kBandRows;
+            const int sbase = sg * kBlk;
 #pragma unroll
-            for (int c = 0; c < KR; ++c) cr.yb[c] = cr.ya[c];
-            cr.byb = cr.bya;
-            if (sg == sg0) load_y_block<KCH>(p, yb_ptr, ynb, sg - 2, lane, cr.yb, cr.byb);
-            load_y_block<KCH>(p, yb_ptr, ynb, sg - 3, lane, cr.ya, cr.bya);
-        }
-        if constexpr (UNFUSED) {
-            load_cost_block(pre[0], cost_b, 0, sg - 2, row0, N, M, p.vec_m != 0, lane);
-            load_cost_block(pre[1], cost_b, 1, sg - 3, row0, N, M, p.vec_m != 0, lane);
-        }
-        float *rd = my_ring + (sg % 3) * kBlk;
-        const double *Rn = Rw + (size_t)(sg > 0 ? sg - 1 : 0) * kBlk * kBandRows;
-        const int sbase = sg * kBlk;
-
-#pragma unroll
-        for (int u = kBlk - 1; u >= 0; --u) {
-            const double down = lane_shl1(right, botv);  // T[i+1][j]; lane 63 takes the row below the band
-            botv = lane_shr1(botv, botv);
-            const float dc = rd[u];
-            const double dg = (sbase + u == s_corner) ? 0.0 : diag;
-            double m;
-            float corr;
-            softmin3_parts(dg, down, right, c2, g2, m, corr);
-            const double cur = (m - (double)corr) + (double)dc;
-            // gamma*Ebar = R[N,M] - R[i,j] - (m - corr)
-            const float gE = (float)(Rq[u] - m) + corr;
-            rd[u] = __builtin_amdgcn_exp2f(gE * c2);
-            Rq[u] = Rfin - Rn[u * kBandRows];
-            edge = lane_shr1(edge, cur);  // lane 0 keeps its own value, the others move up
-            diag = down;
-            right = cur;
-            if constexpr (FUSED_REG) {
-                const int v = kBlk - 1 - u;
-#pragma unroll
-                for (int mi = v * KR / 4; mi < (v + 1) * KR / 4; ++mi) {
-                    const int blk = mi / (4 * KR), c = (mi % (4 * KR)) / 4, e = mi % 4;
-                    if (blk == 0)
-                        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(comp4(cr.xa[0][c], e), comp4(cr.yb[c], e), acc0, 0, 0, 0);
-                    else
-                        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(comp4(cr.xa[1][c], e), comp4(cr.ya[c], e), acc1, 0, 0, 0);
-                }
-                if (v == 15) acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(cr.ax[0], cr.byb, acc0, 0, 0, 0);
-                if (v == 31) acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(cr.ax[1], cr.bya, acc1, 0, 0, 0);
+            for (int u = kBlk - 1; u >= 0; --u) {
+                const double down = lane_shl1(right, bot[u]);  // T[i+1][j]; lane 63 takes the row below the band
+                const float dc = rd[u];
+                const double dg = (sbase + u == s_corner) ? 0.0 : diag;
+                double m;
+                float L;
+                softmin3_parts(dg, down, right, c2, m, L);
+                const double cur = fma(-(double)L, g2d, m + (double)dc);
+                // gamma*Ebar = R[N,M] - R[i,j] - (m - gamma ln2 L)
+                const float gE = fmaf(g2, L, (float)(Rq[u] - m));
+                rd[u] = __builtin_amdgcn_exp2f(gE * c2);
+                Rq[u] = Rfin - Rn[u * kBandRows + lane];
+                edge = lane_shr1(edge, cur);  // lane 0 keeps its own value, the others move up
+                diag = down;
+                right = cur;
             }
+            // first row of the band, columns 32*sg .. 32*sg+31, for the band above
+            if (k > 0 && lane < kBlk) {
+                const int j = sg * kBlk + lane;
+                if (j < M) publish_boundary(brow_out, j, edge);
+            }
+            // E blocks completed by this macro-step: (upper rows, sg) and (lower rows, sg-1)
+            flush_E_block(p, ring, Eb, nzb, 0, sg, row0, lane);
+            flush_E_block(p, ring, Eb, nzb, 1, sg - 1, row0, lane);
+            double bn = kBig;
+            if (has_below) bn = resolve_boundary(p, brow_in, jn, need_n, lane, gave_up, nxt_bits);
+            if (lane >= kBlk) bot[lane - kBlk] = bn;
         }
-        __syncthreads();
-
-        // first row of the band, columns 32*sg .. 32*sg+31, for the band above
-        if (k > 0 && lane < kBlk) {
-            const int j = sg * kBlk + lane;
-            if (j < M) publish_boundary(brow_out, j, edge);
-        }
-        // E blocks completed by this macro-step: (upper rows, sg) and (lower rows, sg-1)
-        flush_E_block(p, ring, Eb, nzb, 0, sg, row0, lane);
-        flush_E_block(p, ring, Eb, nzb, 1, sg - 1, row0, lane);
-        __syncthreads();
-        // cost blocks for the next macro-step
-        if constexpr (FUSED_REG) {
-            store_block_acc(ring, acc0, 0, sg - 2, row0, N, M, lane);
-            store_block_acc(ring, acc1, 1, sg - 3, row0, N, M, lane);
-        } else if constexpr (UNFUSED) {
-            store_cost_block(ring, pre[0], 0, sg - 2, lane);
-            store_cost_block(ring, pre[1], 1, sg - 3, lane);
-        } else {
-            sync_block_generic(p, b, ring, 0, sg - 2, row0, lane);
-            sync_block_generic(p, b, ring, 1, sg - 3, row0, lane);
-        }
-        if (has_below) botv = resolve_boundary(p, brow_in, jn, need_n, lane, gave_up, nxt_bits);
         __syncthreads();
     }
 }

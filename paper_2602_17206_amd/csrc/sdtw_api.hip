@@ -132,20 +132,20 @@ int forward_impl(const sdtw_desc *d, const float *x, const float *y, float *valu
     row_sqnorm_kernel<<<(unsigned)std::min<int64_t>((L.xn_count + 3) / 4, 65535), 256, 0, st>>>(x, p.xn, L.xn_count, d->D);
     row_sqnorm_kernel<<<(unsigned)std::min<int64_t>((L.yn_count + 3) / 4, 65535), 256, 0, st>>>(y, p.yn, L.yn_count, d->D);
     }
-    const unsigned tasks = (unsigned)d->B * (unsigned)L.nbands;
+    const unsigned tasks = (unsigned)((d->B + kSlots - 1) / kSlots) * (unsigned)L.nbands;
     if (d->mode == SDTW_UNFUSED) {
         dim3 g((d->M + 63) / 64, (d->N + 63) / 64, d->B);
         { ProfScope ps("cost_tensor", st); cost_tensor_kernel<<<g, 256, 0, st>>>(p); }
-        { ProfScope ps("forward_dp_unfused", st); forward_dp_kernel<-1><<<tasks, 64, 0, st>>>(p, value); }
+        { ProfScope ps("forward_dp_unfused", st); forward_dp_kernel<-1><<<tasks, kWgThreads, 0, st>>>(p, value); }
     } else {
         ProfScope ps("forward_dp_fused", st);
-        switch (fused_variant(d->D)) {
-            case 1: forward_dp_kernel<1><<<tasks, 64, 0, st>>>(p, value); break;
-            case 2: forward_dp_kernel<2><<<tasks, 64, 0, st>>>(p, value); break;
-            case 4: forward_dp_kernel<4><<<tasks, 64, 0, st>>>(p, value); break;
-            case 8: forward_dp_kernel<8><<<tasks, 64, 0, st>>>(p, value); break;
-            case 16: forward_dp_kernel<16><<<tasks, 64, 0, st>>>(p, value); break;
-            default: forward_dp_kernel<0><<<tasks, 64, 0, st>>>(p, value); break;
+        switch (p.vec_d4 ? fused_variant(d->D) : 0) {
+            case 1: forward_dp_kernel<1><<<tasks, kWgThreads, 0, st>>>(p, value); break;
+            case 2: forward_dp_kernel<2><<<tasks, kWgThreads, 0, st>>>(p, value); break;
+            case 4: forward_dp_kernel<4><<<tasks, kWgThreads, 0, st>>>(p, value); break;
+            case 8: forward_dp_kernel<8><<<tasks, kWgThreads, 0, st>>>(p, value); break;
+            case 16: forward_dp_kernel<16><<<tasks, kWgThreads, 0, st>>>(p, value); break;
+            default: forward_dp_kernel<0><<<tasks, kWgThreads, 0, st>>>(p, value); break;
         }
     }
     return hip_ok();
@@ -158,19 +158,19 @@ int backward_impl(const sdtw_desc *d, const float *x, const float *y, const floa
     const Params p = make_params(d, L, x, y, ws);
     { ProfScope ps("backward_begin", st); backward_begin_kernel<<<1, 64, 0, st>>>(p); }
     { ProfScope ps("fill_boundary", st); fill_boundary(p, st); }
-    const unsigned tasks = (unsigned)d->B * (unsigned)L.nbands;
+    const unsigned tasks = (unsigned)((d->B + kSlots - 1) / kSlots) * (unsigned)L.nbands;
     if (d->mode == SDTW_UNFUSED) {
         ProfScope ps("backward_dp_unfused", st);
-        backward_dp_kernel<-1><<<tasks, 64, 0, st>>>(p);
+        backward_dp_kernel<-1><<<tasks, kWgThreads, 0, st>>>(p);
     } else {
         ProfScope ps("backward_dp_fused", st);
-        switch (fused_variant(d->D)) {
-            case 1: backward_dp_kernel<1><<<tasks, 64, 0, st>>>(p); break;
-            case 2: backward_dp_kernel<2><<<tasks, 64, 0, st>>>(p); break;
-            case 4: backward_dp_kernel<4><<<tasks, 64, 0, st>>>(p); break;
-            case 8: backward_dp_kernel<8><<<tasks, 64, 0, st>>>(p); break;
-            case 16: backward_dp_kernel<16><<<tasks, 64, 0, st>>>(p); break;
-            default: backward_dp_kernel<0><<<tasks, 64, 0, st>>>(p); break;
+        switch (p.vec_d4 ? fused_variant(d->D) : 0) {
+            case 1: backward_dp_kernel<1><<<tasks, kWgThreads, 0, st>>>(p); break;
+            case 2: backward_dp_kernel<2><<<tasks, kWgThreads, 0, st>>>(p); break;
+            case 4: backward_dp_kernel<4><<<tasks, kWgThreads, 0, st>>>(p); break;
+            case 8: backward_dp_kernel<8><<<tasks, kWgThreads, 0, st>>>(p); break;
+            case 16: backward_dp_kernel<16><<<tasks, kWgThreads, 0, st>>>(p); break;
+            default: backward_dp_kernel<0><<<tasks, kWgThreads, 0, st>>>(p); break;
         }
     }
     if (dx || dy) {
