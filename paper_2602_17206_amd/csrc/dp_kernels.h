@@ -38,8 +38,11 @@ namespace sdtw {
 constexpr int kRingCols = 128;     // four phases of 32 steps
 constexpr int kRingStride = 129;   // floats per band row in LDS (odd: lanes hit distinct banks)
 constexpr int kRingFloats = kBandRows * kRingStride;
-constexpr int kSlots = 4;          // bands per workgroup
-constexpr int kWgThreads = 2 * kSlots * 64;
+// Workgroup shapes: SLOTS bands per workgroup, each with one consumer and NPROD producer wavefronts.
+//   SLOTS=4, NPROD=1 (512 threads): large problems; producer and consumer of a band share a SIMD.
+//   SLOTS=1, NPROD=1|2 (128|192 threads): small problems that cannot fill the chip anyway; the
+//   wavefronts of a band land on different SIMDs, so producing the cost never delays the DP chain.
+constexpr int wg_threads(int slots, int nprod) { return slots * (1 + nprod) * 64; }
 constexpr double kBig = 1e300;     // stands for +inf in the DP tables
 constexpr float kBigCost = 3.0e38f;  // cost of a cell outside the grid
 constexpr int kStatusTimeoutDp = 6;  // SDTW_ERR_TIMEOUT
@@ -230,16 +233,19 @@ template <int DIR> __device__ __forceinline__ int blk_cb(int sg, int which)
 // -2*x of the band's two 32-row blocks stays in registers for the whole sweep; y streams through
 // NBUF stage buffers of CPS chunks each, every buffer being reloaded right after its use with the
 // data of the stage NBUF stages later, so loads are in flight for thousands of cycles.
-template <int KCH, int DIR> struct MfmaProducer {
+// A producer makes the blocks W0 .. W0+NW-1 of the two blocks of each macro-step (NW = 2: both).
+template <int KCH, int DIR, int W0, int NW> struct MfmaProducer {
     static constexpr int CPS = KCH >= 8 ? 2 : 1;         // chunks (8 MFMAs' worth of y) per stage
     static constexpr int NQ = KCH / CPS;                 // stages per block
-    static constexpr int NST = 2 * NQ;                   // stages per macro-step
+    static constexpr int NST = NW * NQ;                  // stages per macro-step
     static constexpr int NBUF = KCH >= 8 ? 4 : NST;      // stage buffers
+    static_assert(NST % NBUF == 0, "stage buffers must divide the stages of a macro-step");
+    static constexpr bool owns_rb(int rb) { return NW == 2 || rb == (DIR > 0 ? 1 - W0 : W0); }
 
     float4 xa[2][KCH];
     float ax[2];  // lanes 0-31: ||x_r||^2, lanes 32-63: 1
     float4 ybuf[NBUF][CPS];
-    float by0, by1;  // lanes 0-31: 1, lanes 32-63: ||y_c||^2, for the two blocks of the macro-step
+    float by[2];  // lanes 0-31: 1, lanes 32-63: ||y_c||^2, for the blocks of the macro-step
 
     __device__ __forceinline__ const float *yrow(const Params &p, const float *yb, int cb, int lane) const
     {
@@ -266,6 +272,7 @@ template <int KCH, int DIR> struct MfmaProducer {
     {
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
+            if (!owns_rb(rb)) continue;
             const int row = min(row0 + 32 * rb + (lane & 31), p.N - 1);
 #pragma unroll
             for (int c = 0; c < KCH; ++c) {
@@ -292,21 +299,22 @@ template <int KCH, int DIR> struct MfmaProducer {
     __device__ __forceinline__ void prime(const Params &p, const float *yb, const float *ynb, int sg, int lane)
     {
 #pragma unroll
-        for (int q = 0; q < NBUF; ++q) load_stage(p, yb, q, blk_cb<DIR>(sg, q / NQ), q % NQ, lane);
-        by0 = ynorm(p, ynb, blk_cb<DIR>(sg, 0), lane);
-        by1 = ynorm(p, ynb, blk_cb<DIR>(sg, 1), lane);
+        for (int q = 0; q < NBUF; ++q) load_stage(p, yb, q, blk_cb<DIR>(sg, W0 + q / NQ), q % NQ, lane);
+#pragma unroll
+        for (int i = 0; i < NW; ++i) by[i] = ynorm(p, ynb, blk_cb<DIR>(sg, W0 + i), lane);
     }
     // the two blocks of macro-step sg
     __device__ __forceinline__ void run(const Params &p, const float *yb, const float *ynb, float *ring, int sg,
                                         int row0, int lane)
     {
         const int sgn = sg + DIR;  // next macro-step
-        const float nby0 = ynorm(p, ynb, blk_cb<DIR>(sgn, 0), lane);
-        const float nby1 = ynorm(p, ynb, blk_cb<DIR>(sgn, 1), lane);
+        float nby[2];
+#pragma unroll
+        for (int i = 0; i < NW; ++i) nby[i] = ynorm(p, ynb, blk_cb<DIR>(sgn, W0 + i), lane);
         floatx16 acc = zero16();
 #pragma unroll
         for (int q = 0; q < NST; ++q) {
-            const int which = q / NQ, quarter = q % NQ, buf = q % NBUF;
+            const int which = W0 + q / NQ, quarter = q % NQ, buf = q % NBUF;
             const int rb = blk_rb<DIR>(which);
 #pragma unroll
             for (int c = 0; c < CPS; ++c) acc = mfma4(acc, xa[rb][quarter * CPS + c], ybuf[buf][c]);
@@ -314,32 +322,32 @@ template <int KCH, int DIR> struct MfmaProducer {
             __builtin_amdgcn_sched_barrier(0);
             const int q2 = q + NBUF;
             if (q2 < NST)
-                load_stage(p, yb, buf, blk_cb<DIR>(sg, q2 / NQ), q2 % NQ, lane);
+                load_stage(p, yb, buf, blk_cb<DIR>(sg, W0 + q2 / NQ), q2 % NQ, lane);
             else
-                load_stage(p, yb, buf, blk_cb<DIR>(sgn, (q2 - NST) / NQ), (q2 - NST) % NQ, lane);
+                load_stage(p, yb, buf, blk_cb<DIR>(sgn, W0 + (q2 - NST) / NQ), (q2 - NST) % NQ, lane);
             if (quarter == NQ - 1) {
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(ax[rb], which == 0 ? by0 : by1, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(ax[rb], by[which - W0], acc, 0, 0, 0);
                 store_block_acc(ring, acc, rb, blk_cb<DIR>(sg, which), row0, p.N, p.M, lane);
                 acc = zero16();
             }
         }
-        by0 = nby0;
-        by1 = nby1;
+#pragma unroll
+        for (int i = 0; i < NW; ++i) by[i] = nby[i];
     }
 };
 
 // ---------------------------------------------------------------------------------------------
 // Workgroup bookkeeping shared by both kernels.
 // ---------------------------------------------------------------------------------------------
-struct WgShared {
-    float ring[kSlots][kRingFloats];
-    double edge_in[kSlots][kBlk];  // boundary values of the current macro-step, one per step
+template <int SLOTS> struct WgShared {
+    float ring[SLOTS][kRingFloats];
+    double edge_in[SLOTS][kBlk];  // boundary values of the current macro-step, one per step
     int simd_count[4];
 };
 
 // Pairs the two wavefronts that share a SIMD as consumer (0) and producer (1) of one band slot.
 // If the 8 wavefronts are not spread 2 per SIMD, falls back to wavefront w -> role w/4, slot w%4.
-__device__ __forceinline__ void elect_role(WgShared &sh, int lane, int w, int &producer, int &slot)
+__device__ __forceinline__ void elect_role(WgShared<4> &sh, int lane, int w, int &producer, int &slot)
 {
     if (threadIdx.x < 4) sh.simd_count[threadIdx.x] = 0;
     __syncthreads();
@@ -362,21 +370,30 @@ __device__ __forceinline__ void elect_role(WgShared &sh, int lane, int w, int &p
 // store per step; the band's last row goes to the boundary buffer.
 //   KCH > 0: fused, D <= 8*KCH (register operands);  KCH == 0: fused, any D;  KCH < 0: unfused.
 // ---------------------------------------------------------------------------------------------
-template <int KCH>
-__global__ __launch_bounds__(kWgThreads) void forward_dp_kernel(Params p, float *__restrict__ value)
+template <int KCH, int SLOTS, int NPROD>
+__global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Params p, float *__restrict__ value)
 {
-    __shared__ WgShared sh;
+    static_assert((SLOTS == 4 && NPROD == 1) || SLOTS == 1, "supported workgroup shapes");
+    static_assert(NPROD == 1 || (NPROD == 2 && KCH > 0), "two producers only split MFMA work");
+    constexpr int kThreads = wg_threads(SLOTS, NPROD);
+    __shared__ WgShared<SLOTS> sh;
     __shared__ unsigned ticket_s;
     const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
     if (threadIdx.x == 0) ticket_s = atomicAdd(&p.hdr->fwd_ticket, 1u);
-    for (int e = threadIdx.x; e < kSlots * kRingFloats; e += kWgThreads) (&sh.ring[0][0])[e] = kBigCost;
-    int producer, slot;
-    elect_role(sh, lane, w, producer, slot);  // contains two barriers: ticket_s and the rings are visible
+    for (int e = threadIdx.x; e < SLOTS * kRingFloats; e += kThreads) (&sh.ring[0][0])[e] = kBigCost;
+    int producer, slot;  // producer: 0 = consumer, 1.. = producer number
+    if constexpr (SLOTS == 4) {
+        elect_role(sh, lane, w, producer, slot);  // contains two barriers
+    } else {
+        producer = w;
+        slot = 0;
+        __syncthreads();
+    }
     const unsigned ticket = __builtin_amdgcn_readfirstlane(ticket_s);
-    const int ngroups = (p.B + kSlots - 1) / kSlots;
+    const int ngroups = (p.B + SLOTS - 1) / SLOTS;
     const int k = ticket / (unsigned)ngroups;
-    const int b = (ticket - k * ngroups) * kSlots + slot;
+    const int b = (ticket - k * ngroups) * SLOTS + slot;
     const bool live = (k < p.nbands) && (b < p.B);
 
     const int M = p.M, N = p.N;
@@ -388,8 +405,29 @@ __global__ __launch_bounds__(kWgThreads) void forward_dp_kernel(Params p, float 
 
     if (producer) {
         // ------------------------------------------------------------------ producer wavefront
-        if constexpr (KCH > 0) {
-            MfmaProducer<KCH, +1> mp;
+        if constexpr (KCH > 0 && NPROD == 2) {
+            // producer 1 makes (lower rows, sg), producer 2 makes (upper rows, sg+1)
+            auto body = [&](auto &mp, bool first_block) {
+                if (live) {
+                    mp.init(p, xb, xnb, row0, lane);
+                    if (first_block) mp.block_now(p, yb, ynb, ring, 0, 0, row0, lane);
+                    mp.prime(p, yb, ynb, 0, lane);
+                }
+                __syncthreads();
+                for (int sg = 0; sg < p.nmacro; ++sg) {
+                    if (live) mp.run(p, yb, ynb, ring, sg, row0, lane);
+                    __syncthreads();
+                }
+            };
+            if (producer == 1) {
+                MfmaProducer<KCH, +1, 0, 1> mp;
+                body(mp, false);
+            } else {
+                MfmaProducer<KCH, +1, 1, 1> mp;
+                body(mp, true);
+            }
+        } else if constexpr (KCH > 0) {
+            MfmaProducer<KCH, +1, 0, 2> mp;
             if (live) {
                 mp.init(p, xb, xnb, row0, lane);
                 mp.block_now(p, yb, ynb, ring, 0, 0, row0, lane);  // (upper rows, column block 0)
@@ -552,22 +590,31 @@ __device__ __forceinline__ void flush_E_block(const Params &p, const float *ring
     if (lane == 0) nzb[(size_t)(row0 / kBlk + rb) * p.ncb + cb] = blk_any ? 1 : 0;
 }
 
-template <int KCH>
-__global__ __launch_bounds__(kWgThreads) void backward_dp_kernel(Params p)
+template <int KCH, int SLOTS, int NPROD>
+__global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(Params p)
 {
-    __shared__ WgShared sh;
+    static_assert((SLOTS == 4 && NPROD == 1) || SLOTS == 1, "supported workgroup shapes");
+    static_assert(NPROD == 1 || (NPROD == 2 && KCH > 0), "two producers only split MFMA work");
+    constexpr int kThreads = wg_threads(SLOTS, NPROD);
+    __shared__ WgShared<SLOTS> sh;
     __shared__ unsigned ticket_s;
     const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (p.hdr->abort_backward) return;
 
     if (threadIdx.x == 0) ticket_s = atomicAdd(&p.hdr->bwd_ticket, 1u);
-    for (int e = threadIdx.x; e < kSlots * kRingFloats; e += kWgThreads) (&sh.ring[0][0])[e] = kBigCost;
-    int producer, slot;
-    elect_role(sh, lane, w, producer, slot);
+    for (int e = threadIdx.x; e < SLOTS * kRingFloats; e += kThreads) (&sh.ring[0][0])[e] = kBigCost;
+    int producer, slot;  // producer: 0 = consumer, 1.. = producer number
+    if constexpr (SLOTS == 4) {
+        elect_role(sh, lane, w, producer, slot);
+    } else {
+        producer = w;
+        slot = 0;
+        __syncthreads();
+    }
     const unsigned ticket = __builtin_amdgcn_readfirstlane(ticket_s);
-    const int ngroups = (p.B + kSlots - 1) / kSlots;
+    const int ngroups = (p.B + SLOTS - 1) / SLOTS;
     const int kk = ticket / (unsigned)ngroups;
-    const int b = (ticket - kk * ngroups) * kSlots + slot;
+    const int b = (ticket - kk * ngroups) * SLOTS + slot;
     const int k = p.nbands - 1 - kk;
     const bool live = (kk < p.nbands) && (b < p.B);
 
@@ -581,8 +628,34 @@ __global__ __launch_bounds__(kWgThreads) void backward_dp_kernel(Params p)
 
     if (producer) {
         // blocks the first macro-step reads: (upper rows, sg0-1), (lower rows, sg0-1), (lower rows, sg0-2)
-        if constexpr (KCH > 0) {
-            MfmaProducer<KCH, -1> mp;
+        if constexpr (KCH > 0 && NPROD == 2) {
+            // producer 1 makes (upper rows, sg-2), producer 2 makes (lower rows, sg-3)
+            auto body = [&](auto &mp, bool upper) {
+                if (live) {
+                    mp.init(p, xb, xnb, row0, lane);
+                    if (upper) {
+                        mp.block_now(p, yb, ynb, ring, 0, sg0 - 1, row0, lane);
+                    } else {
+                        mp.block_now(p, yb, ynb, ring, 1, sg0 - 1, row0, lane);
+                        mp.block_now(p, yb, ynb, ring, 1, sg0 - 2, row0, lane);
+                    }
+                    mp.prime(p, yb, ynb, sg0, lane);
+                }
+                __syncthreads();
+                for (int sg = sg0; sg >= 0; --sg) {
+                    if (live) mp.run(p, yb, ynb, ring, sg, row0, lane);
+                    __syncthreads();
+                }
+            };
+            if (producer == 1) {
+                MfmaProducer<KCH, -1, 0, 1> mp;
+                body(mp, true);
+            } else {
+                MfmaProducer<KCH, -1, 1, 1> mp;
+                body(mp, false);
+            }
+        } else if constexpr (KCH > 0) {
+            MfmaProducer<KCH, -1, 0, 2> mp;
             if (live) {
                 mp.init(p, xb, xnb, row0, lane);
                 mp.block_now(p, yb, ynb, ring, 0, sg0 - 1, row0, lane);

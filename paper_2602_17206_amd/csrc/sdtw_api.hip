@@ -106,6 +106,48 @@ int fused_variant(int D)
     return 0;
 }
 
+// Launches the forward (FWD) or backward DP kernel in the workgroup shape that suits the problem:
+// up to 1024 band tasks cannot fill the chip, so each band gets a small workgroup of its own
+// (consumer and producers on different SIMDs); larger problems use 4-band workgroups in which the
+// producer and the consumer of a band share a SIMD.
+template <bool FWD, int KCH, int SLOTS, int NPROD>
+void launch_dp_shape(const sdtw_desc *d, const Layout &L, const Params &p, float *value, hipStream_t st)
+{
+    const unsigned tasks = (unsigned)((d->B + SLOTS - 1) / SLOTS) * (unsigned)L.nbands;
+    if constexpr (FWD)
+        forward_dp_kernel<KCH, SLOTS, NPROD><<<tasks, wg_threads(SLOTS, NPROD), 0, st>>>(p, value);
+    else
+        backward_dp_kernel<KCH, SLOTS, NPROD><<<tasks, wg_threads(SLOTS, NPROD), 0, st>>>(p);
+}
+
+template <bool FWD, int KCH>
+void launch_dp_kch(const sdtw_desc *d, const Layout &L, const Params &p, float *value, hipStream_t st)
+{
+    const bool small = (int64_t)d->B * L.nbands <= 1024;
+    if (small) {
+        if constexpr (KCH > 0)
+            launch_dp_shape<FWD, KCH, 1, 2>(d, L, p, value, st);
+        else
+            launch_dp_shape<FWD, KCH, 1, 1>(d, L, p, value, st);
+    } else {
+        launch_dp_shape<FWD, KCH, 4, 1>(d, L, p, value, st);
+    }
+}
+
+template <bool FWD>
+void launch_dp(const sdtw_desc *d, const Layout &L, const Params &p, float *value, hipStream_t st)
+{
+    if (d->mode == SDTW_UNFUSED) return launch_dp_kch<FWD, -1>(d, L, p, value, st);
+    switch (p.vec_d4 ? fused_variant(d->D) : 0) {
+        case 1: return launch_dp_kch<FWD, 1>(d, L, p, value, st);
+        case 2: return launch_dp_kch<FWD, 2>(d, L, p, value, st);
+        case 4: return launch_dp_kch<FWD, 4>(d, L, p, value, st);
+        case 8: return launch_dp_kch<FWD, 8>(d, L, p, value, st);
+        case 16: return launch_dp_kch<FWD, 16>(d, L, p, value, st);
+        default: return launch_dp_kch<FWD, 0>(d, L, p, value, st);
+    }
+}
+
 int check_ws(const void *ws, size_t bytes, size_t need)
 {
     if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) != 0 || bytes < need) return SDTW_ERR_WORKSPACE;
@@ -132,21 +174,14 @@ int forward_impl(const sdtw_desc *d, const float *x, const float *y, float *valu
     row_sqnorm_kernel<<<(unsigned)std::min<int64_t>((L.xn_count + 3) / 4, 65535), 256, 0, st>>>(x, p.xn, L.xn_count, d->D);
     row_sqnorm_kernel<<<(unsigned)std::min<int64_t>((L.yn_count + 3) / 4, 65535), 256, 0, st>>>(y, p.yn, L.yn_count, d->D);
     }
-    const unsigned tasks = (unsigned)((d->B + kSlots - 1) / kSlots) * (unsigned)L.nbands;
     if (d->mode == SDTW_UNFUSED) {
         dim3 g((d->M + 63) / 64, (d->N + 63) / 64, d->B);
-        { ProfScope ps("cost_tensor", st); cost_tensor_kernel<<<g, 256, 0, st>>>(p); }
-        { ProfScope ps("forward_dp_unfused", st); forward_dp_kernel<-1><<<tasks, kWgThreads, 0, st>>>(p, value); }
-    } else {
-        ProfScope ps("forward_dp_fused", st);
-        switch (p.vec_d4 ? fused_variant(d->D) : 0) {
-            case 1: forward_dp_kernel<1><<<tasks, kWgThreads, 0, st>>>(p, value); break;
-            case 2: forward_dp_kernel<2><<<tasks, kWgThreads, 0, st>>>(p, value); break;
-            case 4: forward_dp_kernel<4><<<tasks, kWgThreads, 0, st>>>(p, value); break;
-            case 8: forward_dp_kernel<8><<<tasks, kWgThreads, 0, st>>>(p, value); break;
-            case 16: forward_dp_kernel<16><<<tasks, kWgThreads, 0, st>>>(p, value); break;
-            default: forward_dp_kernel<0><<<tasks, kWgThreads, 0, st>>>(p, value); break;
-        }
+        ProfScope ps("cost_tensor", st);
+        cost_tensor_kernel<<<g, 256, 0, st>>>(p);
+    }
+    {
+        ProfScope ps(d->mode == SDTW_UNFUSED ? "forward_dp_unfused" : "forward_dp_fused", st);
+        launch_dp<true>(d, L, p, value, st);
     }
     return hip_ok();
 }
@@ -158,20 +193,9 @@ int backward_impl(const sdtw_desc *d, const float *x, const float *y, const floa
     const Params p = make_params(d, L, x, y, ws);
     { ProfScope ps("backward_begin", st); backward_begin_kernel<<<1, 64, 0, st>>>(p); }
     { ProfScope ps("fill_boundary", st); fill_boundary(p, st); }
-    const unsigned tasks = (unsigned)((d->B + kSlots - 1) / kSlots) * (unsigned)L.nbands;
-    if (d->mode == SDTW_UNFUSED) {
-        ProfScope ps("backward_dp_unfused", st);
-        backward_dp_kernel<-1><<<tasks, kWgThreads, 0, st>>>(p);
-    } else {
-        ProfScope ps("backward_dp_fused", st);
-        switch (p.vec_d4 ? fused_variant(d->D) : 0) {
-            case 1: backward_dp_kernel<1><<<tasks, kWgThreads, 0, st>>>(p); break;
-            case 2: backward_dp_kernel<2><<<tasks, kWgThreads, 0, st>>>(p); break;
-            case 4: backward_dp_kernel<4><<<tasks, kWgThreads, 0, st>>>(p); break;
-            case 8: backward_dp_kernel<8><<<tasks, kWgThreads, 0, st>>>(p); break;
-            case 16: backward_dp_kernel<16><<<tasks, kWgThreads, 0, st>>>(p); break;
-            default: backward_dp_kernel<0><<<tasks, kWgThreads, 0, st>>>(p); break;
-        }
+    {
+        ProfScope ps(d->mode == SDTW_UNFUSED ? "backward_dp_unfused" : "backward_dp_fused", st);
+        launch_dp<false>(d, L, p, nullptr, st);
     }
     if (dx || dy) {
         const int P = std::max(dx ? d->N : 0, dy ? d->M : 0);
