@@ -151,6 +151,13 @@ int sdtw_debug_lane_shift(int32_t *out, void *stream);
 int sdtw_debug_set_spin_limit(uint32_t polls);
 
 /*
+ * Test hook: the DP kernels run either one band per workgroup (problems of up to 1024 band tasks)
+ * or four bands per workgroup (larger ones).  1 or 4 forces that shape for later calls whatever the
+ * size, 0 restores the choice by size.  Results do not depend on the shape.  Process-wide; host only.
+ */
+int sdtw_debug_force_workgroup_shape(int bands_per_workgroup);
+
+/*
  * Benchmark hook: per-kernel timing.  sdtw_debug_profile(1) makes every later call bracket each
  * of its kernel launches with two HIP events on the caller's stream (this creates events, so it
  * is not for latency-critical callers); sdtw_debug_profile(0) switches it off and drops what was

@@ -53,7 +53,7 @@ EXPORTED_SYMBOLS = (
     "sdtw_version", "sdtw_status_string", "sdtw_workspace_bytes", "sdtw_forward", "sdtw_backward",
     "sdtw_barycenter_workspace_bytes", "sdtw_barycenter_step", "sdtw_workspace_status",
     "sdtw_debug_export", "sdtw_debug_lane_shift", "sdtw_debug_set_spin_limit",
-    "sdtw_debug_profile", "sdtw_debug_profile_read",
+    "sdtw_debug_profile", "sdtw_debug_profile_read", "sdtw_debug_force_workgroup_shape",
 )
 
 
@@ -93,6 +93,8 @@ def load_library():
     lib.sdtw_debug_lane_shift.argtypes = [vp, vp]
     lib.sdtw_debug_set_spin_limit.restype = i32
     lib.sdtw_debug_set_spin_limit.argtypes = [ctypes.c_uint32]
+    lib.sdtw_debug_force_workgroup_shape.restype = i32
+    lib.sdtw_debug_force_workgroup_shape.argtypes = [i32]
     lib.sdtw_debug_profile.restype = i32
     lib.sdtw_debug_profile.argtypes = [i32]
     lib.sdtw_debug_profile_read.restype = i32
@@ -318,3 +320,9 @@ def debug_profile_read(max_entries=4096):
         raise SdtwError(rc, "sdtw_debug_profile_read")
     labels = names.value.decode().split(";")[:count.value]
     return [(labels[i], float(ms[i])) for i in range(count.value)]
+
+
+def debug_force_workgroup_shape(bands_per_workgroup):
+    rc = load_library().sdtw_debug_force_workgroup_shape(int(bands_per_workgroup))
+    if rc != 0:
+        raise SdtwError(rc, "sdtw_debug_force_workgroup_shape")

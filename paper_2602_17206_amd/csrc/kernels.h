@@ -27,8 +27,17 @@ __global__ void fill_f32_kernel(float *dst, size_t n, float v)
     for (; i < n; i += stride) dst[i] = v;
 }
 
-// Stamps the header at the start of a forward call.
-__global__ void forward_begin_kernel(Params p)
+__device__ __forceinline__ void fill_boundary_rows(const Params &p)
+{
+    const size_t n = (size_t)p.B * p.nbands * p.M;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p.brow[i] = kSentinel;
+}
+
+// Start of a forward call, one launch: stamps the header, resets the band tickets, marks every
+// boundary value "not written yet", and computes the squared row norms ||x_i||^2, ||y_j||^2
+// (Sec. 4.3: the norms are computed once; one wavefront per row, lanes stride over the features).
+__global__ __launch_bounds__(256) void forward_prep_kernel(Params p, int64_t xrows, int64_t yrows)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
         Header *h = p.hdr;
@@ -41,10 +50,26 @@ __global__ void forward_begin_kernel(Params p)
         h->fwd_ticket = 0;
         h->bwd_ticket = 0;
     }
+    fill_boundary_rows(p);
+    const int lane = threadIdx.x & 63;
+    const int64_t rows = xrows + yrows;
+    const int64_t stride = (int64_t)gridDim.x * 4;
+    for (int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); row < rows; row += stride) {
+        const bool isx = row < xrows;
+        const float *r = isx ? p.x + row * p.D : p.y + (row - xrows) * p.D;
+        float acc = 0.f;
+        for (int k = lane; k < p.D; k += 64) acc = fmaf(r[k], r[k], acc);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+        if (lane == 0) {
+            if (isx) p.xn[row] = acc; else p.yn[row - xrows] = acc;
+        }
+    }
 }
 
-// Checks at the start of a backward call that the workspace holds the forward of this descriptor.
-__global__ void backward_begin_kernel(Params p)
+// Start of a backward call, one launch: checks that the workspace holds the forward of this
+// descriptor, resets the ticket and marks every boundary value "not written yet".
+__global__ __launch_bounds__(256) void backward_prep_kernel(Params p)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
         Header *h = p.hdr;
@@ -61,24 +86,7 @@ __global__ void backward_begin_kernel(Params p)
             h->status = kStatusState;
         }
     }
-}
-
-// ||row||^2 for `rows` rows of length D (Sec. 4.3: the squared norms are computed once).
-// One wavefront per row, lanes stride over the features.
-__global__ __launch_bounds__(256) void row_sqnorm_kernel(const float *__restrict__ v, float *__restrict__ out,
-                                                        int64_t rows, int D)
-{
-    const int lane = threadIdx.x & 63;
-    int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int64_t stride = (int64_t)gridDim.x * 4;
-    for (; row < rows; row += stride) {
-        const float *r = v + row * D;
-        float acc = 0.f;
-        for (int k = lane; k < D; k += 64) acc = fmaf(r[k], r[k], acc);
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
-        if (lane == 0) out[row] = acc;
-    }
+    fill_boundary_rows(p);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -18,6 +18,7 @@ namespace {
 using namespace sdtw;
 
 uint32_t g_spin_limit = 1u << 23;  // ~10 s of polling before a band gives up
+int g_force_slots = 0;             // test hook: 0 = choose by problem size, 1 or 4 = force that workgroup shape
 
 // Optional per-kernel timing (test/benchmark hook): when switched on, every kernel launch of the
 // library is bracketed by two HIP events on the caller's stream.
@@ -123,7 +124,7 @@ void launch_dp_shape(const sdtw_desc *d, const Layout &L, const Params &p, float
 template <bool FWD, int KCH>
 void launch_dp_kch(const sdtw_desc *d, const Layout &L, const Params &p, float *value, hipStream_t st)
 {
-    const bool small = (int64_t)d->B * L.nbands <= 1024;
+    const bool small = g_force_slots ? (g_force_slots == 1) : ((int64_t)d->B * L.nbands <= 1024);
     if (small) {
         if constexpr (KCH > 0)
             launch_dp_shape<FWD, KCH, 1, 2>(d, L, p, value, st);
@@ -158,21 +159,23 @@ inline int hip_ok() { return hipGetLastError() == hipSuccess ? SDTW_OK : SDTW_ER
 
 unsigned fill_grid(size_t n) { size_t g = (n + 255) / 256; return (unsigned)(g < 1 ? 1 : (g > 4096 ? 4096 : g)); }
 
-void fill_boundary(const Params &p, hipStream_t st)
+// Blocks for a prep kernel: enough for the boundary fill (one element per thread) and for the row
+// norms (four rows per block), capped.
+unsigned prep_grid(const Params &p, int64_t norm_rows)
 {
-    const size_t n = (size_t)p.B * p.nbands * p.M;
-    fill_u64_kernel<<<fill_grid(n), 256, 0, st>>>(p.brow, n, kSentinel);
+    const size_t fill = ((size_t)p.B * p.nbands * p.M + 255) / 256;
+    const size_t rows = (size_t)(norm_rows + 3) / 4;
+    const size_t g = fill > rows ? fill : rows;
+    return (unsigned)(g < 1 ? 1 : (g > 8192 ? 8192 : g));
 }
 
 int forward_impl(const sdtw_desc *d, const float *x, const float *y, float *value, void *ws, hipStream_t st)
 {
     const Layout L = layout_of(d);
     const Params p = make_params(d, L, x, y, ws);
-    { ProfScope ps("forward_begin", st); forward_begin_kernel<<<1, 64, 0, st>>>(p); }
-    { ProfScope ps("fill_boundary", st); fill_boundary(p, st); }
-    { ProfScope ps("row_sqnorm", st);
-    row_sqnorm_kernel<<<(unsigned)std::min<int64_t>((L.xn_count + 3) / 4, 65535), 256, 0, st>>>(x, p.xn, L.xn_count, d->D);
-    row_sqnorm_kernel<<<(unsigned)std::min<int64_t>((L.yn_count + 3) / 4, 65535), 256, 0, st>>>(y, p.yn, L.yn_count, d->D);
+    {
+        ProfScope ps("forward_prep", st);
+        forward_prep_kernel<<<prep_grid(p, L.xn_count + L.yn_count), 256, 0, st>>>(p, L.xn_count, L.yn_count);
     }
     if (d->mode == SDTW_UNFUSED) {
         dim3 g((d->M + 63) / 64, (d->N + 63) / 64, d->B);
@@ -191,8 +194,10 @@ int backward_impl(const sdtw_desc *d, const float *x, const float *y, const floa
 {
     const Layout L = layout_of(d);
     const Params p = make_params(d, L, x, y, ws);
-    { ProfScope ps("backward_begin", st); backward_begin_kernel<<<1, 64, 0, st>>>(p); }
-    { ProfScope ps("fill_boundary", st); fill_boundary(p, st); }
+    {
+        ProfScope ps("backward_prep", st);
+        backward_prep_kernel<<<prep_grid(p, 0), 256, 0, st>>>(p);
+    }
     {
         ProfScope ps(d->mode == SDTW_UNFUSED ? "backward_dp_unfused" : "backward_dp_fused", st);
         launch_dp<false>(d, L, p, nullptr, st);
@@ -380,6 +385,13 @@ int sdtw_debug_lane_shift(int32_t *out, void *stream)
 int sdtw_debug_set_spin_limit(uint32_t polls)
 {
     g_spin_limit = polls;
+    return SDTW_OK;
+}
+
+int sdtw_debug_force_workgroup_shape(int bands_per_workgroup)
+{
+    if (bands_per_workgroup != 0 && bands_per_workgroup != 1 && bands_per_workgroup != 4) return SDTW_ERR_INVALID_ARG;
+    g_force_slots = bands_per_workgroup;
     return SDTW_OK;
 }
 

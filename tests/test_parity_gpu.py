@@ -137,6 +137,24 @@ def test_value_E_and_gradients(mode, B, N, M, D, gamma):
     np.testing.assert_allclose(E[:, 0, 0], 1.0, atol=1e-4)
 
 
+@pytest.mark.parametrize("shape", [1, 4])
+@pytest.mark.parametrize("mode", ["unfused", "fused"])
+@pytest.mark.parametrize("B,N,M,D,gamma", [(5, 200, 150, 16, 0.1), (2, 130, 257, 128, 0.05), (7, 65, 96, 20, 1.0),
+                                           (3, 100, 90, 200, 0.5)])
+def test_both_workgroup_shapes(shape, mode, B, N, M, D, gamma):
+    # the 4-bands-per-workgroup kernels are normally chosen only for > 1024 band tasks; force them
+    # on small inputs (B not a multiple of 4, D above the register-operand limit of 128 included)
+    say("shape %d %s B=%d N=%d M=%d D=%d gamma=%g" % (shape, mode, B, N, M, D, gamma))
+    x, y = workloads.normal_pairs(900 + N + D, B, N, M, D)
+    ref = oracle.batch(x, y, gamma, want_E=True)
+    binding.debug_force_workgroup_shape(shape)
+    try:
+        got = run_gpu(x, y, gamma, MODES[mode])
+    finally:
+        binding.debug_force_workgroup_shape(0)
+    check_against(ref, got, what="shape %d %s" % (shape, mode))
+
+
 def test_config1_tiny_oracle_case():
     wl = workloads.pair_workload("c1_tiny")
     say("config 1")
