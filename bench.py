@@ -47,6 +47,8 @@ def parse_args():
     ap.add_argument("--modes", default="", help="comma list of unfused,fused (default: the workload's modes)")
     ap.add_argument("--all", action="store_true", help="also report the other configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain device copy of known size (reference for the rocprofv3 HBM counters)")
     return ap.parse_args()
 
 
@@ -234,6 +236,16 @@ def main():
     from paper_2602_17206_amd import workloads
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if args.calibrate_copy:
+        n = 256 * 1024 * 1024  # bytes per buffer
+        src = torch.empty(n // 4, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": True, "bytes_read_per_copy": n, "bytes_written_per_copy": n, "copies": 10}))
+        return
     pkg.load_library()
     wl = workloads.pair_workload(args.workload)
     mode_ids = {"unfused": pkg.UNFUSED, "fused": pkg.FUSED}
