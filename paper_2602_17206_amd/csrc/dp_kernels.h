@@ -39,7 +39,7 @@ constexpr int kRingCols = 128;     // four phases of 32 steps
 constexpr int kRingStride = 129;   // floats per band row in LDS (odd: lanes hit distinct banks)
 constexpr int kRingFloats = kBandRows * kRingStride;
 // Workgroup shapes: SLOTS bands per workgroup, each with one consumer and NPROD producer wavefronts.
-//   SLOTS=4, NPROD=1 (512 threads): large problems; producer and consumer of a band share a SIMD.
+//   SLOTS=4, NPROD=1|2 (512|768 threads): large problems; the wavefronts of a band share a SIMD.
 //   SLOTS=1, NPROD=1|2 (128|192 threads): small problems that cannot fill the chip anyway; the
 //   wavefronts of a band land on different SIMDs, so producing the cost never delays the DP chain.
 constexpr int wg_threads(int slots, int nprod) { return slots * (1 + nprod) * 64; }
@@ -118,30 +118,10 @@ __device__ __forceinline__ void publish_boundary(unsigned long long *row, int j,
 // ---------------------------------------------------------------------------------------------
 // Producer side: cost blocks into the ring.
 // ---------------------------------------------------------------------------------------------
-// MFMA operand chunk: lane (r = lane&31, h = lane>>5) keeps the 4 features 8c+4h .. 8c+4h+3 of its
-// row for chunk c (a group of 8 features).  Features >= D are zero.
-// Requires D % 4 == 0 and 16-byte aligned rows (the host picks the any-D kernel otherwise).
-__device__ __forceinline__ float4 load_chunk(const float *__restrict__ rowptr, int D, int c, int h4)
-{
-    const int k = 8 * c + h4;
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (k < D) v = *reinterpret_cast<const float4 *>(rowptr + k);
-    return v;
-}
-
 __device__ __forceinline__ floatx16 zero16()
 {
     floatx16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     return z;
-}
-
-__device__ __forceinline__ floatx16 mfma4(floatx16 acc, const float4 &a, const float4 &b)
-{
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
-    return acc;
 }
 
 // Writes a 32x32 cost block given in MFMA accumulator layout (acc[i]: row 8*(i/4)+4*(lane>>5)+(i&3),
@@ -229,110 +209,150 @@ template <int DIR> __device__ __forceinline__ int blk_cb(int sg, int which)
     return DIR > 0 ? sg + which : sg - 2 - which;
 }
 
-// Register-operand MFMA producer for D <= 8*KCH (KCH = 1, 2, 4, 8, 16).
-// -2*x of the band's two 32-row blocks stays in registers for the whole sweep; y streams through
-// NBUF stage buffers of CPS chunks each, every buffer being reloaded right after its use with the
-// data of the stage NBUF stages later, so loads are in flight for thousands of cycles.
+// Matrix-core producer for D <= 16*KG (KG = 1, 2, 4, 8 groups of 16 features).
+//
+// The inner products run on the fp16 matrix cores (v_mfma_f32_32x32x16_f16, float32 accumulate),
+// which - unlike the fp32 MFMA, which shares the vector ALUs - execute beside the consumer's VALU
+// work.  Float32 accuracy is kept by the split-half copies the prep kernel made: each scaled
+// element is h1 + h2 (two float16), and <x_i,y_j> = (h1.k1 + h1.k2 + h2.k1) / (s_i s_j) up to
+// ~2^-22 relative (Sec. 4.3 Eq. 8 supplies the norms; they are added in float32 afterwards).
+// Lane (r = lane&31, h = lane>>5) holds features 16g+8h .. 16g+8h+7 of its row for group g; the
+// copies are stored [row][group][piece][16] so that one row pointer plus immediates reaches all.
+// The band's x pieces stay in registers for the whole sweep; y streams through NBUF stage
+// buffers, each reloaded right after use with the data of the stage NBUF stages later.
 // A producer makes the blocks W0 .. W0+NW-1 of the two blocks of each macro-step (NW = 2: both).
-template <int KCH, int DIR, int W0, int NW> struct MfmaProducer {
-    static constexpr int CPS = KCH >= 8 ? 2 : 1;         // chunks (8 MFMAs' worth of y) per stage
-    static constexpr int NQ = KCH / CPS;                 // stages per block
-    static constexpr int NST = NW * NQ;                  // stages per macro-step
-    static constexpr int NBUF = KCH >= 8 ? 4 : NST;      // stage buffers
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+
+template <int KG, int DIR, int W0, int NW> struct HalfProducer {
+    static constexpr int NST = NW * KG;                   // stages (one feature group of one block) per macro-step
+    static constexpr int NBUF = NST < 8 ? NST : 8;        // stage buffers
     static_assert(NST % NBUF == 0, "stage buffers must divide the stages of a macro-step");
     static constexpr bool owns_rb(int rb) { return NW == 2 || rb == (DIR > 0 ? 1 - W0 : W0); }
 
-    float4 xa[2][KCH];
-    float ax[2];  // lanes 0-31: ||x_r||^2, lanes 32-63: 1
-    float4 ybuf[NBUF][CPS];
-    float by[2];  // lanes 0-31: 1, lanes 32-63: ||y_c||^2, for the blocks of the macro-step
+    half8 xa[2][2][KG];     // [row block][piece][group]
+    half8 ybuf[NBUF][2];    // [stage][piece]
+    float yn_c[2], yis_c[2];  // ||y_c||^2 and 1/scale of this lane's column, for the blocks of the macro-step
 
-    __device__ __forceinline__ const float *yrow(const Params &p, const float *yb, int cb, int lane) const
+    __device__ __forceinline__ int ycol(const Params &p, int cb, int lane) const
     {
-        int col = 32 * cb + (lane & 31);
-        col = max(0, min(col, p.M - 1));
-        return yb + (size_t)col * p.D;
+        const int col = 32 * cb + (lane & 31);
+        return max(0, min(col, p.M - 1));
     }
-    __device__ __forceinline__ float ynorm(const Params &p, const float *ynb, int cb, int lane) const
+    __device__ __forceinline__ void load_stage(const Params &p, const uint16_t *yh, int buf, int cb, int g, int lane)
     {
-        int col = 32 * cb + (lane & 31);
-        col = max(0, min(col, p.M - 1));
-        const float v = ynb[col];
-        return (lane >> 5) ? v : 1.0f;
+        const uint16_t *r = yh + (size_t)ycol(p, cb, lane) * (2 * p.Dp) + 8 * (lane >> 5) + 32 * g;
+        ybuf[buf][0] = *reinterpret_cast<const half8 *>(r);
+        ybuf[buf][1] = *reinterpret_cast<const half8 *>(r + 16);
     }
-    __device__ __forceinline__ void load_stage(const Params &p, const float *yb, int buf, int cb, int quarter,
-                                               int lane)
-    {
-        const float *r = yrow(p, yb, cb, lane);
-#pragma unroll
-        for (int c = 0; c < CPS; ++c)
-            ybuf[buf][c] = load_chunk(r, p.D, quarter * CPS + c, (lane >> 5) * 4);
-    }
-    __device__ __forceinline__ void init(const Params &p, const float *xb, const float *xnb, int row0, int lane)
+    // x pieces of the band, and the per-row table (||x_r||^2, -2/scale_r) in LDS
+    __device__ __forceinline__ void init(const Params &p, const uint16_t *xh, const float *xnb, const float *xisb,
+                                         float2 *rowtab, int row0, int lane)
     {
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
             if (!owns_rb(rb)) continue;
             const int row = min(row0 + 32 * rb + (lane & 31), p.N - 1);
+            const uint16_t *r = xh + (size_t)row * (2 * p.Dp) + 8 * (lane >> 5);
 #pragma unroll
-            for (int c = 0; c < KCH; ++c) {
-                const float4 v = load_chunk(xb + (size_t)row * p.D, p.D, c, (lane >> 5) * 4);
-                xa[rb][c] = make_float4(-2.0f * v.x, -2.0f * v.y, -2.0f * v.z, -2.0f * v.w);
+            for (int g = 0; g < KG; ++g) {
+                xa[rb][0][g] = *reinterpret_cast<const half8 *>(r + 32 * g);
+                xa[rb][1][g] = *reinterpret_cast<const half8 *>(r + 32 * g + 16);
             }
-            const float xn = xnb[row];
-            ax[rb] = (lane >> 5) ? 1.0f : xn;
+            if (lane < 32) rowtab[32 * rb + lane] = make_float2(xnb[row], -2.0f * xisb[row]);
         }
     }
-    // one whole block, loads included (start-up only)
-    __device__ __forceinline__ void block_now(const Params &p, const float *yb, const float *ynb, float *ring, int rb,
-                                              int cb, int row0, int lane)
+    __device__ __forceinline__ floatx16 mfma3(floatx16 acc, int rb, int g, const half8 &k1, const half8 &k2) const
     {
-        const float *r = yrow(p, yb, cb, lane);
-        floatx16 acc = zero16();
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[rb][0][g], k1, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[rb][0][g], k2, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[rb][1][g], k1, acc, 0, 0, 0);
+        return acc;
+    }
+    // acc (scaled inner products) -> cost block in the ring:  d = ||x||^2 + ||y||^2 - 2 <x,y>, clamped at 0
+    __device__ __forceinline__ void finish(const Params &p, float *ring, const float2 *rowtab, floatx16 acc,
+                                           int rb, int cb, float ync, float yisc, int row0, int lane) const
+    {
+        const int h = lane >> 5;
 #pragma unroll
-        for (int c = 0; c < KCH; ++c)
-            acc = mfma4(acc, xa[rb][c], load_chunk(r, p.D, c, (lane >> 5) * 4));
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(ax[rb], ynorm(p, ynb, cb, lane), acc, 0, 0, 0);
+        for (int i = 0; i < 16; ++i) {
+            const float2 t = rowtab[32 * rb + 8 * (i >> 2) + 4 * h + (i & 3)];
+            acc[i] = fmaf(acc[i], t.y * yisc, t.x + ync);
+        }
         store_block_acc(ring, acc, rb, cb, row0, p.N, p.M, lane);
     }
-    // stage buffers and norms for the first macro-step `sg`
-    __device__ __forceinline__ void prime(const Params &p, const float *yb, const float *ynb, int sg, int lane)
+    // one whole block, loads included (start-up only)
+    __device__ __forceinline__ void block_now(const Params &p, const uint16_t *yh, const float *ynb,
+                                              const float *yisb, float *ring, const float2 *rowtab, int rb, int cb,
+                                              int row0, int lane)
     {
+        const int col = ycol(p, cb, lane);
+        // goes through the stage buffers (NBUF >= KG) so that start-up needs no registers of its own
 #pragma unroll
-        for (int q = 0; q < NBUF; ++q) load_stage(p, yb, q, blk_cb<DIR>(sg, W0 + q / NQ), q % NQ, lane);
-#pragma unroll
-        for (int i = 0; i < NW; ++i) by[i] = ynorm(p, ynb, blk_cb<DIR>(sg, W0 + i), lane);
-    }
-    // the two blocks of macro-step sg
-    __device__ __forceinline__ void run(const Params &p, const float *yb, const float *ynb, float *ring, int sg,
-                                        int row0, int lane)
-    {
-        const int sgn = sg + DIR;  // next macro-step
-        float nby[2];
-#pragma unroll
-        for (int i = 0; i < NW; ++i) nby[i] = ynorm(p, ynb, blk_cb<DIR>(sgn, W0 + i), lane);
+        for (int g = 0; g < KG; ++g) load_stage(p, yh, g, cb, g, lane);
+        __builtin_amdgcn_sched_barrier(0);
         floatx16 acc = zero16();
 #pragma unroll
-        for (int q = 0; q < NST; ++q) {
-            const int which = W0 + q / NQ, quarter = q % NQ, buf = q % NBUF;
-            const int rb = blk_rb<DIR>(which);
+        for (int g = 0; g < KG; ++g) acc = mfma3(acc, rb, g, ybuf[g][0], ybuf[g][1]);
+        finish(p, ring, rowtab, acc, rb, cb, ynb[col], yisb[col], row0, lane);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // stage buffers and column norms for the first macro-step `sg`
+    __device__ __forceinline__ void prime(const Params &p, const uint16_t *yh, const float *ynb, const float *yisb,
+                                          int sg, int lane)
+    {
 #pragma unroll
-            for (int c = 0; c < CPS; ++c) acc = mfma4(acc, xa[rb][quarter * CPS + c], ybuf[buf][c]);
-            // reload this buffer with the stage NBUF stages later (not earlier: registers are scarce)
-            __builtin_amdgcn_sched_barrier(0);
+        for (int q = 0; q < NBUF; ++q) load_stage(p, yh, q, blk_cb<DIR>(sg, W0 + q / KG), q % KG, lane);
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+            const int col = ycol(p, blk_cb<DIR>(sg, W0 + i), lane);
+            yn_c[i] = ynb[col];
+            yis_c[i] = yisb[col];
+        }
+    }
+    // the blocks of macro-step sg
+    __device__ __forceinline__ void run(const Params &p, const uint16_t *yh, const float *ynb, const float *yisb,
+                                        float *ring, const float2 *rowtab, int sg, int row0, int lane)
+    {
+        const int sgn = sg + DIR;  // next macro-step
+        float nyn[2], nyis[2];
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+            const int col = ycol(p, blk_cb<DIR>(sgn, W0 + i), lane);
+            nyn[i] = ynb[col];
+            nyis[i] = yisb[col];
+        }
+        auto reload = [&](int q) {  // refill the buffer of stage q with the stage NBUF stages later
             const int q2 = q + NBUF;
             if (q2 < NST)
-                load_stage(p, yb, buf, blk_cb<DIR>(sg, W0 + q2 / NQ), q2 % NQ, lane);
+                load_stage(p, yh, q % NBUF, blk_cb<DIR>(sg, W0 + q2 / KG), q2 % KG, lane);
             else
-                load_stage(p, yb, buf, blk_cb<DIR>(sgn, W0 + (q2 - NST) / NQ), (q2 - NST) % NQ, lane);
-            if (quarter == NQ - 1) {
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(ax[rb], by[which - W0], acc, 0, 0, 0);
-                store_block_acc(ring, acc, rb, blk_cb<DIR>(sg, which), row0, p.N, p.M, lane);
-                acc = zero16();
+                load_stage(p, yh, q % NBUF, blk_cb<DIR>(sgn, W0 + (q2 - NST) / KG), (q2 - NST) % KG, lane);
+        };
+        // Reloads of the first half of a block's stages are issued right after their use; those of
+        // the second half wait until the block has been written out, so that the epilogue's
+        // temporaries and all in-flight stage buffers are never live together.
+        constexpr int kEarly = KG > 1 ? KG / 2 : 1;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const int which = W0 + w, rb = blk_rb<DIR>(which);
+            floatx16 acc = zero16();
+#pragma unroll
+            for (int g = 0; g < KG; ++g) {
+                const int q = w * KG + g;
+                acc = mfma3(acc, rb, g, ybuf[q % NBUF][0], ybuf[q % NBUF][1]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (g < kEarly) reload(q);
             }
+            finish(p, ring, rowtab, acc, rb, blk_cb<DIR>(sg, which), yn_c[w], yis_c[w], row0, lane);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int g = kEarly; g < KG; ++g) reload(w * KG + g);
         }
 #pragma unroll
-        for (int i = 0; i < NW; ++i) by[i] = nby[i];
+        for (int i = 0; i < NW; ++i) {
+            yn_c[i] = nyn[i];
+            yis_c[i] = nyis[i];
+        }
     }
 };
 
@@ -342,12 +362,14 @@ template <int KCH, int DIR, int W0, int NW> struct MfmaProducer {
 template <int SLOTS> struct WgShared {
     float ring[SLOTS][kRingFloats];
     double edge_in[SLOTS][kBlk];  // boundary values of the current macro-step, one per step
+    float2 rowtab[SLOTS][kBandRows];  // per band row: (||x_r||^2, -2/scale_r) for the cost epilogue
     int simd_count[4];
 };
 
-// Pairs the two wavefronts that share a SIMD as consumer (0) and producer (1) of one band slot.
-// If the 8 wavefronts are not spread 2 per SIMD, falls back to wavefront w -> role w/4, slot w%4.
-__device__ __forceinline__ void elect_role(WgShared<4> &sh, int lane, int w, int &producer, int &slot)
+// Groups the wavefronts that share a SIMD as consumer (0) and producers (1, 2) of one band slot.
+// If the wavefronts are not spread evenly over the SIMDs, falls back to wavefront w -> role w/4,
+// slot w%4.
+__device__ __forceinline__ void elect_role(WgShared<4> &sh, int lane, int w, int per_simd, int &producer, int &slot)
 {
     if (threadIdx.x < 4) sh.simd_count[threadIdx.x] = 0;
     __syncthreads();
@@ -357,7 +379,8 @@ __device__ __forceinline__ void elect_role(WgShared<4> &sh, int lane, int w, int
     if (lane == 0) idx = atomicAdd(&sh.simd_count[simd], 1);
     idx = __builtin_amdgcn_readfirstlane(idx);
     __syncthreads();
-    const bool even = sh.simd_count[0] == 2 && sh.simd_count[1] == 2 && sh.simd_count[2] == 2 && sh.simd_count[3] == 2;
+    const bool even = sh.simd_count[0] == per_simd && sh.simd_count[1] == per_simd && sh.simd_count[2] == per_simd &&
+                      sh.simd_count[3] == per_simd;
     producer = __builtin_amdgcn_readfirstlane(even ? idx : (w >> 2));
     slot = __builtin_amdgcn_readfirstlane(even ? simd : (w & 3));
 }
@@ -368,12 +391,13 @@ __device__ __forceinline__ void elect_role(WgShared<4> &sh, int lane, int w, int
 // ticket, which is running or done, so the wait ends whatever order the hardware starts
 // workgroups in.  The table goes to HBM step-major, R[b][band][s][lane]: one coalesced 512-byte
 // store per step; the band's last row goes to the boundary buffer.
-//   KCH > 0: fused, D <= 8*KCH (register operands);  KCH == 0: fused, any D;  KCH < 0: unfused.
+//   KCH > 0: fused, D <= 16*KCH (fp16 matrix cores, split-half operands);  KCH == 0: fused, any D
+//   (float32 from x and y);  KCH < 0: unfused.
 // ---------------------------------------------------------------------------------------------
 template <int KCH, int SLOTS, int NPROD>
 __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Params p, float *__restrict__ value)
 {
-    static_assert((SLOTS == 4 && NPROD == 1) || SLOTS == 1, "supported workgroup shapes");
+    static_assert(SLOTS == 4 || SLOTS == 1, "supported workgroup shapes");
     static_assert(NPROD == 1 || (NPROD == 2 && KCH > 0), "two producers only split MFMA work");
     constexpr int kThreads = wg_threads(SLOTS, NPROD);
     __shared__ WgShared<SLOTS> sh;
@@ -384,7 +408,7 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Pa
     for (int e = threadIdx.x; e < SLOTS * kRingFloats; e += kThreads) (&sh.ring[0][0])[e] = kBigCost;
     int producer, slot;  // producer: 0 = consumer, 1.. = producer number
     if constexpr (SLOTS == 4) {
-        elect_role(sh, lane, w, producer, slot);  // contains two barriers
+        elect_role(sh, lane, w, 1 + NPROD, producer, slot);  // contains two barriers
     } else {
         producer = w;
         slot = 0;
@@ -400,8 +424,11 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Pa
     const int row0 = k * kBandRows;
     float *ring = sh.ring[slot];
     const int bb = live ? b : 0;
-    const float *xb = p.x + bb * p.x_stride, *yb = p.y + bb * p.y_stride;
+    [[maybe_unused]] const float *xb = p.x + bb * p.x_stride, *yb = p.y + bb * p.y_stride;
     const float *xnb = p.xn + bb * p.xn_stride, *ynb = p.yn + bb * p.yn_stride;
+    const float *xisb = p.xis + bb * p.xn_stride, *yisb = p.yis + bb * p.yn_stride;
+    const uint16_t *xh = p.xh + bb * p.xh_stride, *yh = p.yh + bb * p.yh_stride;
+    float2 *rowtab = sh.rowtab[slot];
 
     if (producer) {
         // ------------------------------------------------------------------ producer wavefront
@@ -409,33 +436,33 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Pa
             // producer 1 makes (lower rows, sg), producer 2 makes (upper rows, sg+1)
             auto body = [&](auto &mp, bool first_block) {
                 if (live) {
-                    mp.init(p, xb, xnb, row0, lane);
-                    if (first_block) mp.block_now(p, yb, ynb, ring, 0, 0, row0, lane);
-                    mp.prime(p, yb, ynb, 0, lane);
+                    mp.init(p, xh, xnb, xisb, rowtab, row0, lane);
+                    if (first_block) mp.block_now(p, yh, ynb, yisb, ring, rowtab, 0, 0, row0, lane);
+                    mp.prime(p, yh, ynb, yisb, 0, lane);
                 }
                 __syncthreads();
                 for (int sg = 0; sg < p.nmacro; ++sg) {
-                    if (live) mp.run(p, yb, ynb, ring, sg, row0, lane);
+                    if (live) mp.run(p, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
                     __syncthreads();
                 }
             };
             if (producer == 1) {
-                MfmaProducer<KCH, +1, 0, 1> mp;
+                HalfProducer<KCH, +1, 0, 1> mp;
                 body(mp, false);
             } else {
-                MfmaProducer<KCH, +1, 1, 1> mp;
+                HalfProducer<KCH, +1, 1, 1> mp;
                 body(mp, true);
             }
         } else if constexpr (KCH > 0) {
-            MfmaProducer<KCH, +1, 0, 2> mp;
+            HalfProducer<KCH, +1, 0, 2> mp;
             if (live) {
-                mp.init(p, xb, xnb, row0, lane);
-                mp.block_now(p, yb, ynb, ring, 0, 0, row0, lane);  // (upper rows, column block 0)
-                mp.prime(p, yb, ynb, 0, lane);
+                mp.init(p, xh, xnb, xisb, rowtab, row0, lane);
+                mp.block_now(p, yh, ynb, yisb, ring, rowtab, 0, 0, row0, lane);  // (upper rows, column block 0)
+                mp.prime(p, yh, ynb, yisb, 0, lane);
             }
             __syncthreads();
             for (int sg = 0; sg < p.nmacro; ++sg) {
-                if (live) mp.run(p, yb, ynb, ring, sg, row0, lane);
+                if (live) mp.run(p, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
                 __syncthreads();
             }
         } else if constexpr (KCH == 0) {
@@ -516,7 +543,7 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Pa
                 // every addition that builds the table is float64: a float32 rounding here would
                 // differ between the two sweeps and add up along the alignment path
                 const double cur = fma(-(double)L, g2d, m + (double)dc);
-                Rs[u * kBandRows + lane] = cur;
+                __builtin_nontemporal_store(cur, &Rs[u * kBandRows + lane]);  // streamed once: keep it out of the caches
                 edge = lane_shl1(edge, cur);  // lane 63 keeps its own value, the others move down
                 diag = up;
                 left = cur;
@@ -593,7 +620,7 @@ __device__ __forceinline__ void flush_E_block(const Params &p, const float *ring
 template <int KCH, int SLOTS, int NPROD>
 __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(Params p)
 {
-    static_assert((SLOTS == 4 && NPROD == 1) || SLOTS == 1, "supported workgroup shapes");
+    static_assert(SLOTS == 4 || SLOTS == 1, "supported workgroup shapes");
     static_assert(NPROD == 1 || (NPROD == 2 && KCH > 0), "two producers only split MFMA work");
     constexpr int kThreads = wg_threads(SLOTS, NPROD);
     __shared__ WgShared<SLOTS> sh;
@@ -605,7 +632,7 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
     for (int e = threadIdx.x; e < SLOTS * kRingFloats; e += kThreads) (&sh.ring[0][0])[e] = kBigCost;
     int producer, slot;  // producer: 0 = consumer, 1.. = producer number
     if constexpr (SLOTS == 4) {
-        elect_role(sh, lane, w, producer, slot);
+        elect_role(sh, lane, w, 1 + NPROD, producer, slot);
     } else {
         producer = w;
         slot = 0;
@@ -622,8 +649,11 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
     const int row0 = (live ? k : 0) * kBandRows;
     float *ring = sh.ring[slot];
     const int bb = live ? b : 0;
-    const float *xb = p.x + bb * p.x_stride, *yb = p.y + bb * p.y_stride;
+    [[maybe_unused]] const float *xb = p.x + bb * p.x_stride, *yb = p.y + bb * p.y_stride;
     const float *xnb = p.xn + bb * p.xn_stride, *ynb = p.yn + bb * p.yn_stride;
+    const float *xisb = p.xis + bb * p.xn_stride, *yisb = p.yis + bb * p.yn_stride;
+    const uint16_t *xh = p.xh + bb * p.xh_stride, *yh = p.yh + bb * p.yh_stride;
+    float2 *rowtab = sh.rowtab[slot];
     const int sg0 = p.nmacro - 1;
 
     if (producer) {
@@ -632,40 +662,40 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
             // producer 1 makes (upper rows, sg-2), producer 2 makes (lower rows, sg-3)
             auto body = [&](auto &mp, bool upper) {
                 if (live) {
-                    mp.init(p, xb, xnb, row0, lane);
+                    mp.init(p, xh, xnb, xisb, rowtab, row0, lane);
                     if (upper) {
-                        mp.block_now(p, yb, ynb, ring, 0, sg0 - 1, row0, lane);
+                        mp.block_now(p, yh, ynb, yisb, ring, rowtab, 0, sg0 - 1, row0, lane);
                     } else {
-                        mp.block_now(p, yb, ynb, ring, 1, sg0 - 1, row0, lane);
-                        mp.block_now(p, yb, ynb, ring, 1, sg0 - 2, row0, lane);
+                        mp.block_now(p, yh, ynb, yisb, ring, rowtab, 1, sg0 - 1, row0, lane);
+                        mp.block_now(p, yh, ynb, yisb, ring, rowtab, 1, sg0 - 2, row0, lane);
                     }
-                    mp.prime(p, yb, ynb, sg0, lane);
+                    mp.prime(p, yh, ynb, yisb, sg0, lane);
                 }
                 __syncthreads();
                 for (int sg = sg0; sg >= 0; --sg) {
-                    if (live) mp.run(p, yb, ynb, ring, sg, row0, lane);
+                    if (live) mp.run(p, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
                     __syncthreads();
                 }
             };
             if (producer == 1) {
-                MfmaProducer<KCH, -1, 0, 1> mp;
+                HalfProducer<KCH, -1, 0, 1> mp;
                 body(mp, true);
             } else {
-                MfmaProducer<KCH, -1, 1, 1> mp;
+                HalfProducer<KCH, -1, 1, 1> mp;
                 body(mp, false);
             }
         } else if constexpr (KCH > 0) {
-            MfmaProducer<KCH, -1, 0, 2> mp;
+            HalfProducer<KCH, -1, 0, 2> mp;
             if (live) {
-                mp.init(p, xb, xnb, row0, lane);
-                mp.block_now(p, yb, ynb, ring, 0, sg0 - 1, row0, lane);
-                mp.block_now(p, yb, ynb, ring, 1, sg0 - 1, row0, lane);
-                mp.block_now(p, yb, ynb, ring, 1, sg0 - 2, row0, lane);
-                mp.prime(p, yb, ynb, sg0, lane);
+                mp.init(p, xh, xnb, xisb, rowtab, row0, lane);
+                mp.block_now(p, yh, ynb, yisb, ring, rowtab, 0, sg0 - 1, row0, lane);
+                mp.block_now(p, yh, ynb, yisb, ring, rowtab, 1, sg0 - 1, row0, lane);
+                mp.block_now(p, yh, ynb, yisb, ring, rowtab, 1, sg0 - 2, row0, lane);
+                mp.prime(p, yh, ynb, yisb, sg0, lane);
             }
             __syncthreads();
             for (int sg = sg0; sg >= 0; --sg) {
-                if (live) mp.run(p, yb, ynb, ring, sg, row0, lane);
+                if (live) mp.run(p, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
                 __syncthreads();
             }
         } else if constexpr (KCH == 0) {
@@ -768,7 +798,7 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
                 // gamma*Ebar = R[N,M] - R[i,j] - (m - gamma ln2 L)
                 const float gE = fmaf(g2, L, (float)(Rq[u] - m));
                 rd[u] = __builtin_amdgcn_exp2f(gE * c2);
-                Rq[u] = Rfin - Rn[u * kBandRows + lane];
+                Rq[u] = Rfin - __builtin_nontemporal_load(&Rn[u * kBandRows + lane]);
                 edge = lane_shr1(edge, cur);  // lane 0 keeps its own value, the others move up
                 diag = down;
                 right = cur;

@@ -56,13 +56,39 @@ __global__ __launch_bounds__(256) void forward_prep_kernel(Params p, int64_t xro
     const int64_t stride = (int64_t)gridDim.x * 4;
     for (int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); row < rows; row += stride) {
         const bool isx = row < xrows;
-        const float *r = isx ? p.x + row * p.D : p.y + (row - xrows) * p.D;
-        float acc = 0.f;
-        for (int k = lane; k < p.D; k += 64) acc = fmaf(r[k], r[k], acc);
+        const int64_t lr = isx ? row : row - xrows;
+        const float *r = (isx ? p.x : p.y) + lr * p.D;
+        float acc = 0.f, mx = 0.f;
+        for (int k = lane; k < p.D; k += 64) {
+            acc = fmaf(r[k], r[k], acc);
+            mx = fmaxf(mx, fabsf(r[k]));
+        }
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
-        if (lane == 0) {
-            if (isx) p.xn[row] = acc; else p.yn[row - xrows] = acc;
+        for (int o = 32; o > 0; o >>= 1) {
+            acc += __shfl_xor(acc, o);
+            mx = fmaxf(mx, __shfl_xor(mx, o));
+        }
+        if (lane == 0) (isx ? p.xn : p.yn)[lr] = acc;
+        if (p.Dp > 0) {
+            // Split-half copy for the fp16 matrix cores: with a power-of-two scale s that brings the
+            // row's largest magnitude into [2^13, 2^14), v*s = h1 + h2 + e with h1, h2 float16 and
+            // |e| <= 2^-22 |v*s| (two 11-bit significands).  The products h1*k1 + h1*k2 + h2*k1 then
+            // reproduce <x_i, y_j> to about float32 accuracy (the dropped h2*k2 term is ~2^-22 relative).
+            int ex = 0;
+            if (mx > 0.f) (void)frexpf(mx, &ex);
+            ex = max(-100, min(ex, 120));
+            const float sc = ldexpf(1.0f, 14 - ex);
+            if (lane == 0) (isx ? p.xis : p.yis)[lr] = ldexpf(1.0f, ex - 14);
+            // stored [row][group of 16 features][piece][16]
+            uint16_t *h = (isx ? p.xh : p.yh) + lr * (2 * p.Dp);
+            for (int k = lane; k < p.Dp; k += 64) {
+                const float vs = (k < p.D) ? r[k] * sc : 0.f;
+                const _Float16 h1 = (_Float16)vs;
+                const _Float16 h2 = (_Float16)(vs - (float)h1);
+                const int o = 32 * (k >> 4) + (k & 15);
+                h[o] = __builtin_bit_cast(uint16_t, h1);
+                h[o + 16] = __builtin_bit_cast(uint16_t, h2);
+            }
         }
     }
 }

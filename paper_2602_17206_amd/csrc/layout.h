@@ -36,8 +36,14 @@ struct Layout {
     int32_t nmacro;   // macro-steps per band sweep: ceil((M+63)/32)
     int32_t nrb, ncb; // 32x32 block rows / columns: ceil(N/32), ceil(M/32)
     int64_t xn_count, yn_count;  // number of norm entries (1 sequence when the batch stride is 0)
-    size_t off_hdr, off_rfinal, off_xn, off_yn, off_brow, off_R, off_cost, off_E, off_nz, total;
+    int32_t Dp;                  // D rounded up to 16: row length of the split-half operand copies (0: none)
+    size_t off_hdr, off_rfinal, off_xn, off_yn, off_xis, off_yis, off_xh, off_yh, off_brow, off_R, off_cost, off_E,
+        off_nz, total;
 };
+
+// Fused mode with D <= 128 keeps a copy of x and y split into two float16 pieces per element
+// (see split_rows_kernel); larger D computes the cost in float32 straight from x and y.
+constexpr int kMaxSplitD = 128;
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -60,6 +66,11 @@ inline Layout make_layout(int32_t B, int32_t N, int32_t M, int32_t D, int32_t mo
     L.off_rfinal = o;   o = align_up(o + (size_t)B * sizeof(double), 256);
     L.off_xn = o;       o = align_up(o + (size_t)L.xn_count * sizeof(float), 256);
     L.off_yn = o;       o = align_up(o + (size_t)L.yn_count * sizeof(float), 256);
+    L.Dp = (mode == 1 && D <= kMaxSplitD) ? (D + 15) / 16 * 16 : 0;
+    L.off_xis = o;      o = align_up(o + (size_t)(L.Dp ? L.xn_count : 0) * sizeof(float), 256);
+    L.off_yis = o;      o = align_up(o + (size_t)(L.Dp ? L.yn_count : 0) * sizeof(float), 256);
+    L.off_xh = o;       o = align_up(o + (size_t)L.xn_count * L.Dp * 2 * sizeof(uint16_t), 256);
+    L.off_yh = o;       o = align_up(o + (size_t)L.yn_count * L.Dp * 2 * sizeof(uint16_t), 256);
     // boundary rows: one row of M float64 per (pair, band)
     L.off_brow = o;     o = align_up(o + (size_t)B * L.nbands * (size_t)M * sizeof(double), 256);
     // DP table in step-major order: [B][nbands][steps][64] float64
@@ -92,6 +103,10 @@ struct Params {
     Header *hdr;
     double *rfinal;
     float *xn, *yn;
+    int32_t Dp;                    // row length (halves) of the split operand copies, 0 if absent
+    float *xis, *yis;              // per row: 1/scale used for the split copy (a power of two)
+    uint16_t *xh, *yh;             // [rows][Dp/16][2 pieces][16] float16 bit patterns
+    int64_t xh_stride, yh_stride;  // batch strides of the split copies (0 when shared)
     unsigned long long *brow;
     double *R;
     float *cost;

@@ -87,6 +87,13 @@ Params make_params(const sdtw_desc *d, const Layout &L, const float *x, const fl
     p.rfinal = reinterpret_cast<double *>(base + L.off_rfinal);
     p.xn = reinterpret_cast<float *>(base + L.off_xn);
     p.yn = reinterpret_cast<float *>(base + L.off_yn);
+    p.Dp = L.Dp;
+    p.xis = reinterpret_cast<float *>(base + L.off_xis);
+    p.yis = reinterpret_cast<float *>(base + L.off_yis);
+    p.xh = reinterpret_cast<uint16_t *>(base + L.off_xh);
+    p.yh = reinterpret_cast<uint16_t *>(base + L.off_yh);
+    p.xh_stride = d->x_batch_stride == 0 ? 0 : (int64_t)d->N * L.Dp * 2;
+    p.yh_stride = d->y_batch_stride == 0 ? 0 : (int64_t)d->M * L.Dp * 2;
     p.brow = reinterpret_cast<unsigned long long *>(base + L.off_brow);
     p.R = reinterpret_cast<double *>(base + L.off_R);
     p.cost = reinterpret_cast<float *>(base + L.off_cost);
@@ -95,15 +102,14 @@ Params make_params(const sdtw_desc *d, const Layout &L, const float *x, const fl
     return p;
 }
 
-// Fused DP kernel variant: number of 8-feature chunks of the MFMA operands kept in registers
-// (D <= 8, 16, 32, 64, 128), or 0 for the generic kernel that reads x and y per block.
+// Fused DP kernel variant: number of 16-feature groups of the split-half operands (D <= 16, 32,
+// 64, 128), or 0 for the any-D kernel that computes the cost in float32 straight from x and y.
 int fused_variant(int D)
 {
-    if (D <= 8) return 1;
-    if (D <= 16) return 2;
-    if (D <= 32) return 4;
-    if (D <= 64) return 8;
-    if (D <= 128) return 16;
+    if (D <= 16) return 1;
+    if (D <= 32) return 2;
+    if (D <= 64) return 4;
+    if (D <= 128) return 8;
     return 0;
 }
 
@@ -131,7 +137,10 @@ void launch_dp_kch(const sdtw_desc *d, const Layout &L, const Params &p, float *
         else
             launch_dp_shape<FWD, KCH, 1, 1>(d, L, p, value, st);
     } else {
-        launch_dp_shape<FWD, KCH, 4, 1>(d, L, p, value, st);
+        if constexpr (KCH > 0)
+            launch_dp_shape<FWD, KCH, 4, 2>(d, L, p, value, st);
+        else
+            launch_dp_shape<FWD, KCH, 4, 1>(d, L, p, value, st);
     }
 }
 
@@ -139,12 +148,11 @@ template <bool FWD>
 void launch_dp(const sdtw_desc *d, const Layout &L, const Params &p, float *value, hipStream_t st)
 {
     if (d->mode == SDTW_UNFUSED) return launch_dp_kch<FWD, -1>(d, L, p, value, st);
-    switch (p.vec_d4 ? fused_variant(d->D) : 0) {
+    switch (fused_variant(d->D)) {
         case 1: return launch_dp_kch<FWD, 1>(d, L, p, value, st);
         case 2: return launch_dp_kch<FWD, 2>(d, L, p, value, st);
         case 4: return launch_dp_kch<FWD, 4>(d, L, p, value, st);
         case 8: return launch_dp_kch<FWD, 8>(d, L, p, value, st);
-        case 16: return launch_dp_kch<FWD, 16>(d, L, p, value, st);
         default: return launch_dp_kch<FWD, 0>(d, L, p, value, st);
     }
 }
