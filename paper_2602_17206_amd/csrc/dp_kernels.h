@@ -30,6 +30,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "device_core.h"
 #include "layout.h"
 
@@ -43,6 +45,10 @@ constexpr int kRingFloats = kBandRows * kRingStride;
 //   SLOTS=1, NPROD=1|2 (128|192 threads): small problems that cannot fill the chip anyway; the
 //   wavefronts of a band land on different SIMDs, so producing the cost never delays the DP chain.
 constexpr int wg_threads(int slots, int nprod) { return slots * (1 + nprod) * 64; }
+// Large fused problems are bound by HBM traffic, of which the float64 table R is the largest part
+// (8 bytes per cell written, 8 read).  There the forward keeps only the lane state at the start of
+// every macro-step (1/16 of R) and the backward recomputes each macro-step of R before it uses it.
+constexpr bool dp_recompute(int kch, int slots) { return kch >= 0 && slots == 4; }
 constexpr double kBig = 1e300;     // stands for +inf in the DP tables
 constexpr float kBigCost = 3.0e38f;  // cost of a cell outside the grid
 constexpr int kStatusTimeoutDp = 6;  // SDTW_ERR_TIMEOUT
@@ -362,6 +368,7 @@ template <int KG, int DIR, int W0, int NW> struct HalfProducer {
 template <int SLOTS> struct WgShared {
     float ring[SLOTS][kRingFloats];
     double edge_in[SLOTS][kBlk];  // boundary values of the current macro-step, one per step
+    double ftop[SLOTS][kBlk];     // backward with recomputation: the forward's row above the band
     float2 rowtab[SLOTS][kBandRows];  // per band row: (||x_r||^2, -2/scale_r) for the cost epilogue
     int simd_count[4];
 };
@@ -508,7 +515,14 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Pa
     const int kc = live ? k : 0;
     const unsigned long long *brow_in = p.brow + ((size_t)bb * p.nbands + (kc > 0 ? kc - 1 : 0)) * M;
     unsigned long long *brow_out = p.brow + ((size_t)bb * p.nbands + kc) * M;
-    double *Rk = p.R + ((size_t)bb * p.nbands + kc) * (size_t)p.nmacro * kBlk * kBandRows;
+    // RECOMP: the table is not stored; only the lane state at the start of every macro-step is
+    // (checkpoints), and the backward kernel recomputes each macro-step of R from it.
+    constexpr bool RECOMP = dp_recompute(KCH, SLOTS);
+    double *Rk = RECOMP ? nullptr : p.R + ((size_t)bb * p.nbands + kc) * (size_t)p.nmacro * kBlk * kBandRows;
+    double *Ck = RECOMP ? p.ckpt + ((size_t)bb * p.nbands + kc) * (size_t)p.nmacro * 2 * kBandRows : nullptr;
+    const int s_fin = (live && row0 + lane == N - 1) ? (M - 1 + lane) : -1;  // step of cell (N-1, M-1)
+    const bool last_band = live && (k + 1 == p.nbands);
+    double fin = 0.0;
     const bool has_above = live && k > 0;
     const bool emit_bottom = live && (k + 1 < p.nbands);
     const float *my_ring = ring + lane * kRingStride;
@@ -532,22 +546,34 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Pa
             const bool need_n = has_above && lane < kBlk && jn < M;
             if (has_above) nxt_bits = peek_boundary(brow_in, jn, need_n);
             const float *rd = my_ring + (sg & 3) * kBlk;
-            double *Rs = Rk + (size_t)sg * kBlk * kBandRows;
-#pragma unroll
-            for (int u = 0; u < kBlk; ++u) {
-                const double up = lane_shr1(left, top[u]);  // R[i-1][j]; lane 0 takes the row above the band
-                const float dc = rd[u];
-                double m;
-                float L;
-                softmin3_parts(diag, up, left, c2, m, L);
-                // every addition that builds the table is float64: a float32 rounding here would
-                // differ between the two sweeps and add up along the alignment path
-                const double cur = fma(-(double)L, g2d, m + (double)dc);
-                __builtin_nontemporal_store(cur, &Rs[u * kBandRows + lane]);  // streamed once: keep it out of the caches
-                edge = lane_shl1(edge, cur);  // lane 63 keeps its own value, the others move down
-                diag = up;
-                left = cur;
+            double *Rs = RECOMP ? nullptr : Rk + (size_t)sg * kBlk * kBandRows;
+            if constexpr (RECOMP) {
+                __builtin_nontemporal_store(left, &Ck[((size_t)sg * 2 + 0) * kBandRows + lane]);
+                __builtin_nontemporal_store(diag, &Ck[((size_t)sg * 2 + 1) * kBandRows + lane]);
             }
+            auto steps = [&](auto capture) {
+#pragma unroll
+                for (int u = 0; u < kBlk; ++u) {
+                    const double up = lane_shr1(left, top[u]);  // R[i-1][j]; lane 0 takes the row above the band
+                    const float dc = rd[u];
+                    double m;
+                    float L;
+                    softmin3_parts(diag, up, left, c2, m, L);
+                    // every addition that builds the table is float64: a float32 rounding here would
+                    // differ between the two sweeps and add up along the alignment path
+                    const double cur = fma(-(double)L, g2d, m + (double)dc);
+                    if constexpr (!RECOMP)  // streamed once: keep it out of the caches
+                        __builtin_nontemporal_store(cur, &Rs[u * kBandRows + lane]);
+                    if constexpr (decltype(capture)::value) fin = (sg * kBlk + u == s_fin) ? cur : fin;
+                    edge = lane_shl1(edge, cur);  // lane 63 keeps its own value, the others move down
+                    diag = up;
+                    left = cur;
+                }
+            };
+            if (RECOMP && last_band)
+                steps(std::true_type{});
+            else
+                steps(std::false_type{});
             // last row of the band: lanes 32..63 hold columns 32*sg - 63 + (lane - 32)
             if (emit_bottom && lane >= kBlk) {
                 const int j = sg * kBlk + lane - kBlk - (kBandRows - 1);
@@ -562,7 +588,7 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Pa
 
     // R[N,M] of the pair: cell (N-1, M-1) was stored at step M-1+lane by the lane that owns row N-1
     if (live && row0 + lane == N - 1) {
-        const double r = Rk[(size_t)(M - 1 + lane) * kBandRows + lane];
+        const double r = RECOMP ? fin : Rk[(size_t)(M - 1 + lane) * kBandRows + lane];
         p.rfinal[b] = r;
         value[b] = (float)r;
     }
@@ -753,16 +779,32 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
     const double Rfin = live ? p.rfinal[b] : 0.0;
     const int kc = live ? k : 0;
     const bool has_below = live && (k + 1 < p.nbands);
-    const unsigned long long *brow_in = p.brow + ((size_t)bb * p.nbands + (has_below ? kc + 1 : kc)) * M;
-    unsigned long long *brow_out = p.brow + ((size_t)bb * p.nbands + kc) * M;
-    const double *Rk = p.R + ((size_t)bb * p.nbands + kc) * (size_t)p.nmacro * kBlk * kBandRows;
+    constexpr bool RECOMP = dp_recompute(KCH, SLOTS);
+    const unsigned long long *brow_in = p.brow_b + ((size_t)bb * p.nbands + (has_below ? kc + 1 : kc)) * M;
+    unsigned long long *brow_out = p.brow_b + ((size_t)bb * p.nbands + kc) * M;
+    const double *Rk = RECOMP ? nullptr : p.R + ((size_t)bb * p.nbands + kc) * (size_t)p.nmacro * kBlk * kBandRows;
+    const double *Ck = RECOMP ? p.ckpt + ((size_t)bb * p.nbands + kc) * (size_t)p.nmacro * 2 * kBandRows : nullptr;
+    // the forward's row above this band (final values, written by the forward call)
+    const double *ftop_g = reinterpret_cast<const double *>(p.brow) + ((size_t)bb * p.nbands + (kc > 0 ? kc - 1 : 0)) * M;
+    double *ftop = sh.ftop[slot];
     float *my_ring = ring + lane * kRingStride;
     double *bot = sh.edge_in[slot];
 
     // R of the first macro-step; afterwards each value is reloaded one macro-step ahead, right after use
     double Rq[kBlk];
+    double ck_left = kBig, ck_diag = kBig;  // RECOMP: forward lane state at the start of the coming macro-step
+    double ftop_next = kBig;                // RECOMP: forward's row above the band for the coming macro-step
+    if constexpr (RECOMP) {
+        if (live) {
+            ck_left = Ck[((size_t)sg0 * 2 + 0) * kBandRows + lane];
+            ck_diag = Ck[((size_t)sg0 * 2 + 1) * kBandRows + lane];
+            const int jf = sg0 * kBlk + lane;
+            if (k > 0 && lane < kBlk && jf < M) ftop_next = ftop_g[jf];
+        }
+    } else {
 #pragma unroll
-    for (int u = 0; u < kBlk; ++u) Rq[u] = live ? Rfin - Rk[((size_t)sg0 * kBlk + u) * kBandRows + lane] : 0.0;
+        for (int u = 0; u < kBlk; ++u) Rq[u] = live ? Rfin - Rk[((size_t)sg0 * kBlk + u) * kBandRows + lane] : 0.0;
+    }
 
     // row below the band for the first macro-step: lane l >= 32 brings column 32*sg - 63 + (l - 32),
     // which lane 63 meets at step u = l - 32
@@ -784,8 +826,33 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
             const bool need_n = has_below && lane >= kBlk && jn >= 0 && jn < M;
             if (has_below) nxt_bits = peek_boundary(brow_in, jn, need_n);
             float *rd = my_ring + (sg & 3) * kBlk;
-            const double *Rn = Rk + (size_t)(sg > 0 ? sg - 1 : 0) * kBlk * kBandRows;
+            const double *Rn = RECOMP ? nullptr : Rk + (size_t)(sg > 0 ? sg - 1 : 0) * kBlk * kBandRows;
             const int sbase = sg * kBlk;
+            if constexpr (RECOMP) {
+                // recompute R of this macro-step from the forward's checkpoint (same arithmetic, same
+                // cost values, hence the same bits the forward had)
+                double fl = ck_left, fd = ck_diag;
+                if (lane < kBlk) ftop[lane] = ftop_next;
+                if (sg > 0) {  // everything the next macro-step's recomputation needs, one macro-step ahead
+                    ck_left = __builtin_nontemporal_load(&Ck[((size_t)(sg - 1) * 2 + 0) * kBandRows + lane]);
+                    ck_diag = __builtin_nontemporal_load(&Ck[((size_t)(sg - 1) * 2 + 1) * kBandRows + lane]);
+                    const int jf = sbase - kBlk + lane;
+                    ftop_next = kBig;
+                    if (k > 0 && lane < kBlk && jf < M) ftop_next = __builtin_nontemporal_load(&ftop_g[jf]);
+                }
+#pragma unroll
+                for (int u = 0; u < kBlk; ++u) {
+                    const double up = lane_shr1(fl, ftop[u]);
+                    const float dcf = rd[u];
+                    double mf;
+                    float Lf;
+                    softmin3_parts(fd, up, fl, c2, mf, Lf);
+                    const double cur = fma(-(double)Lf, g2d, mf + (double)dcf);
+                    Rq[u] = Rfin - cur;
+                    fd = up;
+                    fl = cur;
+                }
+            }
 #pragma unroll
             for (int u = kBlk - 1; u >= 0; --u) {
                 const double down = lane_shl1(right, bot[u]);  // T[i+1][j]; lane 63 takes the row below the band
@@ -798,7 +865,7 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
                 // gamma*Ebar = R[N,M] - R[i,j] - (m - gamma ln2 L)
                 const float gE = fmaf(g2, L, (float)(Rq[u] - m));
                 rd[u] = __builtin_amdgcn_exp2f(gE * c2);
-                Rq[u] = Rfin - __builtin_nontemporal_load(&Rn[u * kBandRows + lane]);
+                if constexpr (!RECOMP) Rq[u] = Rfin - __builtin_nontemporal_load(&Rn[u * kBandRows + lane]);
                 edge = lane_shr1(edge, cur);  // lane 0 keeps its own value, the others move up
                 diag = down;
                 right = cur;

@@ -27,11 +27,11 @@ __global__ void fill_f32_kernel(float *dst, size_t n, float v)
     for (; i < n; i += stride) dst[i] = v;
 }
 
-__device__ __forceinline__ void fill_boundary_rows(const Params &p)
+__device__ __forceinline__ void fill_boundary_rows(const Params &p, unsigned long long *rows)
 {
     const size_t n = (size_t)p.B * p.nbands * p.M;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p.brow[i] = kSentinel;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) rows[i] = kSentinel;
 }
 
 // Start of a forward call, one launch: stamps the header, resets the band tickets, marks every
@@ -50,7 +50,7 @@ __global__ __launch_bounds__(256) void forward_prep_kernel(Params p, int64_t xro
         h->fwd_ticket = 0;
         h->bwd_ticket = 0;
     }
-    fill_boundary_rows(p);
+    fill_boundary_rows(p, p.brow);
     const int lane = threadIdx.x & 63;
     const int64_t rows = xrows + yrows;
     const int64_t stride = (int64_t)gridDim.x * 4;
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(256) void backward_prep_kernel(Params p)
             h->status = kStatusState;
         }
     }
-    fill_boundary_rows(p);
+    fill_boundary_rows(p, p.brow_b);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -37,8 +37,9 @@ struct Layout {
     int32_t nrb, ncb; // 32x32 block rows / columns: ceil(N/32), ceil(M/32)
     int64_t xn_count, yn_count;  // number of norm entries (1 sequence when the batch stride is 0)
     int32_t Dp;                  // D rounded up to 16: row length of the split-half operand copies (0: none)
-    size_t off_hdr, off_rfinal, off_xn, off_yn, off_xis, off_yis, off_xh, off_yh, off_brow, off_R, off_cost, off_E,
-        off_nz, total;
+    int32_t recompute;           // 1: checkpoints instead of the R table (large fused problems)
+    size_t off_hdr, off_rfinal, off_xn, off_yn, off_xis, off_yis, off_xh, off_yh, off_brow, off_brow_b, off_R,
+        off_ckpt, off_cost, off_E, off_nz, total;
 };
 
 // Fused mode with D <= 128 keeps a copy of x and y split into two float16 pieces per element
@@ -51,7 +52,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int64_t steps_of(const Layout &L) { return (int64_t)L.nmacro * kBlk; }
 
 inline Layout make_layout(int32_t B, int32_t N, int32_t M, int32_t D, int32_t mode, bool x_shared,
-                          bool y_shared)
+                          bool y_shared, bool recompute)
 {
     Layout L{};
     L.B = B; L.N = N; L.M = M; L.D = D; L.mode = mode;
@@ -72,9 +73,18 @@ inline Layout make_layout(int32_t B, int32_t N, int32_t M, int32_t D, int32_t mo
     L.off_xh = o;       o = align_up(o + (size_t)L.xn_count * L.Dp * 2 * sizeof(uint16_t), 256);
     L.off_yh = o;       o = align_up(o + (size_t)L.yn_count * L.Dp * 2 * sizeof(uint16_t), 256);
     // boundary rows: one row of M float64 per (pair, band)
-    L.off_brow = o;     o = align_up(o + (size_t)B * L.nbands * (size_t)M * sizeof(double), 256);
-    // DP table in step-major order: [B][nbands][steps][64] float64
-    L.off_R = o;        o = align_up(o + (size_t)B * L.nbands * (size_t)steps_of(L) * kBandRows * sizeof(double), 256);
+    L.recompute = recompute ? 1 : 0;
+    const size_t brow_bytes = (size_t)B * L.nbands * (size_t)M * sizeof(double);
+    L.off_brow = o;     o = align_up(o + brow_bytes, 256);
+    // with recomputation the backward needs the forward's boundary rows, so it gets rows of its own
+    L.off_brow_b = recompute ? o : L.off_brow;
+    if (recompute) o = align_up(o + brow_bytes, 256);
+    // DP table in step-major order: [B][nbands][steps][64] float64 - or, with recomputation, only
+    // the lane state (left, diagonal) at the start of every macro-step: [B][nbands][nmacro][2][64]
+    L.off_R = o;
+    if (!recompute) o = align_up(o + (size_t)B * L.nbands * (size_t)steps_of(L) * kBandRows * sizeof(double), 256);
+    L.off_ckpt = o;
+    if (recompute) o = align_up(o + (size_t)B * L.nbands * (size_t)L.nmacro * 2 * kBandRows * sizeof(double), 256);
     o += kGuardBytes;
     L.off_cost = o;
     if (mode == 0) o = align_up(o + (size_t)B * N * (size_t)M * sizeof(float), 256);
@@ -107,8 +117,11 @@ struct Params {
     float *xis, *yis;              // per row: 1/scale used for the split copy (a power of two)
     uint16_t *xh, *yh;             // [rows][Dp/16][2 pieces][16] float16 bit patterns
     int64_t xh_stride, yh_stride;  // batch strides of the split copies (0 when shared)
-    unsigned long long *brow;
+    unsigned long long *brow;      // boundary rows of the forward sweep
+    unsigned long long *brow_b;    // boundary rows of the backward sweep (== brow unless recompute)
     double *R;
+    double *ckpt;                  // recompute: forward lane state per macro-step
+    int32_t recompute;
     float *cost;
     float *E;
     unsigned char *nz;

@@ -57,9 +57,17 @@ bool desc_ok(const sdtw_desc *d, int *why)
     return true;
 }
 
+// Problems of up to 1024 band tasks cannot fill the chip: they run one band per workgroup.
+bool small_problem(const sdtw_desc *d)
+{
+    if (g_force_slots) return g_force_slots == 1;
+    return (int64_t)d->B * ((d->N + kBandRows - 1) / kBandRows) <= 1024;
+}
+
 Layout layout_of(const sdtw_desc *d)
 {
-    return make_layout(d->B, d->N, d->M, d->D, d->mode, d->x_batch_stride == 0, d->y_batch_stride == 0);
+    const bool recompute = d->mode == SDTW_FUSED && !small_problem(d);  // == dp_recompute(KCH >= 0, SLOTS == 4)
+    return make_layout(d->B, d->N, d->M, d->D, d->mode, d->x_batch_stride == 0, d->y_batch_stride == 0, recompute);
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -95,7 +103,10 @@ Params make_params(const sdtw_desc *d, const Layout &L, const float *x, const fl
     p.xh_stride = d->x_batch_stride == 0 ? 0 : (int64_t)d->N * L.Dp * 2;
     p.yh_stride = d->y_batch_stride == 0 ? 0 : (int64_t)d->M * L.Dp * 2;
     p.brow = reinterpret_cast<unsigned long long *>(base + L.off_brow);
+    p.brow_b = reinterpret_cast<unsigned long long *>(base + L.off_brow_b);
     p.R = reinterpret_cast<double *>(base + L.off_R);
+    p.ckpt = reinterpret_cast<double *>(base + L.off_ckpt);
+    p.recompute = L.recompute;
     p.cost = reinterpret_cast<float *>(base + L.off_cost);
     p.E = reinterpret_cast<float *>(base + L.off_E);
     p.nz = reinterpret_cast<unsigned char *>(base + L.off_nz);
@@ -130,14 +141,17 @@ void launch_dp_shape(const sdtw_desc *d, const Layout &L, const Params &p, float
 template <bool FWD, int KCH>
 void launch_dp_kch(const sdtw_desc *d, const Layout &L, const Params &p, float *value, hipStream_t st)
 {
-    const bool small = g_force_slots ? (g_force_slots == 1) : ((int64_t)d->B * L.nbands <= 1024);
+    const bool small = small_problem(d);
     if (small) {
         if constexpr (KCH > 0)
             launch_dp_shape<FWD, KCH, 1, 2>(d, L, p, value, st);
         else
             launch_dp_shape<FWD, KCH, 1, 1>(d, L, p, value, st);
     } else {
-        if constexpr (KCH > 0)
+        // The forward splits the cost blocks over two producers per band (register budget 168 per
+        // wavefront); the recomputing backward consumer needs more registers than that, and its
+        // long macro-steps leave a single producer enough time.
+        if constexpr (KCH > 0 && FWD)
             launch_dp_shape<FWD, KCH, 4, 2>(d, L, p, value, st);
         else
             launch_dp_shape<FWD, KCH, 4, 1>(d, L, p, value, st);
@@ -373,6 +387,7 @@ int sdtw_debug_export(const sdtw_desc *desc, const void *workspace, size_t works
             if (hipMemcpyAsync(out, p.cost, n * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) return SDTW_ERR_HIP;
             return SDTW_OK;
         case SDTW_EXPORT_R:
+            if (L.recompute) return SDTW_ERR_UNSUPPORTED;  // the table is not stored in this regime
             export_R_kernel<<<fill_grid(n), 256, 0, st>>>(p, static_cast<double *>(out));
             return hip_ok();
         case SDTW_EXPORT_E:
