@@ -363,6 +363,67 @@ template <int KG, int DIR, int W0, int NW> struct HalfProducer {
 };
 
 // ---------------------------------------------------------------------------------------------
+// Unfused cost tensor d[B,N,M] for D <= 16*KG on the fp16 matrix cores (Sec. 4.3 "unfused":
+// computed once and stored), from the same split-half copies and with the same arithmetic as the
+// fused producer.  One workgroup = 4 wavefronts = a 128 x 128 tile; each wavefront keeps the
+// pieces of its 32 rows in registers and walks four 32-column blocks.
+// ---------------------------------------------------------------------------------------------
+template <int KG>
+__global__ __launch_bounds__(256) void cost_tensor_half_kernel(Params p)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, h = lane >> 5;
+    const int b = blockIdx.z;
+    const int i0 = blockIdx.y * 128 + w * 32;
+    if (i0 >= p.N) return;
+    const uint16_t *xh = p.xh + b * p.xh_stride, *yh = p.yh + b * p.yh_stride;
+    const float *xnb = p.xn + b * p.xn_stride, *ynb = p.yn + b * p.yn_stride;
+    const float *xisb = p.xis + b * p.xn_stride, *yisb = p.yis + b * p.yn_stride;
+    half8 xa[2][KG];
+    {
+        const int row = min(i0 + (lane & 31), p.N - 1);
+        const uint16_t *r = xh + (size_t)row * (2 * p.Dp) + 8 * h;
+#pragma unroll
+        for (int g = 0; g < KG; ++g) {
+            xa[0][g] = *reinterpret_cast<const half8 *>(r + 32 * g);
+            xa[1][g] = *reinterpret_cast<const half8 *>(r + 32 * g + 16);
+        }
+    }
+    float xn_r[16], m2is_r[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int row = min(i0 + acc_row(i, lane), p.N - 1);
+        xn_r[i] = xnb[row];
+        m2is_r[i] = -2.0f * xisb[row];
+    }
+    float *dst = p.cost + (size_t)b * p.N * p.M;
+    for (int cbk = 0; cbk < 4; ++cbk) {
+        const int j0 = blockIdx.x * 128 + cbk * 32;
+        if (j0 >= p.M) break;
+        const int col = j0 + (lane & 31);
+        const int colc = min(col, p.M - 1);
+        const uint16_t *r = yh + (size_t)colc * (2 * p.Dp) + 8 * h;
+        floatx16 acc = zero16();
+#pragma unroll
+        for (int g = 0; g < KG; ++g) {
+            const half8 k1 = *reinterpret_cast<const half8 *>(r + 32 * g);
+            const half8 k2 = *reinterpret_cast<const half8 *>(r + 32 * g + 16);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0][g], k1, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0][g], k2, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[1][g], k1, acc, 0, 0, 0);
+        }
+        const float ync = ynb[colc], yisc = yisb[colc];
+        if (col < p.M) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int row = i0 + acc_row(i, lane);
+                if (row < p.N)
+                    dst[(size_t)row * p.M + col] = fmaxf(fmaf(acc[i], m2is_r[i] * yisc, xn_r[i] + ync), 0.0f);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Workgroup bookkeeping shared by both kernels.
 // ---------------------------------------------------------------------------------------------
 template <int SLOTS> struct WgShared {
@@ -609,8 +670,8 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Pa
 // cell in float64.  E = exp(Ebar) is applied per cell as soon as Ebar is known.
 //
 // Bands run bottom-up; lane t needs lane t+1's values, the band below supplies lane 63's.
-// E replaces the consumed cost value in the ring and leaves as row-major 32x32 blocks, with one
-// flag byte per block saying whether any entry is non-zero.
+// E replaces the consumed cost value in the ring; the producers write it out as row-major 32x32
+// blocks, with one flag byte per block saying whether any entry is non-zero.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ void flush_E_block(const Params &p, const float *ring, float *__restrict__ Eb,
                                               unsigned char *__restrict__ nzb, int rb, int cb, int row0, int lane)
@@ -682,7 +743,21 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
     float2 *rowtab = sh.rowtab[slot];
     const int sg0 = p.nmacro - 1;
 
+    float *Eb = p.E + (size_t)bb * N * M;
+    unsigned char *nzb = p.nz + (size_t)bb * p.nrb * p.ncb;
+    constexpr bool kProducerFlush = !dp_recompute(KCH, SLOTS);
+
     if (producer) {
+        // Besides the cost blocks, the producers write out the E blocks the consumer finished in the
+        // previous macro-step `done`: (upper rows, done) and (lower rows, done-1).  Each producer
+        // touches only the rows it owns and flushes before it overwrites the same ring phase.
+        // (With recomputation the producer is the busier side, so there the consumer keeps this job.)
+        auto flush = [&](int done, bool upper, bool lower) {
+            if constexpr (kProducerFlush) {
+                if (upper) flush_E_block(p, ring, Eb, nzb, 0, done, row0, lane);
+                if (lower) flush_E_block(p, ring, Eb, nzb, 1, done - 1, row0, lane);
+            }
+        };
         // blocks the first macro-step reads: (upper rows, sg0-1), (lower rows, sg0-1), (lower rows, sg0-2)
         if constexpr (KCH > 0 && NPROD == 2) {
             // producer 1 makes (upper rows, sg-2), producer 2 makes (lower rows, sg-3)
@@ -699,9 +774,13 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
                 }
                 __syncthreads();
                 for (int sg = sg0; sg >= 0; --sg) {
-                    if (live) mp.run(p, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
+                    if (live) {
+                        if (sg < sg0) flush(sg + 1, upper, !upper);
+                        mp.run(p, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
+                    }
                     __syncthreads();
                 }
+                if (live) flush(0, upper, !upper);
             };
             if (producer == 1) {
                 HalfProducer<KCH, -1, 0, 1> mp;
@@ -721,9 +800,13 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
             }
             __syncthreads();
             for (int sg = sg0; sg >= 0; --sg) {
-                if (live) mp.run(p, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
+                if (live) {
+                    if (sg < sg0) flush(sg + 1, true, true);
+                    mp.run(p, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
+                }
                 __syncthreads();
             }
+            if (live) flush(0, true, true);
         } else if constexpr (KCH == 0) {
             if (live) {
                 generic_block(p, b, ring, 0, sg0 - 1, row0, lane);
@@ -733,11 +816,13 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
             __syncthreads();
             for (int sg = sg0; sg >= 0; --sg) {
                 if (live) {
+                    if (sg < sg0) flush(sg + 1, true, true);
                     generic_block(p, b, ring, 0, sg - 2, row0, lane);
                     generic_block(p, b, ring, 1, sg - 3, row0, lane);
                 }
                 __syncthreads();
             }
+            if (live) flush(0, true, true);
         } else {
             const float *cost_b = p.cost + (size_t)bb * N * M;
             float4 pre[2][4];
@@ -754,6 +839,7 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
             __syncthreads();
             for (int sg = sg0; sg >= 0; --sg) {
                 if (live) {
+                    if (sg < sg0) flush(sg + 1, true, true);
                     store_cost_block(ring, pre[0], 0, sg - 2, lane);
                     store_cost_block(ring, pre[1], 1, sg - 3, lane);
                     load_cost_block(pre[0], cost_b, 0, sg - 3, row0, N, M, p.vec_m != 0, lane);
@@ -761,6 +847,7 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
                 }
                 __syncthreads();
             }
+            if (live) flush(0, true, true);
         }
         return;
     }
@@ -768,8 +855,6 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
     // ---------------------------------------------------------------------- consumer wavefront
     const float c2 = p.inv_gamma_log2e, g2 = p.gamma_ln2;
     const double g2d = (double)p.gamma_ln2;
-    float *Eb = p.E + (size_t)bb * N * M;
-    unsigned char *nzb = p.nz + (size_t)bb * p.nrb * p.ncb;
     bool gave_up = false;
     double right = kBig;  // T[i][j+1]
     double diag = kBig;   // T[i+1][j+1]
@@ -875,9 +960,12 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
                 const int j = sg * kBlk + lane;
                 if (j < M) publish_boundary(brow_out, j, edge);
             }
-            // E blocks completed by this macro-step: (upper rows, sg) and (lower rows, sg-1)
-            flush_E_block(p, ring, Eb, nzb, 0, sg, row0, lane);
-            flush_E_block(p, ring, Eb, nzb, 1, sg - 1, row0, lane);
+            // the E blocks this macro-step completed, (upper rows, sg) and (lower rows, sg-1): written
+            // out by the producers during the next macro-step, or here
+            if constexpr (!kProducerFlush) {
+                flush_E_block(p, ring, Eb, nzb, 0, sg, row0, lane);
+                flush_E_block(p, ring, Eb, nzb, 1, sg - 1, row0, lane);
+            }
             double bn = kBig;
             if (has_below) bn = resolve_boundary(p, brow_in, jn, need_n, lane, gave_up, nxt_bits);
             if (lane >= kBlk) bot[lane - kBlk] = bn;

@@ -42,8 +42,9 @@ struct Layout {
         off_ckpt, off_cost, off_E, off_nz, total;
 };
 
-// Fused mode with D <= 128 keeps a copy of x and y split into two float16 pieces per element
-// (see split_rows_kernel); larger D computes the cost in float32 straight from x and y.
+// With D <= 128 the workspace keeps a copy of x and y split into two float16 pieces per element
+// (made by forward_prep_kernel) for the fp16 matrix cores; larger D computes the cost in float32
+// straight from x and y.
 constexpr int kMaxSplitD = 128;
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -67,7 +68,7 @@ inline Layout make_layout(int32_t B, int32_t N, int32_t M, int32_t D, int32_t mo
     L.off_rfinal = o;   o = align_up(o + (size_t)B * sizeof(double), 256);
     L.off_xn = o;       o = align_up(o + (size_t)L.xn_count * sizeof(float), 256);
     L.off_yn = o;       o = align_up(o + (size_t)L.yn_count * sizeof(float), 256);
-    L.Dp = (mode == 1 && D <= kMaxSplitD) ? (D + 15) / 16 * 16 : 0;
+    L.Dp = (D <= kMaxSplitD) ? (D + 15) / 16 * 16 : 0;
     L.off_xis = o;      o = align_up(o + (size_t)(L.Dp ? L.xn_count : 0) * sizeof(float), 256);
     L.off_yis = o;      o = align_up(o + (size_t)(L.Dp ? L.yn_count : 0) * sizeof(float), 256);
     L.off_xh = o;       o = align_up(o + (size_t)L.xn_count * L.Dp * 2 * sizeof(uint16_t), 256);

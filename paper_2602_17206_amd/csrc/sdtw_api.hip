@@ -200,9 +200,18 @@ int forward_impl(const sdtw_desc *d, const float *x, const float *y, float *valu
         forward_prep_kernel<<<prep_grid(p, L.xn_count + L.yn_count), 256, 0, st>>>(p, L.xn_count, L.yn_count);
     }
     if (d->mode == SDTW_UNFUSED) {
-        dim3 g((d->M + 63) / 64, (d->N + 63) / 64, d->B);
         ProfScope ps("cost_tensor", st);
-        cost_tensor_kernel<<<g, 256, 0, st>>>(p);
+        dim3 gh((d->M + 127) / 128, (d->N + 127) / 128, d->B);
+        switch (fused_variant(d->D)) {
+            case 1: cost_tensor_half_kernel<1><<<gh, 256, 0, st>>>(p); break;
+            case 2: cost_tensor_half_kernel<2><<<gh, 256, 0, st>>>(p); break;
+            case 4: cost_tensor_half_kernel<4><<<gh, 256, 0, st>>>(p); break;
+            case 8: cost_tensor_half_kernel<8><<<gh, 256, 0, st>>>(p); break;
+            default: {
+                dim3 g((d->M + 63) / 64, (d->N + 63) / 64, d->B);
+                cost_tensor_kernel<<<g, 256, 0, st>>>(p);
+            }
+        }
     }
     {
         ProfScope ps(d->mode == SDTW_UNFUSED ? "forward_dp_unfused" : "forward_dp_fused", st);
