@@ -1,4 +1,4 @@
-// Device-side building blocks: cross-lane shifts, the soft-minimum, the 32x32 cost block.
+// Device-side building blocks: cross-lane shifts and the float32 32x32 cost block.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -38,25 +38,6 @@ __device__ __forceinline__ double read_lane(double v, int src)
     int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
     int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
     return __hiloint2double(hi, lo);
-}
-
-// ---------------------------------------------------------------------------------------------
-// softmin_gamma(a,b,c) = -gamma log(e^{-a/gamma}+e^{-b/gamma}+e^{-c/gamma})     (Sec. 2, Eq. 2)
-// evaluated as  m - gamma ln2 * log2(1 + 2^{-(med-m) c2} + 2^{-(max-m) c2}),  c2 = log2(e)/gamma,
-// i.e. the max-shifted log-sum-exp of Sec. 4.2 with the shift equal to the minimum.
-// The table values (a,b,c,m) are float64 so that differences of neighbours keep an absolute
-// accuracy far below gamma however large R grows; the exponentials and the logarithm see only
-// those differences and run in float32 on the hardware's exp2/log2 units.
-// +inf arguments (cells outside the grid) contribute 2^{-inf} = 0.  If all three are +inf the
-// result is NaN; callers discard it (such a cell is outside the grid).
-__device__ __forceinline__ double softmin3(double a, double b, double c, float c2, float gamma_ln2)
-{
-    const double m = fmin(fmin(a, b), c);
-    const float fa = (float)(a - m), fb = (float)(b - m), fc = (float)(c - m);
-    const float mx = __builtin_fmaxf(__builtin_fmaxf(fa, fb), fc);
-    const float md = __builtin_amdgcn_fmed3f(fa, fb, fc);
-    const float S = 1.0f + __builtin_amdgcn_exp2f(-md * c2) + __builtin_amdgcn_exp2f(-mx * c2);
-    return m - (double)(gamma_ln2 * __builtin_amdgcn_logf(S));
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -60,16 +60,27 @@ __device__ __forceinline__ double min_f64(double a, double b)
     return r;
 }
 
-// softmin_gamma(a,b,c) = m - gamma ln2 * L  with  m = min(a,b,c) (float64) and
-// L = log2(sum_k 2^{-(v_k - m) c2}) in [0, log2 3] (float32), c2 = log2(e)/gamma.
-// (Sec. 2 Eq. 2, evaluated with the max-shift of Sec. 4.2; the term of the minimum is 2^0 = 1.)
-__device__ __forceinline__ void softmin3_parts(double a, double b, double c, float c2, double &m, float &L)
+__device__ __forceinline__ double max_f64(double a, double b)
 {
-    m = min_f64(min_f64(a, b), c);
-    const float fa = (float)(a - m), fb = (float)(b - m), fc = (float)(c - m);
-    const float mx = __builtin_fmaxf(__builtin_fmaxf(fa, fb), fc);
-    const float md = __builtin_amdgcn_fmed3f(fa, fb, fc);
-    const float S = 1.0f + __builtin_amdgcn_exp2f(-md * c2) + __builtin_amdgcn_exp2f(-mx * c2);
+    double r;
+    asm("v_max_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+// The DP tables are kept in units of gamma*ln2: every stored value is the paper's value times
+// c2 = log2(e)/gamma, so that differences of table entries are base-2 exponents as they stand.
+// In these units  softmin_gamma(a,b,c) = m - L  with  m = min(a,b,c) (float64) and
+// L = log2(sum_k 2^{-(v_k - m)}) in [0, log2 3] (float32).
+// (Sec. 2 Eq. 2, evaluated with the max-shift of Sec. 4.2; the term of the minimum is 2^0 = 1.)
+// The two other terms: with lo = min(b,c), hi = max(b,c), either a is the minimum and they are
+// lo-a and hi-a, or lo is and they are a-lo and hi-lo; both cases are |a-lo| and hi-m.
+__device__ __forceinline__ void softmin3_parts(double a, double b, double c, double &m, float &L)
+{
+    const double lo = min_f64(b, c), hi = max_f64(b, c);
+    m = min_f64(a, lo);
+    const float t1 = (float)__builtin_fabs(a - lo);
+    const float t2 = (float)(hi - m);
+    const float S = 1.0f + __builtin_amdgcn_exp2f(-t1) + __builtin_amdgcn_exp2f(-t2);
     L = __builtin_amdgcn_logf(S);
 }
 
@@ -567,8 +578,7 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Pa
     }
 
     // ---------------------------------------------------------------------- consumer wavefront
-    const float c2 = p.inv_gamma_log2e;
-    const double g2d = (double)p.gamma_ln2;
+    const double c2d = p.c2d;  // log2(e)/gamma
     bool gave_up = false;
     double left = kBig;                                  // R[i][j-1]
     double diag = (k == 0 && lane == 0) ? 0.0 : kBig;    // R[i-1][j-1]; R[0,0] = 0 in the paper's indexing
@@ -619,10 +629,10 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Pa
                     const float dc = rd[u];
                     double m;
                     float L;
-                    softmin3_parts(diag, up, left, c2, m, L);
+                    softmin3_parts(diag, up, left, m, L);
                     // every addition that builds the table is float64: a float32 rounding here would
                     // differ between the two sweeps and add up along the alignment path
-                    const double cur = fma(-(double)L, g2d, m + (double)dc);
+                    const double cur = fma((double)dc, c2d, m) - (double)L;
                     if constexpr (!RECOMP)  // streamed once: keep it out of the caches
                         __builtin_nontemporal_store(cur, &Rs[u * kBandRows + lane]);
                     if constexpr (decltype(capture)::value) fin = (sg * kBlk + u == s_fin) ? cur : fin;
@@ -650,8 +660,8 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Pa
     // R[N,M] of the pair: cell (N-1, M-1) was stored at step M-1+lane by the lane that owns row N-1
     if (live && row0 + lane == N - 1) {
         const double r = RECOMP ? fin : Rk[(size_t)(M - 1 + lane) * kBandRows + lane];
-        p.rfinal[b] = r;
-        value[b] = (float)r;
+        p.rfinal[b] = r;                     // table units, for the backward sweep
+        value[b] = (float)(r * p.inv_c2d);   // the paper's units
     }
 }
 
@@ -853,8 +863,7 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
     }
 
     // ---------------------------------------------------------------------- consumer wavefront
-    const float c2 = p.inv_gamma_log2e, g2 = p.gamma_ln2;
-    const double g2d = (double)p.gamma_ln2;
+    const double c2d = p.c2d;  // log2(e)/gamma
     bool gave_up = false;
     double right = kBig;  // T[i][j+1]
     double diag = kBig;   // T[i+1][j+1]
@@ -931,8 +940,8 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
                     const float dcf = rd[u];
                     double mf;
                     float Lf;
-                    softmin3_parts(fd, up, fl, c2, mf, Lf);
-                    const double cur = fma(-(double)Lf, g2d, mf + (double)dcf);
+                    softmin3_parts(fd, up, fl, mf, Lf);
+                    const double cur = fma((double)dcf, c2d, mf) - (double)Lf;
                     Rq[u] = Rfin - cur;
                     fd = up;
                     fl = cur;
@@ -945,11 +954,10 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
                 const double dg = (sbase + u == s_corner) ? 0.0 : diag;
                 double m;
                 float L;
-                softmin3_parts(dg, down, right, c2, m, L);
-                const double cur = fma(-(double)L, g2d, m + (double)dc);
-                // gamma*Ebar = R[N,M] - R[i,j] - (m - gamma ln2 L)
-                const float gE = fmaf(g2, L, (float)(Rq[u] - m));
-                rd[u] = __builtin_amdgcn_exp2f(gE * c2);
+                softmin3_parts(dg, down, right, m, L);
+                const double cur = fma((double)dc, c2d, m) - (double)L;
+                // log2 E = R[N,M] - R[i,j] - (m - L) in table units
+                rd[u] = __builtin_amdgcn_exp2f((float)(Rq[u] - m) + L);
                 if constexpr (!RECOMP) Rq[u] = Rfin - __builtin_nontemporal_load(&Rn[u * kBandRows + lane]);
                 edge = lane_shr1(edge, cur);  // lane 0 keeps its own value, the others move up
                 diag = down;

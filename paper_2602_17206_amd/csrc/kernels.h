@@ -301,7 +301,7 @@ __global__ void export_E_kernel(Params p, float *__restrict__ dst)
     for (; i < n; i += stride) dst[i] = bad ? qnan : p.E[i];
 }
 
-// Un-skews the step-major DP table into row-major R[b][i][j] (test hook).
+// Un-skews the step-major DP table into row-major R[b][i][j], in the paper's units (test hook).
 __global__ void export_R_kernel(Params p, double *__restrict__ dst)
 {
     const size_t n = (size_t)p.B * p.N * p.M;
@@ -314,7 +314,7 @@ __global__ void export_R_kernel(Params p, double *__restrict__ dst)
         const int i = (int)(bi % p.N);
         const int b = (int)(bi / p.N);
         const int k = i / kBandRows, t = i % kBandRows;
-        dst[e] = p.R[((size_t)b * p.nbands + k) * band_elems + (size_t)(j + t) * kBandRows + t];
+        dst[e] = p.R[((size_t)b * p.nbands + k) * band_elems + (size_t)(j + t) * kBandRows + t] * p.inv_c2d;
     }
 }
 

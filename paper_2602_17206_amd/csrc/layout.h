@@ -102,8 +102,8 @@ struct Params {
     int32_t B, N, M, D, mode;
     int32_t nbands, nmacro, nrb, ncb;
     float gamma;
-    float inv_gamma_log2e;  // log2(e)/gamma
-    float gamma_ln2;        // gamma*ln(2)
+    double c2d;             // log2(e)/gamma: paper units -> table units
+    double inv_c2d;         // gamma*ln(2): table units -> paper units
     int64_t x_stride, y_stride;    // batch strides of x, y (elements)
     int64_t xn_stride, yn_stride;  // batch strides of the norm vectors (0 when shared)
     int32_t vec_xy;                // 1: D%8==0 and x,y 16-byte aligned -> float4 operand loads

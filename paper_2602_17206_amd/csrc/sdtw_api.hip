@@ -79,8 +79,8 @@ Params make_params(const sdtw_desc *d, const Layout &L, const float *x, const fl
     p.B = d->B; p.N = d->N; p.M = d->M; p.D = d->D; p.mode = d->mode;
     p.nbands = L.nbands; p.nmacro = L.nmacro; p.nrb = L.nrb; p.ncb = L.ncb;
     p.gamma = d->gamma;
-    p.inv_gamma_log2e = (float)(1.4426950408889634 / (double)d->gamma);
-    p.gamma_ln2 = (float)(0.6931471805599453 * (double)d->gamma);
+    p.c2d = 1.4426950408889634 / (double)d->gamma;
+    p.inv_c2d = 0.6931471805599453 * (double)d->gamma;
     p.x_stride = d->x_batch_stride; p.y_stride = d->y_batch_stride;
     p.xn_stride = d->x_batch_stride == 0 ? 0 : d->N;
     p.yn_stride = d->y_batch_stride == 0 ? 0 : d->M;
