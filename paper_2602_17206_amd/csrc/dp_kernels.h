@@ -481,6 +481,12 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Pa
     constexpr int kThreads = wg_threads(SLOTS, NPROD);
     __shared__ WgShared<SLOTS> sh;
     __shared__ unsigned ticket_s;
+    // Values the band's edge row (last row in the forward sweep, first in the backward sweep)
+    // produced in the current macro-step, one per step, for the neighbouring band.  Every lane
+    // writes its value each step; only the edge lane's address points into [0,32), the others write
+    // to slots of their own behind it.  (An object of its own, so that these stores are known not to
+    // touch the ring or the incoming boundary values.)
+    __shared__ double edge_out[SLOTS][kBlk + kBandRows + kBlk];
     const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
     if (threadIdx.x == 0) ticket_s = atomicAdd(&p.hdr->fwd_ticket, 1u);
@@ -582,7 +588,6 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Pa
     bool gave_up = false;
     double left = kBig;                                  // R[i][j-1]
     double diag = (k == 0 && lane == 0) ? 0.0 : kBig;    // R[i-1][j-1]; R[0,0] = 0 in the paper's indexing
-    double edge = kBig;                                  // collects lane 63's values of a macro-step
     const int kc = live ? k : 0;
     const unsigned long long *brow_in = p.brow + ((size_t)bb * p.nbands + (kc > 0 ? kc - 1 : 0)) * M;
     unsigned long long *brow_out = p.brow + ((size_t)bb * p.nbands + kc) * M;
@@ -598,6 +603,8 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Pa
     const bool emit_bottom = live && (k + 1 < p.nbands);
     const float *my_ring = ring + lane * kRingStride;
     double *top = sh.edge_in[slot];
+    double *eo = edge_out[slot];
+    double *my_eo = eo + ((lane == kBandRows - 1) ? 0 : kBlk + lane);
 
     // row above the band for macro-step 0: lane l < 32 brings column l
     {
@@ -636,7 +643,7 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Pa
                     if constexpr (!RECOMP)  // streamed once: keep it out of the caches
                         __builtin_nontemporal_store(cur, &Rs[u * kBandRows + lane]);
                     if constexpr (decltype(capture)::value) fin = (sg * kBlk + u == s_fin) ? cur : fin;
-                    edge = lane_shl1(edge, cur);  // lane 63 keeps its own value, the others move down
+                    my_eo[u] = cur;  // lane 63: value of column 32*sg + u - 63 for the band below
                     diag = up;
                     left = cur;
                 }
@@ -645,10 +652,11 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Pa
                 steps(std::true_type{});
             else
                 steps(std::false_type{});
-            // last row of the band: lanes 32..63 hold columns 32*sg - 63 + (lane - 32)
+            // last row of the band: lanes 32..63 publish columns 32*sg - 63 + (lane - 32)
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             if (emit_bottom && lane >= kBlk) {
                 const int j = sg * kBlk + lane - kBlk - (kBandRows - 1);
-                if (j >= 0 && j < M) publish_boundary(brow_out, j, edge);
+                if (j >= 0 && j < M) publish_boundary(brow_out, j, eo[lane - kBlk]);
             }
             double tn = kBig;
             if (has_above) tn = resolve_boundary(p, brow_in, jn, need_n, lane, gave_up, nxt_bits);
@@ -722,6 +730,12 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
     constexpr int kThreads = wg_threads(SLOTS, NPROD);
     __shared__ WgShared<SLOTS> sh;
     __shared__ unsigned ticket_s;
+    // Values the band's edge row (last row in the forward sweep, first in the backward sweep)
+    // produced in the current macro-step, one per step, for the neighbouring band.  Every lane
+    // writes its value each step; only the edge lane's address points into [0,32), the others write
+    // to slots of their own behind it.  (An object of its own, so that these stores are known not to
+    // touch the ring or the incoming boundary values.)
+    __shared__ double edge_out[SLOTS][kBlk + kBandRows + kBlk];
     const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (p.hdr->abort_backward) return;
 
@@ -867,9 +881,11 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
     bool gave_up = false;
     double right = kBig;  // T[i][j+1]
     double diag = kBig;   // T[i+1][j+1]
-    double edge = kBig;   // collects lane 0's values of a macro-step
-    // step at which this lane meets the cell whose diagonal successor is T[N+1,M+1] = 0
+    // step at which this lane meets the cell whose diagonal successor is T[N+1,M+1] = 0, and the
+    // macro-step in which that happens in this band
     const int s_corner = (live && row0 + lane == N - 1) ? (M - 1 + lane) : -1;
+    const int t_last = N - 1 - row0;
+    const int sg_corner = (live && t_last < kBandRows) ? (M - 1 + t_last) / kBlk : -1;
     const double Rfin = live ? p.rfinal[b] : 0.0;
     const int kc = live ? k : 0;
     const bool has_below = live && (k + 1 < p.nbands);
@@ -883,6 +899,8 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
     double *ftop = sh.ftop[slot];
     float *my_ring = ring + lane * kRingStride;
     double *bot = sh.edge_in[slot];
+    double *eo = edge_out[slot];
+    double *my_eo = eo + ((lane == 0) ? 0 : kBlk + lane);
 
     // R of the first macro-step; afterwards each value is reloaded one macro-step ahead, right after use
     double Rq[kBlk];
@@ -897,7 +915,8 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
         }
     } else {
 #pragma unroll
-        for (int u = 0; u < kBlk; ++u) Rq[u] = live ? Rfin - Rk[((size_t)sg0 * kBlk + u) * kBandRows + lane] : 0.0;
+        for (int u = 0; u < kBlk; ++u)  // (Rk points at a valid band also for an idle slot: no branch per load)
+            Rq[u] = Rfin - Rk[((size_t)sg0 * kBlk + u) * kBandRows + lane];
     }
 
     // row below the band for the first macro-step: lane l >= 32 brings column 32*sg - 63 + (l - 32),
@@ -947,11 +966,12 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
                     fl = cur;
                 }
             }
+            auto steps = [&](auto corner) {
 #pragma unroll
             for (int u = kBlk - 1; u >= 0; --u) {
                 const double down = lane_shl1(right, bot[u]);  // T[i+1][j]; lane 63 takes the row below the band
                 const float dc = rd[u];
-                const double dg = (sbase + u == s_corner) ? 0.0 : diag;
+                const double dg = (decltype(corner)::value && sbase + u == s_corner) ? 0.0 : diag;
                 double m;
                 float L;
                 softmin3_parts(dg, down, right, m, L);
@@ -959,14 +979,20 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
                 // log2 E = R[N,M] - R[i,j] - (m - L) in table units
                 rd[u] = __builtin_amdgcn_exp2f((float)(Rq[u] - m) + L);
                 if constexpr (!RECOMP) Rq[u] = Rfin - __builtin_nontemporal_load(&Rn[u * kBandRows + lane]);
-                edge = lane_shr1(edge, cur);  // lane 0 keeps its own value, the others move up
+                my_eo[u] = cur;  // lane 0: value of column 32*sg + u for the band above
                 diag = down;
                 right = cur;
             }
+            };
+            if (sg == sg_corner)
+                steps(std::true_type{});
+            else
+                steps(std::false_type{});
             // first row of the band, columns 32*sg .. 32*sg+31, for the band above
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             if (k > 0 && lane < kBlk) {
                 const int j = sg * kBlk + lane;
-                if (j < M) publish_boundary(brow_out, j, edge);
+                if (j < M) publish_boundary(brow_out, j, eo[lane]);
             }
             // the E blocks this macro-step completed, (upper rows, sg) and (lower rows, sg-1): written
             // out by the producers during the next macro-step, or here
