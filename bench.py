@@ -32,9 +32,10 @@ PEAK_MFMA_F32_TFLOPS = 157.3
 PEAK_VALU_TOPS = 256 * 64 * 2.4e9 / 1e12
 
 # Algorithmic work per DP cell: VALU issue slots, a transcendental
-# (exp2/log2, quarter rate) counted as 4 slots.
-SLOTS_FWD_CELL = 30.0
-SLOTS_BWD_CELL = 38.0
+# (exp2/log2, quarter rate) counted as 4 slots.  A sweep (forward, or reverse without E) costs
+# 15 plain operations + 3 transcendentals; the reverse sweep that also forms E 19 + 4.
+SLOTS_SWEEP_CELL = 27.0
+SLOTS_BWD_E_CELL = 35.0
 MODE_NAMES = {0: "unfused", 1: "fused"}
 
 
@@ -64,16 +65,19 @@ def kernel_table(prof, steps):
 def roofline_for(name, ms_per_launch, wl_cells, D, traffic=None):
     """Roofline object for one kernel launch covering wl_cells DP cells."""
     sec = ms_per_launch * 1e-3
-    if name.startswith("forward_dp") or name.startswith("backward_dp"):
-        slots = SLOTS_FWD_CELL if name.startswith("forward") else SLOTS_BWD_CELL
+    if name.startswith("forward_dp") or name.startswith("backward_dp") or name.startswith("both_sweeps"):
+        both = name.startswith("both_sweeps")
+        slots = 2 * SLOTS_SWEEP_CELL if both else (SLOTS_SWEEP_CELL if name.startswith("forward") else SLOTS_BWD_E_CELL)
         achieved = slots * wl_cells / sec / 1e12
         out = {"kernel": name, "bound": "alu", "achieved": achieved, "peak": PEAK_VALU_TOPS,
                "unit": "Tlane-op/s", "frac": achieved / PEAK_VALU_TOPS, "traffic": traffic,
                "per_cell": {"valu_slots": slots}}
         if name.endswith("_fused"):
-            fl = 2.0 * D * wl_cells / sec / 1e12
+            fl = (2 if both else 1) * 2.0 * D * wl_cells / sec / 1e12
             out["mfma"] = {"achieved": fl, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s", "frac": fl / PEAK_MFMA_F32_TFLOPS}
-        nbytes = 8.0 + (4.0 if name.startswith("backward") else 0.0) + (4.0 if name.endswith("_unfused") else 0.0)
+        # table traffic: 8 B per cell and sweep; the E-forming reverse sweep also writes E; unfused reads the cost
+        nbytes = (16.0 if both else 8.0) + (4.0 if name.startswith("backward") else 0.0) + \
+                 ((8.0 if both else 4.0) if name.endswith("_unfused") else 0.0)
         bw = nbytes * wl_cells / sec / 1e9
         out["hbm"] = {"achieved": bw, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": bw / PEAK_HBM_GBS, "bytes_per_cell": nbytes}
         return out
@@ -81,6 +85,10 @@ def roofline_for(name, ms_per_launch, wl_cells, D, traffic=None):
         fl = 2.0 * D * wl_cells / sec / 1e12
         return {"kernel": name, "bound": "mfma", "achieved": fl, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
                 "frac": fl / PEAK_MFMA_F32_TFLOPS, "traffic": traffic}
+    if name == "alignment":
+        bw = 20.0 * wl_cells / sec / 1e9  # reads both float64 tables, writes float32 E
+        return {"kernel": name, "bound": "hbm", "achieved": bw, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": bw / PEAK_HBM_GBS, "traffic": traffic}
     if name == "input_grad":
         bw = 8.0 * wl_cells / sec / 1e9  # E is read once per side
         return {"kernel": name, "bound": "hbm", "achieved": bw, "peak": PEAK_HBM_GBS, "unit": "GB/s",

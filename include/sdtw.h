@@ -45,12 +45,23 @@ typedef enum sdtw_status {
     SDTW_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, gamma not finite or <= 0, bad mode */
     SDTW_ERR_WORKSPACE = 2,   /* workspace missing, misaligned or smaller than required */
     SDTW_ERR_UNSUPPORTED = 3, /* bandwidth != 0 (Algorithm 1 names it, the paper never defines it) */
-    SDTW_ERR_STATE = 4,       /* device: backward on a workspace not filled by a matching forward */
+    SDTW_ERR_STATE = 4,       /* device: backward on a workspace not filled by a matching forward;
+                                 host: backward with a SDTW_FLAG_VALUE_ONLY descriptor */
     SDTW_ERR_HIP = 5,         /* a HIP runtime call failed (launch, copy) */
     SDTW_ERR_TIMEOUT = 6      /* device: a band gave up waiting for the band it depends on */
 } sdtw_status;
 
 enum { SDTW_UNFUSED = 0, SDTW_FUSED = 1 };
+
+/*
+ * sdtw_desc.flags.
+ *   SDTW_FLAG_VALUE_ONLY: the caller wants sdtw_forward's value and will not call sdtw_backward
+ *   with this descriptor (sdtw_backward returns SDTW_ERR_STATE).  Without it, for problems
+ *   too small to fill the chip, sdtw_forward already runs the reverse sweep of the backward pass
+ *   beside the forward sweep (it does not depend on the forward's table), so that sdtw_backward
+ *   only has to combine the two tables.  The flag changes the workspace size.
+ */
+enum { SDTW_FLAG_VALUE_ONLY = 1 };
 
 /* What sdtw_debug_export copies out of a workspace. */
 enum { SDTW_EXPORT_COST = 0, SDTW_EXPORT_R = 1, SDTW_EXPORT_E = 2 };
@@ -63,7 +74,7 @@ typedef struct sdtw_desc {
     int64_t x_batch_stride; /* elements between consecutive x sequences: N*D, or 0 = one x shared */
     int64_t y_batch_stride; /* elements between consecutive y sequences: M*D, or 0 = one y shared */
     int32_t bandwidth;      /* reserved, must be 0 (no band constraint, as in the paper's Sec. 5) */
-    uint32_t flags;         /* reserved, must be 0 */
+    uint32_t flags;         /* 0 or SDTW_FLAG_VALUE_ONLY */
 } sdtw_desc;
 
 /* One barycenter step: K sequences X_k [Lx,D] against the current barycenter z [Lz,D]. */
@@ -88,6 +99,10 @@ size_t sdtw_workspace_bytes(const sdtw_desc *desc);
  *   value [B]: device, out; value[b] = R[N,M] of pair b (float32; the table itself is
  *              carried in float64 inside the workspace).
  * Leaves the DP table (and, unfused, the cost tensor) in `workspace` for sdtw_backward.
+ * For small problems (see SDTW_FLAG_VALUE_ONLY) the same launch also runs the reverse DP
+ * T[i,j] = d[i,j] + softmin_gamma(T[i+1,j+1], T[i+1,j], T[i,j+1]), T[N+1,M+1] = 0, whose table the
+ * backward call combines with R:  E[i,j] = exp((R[N,M] - R[i,j] - T[i,j] + d[i,j]) / gamma),
+ * which is the log-space recurrence of Sec. 4.2 solved for E.
  */
 int sdtw_forward(const sdtw_desc *desc, const float *x, const float *y, float *value,
                  void *workspace, size_t workspace_bytes, void *stream);

@@ -14,6 +14,7 @@ _lib = None
 
 UNFUSED = 0
 FUSED = 1
+FLAG_VALUE_ONLY = 1
 EXPORT_COST, EXPORT_R, EXPORT_E = 0, 1, 2
 
 STATUS_OK = 0
@@ -189,13 +190,16 @@ def _desc_for(x, y, gamma, mode):
     return make_desc(B, N, M, D, gamma, mode, x_shared, y_shared)
 
 
-def sdtw_forward(x, y, gamma, mode=FUSED, workspace=None, value=None, stream=None):
+def sdtw_forward(x, y, gamma, mode=FUSED, workspace=None, value=None, stream=None, value_only=False):
     """value[b] = sdtw_gamma(x_b, y_b).  Returns (value, desc, workspace); keep the last two for
-    :func:`sdtw_backward`.  x [B,N,D] or [N,D]; y [B,M,D] or [M,D]; float32 device tensors."""
+    :func:`sdtw_backward`.  x [B,N,D] or [N,D]; y [B,M,D] or [M,D]; float32 device tensors.
+    ``value_only=True`` sets SDTW_FLAG_VALUE_ONLY: no backward call will follow."""
     import torch
 
     lib = load_library()
     desc = _desc_for(x, y, gamma, mode)
+    if value_only:
+        desc.flags = FLAG_VALUE_ONLY
     if workspace is None:
         nbytes = sdtw_workspace_bytes(desc)
         if nbytes == 0:

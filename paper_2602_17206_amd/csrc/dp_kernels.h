@@ -445,6 +445,13 @@ template <int SLOTS> struct WgShared {
     int simd_count[4];
 };
 
+// Values the band's edge row (last row in the forward sweep, first in the reverse sweep) produced
+// in the current macro-step, one per step, for the neighbouring band: double[SLOTS][kEdgeOut] in
+// LDS.  Every lane writes its value each step; only the edge lane's address points into [0,32),
+// the others write to slots of their own behind it.  (Kept as an object of its own, so that these
+// stores are known not to touch the ring or the incoming boundary values.)
+constexpr int kEdgeOut = kBlk + kBandRows + kBlk;
+
 // Groups the wavefronts that share a SIMD as consumer (0) and producers (1, 2) of one band slot.
 // If the wavefronts are not spread evenly over the SIMDs, falls back to wavefront w -> role w/4,
 // slot w%4.
@@ -474,19 +481,12 @@ __device__ __forceinline__ void elect_role(WgShared<4> &sh, int lane, int w, int
 //   (float32 from x and y);  KCH < 0: unfused.
 // ---------------------------------------------------------------------------------------------
 template <int KCH, int SLOTS, int NPROD>
-__global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Params p, float *__restrict__ value)
+__device__ __forceinline__ void forward_dp_body(const Params &p, float *__restrict__ value, WgShared<SLOTS> &sh,
+                                                unsigned &ticket_s, double (&edge_out)[SLOTS][kEdgeOut])
 {
     static_assert(SLOTS == 4 || SLOTS == 1, "supported workgroup shapes");
     static_assert(NPROD == 1 || (NPROD == 2 && KCH > 0), "two producers only split MFMA work");
     constexpr int kThreads = wg_threads(SLOTS, NPROD);
-    __shared__ WgShared<SLOTS> sh;
-    __shared__ unsigned ticket_s;
-    // Values the band's edge row (last row in the forward sweep, first in the backward sweep)
-    // produced in the current macro-step, one per step, for the neighbouring band.  Every lane
-    // writes its value each step; only the edge lane's address points into [0,32), the others write
-    // to slots of their own behind it.  (An object of its own, so that these stores are known not to
-    // touch the ring or the incoming boundary values.)
-    __shared__ double edge_out[SLOTS][kBlk + kBandRows + kBlk];
     const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
     if (threadIdx.x == 0) ticket_s = atomicAdd(&p.hdr->fwd_ticket, 1u);
@@ -723,19 +723,15 @@ __device__ __forceinline__ void flush_E_block(const Params &p, const float *ring
 }
 
 template <int KCH, int SLOTS, int NPROD>
-__global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(Params p)
+__device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS> &sh, unsigned &ticket_s,
+                                                double (&edge_out)[SLOTS][kEdgeOut])
 {
     static_assert(SLOTS == 4 || SLOTS == 1, "supported workgroup shapes");
     static_assert(NPROD == 1 || (NPROD == 2 && KCH > 0), "two producers only split MFMA work");
     constexpr int kThreads = wg_threads(SLOTS, NPROD);
-    __shared__ WgShared<SLOTS> sh;
-    __shared__ unsigned ticket_s;
-    // Values the band's edge row (last row in the forward sweep, first in the backward sweep)
-    // produced in the current macro-step, one per step, for the neighbouring band.  Every lane
-    // writes its value each step; only the edge lane's address points into [0,32), the others write
-    // to slots of their own behind it.  (An object of its own, so that these stores are known not to
-    // touch the ring or the incoming boundary values.)
-    __shared__ double edge_out[SLOTS][kBlk + kBandRows + kBlk];
+    // One band per workgroup is the shape of small problems, where this sweep runs beside the
+    // forward sweep: it cannot use R, so it only stores its own table for alignment_kernel.
+    constexpr bool TSWEEP = (SLOTS == 1);
     const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (p.hdr->abort_backward) return;
 
@@ -769,7 +765,7 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
 
     float *Eb = p.E + (size_t)bb * N * M;
     unsigned char *nzb = p.nz + (size_t)bb * p.nrb * p.ncb;
-    constexpr bool kProducerFlush = !dp_recompute(KCH, SLOTS);
+    constexpr bool kProducerFlush = !dp_recompute(KCH, SLOTS) && !TSWEEP;
 
     if (producer) {
         // Besides the cost blocks, the producers write out the E blocks the consumer finished in the
@@ -886,13 +882,15 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
     const int s_corner = (live && row0 + lane == N - 1) ? (M - 1 + lane) : -1;
     const int t_last = N - 1 - row0;
     const int sg_corner = (live && t_last < kBandRows) ? (M - 1 + t_last) / kBlk : -1;
-    const double Rfin = live ? p.rfinal[b] : 0.0;
+    const double Rfin = (live && !TSWEEP) ? p.rfinal[b] : 0.0;
     const int kc = live ? k : 0;
     const bool has_below = live && (k + 1 < p.nbands);
     constexpr bool RECOMP = dp_recompute(KCH, SLOTS);
     const unsigned long long *brow_in = p.brow_b + ((size_t)bb * p.nbands + (has_below ? kc + 1 : kc)) * M;
     unsigned long long *brow_out = p.brow_b + ((size_t)bb * p.nbands + kc) * M;
-    const double *Rk = RECOMP ? nullptr : p.R + ((size_t)bb * p.nbands + kc) * (size_t)p.nmacro * kBlk * kBandRows;
+    const size_t band_off = ((size_t)bb * p.nbands + kc) * (size_t)p.nmacro * kBlk * kBandRows;
+    const double *Rk = (RECOMP || TSWEEP) ? nullptr : p.R + band_off;
+    double *Qk = TSWEEP ? p.Q + band_off : nullptr;
     const double *Ck = RECOMP ? p.ckpt + ((size_t)bb * p.nbands + kc) * (size_t)p.nmacro * 2 * kBandRows : nullptr;
     // the forward's row above this band (final values, written by the forward call)
     const double *ftop_g = reinterpret_cast<const double *>(p.brow) + ((size_t)bb * p.nbands + (kc > 0 ? kc - 1 : 0)) * M;
@@ -913,7 +911,7 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
             const int jf = sg0 * kBlk + lane;
             if (k > 0 && lane < kBlk && jf < M) ftop_next = ftop_g[jf];
         }
-    } else {
+    } else if constexpr (!TSWEEP) {
 #pragma unroll
         for (int u = 0; u < kBlk; ++u)  // (Rk points at a valid band also for an idle slot: no branch per load)
             Rq[u] = Rfin - Rk[((size_t)sg0 * kBlk + u) * kBandRows + lane];
@@ -939,7 +937,8 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
             const bool need_n = has_below && lane >= kBlk && jn >= 0 && jn < M;
             if (has_below) nxt_bits = peek_boundary(brow_in, jn, need_n);
             float *rd = my_ring + (sg & 3) * kBlk;
-            const double *Rn = RECOMP ? nullptr : Rk + (size_t)(sg > 0 ? sg - 1 : 0) * kBlk * kBandRows;
+            const double *Rn = (RECOMP || TSWEEP) ? nullptr : Rk + (size_t)(sg > 0 ? sg - 1 : 0) * kBlk * kBandRows;
+            double *Qs = TSWEEP ? Qk + (size_t)sg * kBlk * kBandRows : nullptr;
             const int sbase = sg * kBlk;
             if constexpr (RECOMP) {
                 // recompute R of this macro-step from the forward's checkpoint (same arithmetic, same
@@ -975,10 +974,18 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
                 double m;
                 float L;
                 softmin3_parts(dg, down, right, m, L);
-                const double cur = fma((double)dc, c2d, m) - (double)L;
-                // log2 E = R[N,M] - R[i,j] - (m - L) in table units
-                rd[u] = __builtin_amdgcn_exp2f((float)(Rq[u] - m) + L);
-                if constexpr (!RECOMP) Rq[u] = Rfin - __builtin_nontemporal_load(&Rn[u * kBandRows + lane]);
+                double cur;
+                if constexpr (TSWEEP) {
+                    // the soft-minimum part Q = T - d goes to the table: log2 E = R[N,M] - R[i,j] - Q[i,j]
+                    const double q = m - (double)L;
+                    __builtin_nontemporal_store(q, &Qs[u * kBandRows + lane]);
+                    cur = fma((double)dc, c2d, q);
+                } else {
+                    cur = fma((double)dc, c2d, m) - (double)L;
+                    // log2 E = R[N,M] - R[i,j] - (m - L) in table units
+                    rd[u] = __builtin_amdgcn_exp2f((float)(Rq[u] - m) + L);
+                    if constexpr (!RECOMP) Rq[u] = Rfin - __builtin_nontemporal_load(&Rn[u * kBandRows + lane]);
+                }
                 my_eo[u] = cur;  // lane 0: value of column 32*sg + u for the band above
                 diag = down;
                 right = cur;
@@ -996,7 +1003,7 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
             }
             // the E blocks this macro-step completed, (upper rows, sg) and (lower rows, sg-1): written
             // out by the producers during the next macro-step, or here
-            if constexpr (!kProducerFlush) {
+            if constexpr (!kProducerFlush && !TSWEEP) {
                 flush_E_block(p, ring, Eb, nzb, 0, sg, row0, lane);
                 flush_E_block(p, ring, Eb, nzb, 1, sg - 1, row0, lane);
             }
@@ -1006,6 +1013,41 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
         }
         __syncthreads();
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Kernels: the sweeps alone (large problems: forward call, then backward call), or both in one
+// launch (small problems: even workgroups sweep forward, odd ones in reverse; the two sweeps
+// share nothing but the cost).
+// ---------------------------------------------------------------------------------------------
+template <int KCH, int SLOTS, int NPROD>
+__global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Params p, float *__restrict__ value)
+{
+    __shared__ WgShared<SLOTS> sh;
+    __shared__ unsigned ticket_s;
+    __shared__ double edge_out[SLOTS][kEdgeOut];
+    forward_dp_body<KCH, SLOTS, NPROD>(p, value, sh, ticket_s, edge_out);
+}
+
+template <int KCH, int SLOTS, int NPROD>
+__global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(Params p)
+{
+    __shared__ WgShared<SLOTS> sh;
+    __shared__ unsigned ticket_s;
+    __shared__ double edge_out[SLOTS][kEdgeOut];
+    reverse_dp_body<KCH, SLOTS, NPROD>(p, sh, ticket_s, edge_out);
+}
+
+template <int KCH, int NPROD>
+__global__ __launch_bounds__(wg_threads(1, NPROD)) void both_sweeps_kernel(Params p, float *__restrict__ value)
+{
+    __shared__ WgShared<1> sh;
+    __shared__ unsigned ticket_s;
+    __shared__ double edge_out[1][kEdgeOut];
+    if (blockIdx.x & 1)
+        reverse_dp_body<KCH, 1, NPROD>(p, sh, ticket_s, edge_out);
+    else
+        forward_dp_body<KCH, 1, NPROD>(p, value, sh, ticket_s, edge_out);
 }
 
 }  // namespace sdtw

@@ -45,12 +45,14 @@ __global__ __launch_bounds__(256) void forward_prep_kernel(Params p, int64_t xro
         h->B = p.B; h->N = p.N; h->M = p.M; h->D = p.D; h->mode = p.mode;
         h->gamma_bits = __float_as_uint(p.gamma);
         h->forward_done = 1;
+        h->two_sweep = p.two_sweep;
         h->status = 0;
         h->abort_backward = 0;
         h->fwd_ticket = 0;
         h->bwd_ticket = 0;
     }
     fill_boundary_rows(p, p.brow);
+    if (p.two_sweep) fill_boundary_rows(p, p.brow_b);  // the reverse sweep runs in the same call
     const int lane = threadIdx.x & 63;
     const int64_t rows = xrows + yrows;
     const int64_t stride = (int64_t)gridDim.x * 4;
@@ -93,15 +95,29 @@ __global__ __launch_bounds__(256) void forward_prep_kernel(Params p, int64_t xro
     }
 }
 
-// Start of a backward call, one launch: checks that the workspace holds the forward of this
-// descriptor, resets the ticket and marks every boundary value "not written yet".
+// Does the workspace hold the forward of this descriptor?
+__device__ __forceinline__ bool workspace_matches(const Params &p)
+{
+    const Header *h = p.hdr;
+    return h->magic == kMagic && h->forward_done == 1 && h->B == p.B && h->N == p.N && h->M == p.M &&
+           h->D == p.D && h->mode == p.mode && h->two_sweep == p.two_sweep &&
+           h->gamma_bits == __float_as_uint(p.gamma);
+}
+
+// A backward call's outputs are NaN when the workspace does not match or a sweep gave up waiting.
+__device__ __forceinline__ bool backward_refused(const Params &p)
+{
+    return p.hdr->abort_backward != 0 || !workspace_matches(p) || p.hdr->status != 0;
+}
+
+// Start of a backward call that runs the reverse sweep itself, one launch: checks that the
+// workspace holds the forward of this descriptor, resets the ticket and marks every boundary value
+// "not written yet".
 __global__ __launch_bounds__(256) void backward_prep_kernel(Params p)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
         Header *h = p.hdr;
-        const bool ok = h->magic == kMagic && h->forward_done == 1 && h->B == p.B && h->N == p.N &&
-                        h->M == p.M && h->D == p.D && h->mode == p.mode &&
-                        h->gamma_bits == __float_as_uint(p.gamma);
+        const bool ok = workspace_matches(p);
         h->bwd_ticket = 0;
         if (ok) {
             h->abort_backward = 0;
@@ -141,6 +157,91 @@ __global__ __launch_bounds__(256) void cost_tensor_kernel(Params p)
 }
 
 // ---------------------------------------------------------------------------------------------
+// Alignment matrix from the two tables (small problems, where the forward call ran both sweeps).
+// With T the reverse DP over the same costs, R[i,j] + T[i,j] - d[i,j] is the soft-minimum cost of
+// all alignments through cell (i,j), so
+//     E[i,j] = exp((R[N,M] - R[i,j] - T[i,j] + d[i,j]) / gamma),
+// which satisfies the log-space recurrence of Sec. 4.2 (divide that recurrence by E and substitute).
+// The reverse sweep stores Q = T - d (its soft-minimum part), so no cost is needed here, and both
+// tables are in units of gamma*ln2:  log2 E = R[N,M] - R - Q.
+// One workgroup un-skews 64 rows x 128 columns: it reads the step-major rows s = j + t of both
+// tables (512 contiguous bytes each), drops E into an LDS tile at [t][j], then writes the tile out
+// row-major with the per-32x32-block "any non-zero" flags the gradient kernel uses.
+// ---------------------------------------------------------------------------------------------
+constexpr int kAlignCols = 128;
+constexpr int kAlignStride = kAlignCols + 2;  // floats per LDS row: lane t writes at t*(stride-1)+const, odd => no bank conflicts
+
+__global__ __launch_bounds__(256) void alignment_kernel(Params p)
+{
+    __shared__ float tile[kBandRows * kAlignStride];
+    __shared__ int flags[8];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int j0 = blockIdx.x * kAlignCols, k = blockIdx.y, b = blockIdx.z;
+    const int row0 = k * kBandRows;
+    float *Eb = p.E + (size_t)b * p.N * p.M;
+    unsigned char *nzb = p.nz + (size_t)b * p.nrb * p.ncb;
+
+    if (backward_refused(p)) {
+        // record why (the status word keeps a time-out of the sweeps), leave NaN behind
+        if (tid == 0 && blockIdx.x == 0 && k == 0 && b == 0 && p.hdr->status == 0) {
+            p.hdr->magic = kMagic;
+            p.hdr->status = kStatusState;
+            p.hdr->abort_backward = 1;
+        }
+        return;
+    }
+
+    if (tid < 8) flags[tid] = 0;
+    const size_t band_elems = (size_t)p.nmacro * kBlk * kBandRows;
+    const double *Rk = p.R + ((size_t)b * p.nbands + k) * band_elems;
+    const double *Qk = p.Q + ((size_t)b * p.nbands + k) * band_elems;
+    const double Rfin = p.rfinal[b];
+    const bool row_ok = row0 + lane < p.N;
+    const int s_end = min(j0 + kAlignCols + kBandRows - 1, p.nmacro * kBlk);
+#pragma unroll 4
+    for (int s = j0 + w; s < s_end; s += 4) {
+        const int j = s - lane;
+        const double r = __builtin_nontemporal_load(&Rk[(size_t)s * kBandRows + lane]);
+        const double q = __builtin_nontemporal_load(&Qk[(size_t)s * kBandRows + lane]);
+        if (j >= j0 && j < j0 + kAlignCols) {
+            const float e = __builtin_amdgcn_exp2f((float)((Rfin - r) - q));
+            tile[lane * kAlignStride + (j - j0)] = (row_ok && j < p.M) ? e : 0.f;
+        }
+    }
+    __syncthreads();
+
+    // write-out: wavefront w takes rows w, w+4, ...; a lane takes columns lane and lane+64
+    bool any[2][2] = {{false, false}, {false, false}};  // [row block][column half]
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int r = w + 4 * i;
+        const int row = row0 + r;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int c = lane + 64 * h, j = j0 + c;
+            const float e = tile[r * kAlignStride + c];  // zero outside the grid
+            if (row < p.N && j < p.M) Eb[(size_t)row * p.M + j] = e;
+            any[i >> 3][h] |= (e != 0.f);
+        }
+    }
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const unsigned long long m = __ballot(any[rb][h]);
+            if (lane == 0) {
+                if (m & 0xFFFFFFFFull) atomicOr(&flags[rb * 4 + 2 * h], 1);
+                if (m >> 32) atomicOr(&flags[rb * 4 + 2 * h + 1], 1);
+            }
+        }
+    __syncthreads();
+    if (tid < 8) {
+        const int rb = row0 / kBlk + (tid >> 2), cb = j0 / kBlk + (tid & 3);
+        if (rb < p.nrb && cb < p.ncb) nzb[(size_t)rb * p.ncb + cb] = flags[tid] ? 1 : 0;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Input gradients (Sec. 4.3):  dx_i = 2 g (x_i sum_j E_ij - sum_j E_ij y_j),  dy_j alike.
 // One launch covers both: blockIdx.z = 2*b + side.  A workgroup (4 wavefronts) owns a 64 x 64
 // output tile (64 sequence positions x 64 features) and walks the other sequence in chunks of 32,
@@ -172,7 +273,7 @@ __global__ __launch_bounds__(256) void input_grad_kernel(Params p, const float *
     out += (size_t)b * P * p.D;
     const int wr = w >> 1, wc = w & 1;
 
-    if (p.hdr->abort_backward) {
+    if (backward_refused(p)) {
         const float qnan = __builtin_nanf("");
         for (int e = tid; e < 64 * 64; e += 256) {
             const int m = m0 + (e >> 6), n = n0 + (e & 63);
@@ -294,7 +395,7 @@ __global__ __launch_bounds__(256) void input_grad_kernel(Params p, const float *
 __global__ void export_E_kernel(Params p, float *__restrict__ dst)
 {
     const size_t n = (size_t)p.B * p.N * p.M;
-    const bool bad = p.hdr->abort_backward != 0;
+    const bool bad = backward_refused(p);
     const float qnan = __builtin_nanf("");
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;

@@ -26,7 +26,8 @@ struct Header {
     int32_t abort_backward;
     uint32_t fwd_ticket;   // next band task of the forward sweep
     uint32_t bwd_ticket;   // next band task of the backward sweep
-    uint32_t pad[52];
+    int32_t two_sweep;     // the forward call also ran the reverse sweep
+    uint32_t pad[51];
 };
 static_assert(sizeof(Header) == 256, "header is 256 bytes");
 
@@ -38,8 +39,9 @@ struct Layout {
     int64_t xn_count, yn_count;  // number of norm entries (1 sequence when the batch stride is 0)
     int32_t Dp;                  // D rounded up to 16: row length of the split-half operand copies (0: none)
     int32_t recompute;           // 1: checkpoints instead of the R table (large fused problems)
+    int32_t two_sweep;           // 1: the forward call also runs the reverse sweep and stores its table Q
     size_t off_hdr, off_rfinal, off_xn, off_yn, off_xis, off_yis, off_xh, off_yh, off_brow, off_brow_b, off_R,
-        off_ckpt, off_cost, off_E, off_nz, total;
+        off_Q, off_ckpt, off_cost, off_E, off_nz, total;
 };
 
 // With D <= 128 the workspace keeps a copy of x and y split into two float16 pieces per element
@@ -53,7 +55,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int64_t steps_of(const Layout &L) { return (int64_t)L.nmacro * kBlk; }
 
 inline Layout make_layout(int32_t B, int32_t N, int32_t M, int32_t D, int32_t mode, bool x_shared,
-                          bool y_shared, bool recompute)
+                          bool y_shared, bool recompute, bool two_sweep)
 {
     Layout L{};
     L.B = B; L.N = N; L.M = M; L.D = D; L.mode = mode;
@@ -75,15 +77,22 @@ inline Layout make_layout(int32_t B, int32_t N, int32_t M, int32_t D, int32_t mo
     L.off_yh = o;       o = align_up(o + (size_t)L.yn_count * L.Dp * 2 * sizeof(uint16_t), 256);
     // boundary rows: one row of M float64 per (pair, band)
     L.recompute = recompute ? 1 : 0;
+    L.two_sweep = two_sweep ? 1 : 0;
     const size_t brow_bytes = (size_t)B * L.nbands * (size_t)M * sizeof(double);
     L.off_brow = o;     o = align_up(o + brow_bytes, 256);
-    // with recomputation the backward needs the forward's boundary rows, so it gets rows of its own
-    L.off_brow_b = recompute ? o : L.off_brow;
-    if (recompute) o = align_up(o + brow_bytes, 256);
+    // the reverse sweep gets rows of its own when the forward's must survive (recomputation) or when
+    // both sweeps run at the same time
+    const bool own_rows = recompute || two_sweep;
+    L.off_brow_b = own_rows ? o : L.off_brow;
+    if (own_rows) o = align_up(o + brow_bytes, 256);
     // DP table in step-major order: [B][nbands][steps][64] float64 - or, with recomputation, only
     // the lane state (left, diagonal) at the start of every macro-step: [B][nbands][nmacro][2][64]
+    const size_t table_bytes = (size_t)B * L.nbands * (size_t)steps_of(L) * kBandRows * sizeof(double);
     L.off_R = o;
-    if (!recompute) o = align_up(o + (size_t)B * L.nbands * (size_t)steps_of(L) * kBandRows * sizeof(double), 256);
+    if (!recompute) o = align_up(o + table_bytes, 256);
+    // table of the reverse sweep, same order as R
+    L.off_Q = o;
+    if (two_sweep) o = align_up(o + table_bytes, 256);
     L.off_ckpt = o;
     if (recompute) o = align_up(o + (size_t)B * L.nbands * (size_t)L.nmacro * 2 * kBandRows * sizeof(double), 256);
     o += kGuardBytes;
@@ -121,8 +130,10 @@ struct Params {
     unsigned long long *brow;      // boundary rows of the forward sweep
     unsigned long long *brow_b;    // boundary rows of the backward sweep (== brow unless recompute)
     double *R;
+    double *Q;                     // two_sweep: table of the reverse sweep (soft-minimum part), ordered like R
     double *ckpt;                  // recompute: forward lane state per macro-step
     int32_t recompute;
+    int32_t two_sweep;
     float *cost;
     float *E;
     unsigned char *nz;

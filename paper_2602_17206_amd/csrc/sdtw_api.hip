@@ -48,7 +48,7 @@ bool desc_ok(const sdtw_desc *d, int *why)
     if (d->B > 32767) return false;
     if (!(d->gamma > 0.0f) || !std::isfinite(d->gamma)) return false;
     if (d->mode != SDTW_UNFUSED && d->mode != SDTW_FUSED) return false;
-    if (d->flags != 0) return false;
+    if ((d->flags & ~(uint32_t)SDTW_FLAG_VALUE_ONLY) != 0) return false;
     if (d->x_batch_stride != 0 && d->x_batch_stride != (int64_t)d->N * d->D) return false;
     if (d->y_batch_stride != 0 && d->y_batch_stride != (int64_t)d->M * d->D) return false;
     if ((int64_t)d->M + 128 > 0x3FFFFFFF || (int64_t)d->N + 128 > 0x3FFFFFFF) return false;
@@ -66,8 +66,11 @@ bool small_problem(const sdtw_desc *d)
 
 Layout layout_of(const sdtw_desc *d)
 {
-    const bool recompute = d->mode == SDTW_FUSED && !small_problem(d);  // == dp_recompute(KCH >= 0, SLOTS == 4)
-    return make_layout(d->B, d->N, d->M, d->D, d->mode, d->x_batch_stride == 0, d->y_batch_stride == 0, recompute);
+    const bool small = small_problem(d);
+    const bool recompute = d->mode == SDTW_FUSED && !small;  // == dp_recompute(KCH >= 0, SLOTS == 4)
+    const bool two_sweep = small && !(d->flags & SDTW_FLAG_VALUE_ONLY);
+    return make_layout(d->B, d->N, d->M, d->D, d->mode, d->x_batch_stride == 0, d->y_batch_stride == 0, recompute,
+                       two_sweep);
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -105,6 +108,8 @@ Params make_params(const sdtw_desc *d, const Layout &L, const float *x, const fl
     p.brow = reinterpret_cast<unsigned long long *>(base + L.off_brow);
     p.brow_b = reinterpret_cast<unsigned long long *>(base + L.off_brow_b);
     p.R = reinterpret_cast<double *>(base + L.off_R);
+    p.Q = reinterpret_cast<double *>(base + L.off_Q);
+    p.two_sweep = L.two_sweep;
     p.ckpt = reinterpret_cast<double *>(base + L.off_ckpt);
     p.recompute = L.recompute;
     p.cost = reinterpret_cast<float *>(base + L.off_cost);
@@ -124,37 +129,33 @@ int fused_variant(int D)
     return 0;
 }
 
-// Launches the forward (FWD) or backward DP kernel in the workgroup shape that suits the problem:
-// up to 1024 band tasks cannot fill the chip, so each band gets a small workgroup of its own
-// (consumer and producers on different SIMDs); larger problems use 4-band workgroups in which the
-// producer and the consumer of a band share a SIMD.
-template <bool FWD, int KCH, int SLOTS, int NPROD>
-void launch_dp_shape(const sdtw_desc *d, const Layout &L, const Params &p, float *value, hipStream_t st)
-{
-    const unsigned tasks = (unsigned)((d->B + SLOTS - 1) / SLOTS) * (unsigned)L.nbands;
-    if constexpr (FWD)
-        forward_dp_kernel<KCH, SLOTS, NPROD><<<tasks, wg_threads(SLOTS, NPROD), 0, st>>>(p, value);
-    else
-        backward_dp_kernel<KCH, SLOTS, NPROD><<<tasks, wg_threads(SLOTS, NPROD), 0, st>>>(p);
-}
-
+// Launches the DP kernels in the workgroup shape that suits the problem.  Up to 1024 band tasks
+// cannot fill the chip: each band gets a small workgroup of its own (consumer and producers on
+// different SIMDs), and the forward call runs the reverse sweep in the same launch (FWD, unless
+// only the value is wanted); its backward call launches no DP kernel.  Larger problems use 4-band
+// workgroups in which the producer and the consumer of a band share a SIMD, forward sweep in the
+// forward call, reverse sweep in the backward call.
 template <bool FWD, int KCH>
 void launch_dp_kch(const sdtw_desc *d, const Layout &L, const Params &p, float *value, hipStream_t st)
 {
-    const bool small = small_problem(d);
-    if (small) {
-        if constexpr (KCH > 0)
-            launch_dp_shape<FWD, KCH, 1, 2>(d, L, p, value, st);
-        else
-            launch_dp_shape<FWD, KCH, 1, 1>(d, L, p, value, st);
+    constexpr int NP = KCH > 0 ? 2 : 1;
+    if (small_problem(d)) {
+        const unsigned tasks = (unsigned)d->B * (unsigned)L.nbands;
+        if constexpr (FWD) {
+            if (L.two_sweep)
+                both_sweeps_kernel<KCH, NP><<<2 * tasks, wg_threads(1, NP), 0, st>>>(p, value);
+            else
+                forward_dp_kernel<KCH, 1, NP><<<tasks, wg_threads(1, NP), 0, st>>>(p, value);
+        }
     } else {
+        const unsigned tasks = (unsigned)((d->B + 3) / 4) * (unsigned)L.nbands;
         // The forward splits the cost blocks over two producers per band (register budget 168 per
         // wavefront); the recomputing backward consumer needs more registers than that, and its
         // long macro-steps leave a single producer enough time.
-        if constexpr (KCH > 0 && FWD)
-            launch_dp_shape<FWD, KCH, 4, 2>(d, L, p, value, st);
+        if constexpr (FWD)
+            forward_dp_kernel<KCH, 4, NP><<<tasks, wg_threads(4, NP), 0, st>>>(p, value);
         else
-            launch_dp_shape<FWD, KCH, 4, 1>(d, L, p, value, st);
+            backward_dp_kernel<KCH, 4, 1><<<tasks, wg_threads(4, 1), 0, st>>>(p);
     }
 }
 
@@ -214,7 +215,9 @@ int forward_impl(const sdtw_desc *d, const float *x, const float *y, float *valu
         }
     }
     {
-        ProfScope ps(d->mode == SDTW_UNFUSED ? "forward_dp_unfused" : "forward_dp_fused", st);
+        const bool unf = d->mode == SDTW_UNFUSED;
+        ProfScope ps(L.two_sweep ? (unf ? "both_sweeps_unfused" : "both_sweeps_fused")
+                                 : (unf ? "forward_dp_unfused" : "forward_dp_fused"), st);
         launch_dp<true>(d, L, p, value, st);
     }
     return hip_ok();
@@ -225,13 +228,20 @@ int backward_impl(const sdtw_desc *d, const float *x, const float *y, const floa
 {
     const Layout L = layout_of(d);
     const Params p = make_params(d, L, x, y, ws);
-    {
-        ProfScope ps("backward_prep", st);
-        backward_prep_kernel<<<prep_grid(p, 0), 256, 0, st>>>(p);
-    }
-    {
-        ProfScope ps(d->mode == SDTW_UNFUSED ? "backward_dp_unfused" : "backward_dp_fused", st);
-        launch_dp<false>(d, L, p, nullptr, st);
+    if (L.two_sweep) {
+        // both tables are there: combine them (the kernel checks the workspace itself)
+        ProfScope ps("alignment", st);
+        dim3 g((d->M + kAlignCols - 1) / kAlignCols, L.nbands, d->B);
+        alignment_kernel<<<g, 256, 0, st>>>(p);
+    } else {
+        {
+            ProfScope ps("backward_prep", st);
+            backward_prep_kernel<<<prep_grid(p, 0), 256, 0, st>>>(p);
+        }
+        {
+            ProfScope ps(d->mode == SDTW_UNFUSED ? "backward_dp_unfused" : "backward_dp_fused", st);
+            launch_dp<false>(d, L, p, nullptr, st);
+        }
     }
     if (dx || dy) {
         const int P = std::max(dx ? d->N : 0, dy ? d->M : 0);
@@ -329,6 +339,7 @@ int sdtw_backward(const sdtw_desc *desc, const float *x, const float *y, const f
     int why;
     if (!desc_ok(desc, &why)) return why;
     if (!x || !y) return SDTW_ERR_INVALID_ARG;
+    if (desc->flags & SDTW_FLAG_VALUE_ONLY) return SDTW_ERR_STATE;
     if (int rc = check_ws(workspace, workspace_bytes, layout_of(desc).total)) return rc;
     return backward_impl(desc, x, y, grad_value, dx, dy, E_out, workspace, static_cast<hipStream_t>(stream));
 }

@@ -36,19 +36,27 @@ def test_struct_sizes_match_the_header_layout():
 
 
 def test_workspace_sizes():
+    # small problems (up to 1024 band tasks): float64 tables of both sweeps, float32 E
     d_f = binding.make_desc(32, 1024, 1024, 128, 0.1, pkg.FUSED)
     d_u = binding.make_desc(32, 1024, 1024, 128, 0.1, pkg.UNFUSED)
     wf, wu = pkg.sdtw_workspace_bytes(d_f), pkg.sdtw_workspace_bytes(d_u)
     cells = 32 * 1024 * 1024
-    split = 2 * 32 * 1024 * (128 * 2 * 2 + 4)         # fused only: float16 split copies of x, y and their scales
-    assert 4 * cells - split - 4096 <= wu - wf <= 4 * cells   # the cost tensor exists only in unfused mode
-    assert wf < 13.2 * cells + split                  # float64 table (+ skew padding) and float32 E
+    assert 4 * cells - 4096 <= wu - wf <= 4 * cells   # the cost tensor exists only in unfused mode
+    split = 2 * 32 * 1024 * (128 * 2 * 2 + 4)         # float16 split copies of x, y and their scales
+    assert 20 * cells < wf < 22 * cells + split       # 2 x (8 B + skew padding) + 4 B
+    # value only: one table
+    d_v = binding.make_desc(32, 1024, 1024, 128, 0.1, pkg.FUSED, flags=pkg.FLAG_VALUE_ONLY)
+    wv = pkg.sdtw_workspace_bytes(d_v)
+    assert 8 * cells < wf - wv < 9 * cells
+    # large fused problems keep checkpoints instead of the table
+    d_l = binding.make_desc(32, 8192, 8192, 64, 0.1, pkg.FUSED)
+    assert pkg.sdtw_workspace_bytes(d_l) < 5.0 * 32 * 8192 * 8192
     assert pkg.sdtw_workspace_bytes(binding.make_desc(1, 1, 1, 1, 1.0, pkg.FUSED)) > 0
 
 
 @pytest.mark.parametrize("kw", [
     dict(B=0), dict(N=0), dict(M=-3), dict(D=0), dict(gamma=0.0), dict(gamma=-1.0), dict(gamma=float("nan")),
-    dict(gamma=float("inf")), dict(mode=2), dict(mode=-1), dict(flags=1), dict(bandwidth=5),
+    dict(gamma=float("inf")), dict(mode=2), dict(mode=-1), dict(flags=2), dict(bandwidth=5),
 ])
 def test_invalid_descriptors_need_zero_bytes_and_are_refused(kw):
     args = dict(B=2, N=8, M=8, D=4, gamma=1.0, mode=pkg.FUSED)

@@ -214,6 +214,42 @@ def test_symmetry():
     np.testing.assert_allclose(a["dx"], b["dy"], atol=1e-4 * np.abs(a["dx"]).max())
 
 
+def test_value_only_forward_matches_and_refuses_backward():
+    import torch
+
+    x, y = workloads.normal_pairs(11, 3, 150, 170, 12)
+    xd, yd = to_dev(x), to_dev(y)
+    ref = oracle.batch(x, y, 0.2, backward=False)
+    for mode in (pkg.UNFUSED, pkg.FUSED):
+        value, desc, ws = pkg.sdtw_forward(xd, yd, 0.2, mode, value_only=True)
+        torch.cuda.synchronize()
+        assert binding.workspace_status(ws) == 0
+        np.testing.assert_allclose(value.cpu().numpy(), ref["value"], rtol=VALUE_RTOL)
+        full = pkg.sdtw_workspace_bytes(binding.make_desc(3, 150, 170, 12, 0.2, mode))
+        assert ws.nbytes < full
+        with pytest.raises(pkg.SdtwError) as err:
+            pkg.sdtw_backward(desc, xd, yd, ws)
+        assert err.value.status == binding.STATUS_STATE
+
+
+def test_backward_twice_after_one_forward_gives_the_same_result():
+    import torch
+
+    x, y = workloads.normal_pairs(12, 2, 100, 130, 8)
+    xd, yd = to_dev(x), to_dev(y)
+    for shape in (1, 4):
+        binding.debug_force_workgroup_shape(shape)
+        try:
+            _, desc, ws = pkg.sdtw_forward(xd, yd, 0.3, pkg.FUSED)
+            dx1, dy1, _ = pkg.sdtw_backward(desc, xd, yd, ws)
+            dx2, dy2, _ = pkg.sdtw_backward(desc, xd, yd, ws)
+            torch.cuda.synchronize()
+        finally:
+            binding.debug_force_workgroup_shape(0)
+        assert binding.workspace_status(ws) == 0
+        assert torch.equal(dx1, dx2) and torch.equal(dy1, dy2)
+
+
 # ------------------------------------------------------------------------------- device-side errors
 def test_backward_without_forward_is_refused_on_the_device():
     import torch
