@@ -376,10 +376,12 @@ template <int KG, int DIR, int W0, int NW> struct HalfProducer {
 // ---------------------------------------------------------------------------------------------
 // Unfused cost tensor d[B,N,M] for D <= 16*KG on the fp16 matrix cores (Sec. 4.3 "unfused":
 // computed once and stored), from the same split-half copies and with the same arithmetic as the
-// fused producer.  One workgroup = 4 wavefronts = a 128 x 128 tile; each wavefront keeps the
-// pieces of its 32 rows in registers and walks four 32-column blocks.
+// fused producer.  One workgroup = 4 wavefronts = a 128-row x (32*CB)-column tile; each wavefront
+// keeps the pieces of its 32 rows in registers and walks CB 32-column blocks, loading the
+// operands of the next block while the matrix cores work on the current one.  (CB = 1 for small
+// tensors: four times the workgroups.)
 // ---------------------------------------------------------------------------------------------
-template <int KG>
+template <int KG, int CB>
 __global__ __launch_bounds__(256) void cost_tensor_half_kernel(Params p)
 {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, h = lane >> 5;
@@ -389,7 +391,20 @@ __global__ __launch_bounds__(256) void cost_tensor_half_kernel(Params p)
     const uint16_t *xh = p.xh + b * p.xh_stride, *yh = p.yh + b * p.yh_stride;
     const float *xnb = p.xn + b * p.xn_stride, *ynb = p.yn + b * p.yn_stride;
     const float *xisb = p.xis + b * p.xn_stride, *yisb = p.yis + b * p.yn_stride;
-    half8 xa[2][KG];
+    const int jbase = blockIdx.x * (32 * CB);
+    half8 xa[2][KG], ka[2][KG];
+    float ync, yisc;
+    auto load_cols = [&](int j0) {
+        const int colc = min(j0 + (lane & 31), p.M - 1);
+        const uint16_t *r = yh + (size_t)colc * (2 * p.Dp) + 8 * h;
+#pragma unroll
+        for (int g = 0; g < KG; ++g) {
+            ka[0][g] = *reinterpret_cast<const half8 *>(r + 32 * g);
+            ka[1][g] = *reinterpret_cast<const half8 *>(r + 32 * g + 16);
+        }
+        ync = ynb[colc];
+        yisc = yisb[colc];
+    };
     {
         const int row = min(i0 + (lane & 31), p.N - 1);
         const uint16_t *r = xh + (size_t)row * (2 * p.Dp) + 8 * h;
@@ -399,6 +414,7 @@ __global__ __launch_bounds__(256) void cost_tensor_half_kernel(Params p)
             xa[1][g] = *reinterpret_cast<const half8 *>(r + 32 * g + 16);
         }
     }
+    load_cols(jbase);
     float xn_r[16], m2is_r[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -407,28 +423,32 @@ __global__ __launch_bounds__(256) void cost_tensor_half_kernel(Params p)
         m2is_r[i] = -2.0f * xisb[row];
     }
     float *dst = p.cost + (size_t)b * p.N * p.M;
-    for (int cbk = 0; cbk < 4; ++cbk) {
-        const int j0 = blockIdx.x * 128 + cbk * 32;
+#pragma unroll
+    for (int cbk = 0; cbk < CB; ++cbk) {
+        const int j0 = jbase + cbk * 32;
         if (j0 >= p.M) break;
         const int col = j0 + (lane & 31);
-        const int colc = min(col, p.M - 1);
-        const uint16_t *r = yh + (size_t)colc * (2 * p.Dp) + 8 * h;
+        half8 k1[KG], k2[KG];
+#pragma unroll
+        for (int g = 0; g < KG; ++g) {
+            k1[g] = ka[0][g];
+            k2[g] = ka[1][g];
+        }
+        const float ync_now = ync, yisc_now = yisc;
+        if (cbk + 1 < CB) load_cols(min(j0 + 32, p.M - 1));  // next block's operands (clamped, maybe unused)
         floatx16 acc = zero16();
 #pragma unroll
         for (int g = 0; g < KG; ++g) {
-            const half8 k1 = *reinterpret_cast<const half8 *>(r + 32 * g);
-            const half8 k2 = *reinterpret_cast<const half8 *>(r + 32 * g + 16);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0][g], k1, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0][g], k2, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[1][g], k1, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0][g], k1[g], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0][g], k2[g], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[1][g], k1[g], acc, 0, 0, 0);
         }
-        const float ync = ynb[colc], yisc = yisb[colc];
         if (col < p.M) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int row = i0 + acc_row(i, lane);
                 if (row < p.N)
-                    dst[(size_t)row * p.M + col] = fmaxf(fmaf(acc[i], m2is_r[i] * yisc, xn_r[i] + ync), 0.0f);
+                    dst[(size_t)row * p.M + col] = fmaxf(fmaf(acc[i], m2is_r[i] * yisc_now, xn_r[i] + ync_now), 0.0f);
             }
         }
     }

@@ -56,14 +56,39 @@ __global__ __launch_bounds__(256) void forward_prep_kernel(Params p, int64_t xro
     const int lane = threadIdx.x & 63;
     const int64_t rows = xrows + yrows;
     const int64_t stride = (int64_t)gridDim.x * 4;
-    for (int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); row < rows; row += stride) {
+    // One wavefront per row, lanes stride over the features.  Up to 256 features stay in registers
+    // and the next row is loaded while the current one is reduced and converted.
+    constexpr int kRegs = 4;
+    const bool in_regs = p.D <= 64 * kRegs;
+    auto row_ptr = [&](int64_t row) { return row < xrows ? p.x + row * p.D : p.y + (row - xrows) * p.D; };
+    auto load_row = [&](float (&v)[kRegs], int64_t row) {
+        const float *r = row_ptr(row);
+#pragma unroll
+        for (int c = 0; c < kRegs; ++c) {
+            const int k = lane + 64 * c;
+            v[c] = (k < p.D) ? r[k] : 0.f;
+        }
+    };
+    float cur[kRegs] = {0.f, 0.f, 0.f, 0.f}, nxt[kRegs] = {0.f, 0.f, 0.f, 0.f};
+    int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (in_regs && row < rows) load_row(cur, row);
+    for (; row < rows; row += stride) {
+        if (in_regs && row + stride < rows) load_row(nxt, row + stride);
         const bool isx = row < xrows;
         const int64_t lr = isx ? row : row - xrows;
-        const float *r = (isx ? p.x : p.y) + lr * p.D;
+        const float *r = row_ptr(row);
         float acc = 0.f, mx = 0.f;
-        for (int k = lane; k < p.D; k += 64) {
-            acc = fmaf(r[k], r[k], acc);
-            mx = fmaxf(mx, fabsf(r[k]));
+        if (in_regs) {
+#pragma unroll
+            for (int c = 0; c < kRegs; ++c) {
+                acc = fmaf(cur[c], cur[c], acc);
+                mx = fmaxf(mx, fabsf(cur[c]));
+            }
+        } else {
+            for (int k = lane; k < p.D; k += 64) {
+                acc = fmaf(r[k], r[k], acc);
+                mx = fmaxf(mx, fabsf(r[k]));
+            }
         }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) {
@@ -76,6 +101,7 @@ __global__ __launch_bounds__(256) void forward_prep_kernel(Params p, int64_t xro
             // row's largest magnitude into [2^13, 2^14), v*s = h1 + h2 + e with h1, h2 float16 and
             // |e| <= 2^-22 |v*s| (two 11-bit significands).  The products h1*k1 + h1*k2 + h2*k1 then
             // reproduce <x_i, y_j> to about float32 accuracy (the dropped h2*k2 term is ~2^-22 relative).
+            // (Dp <= 128, so the row is in registers here.)
             int ex = 0;
             if (mx > 0.f) (void)frexpf(mx, &ex);
             ex = max(-100, min(ex, 120));
@@ -83,15 +109,21 @@ __global__ __launch_bounds__(256) void forward_prep_kernel(Params p, int64_t xro
             if (lane == 0) (isx ? p.xis : p.yis)[lr] = ldexpf(1.0f, ex - 14);
             // stored [row][group of 16 features][piece][16]
             uint16_t *h = (isx ? p.xh : p.yh) + lr * (2 * p.Dp);
-            for (int k = lane; k < p.Dp; k += 64) {
-                const float vs = (k < p.D) ? r[k] * sc : 0.f;
-                const _Float16 h1 = (_Float16)vs;
-                const _Float16 h2 = (_Float16)(vs - (float)h1);
-                const int o = 32 * (k >> 4) + (k & 15);
-                h[o] = __builtin_bit_cast(uint16_t, h1);
-                h[o + 16] = __builtin_bit_cast(uint16_t, h2);
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const int k = lane + 64 * c;
+                if (k < p.Dp) {
+                    const float vs = cur[c] * sc;  // zero beyond D
+                    const _Float16 h1 = (_Float16)vs;
+                    const _Float16 h2 = (_Float16)(vs - (float)h1);
+                    const int o = 32 * (k >> 4) + (k & 15);
+                    h[o] = __builtin_bit_cast(uint16_t, h1);
+                    h[o + 16] = __builtin_bit_cast(uint16_t, h2);
+                }
             }
         }
+#pragma unroll
+        for (int c = 0; c < kRegs; ++c) cur[c] = nxt[c];
     }
 }
 
@@ -198,14 +230,24 @@ __global__ __launch_bounds__(256) void alignment_kernel(Params p)
     const double Rfin = p.rfinal[b];
     const bool row_ok = row0 + lane < p.N;
     const int s_end = min(j0 + kAlignCols + kBandRows - 1, p.nmacro * kBlk);
-#pragma unroll 4
-    for (int s = j0 + w; s < s_end; s += 4) {
-        const int j = s - lane;
-        const double r = __builtin_nontemporal_load(&Rk[(size_t)s * kBandRows + lane]);
-        const double q = __builtin_nontemporal_load(&Qk[(size_t)s * kBandRows + lane]);
-        if (j >= j0 && j < j0 + kAlignCols) {
-            const float e = __builtin_amdgcn_exp2f((float)((Rfin - r) - q));
-            tile[lane * kAlignStride + (j - j0)] = (row_ok && j < p.M) ? e : 0.f;
+    // a wavefront takes every fourth step-row; 12 rows of both tables are in flight per wavefront
+    constexpr int kRowsInFlight = 12;
+    for (int s0 = j0 + w; s0 < s_end; s0 += 4 * kRowsInFlight) {
+        double r[kRowsInFlight], q[kRowsInFlight];
+#pragma unroll
+        for (int u = 0; u < kRowsInFlight; ++u) {
+            const int s = min(s0 + 4 * u, s_end - 1);  // clamped: no branch around the loads
+            r[u] = __builtin_nontemporal_load(&Rk[(size_t)s * kBandRows + lane]);
+            q[u] = __builtin_nontemporal_load(&Qk[(size_t)s * kBandRows + lane]);
+        }
+#pragma unroll
+        for (int u = 0; u < kRowsInFlight; ++u) {
+            const int s = s0 + 4 * u;
+            const int j = s - lane;
+            if (s < s_end && j >= j0 && j < j0 + kAlignCols) {
+                const float e = __builtin_amdgcn_exp2f((float)((Rfin - r[u]) - q[u]));
+                tile[lane * kAlignStride + (j - j0)] = (row_ok && j < p.M) ? e : 0.f;
+            }
         }
     }
     __syncthreads();
@@ -219,8 +261,9 @@ __global__ __launch_bounds__(256) void alignment_kernel(Params p)
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int c = lane + 64 * h, j = j0 + c;
-            const float e = tile[r * kAlignStride + c];  // zero outside the grid
-            if (row < p.N && j < p.M) Eb[(size_t)row * p.M + j] = e;
+            const bool inside = row < p.N && j < p.M;
+            const float e = inside ? tile[r * kAlignStride + c] : 0.f;
+            if (inside) Eb[(size_t)row * p.M + j] = e;
             any[i >> 3][h] |= (e != 0.f);
         }
     }
@@ -287,8 +330,8 @@ __global__ __launch_bounds__(256) void input_grad_kernel(Params p, const float *
     floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     float msum = 0.f;  // thread (w, lane): partial sum of E over the reduced index for output row m0+lane
 
-    for (int q0 = 0; q0 < Q; q0 += kBlk) {
-        // skip when both 32x32 E blocks of this chunk are all zero
+    // is any of the two 32x32 E blocks of the chunk at q0 non-zero?
+    auto chunk_live = [&](int q0) {
         const int qb = q0 / kBlk, mb = m0 / kBlk;
         bool live;
         if (side == 0) {
@@ -298,68 +341,71 @@ __global__ __launch_bounds__(256) void input_grad_kernel(Params p, const float *
             live = nzb[(size_t)qb * p.ncb + mb] != 0;
             if (mb + 1 < p.ncb) live |= nzb[(size_t)qb * p.ncb + mb + 1] != 0;
         }
-        if (!live) continue;
-
-        __syncthreads();  // previous chunk's reads are done
-        // A tile, k-major: At[k][m]
-        if (side == 0) {
-            // E rows i = m0+m (64), columns j = q0+k (32): thread -> (m = tid/4 .. , 8 floats)
-            for (int e = tid; e < 64 * 8; e += 256) {
-                const int m = e >> 3, k4 = (e & 7) * 4;
-                const int i = m0 + m;
-                float v[4] = {0.f, 0.f, 0.f, 0.f};
-                if (i < p.N) {
-                    const float *q = Eb + (size_t)i * p.M + q0 + k4;
-                    if (p.vec_m && q0 + k4 + 3 < p.M) {
-                        const float4 t = *reinterpret_cast<const float4 *>(q);
-                        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
-                    } else {
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) if (q0 + k4 + c < p.M) v[c] = q[c];
-                    }
-                }
-#pragma unroll
-                for (int c = 0; c < 4; ++c) At[(k4 + c) * kGradStride + m] = v[c];
-            }
+        return live;
+    };
+    auto next_live = [&](int q0) {
+        while (q0 < Q && !chunk_live(q0)) q0 += kBlk;
+        return q0;
+    };
+    auto load4 = [](const float *q, int first, int limit, bool vec) {
+        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (vec && first + 3 < limit) {
+            t = *reinterpret_cast<const float4 *>(q);
         } else {
-            // E rows i = q0+k (32), columns j = m0+m (64)
-            for (int e = tid; e < 32 * 16; e += 256) {
-                const int k = e >> 4, m4 = (e & 15) * 4;
-                const int i = q0 + k;
-                float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (i < p.N) {
-                    const float *q = Eb + (size_t)i * p.M + m0 + m4;
-                    if (p.vec_m && m0 + m4 + 3 < p.M) {
-                        t = *reinterpret_cast<const float4 *>(q);
-                    } else {
-                        if (m0 + m4 + 0 < p.M) t.x = q[0];
-                        if (m0 + m4 + 1 < p.M) t.y = q[1];
-                        if (m0 + m4 + 2 < p.M) t.z = q[2];
-                        if (m0 + m4 + 3 < p.M) t.w = q[3];
-                    }
-                }
-                *reinterpret_cast<float4 *>(At + k * kGradStride + m4) = t;
-            }
+            if (first + 0 < limit) t.x = q[0];
+            if (first + 1 < limit) t.y = q[1];
+            if (first + 2 < limit) t.z = q[2];
+            if (first + 3 < limit) t.w = q[3];
         }
-        // B tile: Bt[k][n] = oth[q0+k][n0+n]
-        for (int e = tid; e < 32 * 16; e += 256) {
-            const int k = e >> 4, n4 = (e & 15) * 4;
-            const int q = q0 + k;
-            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (q < Q) {
-                const float *src = oth + (size_t)q * p.D + n0 + n4;
-                if (p.vec_xy && n0 + n4 + 3 < p.D) {
-                    t = *reinterpret_cast<const float4 *>(src);
-                } else {
-                    if (n0 + n4 + 0 < p.D) t.x = src[0];
-                    if (n0 + n4 + 1 < p.D) t.y = src[1];
-                    if (n0 + n4 + 2 < p.D) t.z = src[2];
-                    if (n0 + n4 + 3 < p.D) t.w = src[3];
-                }
+        return t;
+    };
+    // A chunk's operands travel global -> registers -> LDS; the loads of the next chunk are issued
+    // before the matrix-core work of the current one.  Per thread: two float4 of E, two of the sequence.
+    //   side 0: E rows i = m0+m (64), columns j = q0+k (32): element e -> m = e/8, k = 4*(e%8)
+    //   side 1: E rows i = q0+k (32), columns j = m0+m (64): element e -> k = e/16, m = 4*(e%16)
+    float4 ra[2], rb[2];
+    auto fetch = [&](int q0) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int e = tid + 256 * r;
+            ra[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (side == 0) {
+                const int i = m0 + (e >> 3), k4 = (e & 7) * 4;
+                if (i < p.N) ra[r] = load4(Eb + (size_t)i * p.M + q0 + k4, q0 + k4, p.M, p.vec_m != 0);
+            } else {
+                const int i = q0 + (e >> 4), m4 = (e & 15) * 4;
+                if (i < p.N) ra[r] = load4(Eb + (size_t)i * p.M + m0 + m4, m0 + m4, p.M, p.vec_m != 0);
             }
-            *reinterpret_cast<float4 *>(Bt + k * kGradStride + n4) = t;
+            const int q = q0 + (e >> 4), n4 = (e & 15) * 4;
+            rb[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (q < Q) rb[r] = load4(oth + (size_t)q * p.D + n0 + n4, n0 + n4, p.D, p.vec_xy != 0);
         }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int e = tid + 256 * r;
+            if (side == 0) {  // k-major: At[k][m]
+                const int m = e >> 3, k4 = (e & 7) * 4;
+                At[(k4 + 0) * kGradStride + m] = ra[r].x;
+                At[(k4 + 1) * kGradStride + m] = ra[r].y;
+                At[(k4 + 2) * kGradStride + m] = ra[r].z;
+                At[(k4 + 3) * kGradStride + m] = ra[r].w;
+            } else {
+                *reinterpret_cast<float4 *>(At + (e >> 4) * kGradStride + (e & 15) * 4) = ra[r];
+            }
+            *reinterpret_cast<float4 *>(Bt + (e >> 4) * kGradStride + (e & 15) * 4) = rb[r];
+        }
+    };
+
+    int q0 = next_live(0);
+    if (q0 < Q) fetch(q0);
+    while (q0 < Q) {
+        __syncthreads();  // previous chunk's reads are done
+        stash();
         __syncthreads();
+        q0 = next_live(q0 + kBlk);
+        if (q0 < Q) fetch(q0);
 
         // marginal sums: wavefront w adds rows k = 8w .. 8w+7 of the A tile for output row `lane`
 #pragma unroll

@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstring>
 #include <string>
+#include <type_traits>
 #include <vector>
 
 #include "../../include/sdtw.h"
@@ -183,11 +184,11 @@ inline int hip_ok() { return hipGetLastError() == hipSuccess ? SDTW_OK : SDTW_ER
 unsigned fill_grid(size_t n) { size_t g = (n + 255) / 256; return (unsigned)(g < 1 ? 1 : (g > 4096 ? 4096 : g)); }
 
 // Blocks for a prep kernel: enough for the boundary fill (one element per thread) and for the row
-// norms (four rows per block), capped.
+// norms (a block takes four rows at a time, four times over), capped.
 unsigned prep_grid(const Params &p, int64_t norm_rows)
 {
     const size_t fill = ((size_t)p.B * p.nbands * p.M + 255) / 256;
-    const size_t rows = (size_t)(norm_rows + 3) / 4;
+    const size_t rows = (size_t)(norm_rows + 15) / 16;
     const size_t g = fill > rows ? fill : rows;
     return (unsigned)(g < 1 ? 1 : (g > 8192 ? 8192 : g));
 }
@@ -202,12 +203,22 @@ int forward_impl(const sdtw_desc *d, const float *x, const float *y, float *valu
     }
     if (d->mode == SDTW_UNFUSED) {
         ProfScope ps("cost_tensor", st);
-        dim3 gh((d->M + 127) / 128, (d->N + 127) / 128, d->B);
+        // 128 x 128 tiles, or 128 x 32 when those would leave most of the chip idle
+        const size_t tiles128 = (size_t)((d->M + 127) / 128) * ((d->N + 127) / 128) * d->B;
+        const bool narrow = tiles128 < 1024;
+        dim3 gh(narrow ? (d->M + 31) / 32 : (d->M + 127) / 128, (d->N + 127) / 128, d->B);
+        auto launch = [&](auto kg) {
+            constexpr int KG = decltype(kg)::value;
+            if (narrow)
+                cost_tensor_half_kernel<KG, 1><<<gh, 256, 0, st>>>(p);
+            else
+                cost_tensor_half_kernel<KG, 4><<<gh, 256, 0, st>>>(p);
+        };
         switch (fused_variant(d->D)) {
-            case 1: cost_tensor_half_kernel<1><<<gh, 256, 0, st>>>(p); break;
-            case 2: cost_tensor_half_kernel<2><<<gh, 256, 0, st>>>(p); break;
-            case 4: cost_tensor_half_kernel<4><<<gh, 256, 0, st>>>(p); break;
-            case 8: cost_tensor_half_kernel<8><<<gh, 256, 0, st>>>(p); break;
+            case 1: launch(std::integral_constant<int, 1>{}); break;
+            case 2: launch(std::integral_constant<int, 2>{}); break;
+            case 4: launch(std::integral_constant<int, 4>{}); break;
+            case 8: launch(std::integral_constant<int, 8>{}); break;
             default: {
                 dim3 g((d->M + 63) / 64, (d->N + 63) / 64, d->B);
                 cost_tensor_kernel<<<g, 256, 0, st>>>(p);
