@@ -37,6 +37,7 @@
 
 namespace sdtw {
 
+constexpr int kPeekStep = 16;      // step of a macro-step at which the next boundary values are requested
 constexpr int kRingCols = 128;     // four phases of 32 steps
 constexpr int kRingStride = 129;   // floats per band row in LDS (odd: lanes hit distinct banks)
 constexpr int kRingFloats = kBandRows * kRingStride;
@@ -642,7 +643,6 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
             unsigned long long nxt_bits = (unsigned long long)__double_as_longlong(kBig);
             const int jn = (sg + 1) * kBlk + lane;
             const bool need_n = has_above && lane < kBlk && jn < M;
-            if (has_above) nxt_bits = peek_boundary(brow_in, jn, need_n);
             const float *rd = my_ring + (sg & 3) * kBlk;
             double *Rs = RECOMP ? nullptr : Rk + (size_t)sg * kBlk * kBandRows;
             if constexpr (RECOMP) {
@@ -652,6 +652,9 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
             auto steps = [&](auto capture) {
 #pragma unroll
                 for (int u = 0; u < kBlk; ++u) {
+                    // ask for the next macro-step's row above about one memory round trip before it
+                    // is needed: asked earlier, the answer would be "not written yet" too often
+                    if (u == kPeekStep && has_above) nxt_bits = peek_boundary(brow_in, jn, need_n);
                     const double up = lane_shr1(left, top[u]);  // R[i-1][j]; lane 0 takes the row above the band
                     const float dc = rd[u];
                     double m;
@@ -711,6 +714,7 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
 // E replaces the consumed cost value in the ring; the producers write it out as row-major 32x32
 // blocks, with one flag byte per block saying whether any entry is non-zero.
 // ---------------------------------------------------------------------------------------------
+template <int COLS = kRingCols, int STRIDE = kRingStride>
 __device__ __forceinline__ void flush_E_block(const Params &p, const float *ring, float *__restrict__ Eb,
                                               unsigned char *__restrict__ nzb, int rb, int cb, int row0, int lane)
 {
@@ -721,11 +725,11 @@ __device__ __forceinline__ void flush_E_block(const Params &p, const float *ring
     for (int it = 0; it < 4; ++it) {
         const int r = (lane >> 3) + 8 * it;
         const int row = row0 + rb * 32 + r;
-        const float *rowp = ring + (32 * rb + r) * kRingStride;
+        const float *rowp = ring + (32 * rb + r) * STRIDE;
         const int base = 32 * (cb + rb) + c4 + r;
         float v[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = rowp[(base + e) & (kRingCols - 1)];
+        for (int e = 0; e < 4; ++e) v[e] = rowp[(base + e) & (COLS - 1)];
         if (row < p.N) {
             float *q = Eb + (size_t)row * p.M + j0 + c4;
             if (p.vec_m && j0 + c4 + 3 < p.M) {
@@ -955,7 +959,6 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
             unsigned long long nxt_bits = (unsigned long long)__double_as_longlong(kBig);
             const int jn = (sg - 1) * kBlk + lane - kBlk - (kBandRows - 1);
             const bool need_n = has_below && lane >= kBlk && jn >= 0 && jn < M;
-            if (has_below) nxt_bits = peek_boundary(brow_in, jn, need_n);
             float *rd = my_ring + (sg & 3) * kBlk;
             const double *Rn = (RECOMP || TSWEEP) ? nullptr : Rk + (size_t)(sg > 0 ? sg - 1 : 0) * kBlk * kBandRows;
             double *Qs = TSWEEP ? Qk + (size_t)sg * kBlk * kBandRows : nullptr;
@@ -988,6 +991,7 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
             auto steps = [&](auto corner) {
 #pragma unroll
             for (int u = kBlk - 1; u >= 0; --u) {
+                if (u == kBlk - 1 - kPeekStep && has_below) nxt_bits = peek_boundary(brow_in, jn, need_n);
                 const double down = lane_shl1(right, bot[u]);  // T[i+1][j]; lane 63 takes the row below the band
                 const float dc = rd[u];
                 const double dg = (decltype(corner)::value && sbase + u == s_corner) ? 0.0 : diag;
@@ -1032,6 +1036,87 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
             if (lane >= kBlk) bot[lane - kBlk] = bn;
         }
         __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Alignment matrix from the two tables (small problems, where the forward call ran both sweeps).
+// With T the reverse DP over the same costs, R[i,j] + T[i,j] - d[i,j] is the soft-minimum cost of
+// all alignments through cell (i,j), so
+//     E[i,j] = exp((R[N,M] - R[i,j] - T[i,j] + d[i,j]) / gamma),
+// which satisfies the log-space recurrence of Sec. 4.2 (divide that recurrence by E and substitute).
+// The reverse sweep stores Q = T - d (its soft-minimum part), so no cost is needed here, and both
+// tables are in units of gamma*ln2:  log2 E = R[N,M] - R - Q.
+// One wavefront (a workgroup of its own, no barriers) streams a run of `seg_blocks` 32-column
+// blocks of one band: per macro-step it reads the 32 step-rows of both tables (512 contiguous
+// bytes each, the next macro-step's already in flight), puts E into its LDS ring exactly as the
+// reverse-sweep consumer of the large problems does, and writes out the two 32x32 blocks that
+// became complete, row-major, with their "any non-zero" flags.  Both blocks only hold cells of
+// the last two macro-steps, so the ring has two phases of 32 steps.  Only the two macro-steps
+// past a run's end are read twice.
+// ---------------------------------------------------------------------------------------------
+constexpr int kAlignRingCols = 64, kAlignRingStride = 65;
+
+__global__ __launch_bounds__(64) void alignment_kernel(Params p, int seg_blocks)
+{
+    __shared__ float ring[kBandRows * kAlignRingStride];
+    const int lane = threadIdx.x;
+    const int k = blockIdx.y, b = blockIdx.z;
+    const int cb0 = blockIdx.x * seg_blocks, cb1 = min(cb0 + seg_blocks, p.ncb);
+    const int row0 = k * kBandRows;
+
+    if (backward_refused(p)) {
+        // record why (the status word keeps a time-out of the sweeps), leave NaN to the later kernels
+        if (lane == 0 && blockIdx.x == 0 && k == 0 && b == 0 && p.hdr->status == 0) {
+            p.hdr->magic = kMagic;
+            p.hdr->status = kStatusState;
+            p.hdr->abort_backward = 1;
+        }
+        return;
+    }
+
+    float *Eb = p.E + (size_t)b * p.N * p.M;
+    unsigned char *nzb = p.nz + (size_t)b * p.nrb * p.ncb;
+    const size_t band_off = ((size_t)b * p.nbands + k) * (size_t)p.nmacro * kBlk * kBandRows;
+    const double *Rk = p.R + band_off, *Qk = p.Q + band_off;
+    const double Rfin = p.rfinal[b];
+    float *my_ring = ring + lane * kAlignRingStride;
+    const int g_end = min(cb1 + 2, p.nmacro);  // macro-steps [cb0, g_end) hold every cell of the run
+
+    auto load = [&](int g, double (&r)[kBlk], double (&q)[kBlk]) {
+        const size_t o = (size_t)g * kBlk * kBandRows + lane;
+#pragma unroll
+        for (int u = 0; u < kBlk; ++u) {
+            r[u] = __builtin_nontemporal_load(&Rk[o + (size_t)u * kBandRows]);
+            q[u] = __builtin_nontemporal_load(&Qk[o + (size_t)u * kBandRows]);
+        }
+    };
+    auto process = [&](int g, const double (&r)[kBlk], const double (&q)[kBlk]) {
+        float *wr = my_ring + (g & 1) * kBlk;  // step s = 32g + u sits at ring slot s mod 64
+#pragma unroll
+        for (int u = 0; u < kBlk; ++u) wr[u] = __builtin_amdgcn_exp2f((float)((Rfin - r[u]) - q[u]));
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        // complete now: (upper rows, block g-1) and (lower rows, block g-2)
+        if (g - 1 >= cb0 && g - 1 < cb1) flush_E_block<kAlignRingCols, kAlignRingStride>(p, ring, Eb, nzb, 0, g - 1, row0, lane);
+        if (g - 2 >= cb0 && g - 2 < cb1) flush_E_block<kAlignRingCols, kAlignRingStride>(p, ring, Eb, nzb, 1, g - 2, row0, lane);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    };
+
+    double ra[kBlk], qa[kBlk], rb[kBlk], qb[kBlk];
+    int g = cb0;
+    load(g, ra, qa);
+    while (g < g_end) {
+        if (g + 1 < g_end) load(g + 1, rb, qb);
+        process(g, ra, qa);
+        if (++g >= g_end) break;
+        if (g + 1 < g_end) load(g + 1, ra, qa);
+        process(g, rb, qb);
+        ++g;
+    }
+    // blocks whose last macro-steps lie beyond the table (all their cells are already in the ring)
+    for (; g < cb1 + 2; ++g) {
+        if (g - 1 >= cb0 && g - 1 < cb1) flush_E_block<kAlignRingCols, kAlignRingStride>(p, ring, Eb, nzb, 0, g - 1, row0, lane);
+        if (g - 2 >= cb0 && g - 2 < cb1) flush_E_block<kAlignRingCols, kAlignRingStride>(p, ring, Eb, nzb, 1, g - 2, row0, lane);
     }
 }
 

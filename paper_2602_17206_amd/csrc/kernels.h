@@ -189,102 +189,6 @@ __global__ __launch_bounds__(256) void cost_tensor_kernel(Params p)
 }
 
 // ---------------------------------------------------------------------------------------------
-// Alignment matrix from the two tables (small problems, where the forward call ran both sweeps).
-// With T the reverse DP over the same costs, R[i,j] + T[i,j] - d[i,j] is the soft-minimum cost of
-// all alignments through cell (i,j), so
-//     E[i,j] = exp((R[N,M] - R[i,j] - T[i,j] + d[i,j]) / gamma),
-// which satisfies the log-space recurrence of Sec. 4.2 (divide that recurrence by E and substitute).
-// The reverse sweep stores Q = T - d (its soft-minimum part), so no cost is needed here, and both
-// tables are in units of gamma*ln2:  log2 E = R[N,M] - R - Q.
-// One workgroup un-skews 64 rows x 128 columns: it reads the step-major rows s = j + t of both
-// tables (512 contiguous bytes each), drops E into an LDS tile at [t][j], then writes the tile out
-// row-major with the per-32x32-block "any non-zero" flags the gradient kernel uses.
-// ---------------------------------------------------------------------------------------------
-constexpr int kAlignCols = 128;
-constexpr int kAlignStride = kAlignCols + 2;  // floats per LDS row: lane t writes at t*(stride-1)+const, odd => no bank conflicts
-
-__global__ __launch_bounds__(256) void alignment_kernel(Params p)
-{
-    __shared__ float tile[kBandRows * kAlignStride];
-    __shared__ int flags[8];
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int j0 = blockIdx.x * kAlignCols, k = blockIdx.y, b = blockIdx.z;
-    const int row0 = k * kBandRows;
-    float *Eb = p.E + (size_t)b * p.N * p.M;
-    unsigned char *nzb = p.nz + (size_t)b * p.nrb * p.ncb;
-
-    if (backward_refused(p)) {
-        // record why (the status word keeps a time-out of the sweeps), leave NaN behind
-        if (tid == 0 && blockIdx.x == 0 && k == 0 && b == 0 && p.hdr->status == 0) {
-            p.hdr->magic = kMagic;
-            p.hdr->status = kStatusState;
-            p.hdr->abort_backward = 1;
-        }
-        return;
-    }
-
-    if (tid < 8) flags[tid] = 0;
-    const size_t band_elems = (size_t)p.nmacro * kBlk * kBandRows;
-    const double *Rk = p.R + ((size_t)b * p.nbands + k) * band_elems;
-    const double *Qk = p.Q + ((size_t)b * p.nbands + k) * band_elems;
-    const double Rfin = p.rfinal[b];
-    const bool row_ok = row0 + lane < p.N;
-    const int s_end = min(j0 + kAlignCols + kBandRows - 1, p.nmacro * kBlk);
-    // a wavefront takes every fourth step-row; 12 rows of both tables are in flight per wavefront
-    constexpr int kRowsInFlight = 12;
-    for (int s0 = j0 + w; s0 < s_end; s0 += 4 * kRowsInFlight) {
-        double r[kRowsInFlight], q[kRowsInFlight];
-#pragma unroll
-        for (int u = 0; u < kRowsInFlight; ++u) {
-            const int s = min(s0 + 4 * u, s_end - 1);  // clamped: no branch around the loads
-            r[u] = __builtin_nontemporal_load(&Rk[(size_t)s * kBandRows + lane]);
-            q[u] = __builtin_nontemporal_load(&Qk[(size_t)s * kBandRows + lane]);
-        }
-#pragma unroll
-        for (int u = 0; u < kRowsInFlight; ++u) {
-            const int s = s0 + 4 * u;
-            const int j = s - lane;
-            if (s < s_end && j >= j0 && j < j0 + kAlignCols) {
-                const float e = __builtin_amdgcn_exp2f((float)((Rfin - r[u]) - q[u]));
-                tile[lane * kAlignStride + (j - j0)] = (row_ok && j < p.M) ? e : 0.f;
-            }
-        }
-    }
-    __syncthreads();
-
-    // write-out: wavefront w takes rows w, w+4, ...; a lane takes columns lane and lane+64
-    bool any[2][2] = {{false, false}, {false, false}};  // [row block][column half]
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int r = w + 4 * i;
-        const int row = row0 + r;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int c = lane + 64 * h, j = j0 + c;
-            const bool inside = row < p.N && j < p.M;
-            const float e = inside ? tile[r * kAlignStride + c] : 0.f;
-            if (inside) Eb[(size_t)row * p.M + j] = e;
-            any[i >> 3][h] |= (e != 0.f);
-        }
-    }
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const unsigned long long m = __ballot(any[rb][h]);
-            if (lane == 0) {
-                if (m & 0xFFFFFFFFull) atomicOr(&flags[rb * 4 + 2 * h], 1);
-                if (m >> 32) atomicOr(&flags[rb * 4 + 2 * h + 1], 1);
-            }
-        }
-    __syncthreads();
-    if (tid < 8) {
-        const int rb = row0 / kBlk + (tid >> 2), cb = j0 / kBlk + (tid & 3);
-        if (rb < p.nrb && cb < p.ncb) nzb[(size_t)rb * p.ncb + cb] = flags[tid] ? 1 : 0;
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
 // Input gradients (Sec. 4.3):  dx_i = 2 g (x_i sum_j E_ij - sum_j E_ij y_j),  dy_j alike.
 // One launch covers both: blockIdx.z = 2*b + side.  A workgroup (4 wavefronts) owns a 64 x 64
 // output tile (64 sequence positions x 64 features) and walks the other sequence in chunks of 32,

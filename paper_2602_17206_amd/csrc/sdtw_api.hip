@@ -2,6 +2,7 @@
 // workspace carving and kernel launches.  No device memory is allocated here.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -242,8 +243,13 @@ int backward_impl(const sdtw_desc *d, const float *x, const float *y, const floa
     if (L.two_sweep) {
         // both tables are there: combine them (the kernel checks the workspace itself)
         ProfScope ps("alignment", st);
-        dim3 g((d->M + kAlignCols - 1) / kAlignCols, L.nbands, d->B);
-        alignment_kernel<<<g, 256, 0, st>>>(p);
+        // runs of 32-column blocks per band: whole bands when there are at least 512 of them,
+        // shorter runs otherwise (more wavefronts; the two macro-steps past a run's end are re-read)
+        const int64_t bands = (int64_t)d->B * L.nbands;
+        const int nseg = (int)std::max<int64_t>(1, std::min<int64_t>(L.ncb, (512 + bands - 1) / bands));
+        const int seg_blocks = (L.ncb + nseg - 1) / nseg;
+        dim3 g((L.ncb + seg_blocks - 1) / seg_blocks, L.nbands, d->B);
+        alignment_kernel<<<g, 64, 0, st>>>(p, seg_blocks);
     } else {
         {
             ProfScope ps("backward_prep", st);
