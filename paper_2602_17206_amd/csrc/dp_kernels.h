@@ -37,7 +37,7 @@
 
 namespace sdtw {
 
-constexpr int kPeekStep = 16;      // step of a macro-step at which the next boundary values are requested
+constexpr int kPeekStep = 24;      // step of a macro-step at which the next boundary values are requested
 constexpr int kRingCols = 128;     // four phases of 32 steps
 constexpr int kRingStride = 129;   // floats per band row in LDS (odd: lanes hit distinct banks)
 constexpr int kRingFloats = kBandRows * kRingStride;
