@@ -7,6 +7,7 @@
 namespace sdtw {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 
 // ---------------------------------------------------------------------------------------------
 // Cross-lane shifts over the 64 lanes of a wavefront (DPP wave_shr:1 / wave_shl:1).

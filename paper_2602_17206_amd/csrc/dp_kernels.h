@@ -239,7 +239,6 @@ template <int DIR> __device__ __forceinline__ int blk_cb(int sg, int which)
 // The band's x pieces stay in registers for the whole sweep; y streams through NBUF stage
 // buffers, each reloaded right after use with the data of the stage NBUF stages later.
 // A producer makes the blocks W0 .. W0+NW-1 of the two blocks of each macro-step (NW = 2: both).
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 
 template <int KG, int DIR, int W0, int NW> struct HalfProducer {
     static constexpr int NST = NW * KG;                   // stages (one feature group of one block) per macro-step

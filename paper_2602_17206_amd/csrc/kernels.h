@@ -341,6 +341,244 @@ __global__ __launch_bounds__(256) void input_grad_kernel(Params p, const float *
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Input gradients for D <= 128 on the fp16 matrix cores (same formulas, Sec. 4.3).
+// Both operands of  sum_q E[m,q] * oth[q,n]  are split into two float16 pieces: E * 2^10 (entries
+// in [0,1]) and oth * s with one power-of-two scale s per chunk of 32 reduced positions that brings
+// the chunk's largest magnitude into [2^13, 2^14) (from the per-row scales the forward call
+// stored); a chunk's products are accumulated from zero and added to the total with 1/(2^10 s).  With
+// a = a1 + a2, b = b1 + b2 the product is a1*b1 + a1*b2 + a2*b1 (the dropped a2*b2 is ~2^-22
+// relative), accumulated in float32 by v_mfma_f32_32x32x16_f16; the marginal sums of E are added up
+// in float32 from the unsplit values.  Tiles, zero-block skipping and the epilogue are those of
+// input_grad_kernel; the pieces sit in LDS as [row][32 reduced positions] with 80-byte rows, so that
+// a lane's 8 consecutive reduced positions are one 16-byte read.
+// ---------------------------------------------------------------------------------------------
+constexpr int kLiveCap = 2048;     // chunks listed at a time
+constexpr int kGradHalfRow = 40;  // float16 per LDS row: 32 used, padded to 80 bytes against bank conflicts
+
+__device__ __forceinline__ void split8(const float (&v)[8], float scale, half8 &h1, half8 &h2)
+{
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        const float vs = v[c] * scale;
+        const _Float16 a = (_Float16)vs;
+        h1[c] = a;
+        h2[c] = (_Float16)(vs - (float)a);
+    }
+}
+
+__global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const float *__restrict__ grad_value,
+                                                             float *__restrict__ dx, float *__restrict__ dy)
+{
+    __shared__ __attribute__((aligned(16))) _Float16 Ah[2][64 * kGradHalfRow];  // [piece][m][k]
+    __shared__ __attribute__((aligned(16))) _Float16 Bh[2][64 * kGradHalfRow];  // [piece][n][k]
+    __shared__ float msum_part[4][64];
+    __shared__ int live_list[kLiveCap];          // first reduced position of every chunk that has a non-zero
+    __shared__ unsigned long long wave_mask[2][4];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int b = blockIdx.z >> 1, side = blockIdx.z & 1;
+    float *out = side == 0 ? dx : dy;
+    if (out == nullptr) return;
+    const int P = side == 0 ? p.N : p.M;  // output positions
+    const int Q = side == 0 ? p.M : p.N;  // reduced positions
+    const int m0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
+    if (m0 >= P) return;
+    const float *own = side == 0 ? p.x + b * p.x_stride : p.y + b * p.y_stride;   // sequence of the output side
+    const float *oth = side == 0 ? p.y + b * p.y_stride : p.x + b * p.x_stride;   // sequence reduced over
+    // its rows' 1/scale (positive powers of two: their bit patterns order like the values)
+    const unsigned *oth_is = reinterpret_cast<const unsigned *>(side == 0 ? p.yis + b * p.yn_stride : p.xis + b * p.xn_stride);
+    out += (size_t)b * P * p.D;
+    const int wr = w >> 1, wc = w & 1;
+
+    if (backward_refused(p)) {
+        const float qnan = __builtin_nanf("");
+        for (int e = tid; e < 64 * 64; e += 256) {
+            const int m = m0 + (e >> 6), n = n0 + (e & 63);
+            if (m < P && n < p.D) out[(size_t)m * p.D + n] = qnan;
+        }
+        return;
+    }
+
+    const float sA = 1024.0f;
+    // the largest 1/scale among the chunk's 32 rows: one row per lane (mod 32), then a butterfly
+    auto chunk_ismax = [&](int q0) {
+        unsigned mx = oth_is[min(q0 + (lane & 31), Q - 1)];
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) mx = max(mx, (unsigned)__shfl_xor((int)mx, o));
+        return __uint_as_float(mx);
+    };
+
+    const float *Eb = p.E + (size_t)b * p.N * p.M;
+    const unsigned char *nzb = p.nz + (size_t)b * p.nrb * p.ncb;
+    floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const floatx16 zero = acc;
+    float msum = 0.f;  // partial sum of E over the reduced index for one output row (which: see stash)
+
+    // is any of the two 32x32 E blocks of the chunk at q0 non-zero?
+    auto chunk_live = [&](int q0) {
+        const int qb = q0 / kBlk, mb = m0 / kBlk;
+        bool live;
+        if (side == 0) {
+            live = nzb[(size_t)mb * p.ncb + qb] != 0;
+            if (mb + 1 < p.nrb) live |= nzb[(size_t)(mb + 1) * p.ncb + qb] != 0;
+        } else {
+            live = nzb[(size_t)qb * p.ncb + mb] != 0;
+            if (mb + 1 < p.ncb) live |= nzb[(size_t)qb * p.ncb + mb + 1] != 0;
+        }
+        return live;
+    };
+
+    // Per thread and chunk: 8 values of E and 8 of the reduced sequence, each run along the reduced
+    // index k (the fast index of the LDS rows).
+    //   side 0, E rows i = m0+m, columns q0+k:  m = tid/4, k = 8*(tid%4) .. +7  (32 contiguous bytes)
+    //   side 1, E rows q0+k, columns j = m0+m:  m = tid%64, k = 8*(tid/64) .. +7  (8 rows, lanes along j)
+    //   sequence rows q0+k, features n0+n:      n = tid%64, k = 8*(tid/64) .. +7
+    const int am = side == 0 ? (tid >> 2) : lane, ak = side == 0 ? (tid & 3) * 8 : w * 8;
+    const int bn = lane, bk = w * 8;
+    auto fetch = [&](int q0, float (&ea)[8], float (&bv)[8], float &ismax) {
+        ismax = chunk_ismax(q0);
+        if (side == 0) {
+            const int i = m0 + am;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) ea[c] = 0.f;
+            if (i < p.N) {
+                const float *q = Eb + (size_t)i * p.M + q0 + ak;
+                if (p.vec_m && q0 + ak + 7 < p.M) {
+                    const float4 t0 = *reinterpret_cast<const float4 *>(q), t1 = *reinterpret_cast<const float4 *>(q + 4);
+                    ea[0] = t0.x; ea[1] = t0.y; ea[2] = t0.z; ea[3] = t0.w;
+                    ea[4] = t1.x; ea[5] = t1.y; ea[6] = t1.z; ea[7] = t1.w;
+                } else {
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) if (q0 + ak + c < p.M) ea[c] = q[c];
+                }
+            }
+        } else {
+            const int j = m0 + am;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                const int i = q0 + ak + c;
+                ea[c] = (i < p.N && j < p.M) ? Eb[(size_t)i * p.M + j] : 0.f;
+            }
+        }
+        const int n = n0 + bn;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const int q = q0 + bk + c;
+            bv[c] = (q < Q && n < p.D) ? oth[(size_t)q * p.D + n] : 0.f;
+        }
+    };
+    auto stash = [&](const float (&ea)[8], const float (&bv)[8], float ismax) {
+        half8 h1, h2;
+        const float sB = 1.0f / ismax;  // exact: a power of two
+        split8(ea, sA, h1, h2);
+        *reinterpret_cast<half8 *>(&Ah[0][am * kGradHalfRow + ak]) = h1;
+        *reinterpret_cast<half8 *>(&Ah[1][am * kGradHalfRow + ak]) = h2;
+        split8(bv, sB, h1, h2);
+        *reinterpret_cast<half8 *>(&Bh[0][bn * kGradHalfRow + bk]) = h1;
+        *reinterpret_cast<half8 *>(&Bh[1][bn * kGradHalfRow + bk]) = h2;
+        // marginal sums from the unsplit values: this thread's 8 entries of output row `am`
+        msum += ((ea[0] + ea[1]) + (ea[2] + ea[3])) + ((ea[4] + ea[5]) + (ea[6] + ea[7]));
+    };
+    // the matrix-core work of one chunk, added to the total with the chunk's scale undone
+    auto contract = [&](float ismax) {
+        const int ar = (wr * 32 + (lane & 31)) * kGradHalfRow, br = (wc * 32 + (lane & 31)) * kGradHalfRow;
+        const int kh = (lane >> 5) * 8;
+        floatx16 part = zero;
+#pragma unroll
+        for (int ks = 0; ks < kBlk; ks += 16) {
+            const half8 a1 = *reinterpret_cast<const half8 *>(&Ah[0][ar + ks + kh]);
+            const half8 a2 = *reinterpret_cast<const half8 *>(&Ah[1][ar + ks + kh]);
+            const half8 b1 = *reinterpret_cast<const half8 *>(&Bh[0][br + ks + kh]);
+            const half8 b2 = *reinterpret_cast<const half8 *>(&Bh[1][br + ks + kh]);
+            part = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, b1, part, 0, 0, 0);
+            part = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, b2, part, 0, 0, 0);
+            part = __builtin_amdgcn_mfma_f32_32x32x16_f16(a2, b1, part, 0, 0, 0);
+        }
+        const float unscale = ismax * (1.0f / 1024.0f);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = fmaf(part[i], unscale, acc[i]);
+    };
+
+    // The chunks are examined kLiveCap at a time: first, 256 per round, every thread reads the flags
+    // of one chunk and the live ones are listed in order (ballot + prefix counts, so the order and
+    // with it the rounding never changes); then the listed chunks are contracted with two of them in
+    // flight: while chunk c is contracted, the values of chunk c+1 are arriving and those of chunk
+    // c+2 are requested.
+    const int nchunk = (Q + kBlk - 1) / kBlk;
+    // the output side's own values for the epilogue, requested now so that they are there by then
+    float own_v[16];
+    {
+        const int n = n0 + wc * 32 + (lane & 31);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int m = m0 + wr * 32 + acc_row(i, lane);
+            own_v[i] = (m < P && n < p.D) ? own[(size_t)m * p.D + n] : 0.f;
+        }
+    }
+    float ea0[8], bv0[8], ea1[8], bv1[8], is0 = 1.f, is1 = 1.f;
+    for (int base = 0; base < nchunk; base += kLiveCap) {
+        const int lim = min(nchunk, base + kLiveCap);
+        int nlive = 0;
+        for (int g = base, round = 0; g < lim; g += 256, ++round) {
+            const int c = g + tid;
+            const bool lv = c < lim && chunk_live(c * kBlk);
+            const unsigned long long m = __ballot(lv);
+            if (lane == 0) wave_mask[round & 1][w] = m;
+            __syncthreads();
+            int off = nlive, total = 0;
+#pragma unroll
+            for (int ww = 0; ww < 4; ++ww) {
+                const int cnt = __popcll(wave_mask[round & 1][ww]);
+                if (ww < w) off += cnt;
+                total += cnt;
+            }
+            if (lv) live_list[off + __popcll(m & ((1ull << lane) - 1ull))] = c * kBlk;
+            nlive += total;
+        }
+        __syncthreads();
+
+        int i = 0;
+        if (nlive > 0) fetch(live_list[0], ea0, bv0, is0);
+        if (nlive > 1) fetch(live_list[1], ea1, bv1, is1);
+        while (i < nlive) {
+            __syncthreads();  // previous chunk's reads are done
+            stash(ea0, bv0, is0);
+            const float isc0 = is0;
+            __syncthreads();
+            if (i + 2 < nlive) fetch(live_list[i + 2], ea0, bv0, is0);
+            contract(isc0);
+            if (++i >= nlive) break;
+
+            __syncthreads();
+            stash(ea1, bv1, is1);
+            const float isc1 = is1;
+            __syncthreads();
+            if (i + 2 < nlive) fetch(live_list[i + 2], ea1, bv1, is1);
+            contract(isc1);
+            ++i;
+        }
+        __syncthreads();  // the list is rebuilt next
+    }
+
+    // side 0: four threads (tid%4) hold parts of row tid/4; side 1: four wavefronts hold parts of row tid%64
+    msum_part[side == 0 ? (tid & 3) : w][am] = msum;
+    __syncthreads();
+    const float scale = 2.0f * (grad_value ? grad_value[b] : 1.0f);
+    const int n = n0 + wc * 32 + (lane & 31);
+    if (n < p.D) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int ml = wr * 32 + acc_row(i, lane);
+            const int m = m0 + ml;
+            if (m < P) {
+                const float tot = (msum_part[0][ml] + msum_part[1][ml]) + (msum_part[2][ml] + msum_part[3][ml]);
+                out[(size_t)m * p.D + n] = scale * (own_v[i] * tot - acc[i]);
+            }
+        }
+    }
+}
+
 // Copies E to the caller's buffer (NaN when the backward call was refused).
 __global__ void export_E_kernel(Params p, float *__restrict__ dst)
 {

@@ -264,7 +264,10 @@ int backward_impl(const sdtw_desc *d, const float *x, const float *y, const floa
         const int P = std::max(dx ? d->N : 0, dy ? d->M : 0);
         dim3 g((P + 63) / 64, (d->D + 63) / 64, 2 * d->B);
         ProfScope ps("input_grad", st);
-        input_grad_kernel<<<g, 256, 0, st>>>(p, grad_value, dx, dy);
+        if (L.Dp > 0)
+            input_grad_half_kernel<<<g, 256, 0, st>>>(p, grad_value, dx, dy);
+        else
+            input_grad_kernel<<<g, 256, 0, st>>>(p, grad_value, dx, dy);
     }
     if (E_out) {
         const size_t n = (size_t)d->B * d->N * d->M;
