@@ -376,35 +376,44 @@ template <int KG, int DIR, int W0, int NW> struct HalfProducer {
 // ---------------------------------------------------------------------------------------------
 // Unfused cost tensor d[B,N,M] for D <= 16*KG on the fp16 matrix cores (Sec. 4.3 "unfused":
 // computed once and stored), from the same split-half copies and with the same arithmetic as the
-// fused producer.  One workgroup = 4 wavefronts = a 128-row x (32*CB)-column tile; each wavefront
-// keeps the pieces of its 32 rows in registers and walks CB 32-column blocks, loading the
-// operands of the next block while the matrix cores work on the current one.  (CB = 1 for small
-// tensors: four times the workgroups.)
+// fused producer.  One workgroup = 4 wavefronts = a 128-row x (32*CB)-column tile.  The y pieces of
+// the tile's columns are brought into LDS once (coalesced 512-byte rows; the kernel is bound by
+// operand traffic from L2, so no wavefront fetches what another one of its workgroup fetches); each
+// wavefront keeps the pieces of its 32 rows in registers and walks the CB column blocks.
+// LDS column stride 512+16 bytes: the 16-byte operand reads of 8 consecutive columns hit all banks.
 // ---------------------------------------------------------------------------------------------
+template <int KG> constexpr int cost_col_halfs() { return 32 * KG + 8; }
+
 template <int KG, int CB>
 __global__ __launch_bounds__(256) void cost_tensor_half_kernel(Params p)
 {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, h = lane >> 5;
+    constexpr int kCol = cost_col_halfs<KG>();
+    __shared__ __attribute__((aligned(16))) _Float16 ys[32 * CB * kCol];
+    __shared__ float2 ytab[32 * CB];  // (||y_j||^2, 1/scale_j)
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, h = lane >> 5;
     const int b = blockIdx.z;
     const int i0 = blockIdx.y * 128 + w * 32;
-    if (i0 >= p.N) return;
     const uint16_t *xh = p.xh + b * p.xh_stride, *yh = p.yh + b * p.yh_stride;
     const float *xnb = p.xn + b * p.xn_stride, *ynb = p.yn + b * p.yn_stride;
     const float *xisb = p.xis + b * p.xn_stride, *yisb = p.yis + b * p.yn_stride;
     const int jbase = blockIdx.x * (32 * CB);
-    half8 xa[2][KG], ka[2][KG];
-    float ync, yisc;
-    auto load_cols = [&](int j0) {
-        const int colc = min(j0 + (lane & 31), p.M - 1);
-        const uint16_t *r = yh + (size_t)colc * (2 * p.Dp) + 8 * h;
-#pragma unroll
-        for (int g = 0; g < KG; ++g) {
-            ka[0][g] = *reinterpret_cast<const half8 *>(r + 32 * g);
-            ka[1][g] = *reinterpret_cast<const half8 *>(r + 32 * g + 16);
-        }
-        ync = ynb[colc];
-        yisc = yisb[colc];
-    };
+
+    // y pieces of the tile's columns -> LDS: a column is 4*KG chunks of 16 bytes
+    constexpr int kChunks = 4 * KG;
+    for (int e = tid; e < 32 * CB * kChunks; e += 256) {
+        const int c = e / kChunks, ch = e % kChunks;
+        const int colc = min(jbase + c, p.M - 1);
+        const half8 v = *reinterpret_cast<const half8 *>(yh + (size_t)colc * (2 * p.Dp) + 8 * ch);
+        *reinterpret_cast<half8 *>(&ys[c * kCol + 8 * ch]) = v;
+    }
+    if (tid < 32 * CB) {
+        const int colc = min(jbase + tid, p.M - 1);
+        ytab[tid] = make_float2(ynb[colc], yisb[colc]);
+    }
+    // own rows' pieces -> registers
+    half8 xa[2][KG];
+    float xn_r[16], m2is_r[16];
+    const bool rows_live = i0 < p.N;
     {
         const int row = min(i0 + (lane & 31), p.N - 1);
         const uint16_t *r = xh + (size_t)row * (2 * p.Dp) + 8 * h;
@@ -413,42 +422,40 @@ __global__ __launch_bounds__(256) void cost_tensor_half_kernel(Params p)
             xa[0][g] = *reinterpret_cast<const half8 *>(r + 32 * g);
             xa[1][g] = *reinterpret_cast<const half8 *>(r + 32 * g + 16);
         }
-    }
-    load_cols(jbase);
-    float xn_r[16], m2is_r[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int row = min(i0 + acc_row(i, lane), p.N - 1);
-        xn_r[i] = xnb[row];
-        m2is_r[i] = -2.0f * xisb[row];
+        for (int i = 0; i < 16; ++i) {
+            const int rr = min(i0 + acc_row(i, lane), p.N - 1);
+            xn_r[i] = xnb[rr];
+            m2is_r[i] = -2.0f * xisb[rr];
+        }
     }
+    __syncthreads();
+    if (!rows_live) return;
+
     float *dst = p.cost + (size_t)b * p.N * p.M;
 #pragma unroll
     for (int cbk = 0; cbk < CB; ++cbk) {
         const int j0 = jbase + cbk * 32;
         if (j0 >= p.M) break;
         const int col = j0 + (lane & 31);
-        half8 k1[KG], k2[KG];
-#pragma unroll
-        for (int g = 0; g < KG; ++g) {
-            k1[g] = ka[0][g];
-            k2[g] = ka[1][g];
-        }
-        const float ync_now = ync, yisc_now = yisc;
-        if (cbk + 1 < CB) load_cols(min(j0 + 32, p.M - 1));  // next block's operands (clamped, maybe unused)
+        const _Float16 *yc = ys + (cbk * 32 + (lane & 31)) * kCol + 8 * h;
         floatx16 acc = zero16();
 #pragma unroll
         for (int g = 0; g < KG; ++g) {
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0][g], k1[g], acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0][g], k2[g], acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[1][g], k1[g], acc, 0, 0, 0);
+            const half8 k1 = *reinterpret_cast<const half8 *>(yc + 32 * g);
+            const half8 k2 = *reinterpret_cast<const half8 *>(yc + 32 * g + 16);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0][g], k1, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0][g], k2, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[1][g], k1, acc, 0, 0, 0);
         }
+        const float2 yt = ytab[cbk * 32 + (lane & 31)];
         if (col < p.M) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int row = i0 + acc_row(i, lane);
                 if (row < p.N)
-                    dst[(size_t)row * p.M + col] = fmaxf(fmaf(acc[i], m2is_r[i] * yisc_now, xn_r[i] + ync_now), 0.0f);
+                    __builtin_nontemporal_store(fmaxf(fmaf(acc[i], m2is_r[i] * yt.y, xn_r[i] + yt.x), 0.0f),
+                                                &dst[(size_t)row * p.M + col]);
             }
         }
     }

@@ -37,7 +37,7 @@ struct Layout {
     int32_t nmacro;   // macro-steps per band sweep: ceil((M+63)/32)
     int32_t nrb, ncb; // 32x32 block rows / columns: ceil(N/32), ceil(M/32)
     int64_t xn_count, yn_count;  // number of norm entries (1 sequence when the batch stride is 0)
-    int32_t Dp;                  // D rounded up to 16: row length of the split-half operand copies (0: none)
+    int32_t Dp;                  // D rounded up to 16, 32, 64 or 128: row length of the split-half operand copies (0: none)
     int32_t recompute;           // 1: checkpoints instead of the R table (large fused problems)
     int32_t two_sweep;           // 1: the forward call also runs the reverse sweep and stores its table Q
     size_t off_hdr, off_rfinal, off_xn, off_yn, off_xis, off_yis, off_xh, off_yh, off_brow, off_brow_b, off_R,
@@ -70,7 +70,7 @@ inline Layout make_layout(int32_t B, int32_t N, int32_t M, int32_t D, int32_t mo
     L.off_rfinal = o;   o = align_up(o + (size_t)B * sizeof(double), 256);
     L.off_xn = o;       o = align_up(o + (size_t)L.xn_count * sizeof(float), 256);
     L.off_yn = o;       o = align_up(o + (size_t)L.yn_count * sizeof(float), 256);
-    L.Dp = (D <= kMaxSplitD) ? (D + 15) / 16 * 16 : 0;
+    L.Dp = D <= 16 ? 16 : (D <= 32 ? 32 : (D <= 64 ? 64 : (D <= kMaxSplitD ? 128 : 0)));
     L.off_xis = o;      o = align_up(o + (size_t)(L.Dp ? L.xn_count : 0) * sizeof(float), 256);
     L.off_yis = o;      o = align_up(o + (size_t)(L.Dp ? L.yn_count : 0) * sizeof(float), 256);
     L.off_xh = o;       o = align_up(o + (size_t)L.xn_count * L.Dp * 2 * sizeof(uint16_t), 256);

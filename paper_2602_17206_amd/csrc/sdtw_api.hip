@@ -204,14 +204,14 @@ int forward_impl(const sdtw_desc *d, const float *x, const float *y, float *valu
     }
     if (d->mode == SDTW_UNFUSED) {
         ProfScope ps("cost_tensor", st);
-        // 128 x 128 tiles, or 128 x 32 when those would leave most of the chip idle
+        // 128 x 128 tiles, or 128 x 64 when those would leave most of the chip idle
         const size_t tiles128 = (size_t)((d->M + 127) / 128) * ((d->N + 127) / 128) * d->B;
-        const bool narrow = tiles128 < 1024;
-        dim3 gh(narrow ? (d->M + 31) / 32 : (d->M + 127) / 128, (d->N + 127) / 128, d->B);
+        const bool narrow = tiles128 < 512;
+        dim3 gh(narrow ? (d->M + 63) / 64 : (d->M + 127) / 128, (d->N + 127) / 128, d->B);
         auto launch = [&](auto kg) {
             constexpr int KG = decltype(kg)::value;
             if (narrow)
-                cost_tensor_half_kernel<KG, 1><<<gh, 256, 0, st>>>(p);
+                cost_tensor_half_kernel<KG, 2><<<gh, 256, 0, st>>>(p);
             else
                 cost_tensor_half_kernel<KG, 4><<<gh, 256, 0, st>>>(p);
         };

@@ -120,6 +120,8 @@ SHAPES = [
     (2, 96, 160, 16, 0.1),     # N != M, several bands and macro-steps
     (2, 200, 129, 24, 0.01),   # small gamma, ragged tail in the last band and the last block
     (1, 257, 70, 128, 0.1),
+    (2, 70, 90, 40, 0.2),      # D between the sizes the split operand copies are padded to
+    (2, 66, 40, 72, 0.2),
 ]
 
 
