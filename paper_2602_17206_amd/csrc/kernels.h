@@ -56,6 +56,60 @@ __global__ __launch_bounds__(256) void forward_prep_kernel(Params p, int64_t xro
     const int lane = threadIdx.x & 63;
     const int64_t rows = xrows + yrows;
     const int64_t stride = (int64_t)gridDim.x * 4;
+    if (p.Dp > 0 && p.vec_d4) {
+        // Rows of up to 128 features, 16-byte loads: a lane takes 4 consecutive features, Dp/4 lanes
+        // take a row, a wavefront takes 64/(Dp/4) rows at a time with the next ones in flight.
+        // The pieces leave as 8-byte stores.
+        const int lpr = p.Dp >> 2, rpw = 64 / lpr;
+        const int sub = lane / lpr, k0 = 4 * (lane % lpr);
+        auto load_v = [&](int64_t grp) {
+            const int64_t row = grp * rpw + sub;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < rows && k0 < p.D)
+                v = *reinterpret_cast<const float4 *>((row < xrows ? p.x + row * p.D : p.y + (row - xrows) * p.D) + k0);
+            return v;
+        };
+        const int64_t ngrp = (rows + rpw - 1) / rpw;
+        int64_t grp = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+        float4 cur = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (grp < ngrp) cur = load_v(grp);
+        for (; grp < ngrp; grp += stride) {
+            float4 nxt = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (grp + stride < ngrp) nxt = load_v(grp + stride);
+            const int64_t row = grp * rpw + sub;
+            const bool isx = row < xrows;
+            const int64_t lr = isx ? row : row - xrows;
+            float acc = fmaf(cur.x, cur.x, fmaf(cur.y, cur.y, fmaf(cur.z, cur.z, cur.w * cur.w)));
+            float mx = fmaxf(fmaxf(fabsf(cur.x), fabsf(cur.y)), fmaxf(fabsf(cur.z), fabsf(cur.w)));
+            for (int o = lpr >> 1; o > 0; o >>= 1) {
+                acc += __shfl_xor(acc, o);
+                mx = fmaxf(mx, __shfl_xor(mx, o));
+            }
+            int ex = 0;
+            if (mx > 0.f) (void)frexpf(mx, &ex);
+            ex = max(-100, min(ex, 120));
+            const float sc = ldexpf(1.0f, 14 - ex);  // see the comment on the split below
+            if (row < rows) {
+                if (k0 == 0) {
+                    (isx ? p.xn : p.yn)[lr] = acc;
+                    (isx ? p.xis : p.yis)[lr] = ldexpf(1.0f, ex - 14);
+                }
+                typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+                half4 h1, h2;
+                const float vs[4] = {cur.x * sc, cur.y * sc, cur.z * sc, cur.w * sc};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    h1[c] = (_Float16)vs[c];
+                    h2[c] = (_Float16)(vs[c] - (float)h1[c]);
+                }
+                uint16_t *h = (isx ? p.xh : p.yh) + lr * (2 * p.Dp) + 32 * (k0 >> 4) + (k0 & 15);
+                *reinterpret_cast<half4 *>(h) = h1;
+                *reinterpret_cast<half4 *>(h + 16) = h2;
+            }
+            cur = nxt;
+        }
+        return;
+    }
     // One wavefront per row, lanes stride over the features.  Up to 256 features stay in registers
     // and the next row is loaded while the current one is reduced and converted.
     constexpr int kRegs = 4;
