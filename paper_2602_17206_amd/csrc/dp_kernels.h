@@ -45,7 +45,16 @@ constexpr int kRingFloats = kBandRows * kRingStride;
 //   SLOTS=4, NPROD=1|2 (512|768 threads): large problems; the wavefronts of a band share a SIMD.
 //   SLOTS=1, NPROD=1|2 (128|192 threads): small problems that cannot fill the chip anyway; the
 //   wavefronts of a band land on different SIMDs, so producing the cost never delays the DP chain.
-constexpr int wg_threads(int slots, int nprod) { return slots * (1 + nprod) * 64; }
+// Workgroup shapes: 1 band (consumer + producers), 4 bands of 4 pairs, or 2 consecutive bands of one
+// pair ("chained": the upper band hands its last row to the lower one through LDS).  The chained
+// shape with two producers per band has 8 wavefronts of which two stay unused, so that the two
+// consumers (wavefronts 0 and 1) share their SIMD with nobody.
+constexpr int wg_threads(int slots, int nprod) { return (slots == 2 && nprod == 2) ? 512 : slots * (1 + nprod) * 64; }
+constexpr int kChainLag = 3;  // macro-steps the second band of a chained pair runs behind the first
+// LDS hand-over ring of a chained pair: 4 phases of 32 edge values, then the slots the other lanes
+// write to (see kEdgeOut below)
+constexpr int kHandRing = 4 * kBlk;
+constexpr int kHandDoubles = kHandRing + kBandRows + kBlk;
 // Large fused problems are bound by HBM traffic, of which the float64 table R is the largest part
 // (8 bytes per cell written, 8 read).  There the forward keeps only the lane state at the start of
 // every macro-step (1/16 of R) and the backward recomputes each macro-step of R before it uses it.
@@ -498,6 +507,16 @@ __device__ __forceinline__ void elect_role(WgShared<4> &sh, int lane, int w, int
     slot = __builtin_amdgcn_readfirstlane(even ? simd : (w & 3));
 }
 
+// Roles in a chained pair: wavefronts 0, 1 are the consumers of the pair's first and second band,
+// 2, 3 their (first) producers, 6, 7 their second producers; 4, 5 stay unused.  Wavefront i of a
+// workgroup lands on SIMD i mod 4, so each consumer has a SIMD to itself.
+__device__ __forceinline__ void chain_role(int w, int &producer, int &slot)
+{
+    slot = w & 1;
+    const int r = w >> 1;
+    producer = r == 0 ? 0 : (r == 1 ? 1 : (r == 3 ? 2 : -1));
+}
+
 // ---------------------------------------------------------------------------------------------
 // Forward DP (Sec. 2 Eq. 1-2 in the anti-diagonal order of Sec. 4.1).
 // Workgroups take tickets in band-major order: a band only ever waits for a band with a smaller
@@ -509,9 +528,10 @@ __device__ __forceinline__ void elect_role(WgShared<4> &sh, int lane, int w, int
 // ---------------------------------------------------------------------------------------------
 template <int KCH, int SLOTS, int NPROD>
 __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restrict__ value, WgShared<SLOTS> &sh,
-                                                unsigned &ticket_s, double (&edge_out)[SLOTS][kEdgeOut])
+                                                unsigned &ticket_s, double (&edge_out)[SLOTS][kEdgeOut],
+                                                double (&hand)[kHandDoubles])
 {
-    static_assert(SLOTS == 4 || SLOTS == 1, "supported workgroup shapes");
+    static_assert(SLOTS == 4 || SLOTS == 2 || SLOTS == 1, "supported workgroup shapes");
     static_assert(NPROD == 1 || (NPROD == 2 && KCH > 0), "two producers only split MFMA work");
     constexpr int kThreads = wg_threads(SLOTS, NPROD);
     const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -521,16 +541,34 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
     int producer, slot;  // producer: 0 = consumer, 1.. = producer number
     if constexpr (SLOTS == 4) {
         elect_role(sh, lane, w, 1 + NPROD, producer, slot);  // contains two barriers
+    } else if constexpr (SLOTS == 2) {
+        for (int e = threadIdx.x; e < kHandDoubles; e += kThreads) hand[e] = kBig;
+        chain_role(w, producer, slot);
+        __syncthreads();
+        if (producer < 0) {  // unused wavefront: only keeps the barrier count (one before the loop, one per iteration)
+            for (int it = 0; it <= p.nmacro + kChainLag; ++it) __syncthreads();
+            return;
+        }
     } else {
         producer = w;
         slot = 0;
         __syncthreads();
     }
     const unsigned ticket = __builtin_amdgcn_readfirstlane(ticket_s);
-    const int ngroups = (p.B + SLOTS - 1) / SLOTS;
-    const int k = ticket / (unsigned)ngroups;
-    const int b = (ticket - k * ngroups) * SLOTS + slot;
+    int k, b;
+    if constexpr (SLOTS == 2) {  // ticket -> (pair of bands, pair of sequences); the slot is the band of the pair
+        const int kp = ticket / (unsigned)p.B;
+        b = ticket - kp * p.B;
+        k = 2 * kp + slot;
+    } else {
+        const int ngroups = (p.B + SLOTS - 1) / SLOTS;
+        k = ticket / (unsigned)ngroups;
+        b = (ticket - k * ngroups) * SLOTS + slot;
+    }
     const bool live = (k < p.nbands) && (b < p.B);
+    // chained pair: the second band does macro-step sg in workgroup iteration sg + kChainLag
+    const int lag = (SLOTS == 2) ? kChainLag * slot : 0;
+    const int niter = p.nmacro + ((SLOTS == 2) ? kChainLag : 0);
 
     const int M = p.M, N = p.N;
     const int row0 = k * kBandRows;
@@ -553,8 +591,9 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
                     mp.prime(p, yh, ynb, yisb, 0, lane);
                 }
                 __syncthreads();
-                for (int sg = 0; sg < p.nmacro; ++sg) {
-                    if (live) mp.run(p, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
+                for (int it = 0; it < niter; ++it) {
+                    const int sg = it - lag;
+                    if (live && sg >= 0 && sg < p.nmacro) mp.run(p, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
                     __syncthreads();
                 }
             };
@@ -573,15 +612,17 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
                 mp.prime(p, yh, ynb, yisb, 0, lane);
             }
             __syncthreads();
-            for (int sg = 0; sg < p.nmacro; ++sg) {
-                if (live) mp.run(p, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
+            for (int it = 0; it < niter; ++it) {
+                const int sg = it - lag;
+                if (live && sg >= 0 && sg < p.nmacro) mp.run(p, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
                 __syncthreads();
             }
         } else if constexpr (KCH == 0) {
             if (live) generic_block(p, b, ring, 0, 0, row0, lane);
             __syncthreads();
-            for (int sg = 0; sg < p.nmacro; ++sg) {
-                if (live) {
+            for (int it = 0; it < niter; ++it) {
+                const int sg = it - lag;
+                if (live && sg >= 0 && sg < p.nmacro) {
                     generic_block(p, b, ring, 1, sg, row0, lane);
                     generic_block(p, b, ring, 0, sg + 1, row0, lane);
                 }
@@ -597,8 +638,9 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
                 load_cost_block(pre[1], cost_b, 0, 1, row0, N, M, p.vec_m != 0, lane);
             }
             __syncthreads();
-            for (int sg = 0; sg < p.nmacro; ++sg) {
-                if (live) {
+            for (int it = 0; it < niter; ++it) {
+                const int sg = it - lag;
+                if (live && sg >= 0 && sg < p.nmacro) {
                     store_cost_block(ring, pre[0], 1, sg, lane);
                     store_cost_block(ring, pre[1], 0, sg + 1, lane);
                     load_cost_block(pre[0], cost_b, 1, sg + 1, row0, N, M, p.vec_m != 0, lane);
@@ -611,6 +653,11 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
     }
 
     // ---------------------------------------------------------------------- consumer wavefront
+    // CH: -1 = both neighbouring bands are reached through memory; 0 = the band below is the other
+    // band of this workgroup (edge values go to the LDS hand-over ring); 1 = the band above is.
+    // (Separate instances, so that each one reads and writes distinct LDS objects.)
+    auto consume = [&](auto chain_c) {
+    constexpr int CH = decltype(chain_c)::value;
     const double c2d = p.c2d;  // log2(e)/gamma
     bool gave_up = false;
     double left = kBig;                                  // R[i][j-1]
@@ -626,15 +673,14 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
     const int s_fin = (live && row0 + lane == N - 1) ? (M - 1 + lane) : -1;  // step of cell (N-1, M-1)
     const bool last_band = live && (k + 1 == p.nbands);
     double fin = 0.0;
-    const bool has_above = live && k > 0;
-    const bool emit_bottom = live && (k + 1 < p.nbands);
+    const bool has_above = live && k > 0 && CH != 1;                // through memory
+    const bool emit_bottom = live && (k + 1 < p.nbands) && CH != 0;  // through memory
     const float *my_ring = ring + lane * kRingStride;
     double *top = sh.edge_in[slot];
     double *eo = edge_out[slot];
-    double *my_eo = eo + ((lane == kBandRows - 1) ? 0 : kBlk + lane);
 
     // row above the band for macro-step 0: lane l < 32 brings column l
-    {
+    if constexpr (CH != 1) {
         double t0 = kBig;
         if (has_above) {
             const bool need = lane < kBlk && lane < M;
@@ -644,12 +690,24 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
     }
     __syncthreads();
 
-    for (int sg = 0; sg < p.nmacro; ++sg) {
-        if (live) {
+    for (int it = 0; it < niter; ++it) {
+        const int sg = it - lag;
+        if (live && sg >= 0 && sg < p.nmacro) {
             unsigned long long nxt_bits = (unsigned long long)__double_as_longlong(kBig);
             const int jn = (sg + 1) * kBlk + lane;
             const bool need_n = has_above && lane < kBlk && jn < M;
             const float *rd = my_ring + (sg & 3) * kBlk;
+            // The row above, column 32*sg + u at step u: from the incoming boundary values, or from
+            // the hand-over ring, where the band above put column c at slot (c + 63) mod 128.
+            const double *top0 = top, *top1 = top + 1;  // step 0, steps 1..31
+            if constexpr (CH == 1) {
+                top0 = hand + ((sg + 1) & 3) * kBlk + (kBlk - 1);
+                top1 = hand + ((sg + 2) & 3) * kBlk;
+            }
+            // Where this macro-step's values go: lane 63's are the band's last row (column
+            // 32*sg + u - 63 at step u), the other lanes write to slots of their own.
+            double *my_eo = eo + ((lane == kBandRows - 1) ? 0 : kBlk + lane);
+            if constexpr (CH == 0) my_eo = hand + ((lane == kBandRows - 1) ? (sg & 3) * kBlk : kHandRing + lane);
             double *Rs = RECOMP ? nullptr : Rk + (size_t)sg * kBlk * kBandRows;
             if constexpr (RECOMP) {
                 __builtin_nontemporal_store(left, &Ck[((size_t)sg * 2 + 0) * kBandRows + lane]);
@@ -661,7 +719,7 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
                     // ask for the next macro-step's row above about one memory round trip before it
                     // is needed: asked earlier, the answer would be "not written yet" too often
                     if (u == kPeekStep && has_above) nxt_bits = peek_boundary(brow_in, jn, need_n);
-                    const double up = lane_shr1(left, top[u]);  // R[i-1][j]; lane 0 takes the row above the band
+                    const double up = lane_shr1(left, u == 0 ? top0[0] : top1[u - 1]);  // R[i-1][j]; lane 0 takes the row above the band
                     const float dc = rd[u];
                     double m;
                     float L;
@@ -687,9 +745,11 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
                 const int j = sg * kBlk + lane - kBlk - (kBandRows - 1);
                 if (j >= 0 && j < M) publish_boundary(brow_out, j, eo[lane - kBlk]);
             }
-            double tn = kBig;
-            if (has_above) tn = resolve_boundary(p, brow_in, jn, need_n, lane, gave_up, nxt_bits);
-            if (lane < kBlk) top[lane] = tn;
+            if constexpr (CH != 1) {
+                double tn = kBig;
+                if (has_above) tn = resolve_boundary(p, brow_in, jn, need_n, lane, gave_up, nxt_bits);
+                if (lane < kBlk) top[lane] = tn;
+            }
         }
         __syncthreads();
     }
@@ -699,6 +759,15 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
         const double r = RECOMP ? fin : Rk[(size_t)(M - 1 + lane) * kBandRows + lane];
         p.rfinal[b] = r;                     // table units, for the backward sweep
         value[b] = (float)(r * p.inv_c2d);   // the paper's units
+    }
+    };
+    if constexpr (SLOTS == 2) {
+        if (slot == 0)
+            consume(std::integral_constant<int, 0>{});
+        else
+            consume(std::integral_constant<int, 1>{});
+    } else {
+        consume(std::integral_constant<int, -1>{});
     }
 }
 
@@ -754,14 +823,15 @@ __device__ __forceinline__ void flush_E_block(const Params &p, const float *ring
 
 template <int KCH, int SLOTS, int NPROD>
 __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS> &sh, unsigned &ticket_s,
-                                                double (&edge_out)[SLOTS][kEdgeOut])
+                                                double (&edge_out)[SLOTS][kEdgeOut], double (&hand)[kHandDoubles])
 {
-    static_assert(SLOTS == 4 || SLOTS == 1, "supported workgroup shapes");
+    static_assert(SLOTS == 4 || SLOTS == 2 || SLOTS == 1, "supported workgroup shapes");
     static_assert(NPROD == 1 || (NPROD == 2 && KCH > 0), "two producers only split MFMA work");
     constexpr int kThreads = wg_threads(SLOTS, NPROD);
-    // One band per workgroup is the shape of small problems, where this sweep runs beside the
-    // forward sweep: it cannot use R, so it only stores its own table for alignment_kernel.
-    constexpr bool TSWEEP = (SLOTS == 1);
+    // One band or a chained pair per workgroup are the shapes of small problems, where this sweep
+    // runs beside the forward sweep: it cannot use R, so it only stores its own table for
+    // alignment_kernel.
+    constexpr bool TSWEEP = (SLOTS == 1 || SLOTS == 2);
     const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (p.hdr->abort_backward) return;
 
@@ -770,17 +840,34 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
     int producer, slot;  // producer: 0 = consumer, 1.. = producer number
     if constexpr (SLOTS == 4) {
         elect_role(sh, lane, w, 1 + NPROD, producer, slot);
+    } else if constexpr (SLOTS == 2) {
+        for (int e = threadIdx.x; e < kHandDoubles; e += kThreads) hand[e] = kBig;
+        chain_role(w, producer, slot);
+        __syncthreads();
+        if (producer < 0) {  // unused wavefront: only keeps the barrier count (one before the loop, one per iteration)
+            for (int it = 0; it <= p.nmacro + kChainLag; ++it) __syncthreads();
+            return;
+        }
     } else {
         producer = w;
         slot = 0;
         __syncthreads();
     }
     const unsigned ticket = __builtin_amdgcn_readfirstlane(ticket_s);
-    const int ngroups = (p.B + SLOTS - 1) / SLOTS;
-    const int kk = ticket / (unsigned)ngroups;
-    const int b = (ticket - kk * ngroups) * SLOTS + slot;
+    int kk, b;  // kk counts bands from the last one
+    if constexpr (SLOTS == 2) {
+        const int kp = ticket / (unsigned)p.B;
+        b = ticket - kp * p.B;
+        kk = 2 * kp + slot;
+    } else {
+        const int ngroups = (p.B + SLOTS - 1) / SLOTS;
+        kk = ticket / (unsigned)ngroups;
+        b = (ticket - kk * ngroups) * SLOTS + slot;
+    }
     const int k = p.nbands - 1 - kk;
     const bool live = (kk < p.nbands) && (b < p.B);
+    const int lag = (SLOTS == 2) ? kChainLag * slot : 0;
+    const int niter = p.nmacro + ((SLOTS == 2) ? kChainLag : 0);
 
     const int M = p.M, N = p.N;
     const int row0 = (live ? k : 0) * kBandRows;
@@ -823,8 +910,9 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
                     mp.prime(p, yh, ynb, yisb, sg0, lane);
                 }
                 __syncthreads();
-                for (int sg = sg0; sg >= 0; --sg) {
-                    if (live) {
+                for (int it = 0; it < niter; ++it) {
+                    const int sg = sg0 - (it - lag);
+                    if (live && sg >= 0 && sg <= sg0) {
                         if (sg < sg0) flush(sg + 1, upper, !upper);
                         mp.run(p, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
                     }
@@ -849,8 +937,9 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
                 mp.prime(p, yh, ynb, yisb, sg0, lane);
             }
             __syncthreads();
-            for (int sg = sg0; sg >= 0; --sg) {
-                if (live) {
+            for (int it = 0; it < niter; ++it) {
+                const int sg = sg0 - (it - lag);
+                if (live && sg >= 0 && sg <= sg0) {
                     if (sg < sg0) flush(sg + 1, true, true);
                     mp.run(p, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
                 }
@@ -864,8 +953,9 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
                 generic_block(p, b, ring, 1, sg0 - 2, row0, lane);
             }
             __syncthreads();
-            for (int sg = sg0; sg >= 0; --sg) {
-                if (live) {
+            for (int it = 0; it < niter; ++it) {
+                const int sg = sg0 - (it - lag);
+                if (live && sg >= 0 && sg <= sg0) {
                     if (sg < sg0) flush(sg + 1, true, true);
                     generic_block(p, b, ring, 0, sg - 2, row0, lane);
                     generic_block(p, b, ring, 1, sg - 3, row0, lane);
@@ -887,8 +977,9 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
                 load_cost_block(pre[1], cost_b, 1, sg0 - 3, row0, N, M, p.vec_m != 0, lane);
             }
             __syncthreads();
-            for (int sg = sg0; sg >= 0; --sg) {
-                if (live) {
+            for (int it = 0; it < niter; ++it) {
+                const int sg = sg0 - (it - lag);
+                if (live && sg >= 0 && sg <= sg0) {
                     if (sg < sg0) flush(sg + 1, true, true);
                     store_cost_block(ring, pre[0], 0, sg - 2, lane);
                     store_cost_block(ring, pre[1], 1, sg - 3, lane);
@@ -903,6 +994,11 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
     }
 
     // ---------------------------------------------------------------------- consumer wavefront
+    // CH: -1 = both neighbouring bands are reached through memory; 0 = the band above is the other
+    // band of this workgroup (this band's first row goes to the LDS hand-over ring); 1 = the band
+    // below is.
+    auto consume = [&](auto chain_c) {
+    constexpr int CH = decltype(chain_c)::value;
     const double c2d = p.c2d;  // log2(e)/gamma
     bool gave_up = false;
     double right = kBig;  // T[i][j+1]
@@ -914,7 +1010,8 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
     const int sg_corner = (live && t_last < kBandRows) ? (M - 1 + t_last) / kBlk : -1;
     const double Rfin = (live && !TSWEEP) ? p.rfinal[b] : 0.0;
     const int kc = live ? k : 0;
-    const bool has_below = live && (k + 1 < p.nbands);
+    const bool has_below = live && (k + 1 < p.nbands) && CH != 1;  // through memory
+    const bool emit_top = live && k > 0 && CH != 0;                // through memory
     constexpr bool RECOMP = dp_recompute(KCH, SLOTS);
     const unsigned long long *brow_in = p.brow_b + ((size_t)bb * p.nbands + (has_below ? kc + 1 : kc)) * M;
     unsigned long long *brow_out = p.brow_b + ((size_t)bb * p.nbands + kc) * M;
@@ -928,7 +1025,6 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
     float *my_ring = ring + lane * kRingStride;
     double *bot = sh.edge_in[slot];
     double *eo = edge_out[slot];
-    double *my_eo = eo + ((lane == 0) ? 0 : kBlk + lane);
 
     // R of the first macro-step; afterwards each value is reloaded one macro-step ahead, right after use
     double Rq[kBlk];
@@ -949,7 +1045,7 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
 
     // row below the band for the first macro-step: lane l >= 32 brings column 32*sg - 63 + (l - 32),
     // which lane 63 meets at step u = l - 32
-    {
+    if constexpr (CH != 1) {
         double b0 = kBig;
         if (has_below) {
             const int jj = sg0 * kBlk + lane - kBlk - (kBandRows - 1);
@@ -960,12 +1056,23 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
     }
     __syncthreads();
 
-    for (int sg = sg0; sg >= 0; --sg) {
-        if (live) {
+    for (int it = 0; it < niter; ++it) {
+        const int sg = sg0 - (it - lag);
+        if (live && sg >= 0 && sg <= sg0) {
             unsigned long long nxt_bits = (unsigned long long)__double_as_longlong(kBig);
             const int jn = (sg - 1) * kBlk + lane - kBlk - (kBandRows - 1);
             const bool need_n = has_below && lane >= kBlk && jn >= 0 && jn < M;
             float *rd = my_ring + (sg & 3) * kBlk;
+            // The row below, column 32*sg + u - 63 at step u: from the incoming boundary values, or
+            // from the hand-over ring, where the band below put column c at slot c mod 128.
+            const double *bot31 = bot + (kBlk - 1), *bot0 = bot;  // step 31, steps 0..30
+            if constexpr (CH == 1) {
+                bot31 = hand + ((sg - 1) & 3) * kBlk;
+                bot0 = hand + ((sg - 2) & 3) * kBlk + 1;
+            }
+            // lane 0's values are the band's first row (column 32*sg + u at step u)
+            double *my_eo = eo + ((lane == 0) ? 0 : kBlk + lane);
+            if constexpr (CH == 0) my_eo = hand + ((lane == 0) ? (sg & 3) * kBlk : kHandRing + lane);
             const double *Rn = (RECOMP || TSWEEP) ? nullptr : Rk + (size_t)(sg > 0 ? sg - 1 : 0) * kBlk * kBandRows;
             double *Qs = TSWEEP ? Qk + (size_t)sg * kBlk * kBandRows : nullptr;
             const int sbase = sg * kBlk;
@@ -998,7 +1105,7 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
 #pragma unroll
             for (int u = kBlk - 1; u >= 0; --u) {
                 if (u == kBlk - 1 - kPeekStep && has_below) nxt_bits = peek_boundary(brow_in, jn, need_n);
-                const double down = lane_shl1(right, bot[u]);  // T[i+1][j]; lane 63 takes the row below the band
+                const double down = lane_shl1(right, u == kBlk - 1 ? bot31[0] : bot0[u]);  // T[i+1][j]; lane 63 takes the row below the band
                 const float dc = rd[u];
                 const double dg = (decltype(corner)::value && sbase + u == s_corner) ? 0.0 : diag;
                 double m;
@@ -1027,7 +1134,7 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
                 steps(std::false_type{});
             // first row of the band, columns 32*sg .. 32*sg+31, for the band above
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            if (k > 0 && lane < kBlk) {
+            if (emit_top && lane < kBlk) {
                 const int j = sg * kBlk + lane;
                 if (j < M) publish_boundary(brow_out, j, eo[lane]);
             }
@@ -1037,11 +1144,22 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
                 flush_E_block(p, ring, Eb, nzb, 0, sg, row0, lane);
                 flush_E_block(p, ring, Eb, nzb, 1, sg - 1, row0, lane);
             }
-            double bn = kBig;
-            if (has_below) bn = resolve_boundary(p, brow_in, jn, need_n, lane, gave_up, nxt_bits);
-            if (lane >= kBlk) bot[lane - kBlk] = bn;
+            if constexpr (CH != 1) {
+                double bn = kBig;
+                if (has_below) bn = resolve_boundary(p, brow_in, jn, need_n, lane, gave_up, nxt_bits);
+                if (lane >= kBlk) bot[lane - kBlk] = bn;
+            }
         }
         __syncthreads();
+    }
+    };
+    if constexpr (SLOTS == 2) {
+        if (slot == 0)
+            consume(std::integral_constant<int, 0>{});
+        else
+            consume(std::integral_constant<int, 1>{});
+    } else {
+        consume(std::integral_constant<int, -1>{});
     }
 }
 
@@ -1137,7 +1255,8 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Pa
     __shared__ WgShared<SLOTS> sh;
     __shared__ unsigned ticket_s;
     __shared__ double edge_out[SLOTS][kEdgeOut];
-    forward_dp_body<KCH, SLOTS, NPROD>(p, value, sh, ticket_s, edge_out);
+    __shared__ double hand[kHandDoubles];
+    forward_dp_body<KCH, SLOTS, NPROD>(p, value, sh, ticket_s, edge_out, hand);
 }
 
 template <int KCH, int SLOTS, int NPROD>
@@ -1146,19 +1265,22 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(P
     __shared__ WgShared<SLOTS> sh;
     __shared__ unsigned ticket_s;
     __shared__ double edge_out[SLOTS][kEdgeOut];
-    reverse_dp_body<KCH, SLOTS, NPROD>(p, sh, ticket_s, edge_out);
+    __shared__ double hand[kHandDoubles];
+    reverse_dp_body<KCH, SLOTS, NPROD>(p, sh, ticket_s, edge_out, hand);
 }
 
-template <int KCH, int NPROD>
-__global__ __launch_bounds__(wg_threads(1, NPROD)) void both_sweeps_kernel(Params p, float *__restrict__ value)
+template <int KCH, int SLOTS, int NPROD>
+__global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void both_sweeps_kernel(Params p, float *__restrict__ value)
 {
-    __shared__ WgShared<1> sh;
+    static_assert(SLOTS == 1 || SLOTS == 2, "the shapes of small problems");
+    __shared__ WgShared<SLOTS> sh;
     __shared__ unsigned ticket_s;
-    __shared__ double edge_out[1][kEdgeOut];
+    __shared__ double edge_out[SLOTS][kEdgeOut];
+    __shared__ double hand[kHandDoubles];
     if (blockIdx.x & 1)
-        reverse_dp_body<KCH, 1, NPROD>(p, sh, ticket_s, edge_out);
+        reverse_dp_body<KCH, SLOTS, NPROD>(p, sh, ticket_s, edge_out, hand);
     else
-        forward_dp_body<KCH, 1, NPROD>(p, value, sh, ticket_s, edge_out);
+        forward_dp_body<KCH, SLOTS, NPROD>(p, value, sh, ticket_s, edge_out, hand);
 }
 
 }  // namespace sdtw

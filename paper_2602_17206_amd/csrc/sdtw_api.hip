@@ -20,7 +20,7 @@ namespace {
 using namespace sdtw;
 
 uint32_t g_spin_limit = 1u << 23;  // ~10 s of polling before a band gives up
-int g_force_slots = 0;             // test hook: 0 = choose by problem size, 1 or 4 = force that workgroup shape
+int g_force_slots = 0;             // test hook: 0 = choose by problem size, 1, 2 or 4 = force that workgroup shape
 
 // Optional per-kernel timing (test/benchmark hook): when switched on, every kernel launch of the
 // library is bracketed by two HIP events on the caller's stream.
@@ -62,7 +62,7 @@ bool desc_ok(const sdtw_desc *d, int *why)
 // Problems of up to 1024 band tasks cannot fill the chip: they run one band per workgroup.
 bool small_problem(const sdtw_desc *d)
 {
-    if (g_force_slots) return g_force_slots == 1;
+    if (g_force_slots) return g_force_slots != 4;
     return (int64_t)d->B * ((d->N + kBandRows - 1) / kBandRows) <= 1024;
 }
 
@@ -142,12 +142,23 @@ void launch_dp_kch(const sdtw_desc *d, const Layout &L, const Params &p, float *
 {
     constexpr int NP = KCH > 0 ? 2 : 1;
     if (small_problem(d)) {
-        const unsigned tasks = (unsigned)d->B * (unsigned)L.nbands;
+        // pairs of consecutive bands share a workgroup (the hand-over between them stays in LDS),
+        // unless there is only one band
+        const bool chained = g_force_slots ? g_force_slots == 2 : L.nbands >= 2;
         if constexpr (FWD) {
-            if (L.two_sweep)
-                both_sweeps_kernel<KCH, NP><<<2 * tasks, wg_threads(1, NP), 0, st>>>(p, value);
-            else
-                forward_dp_kernel<KCH, 1, NP><<<tasks, wg_threads(1, NP), 0, st>>>(p, value);
+            if (chained) {
+                const unsigned tasks = (unsigned)d->B * (unsigned)((L.nbands + 1) / 2);
+                if (L.two_sweep)
+                    both_sweeps_kernel<KCH, 2, NP><<<2 * tasks, wg_threads(2, NP), 0, st>>>(p, value);
+                else
+                    forward_dp_kernel<KCH, 2, NP><<<tasks, wg_threads(2, NP), 0, st>>>(p, value);
+            } else {
+                const unsigned tasks = (unsigned)d->B * (unsigned)L.nbands;
+                if (L.two_sweep)
+                    both_sweeps_kernel<KCH, 1, NP><<<2 * tasks, wg_threads(1, NP), 0, st>>>(p, value);
+                else
+                    forward_dp_kernel<KCH, 1, NP><<<tasks, wg_threads(1, NP), 0, st>>>(p, value);
+            }
         }
     } else {
         const unsigned tasks = (unsigned)((d->B + 3) / 4) * (unsigned)L.nbands;
@@ -453,7 +464,8 @@ int sdtw_debug_set_spin_limit(uint32_t polls)
 
 int sdtw_debug_force_workgroup_shape(int bands_per_workgroup)
 {
-    if (bands_per_workgroup != 0 && bands_per_workgroup != 1 && bands_per_workgroup != 4) return SDTW_ERR_INVALID_ARG;
+    if (bands_per_workgroup != 0 && bands_per_workgroup != 1 && bands_per_workgroup != 2 && bands_per_workgroup != 4)
+        return SDTW_ERR_INVALID_ARG;
     g_force_slots = bands_per_workgroup;
     return SDTW_OK;
 }

@@ -139,13 +139,15 @@ def test_value_E_and_gradients(mode, B, N, M, D, gamma):
     np.testing.assert_allclose(E[:, 0, 0], 1.0, atol=1e-4)
 
 
-@pytest.mark.parametrize("shape", [1, 4])
+@pytest.mark.parametrize("shape", [1, 2, 4])
 @pytest.mark.parametrize("mode", ["unfused", "fused"])
 @pytest.mark.parametrize("B,N,M,D,gamma", [(5, 200, 150, 16, 0.1), (2, 130, 257, 128, 0.05), (7, 65, 96, 20, 1.0),
-                                           (3, 100, 90, 200, 0.5)])
-def test_both_workgroup_shapes(shape, mode, B, N, M, D, gamma):
-    # the 4-bands-per-workgroup kernels are normally chosen only for > 1024 band tasks; force them
-    # on small inputs (B not a multiple of 4, D above the register-operand limit of 128 included)
+                                           (3, 100, 90, 200, 0.5), (2, 300, 40, 8, 0.3), (3, 50, 70, 4, 1.0)])
+def test_all_workgroup_shapes(shape, mode, B, N, M, D, gamma):
+    # one band per workgroup, a chained pair of bands per workgroup (normally for 2 or more bands),
+    # or 4 bands of 4 pairs (normally only for > 1024 band tasks): force each on small inputs
+    # (odd numbers of bands, a single band, B not a multiple of 4, D above the register-operand
+    # limit of 128 included)
     say("shape %d %s B=%d N=%d M=%d D=%d gamma=%g" % (shape, mode, B, N, M, D, gamma))
     x, y = workloads.normal_pairs(900 + N + D, B, N, M, D)
     ref = oracle.batch(x, y, gamma, want_E=True)
@@ -239,7 +241,7 @@ def test_backward_twice_after_one_forward_gives_the_same_result():
 
     x, y = workloads.normal_pairs(12, 2, 100, 130, 8)
     xd, yd = to_dev(x), to_dev(y)
-    for shape in (1, 4):
+    for shape in (1, 2, 4):
         binding.debug_force_workgroup_shape(shape)
         try:
             _, desc, ws = pkg.sdtw_forward(xd, yd, 0.3, pkg.FUSED)
