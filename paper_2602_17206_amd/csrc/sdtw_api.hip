@@ -142,9 +142,15 @@ void launch_dp_kch(const sdtw_desc *d, const Layout &L, const Params &p, float *
 {
     constexpr int NP = KCH > 0 ? 2 : 1;
     if (small_problem(d)) {
-        // pairs of consecutive bands share a workgroup (the hand-over between them stays in LDS),
-        // unless there is only one band
-        const bool chained = g_force_slots ? g_force_slots == 2 : L.nbands >= 2;
+        // Pairs of consecutive bands share a workgroup (the hand-over between them stays in LDS)
+        // when there are at least two bands and the producers are light: in the chained shape the
+        // producers of a band share one SIMD, which the D = 128 matrix-core producers fill
+        // (measured at N = M = 256: 57 us chained against 54 us, but 50 us against 53 us unfused).
+        // It also wants a compute unit per workgroup: two chained workgroups on one compute unit put
+        // two consumers on one SIMD (measured at N = M = 1024, B = 32: 5 % slower than unchained).
+        const bool light = d->mode == SDTW_UNFUSED || d->D <= 64;
+        const bool roomy = (int64_t)d->B * ((L.nbands + 1) / 2) * (L.two_sweep ? 2 : 1) <= 256;
+        const bool chained = g_force_slots ? g_force_slots == 2 : (L.nbands >= 2 && light && roomy);
         if constexpr (FWD) {
             if (chained) {
                 const unsigned tasks = (unsigned)d->B * (unsigned)((L.nbands + 1) / 2);
