@@ -26,6 +26,7 @@ if ROOT not in sys.path:
 # Published MI355X peaks used for the roofline fractions.
 PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_F32_TFLOPS = 157.3
+PEAK_MFMA_F16_TFLOPS = 2500.0  # dense; the cost and gradient contractions run there for D <= 128 (split operands)
 # Plain (non-packed, non-FMA) vector issue rate: 256 CUs x 64 lanes x 2.4 GHz.  The DP recurrence is
 # a dependent chain of min/sub/convert/exp2/log2 operations that can use neither FMA nor packing,
 # so this, not the 157.3 TFLOP/s packed-FMA figure (= 4x this), is the ceiling of its ALU work.
@@ -74,7 +75,9 @@ def roofline_for(name, ms_per_launch, wl_cells, D, traffic=None):
                "per_cell": {"valu_slots": slots}}
         if name.endswith("_fused"):
             fl = (2 if both else 1) * 2.0 * D * wl_cells / sec / 1e12
-            out["mfma"] = {"achieved": fl, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s", "frac": fl / PEAK_MFMA_F32_TFLOPS}
+            pk = PEAK_MFMA_F16_TFLOPS if D <= 128 else PEAK_MFMA_F32_TFLOPS
+            out["mfma"] = {"achieved": fl, "peak": pk, "unit": "TFLOP/s", "frac": fl / pk,
+                           "dtype": "f16 x3 (split operands)" if D <= 128 else "f32"}
         # table traffic: 8 B per cell and sweep; the E-forming reverse sweep also writes E; unfused reads the cost
         nbytes = (16.0 if both else 8.0) + (4.0 if name.startswith("backward") else 0.0) + \
                  ((8.0 if both else 4.0) if name.endswith("_unfused") else 0.0)
@@ -82,9 +85,9 @@ def roofline_for(name, ms_per_launch, wl_cells, D, traffic=None):
         out["hbm"] = {"achieved": bw, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": bw / PEAK_HBM_GBS, "bytes_per_cell": nbytes}
         return out
     if name == "cost_tensor":
-        fl = 2.0 * D * wl_cells / sec / 1e12
-        return {"kernel": name, "bound": "mfma", "achieved": fl, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
-                "frac": fl / PEAK_MFMA_F32_TFLOPS, "traffic": traffic}
+        bw = 4.0 * wl_cells / sec / 1e9  # the stored tensor
+        return {"kernel": name, "bound": "hbm", "achieved": bw, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": bw / PEAK_HBM_GBS, "traffic": traffic}
     if name == "alignment":
         bw = 20.0 * wl_cells / sec / 1e9  # reads both float64 tables, writes float32 E
         return {"kernel": name, "bound": "hbm", "achieved": bw, "peak": PEAK_HBM_GBS, "unit": "GB/s",
