@@ -301,6 +301,31 @@ def test_a_band_that_cannot_wait_gives_up_instead_of_hanging():
     np.testing.assert_allclose(value[:2].cpu().numpy(), ref["value"], rtol=VALUE_RTOL)
 
 
+# ------------------------------------------------------------------------------- rectangular at scale
+@pytest.mark.parametrize("mode", ["unfused", "fused"])
+@pytest.mark.parametrize("B,N,M,D,gamma", [(3, 4096, 320, 32, 0.1), (3, 200, 5000, 16, 0.05)])
+def test_rectangular_at_scale(mode, B, N, M, D, gamma):
+    # N != M well beyond one band / a few macro-steps in either direction (Sec. 5 allows unequal
+    # lengths; the paper only times squares).  The alignment hugs one side for most of its length.
+    say("rectangular %s B=%d N=%d M=%d D=%d gamma=%g" % (mode, B, N, M, D, gamma))
+    x, y = workloads.walk_pairs(40 + N % 7, B, N, M, D)
+    ref = oracle.batch(x, y, gamma)
+    got = run_gpu(x, y, gamma, MODES[mode], want_E=False)
+    check_against(ref, got, what="rectangular %s %dx%d" % (mode, N, M))
+
+
+def test_rectangular_large_regime():
+    # more than 1024 band tasks with N != M: the 4-band workgroups, recomputing fused backward
+    B, N, M, D, gamma = 40, 1700, 300, 24, 0.2
+    say("rectangular, large regime B=%d N=%d M=%d" % (B, N, M))
+    x, y = workloads.normal_pairs(51, B, N, M, D)
+    pairs = [0, 17, 39]
+    ref = oracle.batch(x[pairs], y[pairs], gamma)
+    for mode in ("unfused", "fused"):
+        got = run_gpu(x, y, gamma, MODES[mode], want_E=False)
+        check_against(ref, got, pairs=pairs, what="rectangular large " + mode)
+
+
 # ------------------------------------------------------------------------------- benchmark configurations
 @pytest.mark.parametrize("mode", ["unfused", "fused"])
 def test_config2_full(mode):
