@@ -6,4 +6,5 @@ from .sdtw_oracle import (  # noqa: F401
     from_cost,
     barycenter_step,
     max_threads,
+    normalized,
 )

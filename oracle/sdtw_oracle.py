@@ -112,6 +112,26 @@ def batch(x, y, gamma, grad_value=None, backward=True, want_E=False, nthreads=0)
     return out
 
 
+def normalized(x, y, gamma, grad_value=None, backward=True, nthreads=0):
+    """Normalised Soft-DTW (Sec. 6, the normalisation paragraph):
+    value = sdtw(x,y) - (sdtw(x,x) + sdtw(y,y)) / 2 per pair, written out as three plain calls
+    of :func:`batch`; the self terms are differentiated with respect to both of their arguments.
+    x [B,N,D], y [B,M,D] (N and M need not be equal here: each self term is a square problem of
+    its own).  Returns ``value`` [B] and, when ``backward``, ``dx``, ``dy``; the three plain values
+    are returned as ``parts`` [3,B] (xy, xx, yy)."""
+    x = np.asarray(x)
+    y = np.asarray(y)
+    xy = batch(x, y, gamma, grad_value=grad_value, backward=backward, nthreads=nthreads)
+    xx = batch(x, x, gamma, grad_value=grad_value, backward=backward, nthreads=nthreads)
+    yy = batch(y, y, gamma, grad_value=grad_value, backward=backward, nthreads=nthreads)
+    out = {"value": xy["value"] - 0.5 * (xx["value"] + yy["value"]),
+           "parts": np.stack([xy["value"], xx["value"], yy["value"]])}
+    if backward:
+        out["dx"] = xy["dx"] - 0.5 * (xx["dx"] + xx["dy"])
+        out["dy"] = xy["dy"] - 0.5 * (yy["dx"] + yy["dy"])
+    return out
+
+
 def pair_tables(x, y, gamma):
     """One pair x [N,D], y [M,D]; returns value, d [N,M], R [(N+2),(M+2)], E [N,M], dx, dy."""
     lib = _load()

@@ -307,6 +307,66 @@ def test_thread_count_does_not_change_results():
 
 
 # ----------------------------------------------------------------------------- barycenter step
+# ----------------------------------------------------------------------------- normalised Soft-DTW
+def test_normalized_value_against_enumeration_and_classic_dtw():
+    # Sec. 6 (normalisation): sdtw(x,y) - (sdtw(x,x) + sdtw(y,y))/2, each term pinned by path
+    # enumeration on its own cost matrix; as gamma -> 0 the self terms vanish (DTW(x,x) = 0)
+    rng = np.random.default_rng(23)
+    x = grid_inputs(rng, (5, 2))
+    y = grid_inputs(rng, (4, 2))
+
+    def cost(a, b):
+        return ((a[:, None, :].astype(np.float64) - b[None, :, :].astype(np.float64)) ** 2).sum(-1)
+
+    for gamma in (1.0, 0.2):
+        want = brute_force(cost(x, y), gamma)[0] - 0.5 * (brute_force(cost(x, x), gamma)[0] +
+                                                           brute_force(cost(y, y), gamma)[0])
+        got = oracle.normalized(x[None], y[None], gamma, backward=False)
+        assert got["value"][0] == pytest.approx(want, rel=1e-12, abs=1e-12)
+    g = 1e-5
+    tiny = oracle.normalized(x[None], y[None], g, backward=False)
+    logdel = math.log(int(delannoy_table(4, 4)[4, 4]))
+    assert tiny["value"][0] == pytest.approx(hard_dtw(cost(x, y)), abs=2 * g * logdel)
+    assert abs(tiny["parts"][1, 0]) <= g * logdel and abs(tiny["parts"][2, 0]) <= g * logdel
+
+
+def test_normalized_is_zero_on_the_diagonal_symmetric_and_differentiable():
+    rng = np.random.default_rng(29)
+    B, N, M, D, gamma = 2, 8, 6, 3, 0.5
+    x = grid_inputs(rng, (B, N, D))
+    y = grid_inputs(rng, (B, M, D))
+    same = oracle.normalized(x, x, gamma)
+    np.testing.assert_allclose(same["value"], 0.0, atol=1e-12)
+    np.testing.assert_allclose(same["dx"] + same["dy"], 0.0, atol=1e-12)  # a minimum along x = y
+    a = oracle.normalized(x, y, gamma)
+    b = oracle.normalized(y, x, gamma)
+    np.testing.assert_allclose(a["value"], b["value"], rtol=1e-12)
+    np.testing.assert_allclose(a["dx"], b["dy"], rtol=1e-10, atol=1e-12)
+    assert np.all(a["value"] > 0)   # a divergence: positive for x != y on these inputs
+    # finite differences through all three terms
+    h = 2.0 ** -10
+
+    def val(xx, yy):
+        return oracle.normalized(xx, yy, gamma, backward=False)["value"]
+
+    for (bb, i, k) in [(0, 0, 0), (1, 5, 2), (0, N - 1, 1)]:
+        xp, xm = x.copy(), x.copy()
+        xp[bb, i, k] += h
+        xm[bb, i, k] -= h
+        fd = (val(xp, y)[bb] - val(xm, y)[bb]) / (2 * h)
+        assert a["dx"][bb, i, k] == pytest.approx(fd, rel=2e-5, abs=1e-6)
+    for (bb, j, k) in [(1, 0, 1), (0, M - 1, 0)]:
+        yp, ym = y.copy(), y.copy()
+        yp[bb, j, k] += h
+        ym[bb, j, k] -= h
+        fd = (val(x, yp)[bb] - val(x, ym)[bb]) / (2 * h)
+        assert a["dy"][bb, j, k] == pytest.approx(fd, rel=2e-5, abs=1e-6)
+    # upstream gradient scales all three terms alike
+    gv = np.array([2.0, -0.5])
+    c = oracle.normalized(x, y, gamma, grad_value=gv)
+    np.testing.assert_allclose(c["dx"], a["dx"] * gv[:, None, None], rtol=1e-12, atol=1e-14)
+
+
 def test_barycenter_step_loss_gradient_and_first_adam_update():
     rng = np.random.default_rng(41)
     K, L, D, g = 5, 9, 2, 0.7
