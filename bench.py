@@ -216,6 +216,34 @@ def bench_barycenter(steps, warmup):
     return out
 
 
+def bench_normalized(wl, steps, warmup):
+    """Normalised Soft-DTW (cross term + two self terms), fused, forward+backward."""
+    import torch
+
+    import paper_2602_17206_amd as pkg
+
+    xd = torch.from_numpy(wl.x).cuda()
+    yd = torch.from_numpy(wl.y).cuda()
+    value, desc, ws = pkg.sdtw_normalized_forward(xd, yd, wl.gamma, pkg.FUSED)
+    dx, dy = torch.empty_like(xd), torch.empty_like(yd)
+
+    def step():
+        pkg.sdtw_normalized_forward(xd, yd, wl.gamma, pkg.FUSED, workspace=ws, value=value)
+        pkg.sdtw_normalized_backward(desc, xd, yd, ws, dx=dx, dy=dy)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    cells = wl.B * (wl.N * wl.M + wl.N * wl.N + wl.M * wl.M)
+    return {"workload": wl.name, "mode": "fused", "ms_per_step": dt * 1e3, "cells_per_step_three_terms": cells,
+            "fwd_bwd_cells_per_s": cells / dt, "workspace_bytes": ws.nbytes}
+
+
 def cpu_baseline(wl, target_wall_s=2.0):
     """The CPU oracle as it stands, forward+backward, all host threads, on whole batches of the
     workload repeated until about target_wall_s has passed."""
@@ -303,6 +331,7 @@ def main():
             del r2
             torch.cuda.empty_cache()
         others["c5_barycenter"] = bench_barycenter(50, 3)
+        others["normalized_c2"] = bench_normalized(wl, 20, 3)
         line["other_workloads"] = others
     print(json.dumps(line))
 

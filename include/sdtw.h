@@ -136,6 +136,24 @@ int sdtw_barycenter_step(const sdtw_bary_desc *desc, float *z, const float *X, f
                          size_t workspace_bytes, void *stream);
 
 /*
+ * Normalised Soft-DTW (Sec. 6, the normalisation paragraph):
+ *   value[b] = sdtw(x_b, y_b) - (sdtw(x_b, x_b) + sdtw(y_b, y_b)) / 2,
+ * three forward (and backward) passes through the kernels above: the cross term and the two self
+ * terms, each self term a square problem of its own, so N and M need not be equal.  A sequence
+ * shared by all pairs (batch stride 0) has its self term computed once.  The self terms are
+ * symmetric in their two arguments, so d/dx of sdtw(x,x)/2 is the gradient with respect to the
+ * first argument alone.  Arguments as for sdtw_forward / sdtw_backward (no E output); the
+ * workspace holds the three plain workspaces and the self terms' gradients, and its status word
+ * (sdtw_workspace_status) reports the worst of the three.
+ */
+size_t sdtw_normalized_workspace_bytes(const sdtw_desc *desc);
+int sdtw_normalized_forward(const sdtw_desc *desc, const float *x, const float *y, float *value,
+                            void *workspace, size_t workspace_bytes, void *stream);
+int sdtw_normalized_backward(const sdtw_desc *desc, const float *x, const float *y,
+                             const float *grad_value, float *dx, float *dy, void *workspace,
+                             size_t workspace_bytes, void *stream);
+
+/*
  * Reads the device-side status word of a workspace: waits for `stream`, copies 4 bytes to the
  * host.  *device_status receives SDTW_OK, SDTW_ERR_STATE or SDTW_ERR_TIMEOUT.  When a backward
  * call found SDTW_ERR_STATE its dx, dy and E outputs are filled with NaN.

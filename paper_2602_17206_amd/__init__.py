@@ -17,6 +17,9 @@ from .binding import (  # noqa: F401
     sdtw_barycenter_step,
     sdtw_barycenter_workspace_bytes,
     sdtw_forward,
+    sdtw_normalized_backward,
+    sdtw_normalized_forward,
+    sdtw_normalized_workspace_bytes,
     sdtw_status_string,
     sdtw_version,
     sdtw_workspace_bytes,

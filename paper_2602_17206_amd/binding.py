@@ -53,6 +53,7 @@ class BaryDesc(ctypes.Structure):
 EXPORTED_SYMBOLS = (
     "sdtw_version", "sdtw_status_string", "sdtw_workspace_bytes", "sdtw_forward", "sdtw_backward",
     "sdtw_barycenter_workspace_bytes", "sdtw_barycenter_step", "sdtw_workspace_status",
+    "sdtw_normalized_workspace_bytes", "sdtw_normalized_forward", "sdtw_normalized_backward",
     "sdtw_debug_export", "sdtw_debug_lane_shift", "sdtw_debug_set_spin_limit",
     "sdtw_debug_profile", "sdtw_debug_profile_read", "sdtw_debug_force_workgroup_shape",
 )
@@ -86,6 +87,12 @@ def load_library():
     lib.sdtw_barycenter_workspace_bytes.argtypes = [ctypes.POINTER(BaryDesc)]
     lib.sdtw_barycenter_step.restype = i32
     lib.sdtw_barycenter_step.argtypes = [ctypes.POINTER(BaryDesc), vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.sdtw_normalized_workspace_bytes.restype = sz
+    lib.sdtw_normalized_workspace_bytes.argtypes = [ctypes.POINTER(Desc)]
+    lib.sdtw_normalized_forward.restype = i32
+    lib.sdtw_normalized_forward.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, sz, vp]
+    lib.sdtw_normalized_backward.restype = i32
+    lib.sdtw_normalized_backward.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, sz, vp]
     lib.sdtw_workspace_status.restype = i32
     lib.sdtw_workspace_status.argtypes = [vp, sz, vp, ctypes.POINTER(ctypes.c_int32)]
     lib.sdtw_debug_export.restype = i32
@@ -239,6 +246,53 @@ def sdtw_backward(desc, x, y, workspace, grad_value=None, want_dx=True, want_dy=
     if rc != 0:
         raise SdtwError(rc, "sdtw_backward")
     return dx, dy, E
+
+
+def sdtw_normalized_workspace_bytes(desc):
+    return int(load_library().sdtw_normalized_workspace_bytes(ctypes.byref(desc)))
+
+
+def sdtw_normalized_forward(x, y, gamma, mode=FUSED, workspace=None, value=None, stream=None):
+    """value[b] = sdtw(x_b,y_b) - (sdtw(x_b,x_b) + sdtw(y_b,y_b)) / 2.  Returns (value, desc, workspace)."""
+    import torch
+
+    lib = load_library()
+    desc = _desc_for(x, y, gamma, mode)
+    if workspace is None:
+        nbytes = sdtw_normalized_workspace_bytes(desc)
+        if nbytes == 0:
+            raise SdtwError(STATUS_INVALID_ARG, "sdtw_normalized_workspace_bytes")
+        workspace = Workspace(nbytes, x.device)
+    if value is None:
+        value = torch.empty(desc.B, dtype=torch.float32, device=x.device)
+    rc = lib.sdtw_normalized_forward(ctypes.byref(desc), _ptr(x, torch.float32, name="x"),
+                                     _ptr(y, torch.float32, name="y"), _ptr(value, torch.float32, (desc.B,), "value"),
+                                     workspace.ptr, workspace.nbytes, _stream_ptr(stream))
+    if rc != 0:
+        raise SdtwError(rc, "sdtw_normalized_forward")
+    return value, desc, workspace
+
+
+def sdtw_normalized_backward(desc, x, y, workspace, grad_value=None, want_dx=True, want_dy=True, dx=None, dy=None,
+                             stream=None):
+    """Gradients of the normalised values.  Returns (dx [B,N,D] or None, dy [B,M,D] or None)."""
+    import torch
+
+    lib = load_library()
+    dev = x.device
+    if want_dx and dx is None:
+        dx = torch.empty((desc.B, desc.N, desc.D), dtype=torch.float32, device=dev)
+    if want_dy and dy is None:
+        dy = torch.empty((desc.B, desc.M, desc.D), dtype=torch.float32, device=dev)
+    rc = lib.sdtw_normalized_backward(
+        ctypes.byref(desc), _ptr(x, torch.float32, name="x"), _ptr(y, torch.float32, name="y"),
+        _ptr(grad_value, torch.float32, (desc.B,), "grad_value"),
+        _ptr(dx, torch.float32, (desc.B, desc.N, desc.D), "dx"),
+        _ptr(dy, torch.float32, (desc.B, desc.M, desc.D), "dy"),
+        workspace.ptr, workspace.nbytes, _stream_ptr(stream))
+    if rc != 0:
+        raise SdtwError(rc, "sdtw_normalized_backward")
+    return dx, dy
 
 
 def make_bary_desc(K, Lz, Lx, D, gamma, mode, lr, beta1, beta2, eps, step):

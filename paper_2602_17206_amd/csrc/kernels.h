@@ -662,6 +662,44 @@ __global__ void export_R_kernel(Params p, double *__restrict__ dst)
 }
 
 // ---------------------------------------------------------------------------------------------
+// Normalised Soft-DTW (Sec. 6): combination of the cross term and the two self terms.
+// ---------------------------------------------------------------------------------------------
+// value[b] = xy[b] - (xx[bx] + yy[by]) / 2; a shared sequence has one self term (index 0)
+__global__ void normalized_value_kernel(float *__restrict__ value, const float *__restrict__ vxy,
+                                        const float *__restrict__ vxx, const float *__restrict__ vyy, int B,
+                                        int x_shared, int y_shared)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B) value[b] = vxy[b] - 0.5f * (vxx[x_shared ? 0 : b] + vyy[y_shared ? 0 : b]);
+}
+
+// g[b][e] -= grad_value[b] * self[b or 0][e]: the self term's gradient with respect to its first
+// argument (computed with upstream gradient 1) is the gradient of half the self term.
+__global__ void normalized_grad_kernel(float *__restrict__ g, const float *__restrict__ self,
+                                       const float *__restrict__ grad_value, int B, int64_t per_pair, int shared)
+{
+    const int64_t n = (int64_t)B * per_pair;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) {
+        const int64_t b = i / per_pair, e = i - b * per_pair;
+        const float gv = grad_value ? grad_value[b] : 1.0f;
+        g[i] -= gv * self[(shared ? 0 : b) * per_pair + e];
+    }
+}
+
+// the cross term's header reports the worst status of the three workspaces
+__global__ void merge_status_kernel(Header *xy, const Header *xx, const Header *yy)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        int st = xy->status;
+        if (xx->magic == kMagic) st = max(st, xx->status);
+        if (yy->magic == kMagic) st = max(st, yy->status);
+        xy->status = st;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Barycenter step (Sec. 4.4): reduce over the K pairs, then Adam.
 // ---------------------------------------------------------------------------------------------
 struct AdamParams {

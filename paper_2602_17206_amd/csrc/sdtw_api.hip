@@ -333,6 +333,38 @@ BaryLayout bary_layout(const sdtw_bary_desc *d)
     return L;
 }
 
+// Normalised Soft-DTW: the three plain problems and where their workspaces sit.
+struct NormPlan {
+    sdtw_desc xy, xx, yy;
+    bool x_shared, y_shared;
+    size_t off_xy, off_xx, off_yy, off_vals, off_gx, off_gy, total;
+};
+
+NormPlan norm_plan(const sdtw_desc *d)
+{
+    NormPlan P{};
+    P.x_shared = d->x_batch_stride == 0;
+    P.y_shared = d->y_batch_stride == 0;
+    P.xy = *d;
+    P.xx = *d;
+    P.xx.B = P.x_shared ? 1 : d->B;
+    P.xx.M = d->N;
+    P.xx.y_batch_stride = d->x_batch_stride;
+    P.yy = *d;
+    P.yy.B = P.y_shared ? 1 : d->B;
+    P.yy.N = d->M;
+    P.yy.x_batch_stride = d->y_batch_stride;
+    size_t o = 0;
+    P.off_xy = o; o = align_up(o + layout_of(&P.xy).total, 256);  // first: its header carries the status word
+    P.off_xx = o; o = align_up(o + layout_of(&P.xx).total, 256);
+    P.off_yy = o; o = align_up(o + layout_of(&P.yy).total, 256);
+    P.off_vals = o; o = align_up(o + 3 * (size_t)d->B * sizeof(float), 256);
+    P.off_gx = o; o = align_up(o + (size_t)P.xx.B * d->N * (size_t)d->D * sizeof(float), 256);
+    P.off_gy = o; o = align_up(o + (size_t)P.yy.B * d->M * (size_t)d->D * sizeof(float), 256);
+    P.total = o;
+    return P;
+}
+
 }  // namespace
 
 extern "C" {
@@ -412,6 +444,64 @@ int sdtw_barycenter_step(const sdtw_bary_desc *desc, float *z, const float *X, f
         ProfScope ps("barycenter_update", st);
         barycenter_update_kernel<<<(unsigned)((a.n + 255) / 256), 256, 0, st>>>(a, dxk, values, z, adam_m, adam_v, loss, dz_out);
     }
+    return hip_ok();
+}
+
+size_t sdtw_normalized_workspace_bytes(const sdtw_desc *desc)
+{
+    int why;
+    if (!desc_ok(desc, &why)) return 0;
+    return norm_plan(desc).total;
+}
+
+int sdtw_normalized_forward(const sdtw_desc *desc, const float *x, const float *y, float *value, void *workspace,
+                            size_t workspace_bytes, void *stream)
+{
+    int why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!x || !y || !value) return SDTW_ERR_INVALID_ARG;
+    const NormPlan P = norm_plan(desc);
+    if (int rc = check_ws(workspace, workspace_bytes, P.total)) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *base = static_cast<char *>(workspace);
+    float *vals = reinterpret_cast<float *>(base + P.off_vals);
+    float *vxy = vals, *vxx = vals + desc->B, *vyy = vals + 2 * (size_t)desc->B;
+    if (int rc = forward_impl(&P.xy, x, y, vxy, base + P.off_xy, st)) return rc;
+    if (int rc = forward_impl(&P.xx, x, x, vxx, base + P.off_xx, st)) return rc;
+    if (int rc = forward_impl(&P.yy, y, y, vyy, base + P.off_yy, st)) return rc;
+    normalized_value_kernel<<<(desc->B + 255) / 256, 256, 0, st>>>(value, vxy, vxx, vyy, desc->B, P.x_shared, P.y_shared);
+    merge_status_kernel<<<1, 64, 0, st>>>(reinterpret_cast<Header *>(base + P.off_xy),
+                                          reinterpret_cast<const Header *>(base + P.off_xx),
+                                          reinterpret_cast<const Header *>(base + P.off_yy));
+    return hip_ok();
+}
+
+int sdtw_normalized_backward(const sdtw_desc *desc, const float *x, const float *y, const float *grad_value,
+                             float *dx, float *dy, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!x || !y) return SDTW_ERR_INVALID_ARG;
+    if (desc->flags & SDTW_FLAG_VALUE_ONLY) return SDTW_ERR_STATE;
+    const NormPlan P = norm_plan(desc);
+    if (int rc = check_ws(workspace, workspace_bytes, P.total)) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *base = static_cast<char *>(workspace);
+    float *gx = reinterpret_cast<float *>(base + P.off_gx), *gy = reinterpret_cast<float *>(base + P.off_gy);
+    if (int rc = backward_impl(&P.xy, x, y, grad_value, dx, dy, nullptr, base + P.off_xy, st)) return rc;
+    if (dx) {
+        if (int rc = backward_impl(&P.xx, x, x, nullptr, gx, nullptr, nullptr, base + P.off_xx, st)) return rc;
+        const int64_t per = (int64_t)desc->N * desc->D;
+        normalized_grad_kernel<<<fill_grid((size_t)desc->B * per), 256, 0, st>>>(dx, gx, grad_value, desc->B, per, P.x_shared);
+    }
+    if (dy) {
+        if (int rc = backward_impl(&P.yy, y, y, nullptr, gy, nullptr, nullptr, base + P.off_yy, st)) return rc;
+        const int64_t per = (int64_t)desc->M * desc->D;
+        normalized_grad_kernel<<<fill_grid((size_t)desc->B * per), 256, 0, st>>>(dy, gy, grad_value, desc->B, per, P.y_shared);
+    }
+    merge_status_kernel<<<1, 64, 0, st>>>(reinterpret_cast<Header *>(base + P.off_xy),
+                                          reinterpret_cast<const Header *>(base + P.off_xx),
+                                          reinterpret_cast<const Header *>(base + P.off_yy));
     return hip_ok();
 }
 

@@ -254,6 +254,49 @@ def test_backward_twice_after_one_forward_gives_the_same_result():
         assert torch.equal(dx1, dx2) and torch.equal(dy1, dy2)
 
 
+# ------------------------------------------------------------------------------- normalised Soft-DTW
+@pytest.mark.parametrize("mode", ["unfused", "fused"])
+@pytest.mark.parametrize("B,N,M,D,gamma,shared", [(3, 40, 40, 8, 0.5, False), (2, 130, 75, 16, 0.1, False),
+                                                  (4, 70, 200, 12, 1.0, True)])
+def test_normalized_value_and_gradients(mode, B, N, M, D, gamma, shared):
+    import torch
+
+    say("normalised %s B=%d N=%d M=%d D=%d gamma=%g shared_x=%s" % (mode, B, N, M, D, gamma, shared))
+    x, y = workloads.normal_pairs(700 + N, B, N, M, D)
+    if shared:
+        x = x[0]
+    gv = np.linspace(0.5, 2.0, B)
+    ref = oracle.normalized(np.broadcast_to(x, (B, N, D)) if shared else x, y, gamma, grad_value=gv)
+    plain = oracle.batch(x, y, gamma, grad_value=gv)  # scale of the terms that cancel
+    xd, yd = to_dev(x), to_dev(y)
+    value, desc, ws = pkg.sdtw_normalized_forward(xd, yd, gamma, MODES[mode])
+    dx, dy = pkg.sdtw_normalized_backward(desc, xd, yd, ws, grad_value=to_dev(gv.astype(np.float32)))
+    torch.cuda.synchronize()
+    assert binding.workspace_status(ws) == 0
+    v = value.cpu().numpy().astype(np.float64)
+    for b in range(B):
+        scale = max(np.abs(ref["parts"][:, b]).max(), 1.0)
+        assert abs(v[b] - ref["value"][b]) <= VALUE_RTOL * scale, (b, v[b], ref["value"][b])
+    for got, key in ((dx, "dx"), (dy, "dy")):
+        g = got.cpu().numpy().astype(np.float64)
+        for b in range(B):
+            scale = np.abs(plain[key][b]).max()
+            assert np.abs(g[b] - ref[key][b]).max() <= GRAD_RTOL * scale, (key, b)
+
+
+def test_normalized_of_identical_sequences_is_zero():
+    import torch
+
+    x, _ = workloads.normal_pairs(15, 3, 90, 90, 8)
+    xd = to_dev(x)
+    value, desc, ws = pkg.sdtw_normalized_forward(xd, xd, 0.3, pkg.FUSED)
+    dx, dy = pkg.sdtw_normalized_backward(desc, xd, xd, ws)
+    torch.cuda.synchronize()
+    assert binding.workspace_status(ws) == 0
+    assert torch.all(value.abs() <= 1e-3)
+    assert torch.all((dx + dy).abs() <= 1e-3 * max(dx.abs().max().item(), 1.0))
+
+
 # ------------------------------------------------------------------------------- device-side errors
 def test_backward_without_forward_is_refused_on_the_device():
     import torch
