@@ -119,6 +119,23 @@ int sdtw_backward(const sdtw_desc *desc, const float *x, const float *y, const f
                   float *dx, float *dy, float *E_out, void *workspace, size_t workspace_bytes,
                   void *stream);
 
+/*
+ * Ragged batches: pair b uses only the first x_len[b] rows of x_b and the first y_len[b] rows of
+ * y_b (Sec. 5 allows unequal lengths; here they may also differ from pair to pair).
+ *   x_len, y_len [B]: device, int32, read only; either may be NULL (every pair has the full
+ *        length N or M).  Values are clamped to [1, N] and [1, M].
+ *   value[b] = sdtw(x_b[:x_len[b]], y_b[:y_len[b]]);  dx, dy and E are 0 beyond a pair's lengths.
+ * Everything else as sdtw_forward / sdtw_backward (same descriptor and workspace size: the
+ * tensors keep their padded shapes [B,N,D], [B,M,D]).  The backward call must be given the same
+ * length vectors as the forward call (checked on the device by address: SDTW_ERR_STATE).
+ */
+int sdtw_forward_ragged(const sdtw_desc *desc, const float *x, const float *y, const int32_t *x_len,
+                        const int32_t *y_len, float *value, void *workspace, size_t workspace_bytes,
+                        void *stream);
+int sdtw_backward_ragged(const sdtw_desc *desc, const float *x, const float *y, const int32_t *x_len,
+                         const int32_t *y_len, const float *grad_value, float *dx, float *dy,
+                         float *E_out, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Bytes of workspace for sdtw_barycenter_step; 0 if the descriptor is invalid.  Host only. */
 size_t sdtw_barycenter_workspace_bytes(const sdtw_bary_desc *desc);
 

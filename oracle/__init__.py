@@ -7,4 +7,5 @@ from .sdtw_oracle import (  # noqa: F401
     barycenter_step,
     max_threads,
     normalized,
+    ragged_batch,
 )

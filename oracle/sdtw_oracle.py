@@ -112,6 +112,31 @@ def batch(x, y, gamma, grad_value=None, backward=True, want_E=False, nthreads=0)
     return out
 
 
+def ragged_batch(x, y, x_len, y_len, gamma, grad_value=None, want_E=False):
+    """Pairs of individual lengths inside padded tensors x [B,N,D], y [B,M,D] (Sec. 5: the lengths of
+    the two sequences of a pair may differ; here also from pair to pair): pair b is the plain
+    problem on x[b, :x_len[b]], y[b, :y_len[b]], one call of :func:`batch` each; gradients and E
+    are zero beyond a pair's lengths."""
+    x = np.asarray(x)
+    y = np.asarray(y)
+    B, N, D = x.shape
+    M = y.shape[1]
+    out = {"value": np.zeros(B), "dx": np.zeros((B, N, D)), "dy": np.zeros((B, M, D))}
+    if want_E:
+        out["E"] = np.zeros((B, N, M))
+    for b in range(B):
+        n = N if x_len is None else int(x_len[b])
+        m = M if y_len is None else int(y_len[b])
+        gv = None if grad_value is None else np.asarray(grad_value, dtype=np.float64)[b:b + 1]
+        o = batch(x[b:b + 1, :n], y[b:b + 1, :m], gamma, grad_value=gv, want_E=want_E)
+        out["value"][b] = o["value"][0]
+        out["dx"][b, :n] = o["dx"][0]
+        out["dy"][b, :m] = o["dy"][0]
+        if want_E:
+            out["E"][b, :n, :m] = o["E"][0]
+    return out
+
+
 def normalized(x, y, gamma, grad_value=None, backward=True, nthreads=0):
     """Normalised Soft-DTW (Sec. 6, the normalisation paragraph):
     value = sdtw(x,y) - (sdtw(x,x) + sdtw(y,y)) / 2 per pair, written out as three plain calls

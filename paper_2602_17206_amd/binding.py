@@ -54,6 +54,7 @@ EXPORTED_SYMBOLS = (
     "sdtw_version", "sdtw_status_string", "sdtw_workspace_bytes", "sdtw_forward", "sdtw_backward",
     "sdtw_barycenter_workspace_bytes", "sdtw_barycenter_step", "sdtw_workspace_status",
     "sdtw_normalized_workspace_bytes", "sdtw_normalized_forward", "sdtw_normalized_backward",
+    "sdtw_forward_ragged", "sdtw_backward_ragged",
     "sdtw_debug_export", "sdtw_debug_lane_shift", "sdtw_debug_set_spin_limit",
     "sdtw_debug_profile", "sdtw_debug_profile_read", "sdtw_debug_force_workgroup_shape",
 )
@@ -87,6 +88,10 @@ def load_library():
     lib.sdtw_barycenter_workspace_bytes.argtypes = [ctypes.POINTER(BaryDesc)]
     lib.sdtw_barycenter_step.restype = i32
     lib.sdtw_barycenter_step.argtypes = [ctypes.POINTER(BaryDesc), vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.sdtw_forward_ragged.restype = i32
+    lib.sdtw_forward_ragged.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.sdtw_backward_ragged.restype = i32
+    lib.sdtw_backward_ragged.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.sdtw_normalized_workspace_bytes.restype = sz
     lib.sdtw_normalized_workspace_bytes.argtypes = [ctypes.POINTER(Desc)]
     lib.sdtw_normalized_forward.restype = i32
@@ -245,6 +250,52 @@ def sdtw_backward(desc, x, y, workspace, grad_value=None, want_dx=True, want_dy=
         workspace.ptr, workspace.nbytes, _stream_ptr(stream))
     if rc != 0:
         raise SdtwError(rc, "sdtw_backward")
+    return dx, dy, E
+
+
+def sdtw_forward_ragged(x, y, x_len, y_len, gamma, mode=FUSED, workspace=None, value=None, stream=None):
+    """As :func:`sdtw_forward` for pairs of individual lengths: x_len, y_len are int32 device tensors
+    [B] (or None).  Returns (value, desc, workspace)."""
+    import torch
+
+    lib = load_library()
+    desc = _desc_for(x, y, gamma, mode)
+    if workspace is None:
+        workspace = Workspace(sdtw_workspace_bytes(desc), x.device)
+    if value is None:
+        value = torch.empty(desc.B, dtype=torch.float32, device=x.device)
+    rc = lib.sdtw_forward_ragged(ctypes.byref(desc), _ptr(x, torch.float32, name="x"), _ptr(y, torch.float32, name="y"),
+                                 _ptr(x_len, torch.int32, (desc.B,), "x_len"), _ptr(y_len, torch.int32, (desc.B,), "y_len"),
+                                 _ptr(value, torch.float32, (desc.B,), "value"), workspace.ptr, workspace.nbytes,
+                                 _stream_ptr(stream))
+    if rc != 0:
+        raise SdtwError(rc, "sdtw_forward_ragged")
+    return value, desc, workspace
+
+
+def sdtw_backward_ragged(desc, x, y, x_len, y_len, workspace, grad_value=None, want_E=False, dx=None, dy=None,
+                         E=None, stream=None):
+    """Gradients for :func:`sdtw_forward_ragged` (same length vectors).  Returns (dx, dy, E or None)."""
+    import torch
+
+    lib = load_library()
+    dev = x.device
+    if dx is None:
+        dx = torch.empty((desc.B, desc.N, desc.D), dtype=torch.float32, device=dev)
+    if dy is None:
+        dy = torch.empty((desc.B, desc.M, desc.D), dtype=torch.float32, device=dev)
+    if want_E and E is None:
+        E = torch.empty((desc.B, desc.N, desc.M), dtype=torch.float32, device=dev)
+    rc = lib.sdtw_backward_ragged(
+        ctypes.byref(desc), _ptr(x, torch.float32, name="x"), _ptr(y, torch.float32, name="y"),
+        _ptr(x_len, torch.int32, (desc.B,), "x_len"), _ptr(y_len, torch.int32, (desc.B,), "y_len"),
+        _ptr(grad_value, torch.float32, (desc.B,), "grad_value"),
+        _ptr(dx, torch.float32, (desc.B, desc.N, desc.D), "dx"),
+        _ptr(dy, torch.float32, (desc.B, desc.M, desc.D), "dy"),
+        _ptr(E, torch.float32, (desc.B, desc.N, desc.M), "E"),
+        workspace.ptr, workspace.nbytes, _stream_ptr(stream))
+    if rc != 0:
+        raise SdtwError(rc, "sdtw_backward_ragged")
     return dx, dy, E
 
 

@@ -101,4 +101,11 @@ __device__ __forceinline__ void cost_block(const Params &p, const float *__restr
     }
 }
 
+// Length of pair b's sequence when the batch is ragged (lens != nullptr), clamped to [1, full].
+__device__ __forceinline__ int pair_len(const int32_t *lens, int b, int full)
+{
+    if (lens == nullptr) return full;
+    return __builtin_amdgcn_readfirstlane(max(1, min(lens[b], full)));
+}
+
 }  // namespace sdtw

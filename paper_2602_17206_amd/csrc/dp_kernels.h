@@ -173,10 +173,10 @@ __device__ __forceinline__ void store_block_acc(float *ring, const floatx16 &acc
     }
 }
 
-// Unfused mode: the 32x32 block of the stored cost tensor as 4 float4 per lane
-// (lane -> row (lane>>3) + 8*it of the block, columns 4*(lane&7) ..), kBigCost outside the grid.
+// Unfused mode: the 32x32 block of the stored cost tensor (row length ld) as 4 float4 per lane
+// (lane -> row (lane>>3) + 8*it of the block, columns 4*(lane&7) ..), kBigCost outside the N x M grid.
 __device__ __forceinline__ void load_cost_block(float4 (&v)[4], const float *__restrict__ cost_b, int rb, int cb,
-                                                int row0, int N, int M, bool vec_m, int lane)
+                                                int row0, int N, int M, int ld, bool vec_m, int lane)
 {
     const int c4 = (lane & 7) * 4, j0 = 32 * cb;
 #pragma unroll
@@ -185,7 +185,7 @@ __device__ __forceinline__ void load_cost_block(float4 (&v)[4], const float *__r
         const int col = j0 + c4;
         float4 t = make_float4(kBigCost, kBigCost, kBigCost, kBigCost);
         if (row < N && col >= 0) {
-            const float *q = cost_b + (size_t)row * M + col;
+            const float *q = cost_b + (size_t)row * ld + col;
             if (vec_m && col + 3 < M) {
                 t = *reinterpret_cast<const float4 *>(q);
             } else {
@@ -574,6 +574,12 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
     const int row0 = k * kBandRows;
     float *ring = sh.ring[slot];
     const int bb = live ? b : 0;
+    // The pair's own lengths (ragged batches): cells beyond them are outside the grid for the cost
+    // producers (cost kBigCost), which is all it takes - their table entries are huge, their E is 0.
+    const int Nl = pair_len(p.x_len, bb, N), Ml = pair_len(p.y_len, bb, M);
+    Params pl = p;
+    pl.N = Nl;
+    pl.M = Ml;
     [[maybe_unused]] const float *xb = p.x + bb * p.x_stride, *yb = p.y + bb * p.y_stride;
     const float *xnb = p.xn + bb * p.xn_stride, *ynb = p.yn + bb * p.yn_stride;
     const float *xisb = p.xis + bb * p.xn_stride, *yisb = p.yis + bb * p.yn_stride;
@@ -586,14 +592,14 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
             // producer 1 makes (lower rows, sg), producer 2 makes (upper rows, sg+1)
             auto body = [&](auto &mp, bool first_block) {
                 if (live) {
-                    mp.init(p, xh, xnb, xisb, rowtab, row0, lane);
-                    if (first_block) mp.block_now(p, yh, ynb, yisb, ring, rowtab, 0, 0, row0, lane);
-                    mp.prime(p, yh, ynb, yisb, 0, lane);
+                    mp.init(pl, xh, xnb, xisb, rowtab, row0, lane);
+                    if (first_block) mp.block_now(pl, yh, ynb, yisb, ring, rowtab, 0, 0, row0, lane);
+                    mp.prime(pl, yh, ynb, yisb, 0, lane);
                 }
                 __syncthreads();
                 for (int it = 0; it < niter; ++it) {
                     const int sg = it - lag;
-                    if (live && sg >= 0 && sg < p.nmacro) mp.run(p, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
+                    if (live && sg >= 0 && sg < p.nmacro) mp.run(pl, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
                     __syncthreads();
                 }
             };
@@ -607,24 +613,24 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
         } else if constexpr (KCH > 0) {
             HalfProducer<KCH, +1, 0, 2> mp;
             if (live) {
-                mp.init(p, xh, xnb, xisb, rowtab, row0, lane);
-                mp.block_now(p, yh, ynb, yisb, ring, rowtab, 0, 0, row0, lane);  // (upper rows, column block 0)
-                mp.prime(p, yh, ynb, yisb, 0, lane);
+                mp.init(pl, xh, xnb, xisb, rowtab, row0, lane);
+                mp.block_now(pl, yh, ynb, yisb, ring, rowtab, 0, 0, row0, lane);  // (upper rows, column block 0)
+                mp.prime(pl, yh, ynb, yisb, 0, lane);
             }
             __syncthreads();
             for (int it = 0; it < niter; ++it) {
                 const int sg = it - lag;
-                if (live && sg >= 0 && sg < p.nmacro) mp.run(p, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
+                if (live && sg >= 0 && sg < p.nmacro) mp.run(pl, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
                 __syncthreads();
             }
         } else if constexpr (KCH == 0) {
-            if (live) generic_block(p, b, ring, 0, 0, row0, lane);
+            if (live) generic_block(pl, b, ring, 0, 0, row0, lane);
             __syncthreads();
             for (int it = 0; it < niter; ++it) {
                 const int sg = it - lag;
                 if (live && sg >= 0 && sg < p.nmacro) {
-                    generic_block(p, b, ring, 1, sg, row0, lane);
-                    generic_block(p, b, ring, 0, sg + 1, row0, lane);
+                    generic_block(pl, b, ring, 1, sg, row0, lane);
+                    generic_block(pl, b, ring, 0, sg + 1, row0, lane);
                 }
                 __syncthreads();
             }
@@ -632,10 +638,10 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
             const float *cost_b = p.cost + (size_t)bb * N * M;
             float4 pre[2][4];
             if (live) {
-                load_cost_block(pre[0], cost_b, 0, 0, row0, N, M, p.vec_m != 0, lane);
+                load_cost_block(pre[0], cost_b, 0, 0, row0, Nl, Ml, M, p.vec_m != 0, lane);
                 store_cost_block(ring, pre[0], 0, 0, lane);
-                load_cost_block(pre[0], cost_b, 1, 0, row0, N, M, p.vec_m != 0, lane);
-                load_cost_block(pre[1], cost_b, 0, 1, row0, N, M, p.vec_m != 0, lane);
+                load_cost_block(pre[0], cost_b, 1, 0, row0, Nl, Ml, M, p.vec_m != 0, lane);
+                load_cost_block(pre[1], cost_b, 0, 1, row0, Nl, Ml, M, p.vec_m != 0, lane);
             }
             __syncthreads();
             for (int it = 0; it < niter; ++it) {
@@ -643,8 +649,8 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
                 if (live && sg >= 0 && sg < p.nmacro) {
                     store_cost_block(ring, pre[0], 1, sg, lane);
                     store_cost_block(ring, pre[1], 0, sg + 1, lane);
-                    load_cost_block(pre[0], cost_b, 1, sg + 1, row0, N, M, p.vec_m != 0, lane);
-                    load_cost_block(pre[1], cost_b, 0, sg + 2, row0, N, M, p.vec_m != 0, lane);
+                    load_cost_block(pre[0], cost_b, 1, sg + 1, row0, Nl, Ml, M, p.vec_m != 0, lane);
+                    load_cost_block(pre[1], cost_b, 0, sg + 2, row0, Nl, Ml, M, p.vec_m != 0, lane);
                 }
                 __syncthreads();
             }
@@ -670,8 +676,8 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
     constexpr bool RECOMP = dp_recompute(KCH, SLOTS);
     double *Rk = RECOMP ? nullptr : p.R + ((size_t)bb * p.nbands + kc) * (size_t)p.nmacro * kBlk * kBandRows;
     double *Ck = RECOMP ? p.ckpt + ((size_t)bb * p.nbands + kc) * (size_t)p.nmacro * 2 * kBandRows : nullptr;
-    const int s_fin = (live && row0 + lane == N - 1) ? (M - 1 + lane) : -1;  // step of cell (N-1, M-1)
-    const bool last_band = live && (k + 1 == p.nbands);
+    const int s_fin = (live && row0 + lane == Nl - 1) ? (Ml - 1 + lane) : -1;  // step of the pair's last cell
+    const bool last_band = live && (k == (Nl - 1) / kBandRows);
     double fin = 0.0;
     const bool has_above = live && k > 0 && CH != 1;                // through memory
     const bool emit_bottom = live && (k + 1 < p.nbands) && CH != 0;  // through memory
@@ -755,8 +761,8 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
     }
 
     // R[N,M] of the pair: cell (N-1, M-1) was stored at step M-1+lane by the lane that owns row N-1
-    if (live && row0 + lane == N - 1) {
-        const double r = RECOMP ? fin : Rk[(size_t)(M - 1 + lane) * kBandRows + lane];
+    if (live && row0 + lane == Nl - 1) {
+        const double r = RECOMP ? fin : Rk[(size_t)(Ml - 1 + lane) * kBandRows + lane];
         p.rfinal[b] = r;                     // table units, for the backward sweep
         value[b] = (float)(r * p.inv_c2d);   // the paper's units
     }
@@ -873,6 +879,10 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
     const int row0 = (live ? k : 0) * kBandRows;
     float *ring = sh.ring[slot];
     const int bb = live ? b : 0;
+    const int Nl = pair_len(p.x_len, bb, N), Ml = pair_len(p.y_len, bb, M);  // the pair's own lengths
+    Params pl = p;
+    pl.N = Nl;
+    pl.M = Ml;
     [[maybe_unused]] const float *xb = p.x + bb * p.x_stride, *yb = p.y + bb * p.y_stride;
     const float *xnb = p.xn + bb * p.xn_stride, *ynb = p.yn + bb * p.yn_stride;
     const float *xisb = p.xis + bb * p.xn_stride, *yisb = p.yis + bb * p.yn_stride;
@@ -900,21 +910,21 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
             // producer 1 makes (upper rows, sg-2), producer 2 makes (lower rows, sg-3)
             auto body = [&](auto &mp, bool upper) {
                 if (live) {
-                    mp.init(p, xh, xnb, xisb, rowtab, row0, lane);
+                    mp.init(pl, xh, xnb, xisb, rowtab, row0, lane);
                     if (upper) {
-                        mp.block_now(p, yh, ynb, yisb, ring, rowtab, 0, sg0 - 1, row0, lane);
+                        mp.block_now(pl, yh, ynb, yisb, ring, rowtab, 0, sg0 - 1, row0, lane);
                     } else {
-                        mp.block_now(p, yh, ynb, yisb, ring, rowtab, 1, sg0 - 1, row0, lane);
-                        mp.block_now(p, yh, ynb, yisb, ring, rowtab, 1, sg0 - 2, row0, lane);
+                        mp.block_now(pl, yh, ynb, yisb, ring, rowtab, 1, sg0 - 1, row0, lane);
+                        mp.block_now(pl, yh, ynb, yisb, ring, rowtab, 1, sg0 - 2, row0, lane);
                     }
-                    mp.prime(p, yh, ynb, yisb, sg0, lane);
+                    mp.prime(pl, yh, ynb, yisb, sg0, lane);
                 }
                 __syncthreads();
                 for (int it = 0; it < niter; ++it) {
                     const int sg = sg0 - (it - lag);
                     if (live && sg >= 0 && sg <= sg0) {
                         if (sg < sg0) flush(sg + 1, upper, !upper);
-                        mp.run(p, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
+                        mp.run(pl, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
                     }
                     __syncthreads();
                 }
@@ -930,35 +940,35 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
         } else if constexpr (KCH > 0) {
             HalfProducer<KCH, -1, 0, 2> mp;
             if (live) {
-                mp.init(p, xh, xnb, xisb, rowtab, row0, lane);
-                mp.block_now(p, yh, ynb, yisb, ring, rowtab, 0, sg0 - 1, row0, lane);
-                mp.block_now(p, yh, ynb, yisb, ring, rowtab, 1, sg0 - 1, row0, lane);
-                mp.block_now(p, yh, ynb, yisb, ring, rowtab, 1, sg0 - 2, row0, lane);
-                mp.prime(p, yh, ynb, yisb, sg0, lane);
+                mp.init(pl, xh, xnb, xisb, rowtab, row0, lane);
+                mp.block_now(pl, yh, ynb, yisb, ring, rowtab, 0, sg0 - 1, row0, lane);
+                mp.block_now(pl, yh, ynb, yisb, ring, rowtab, 1, sg0 - 1, row0, lane);
+                mp.block_now(pl, yh, ynb, yisb, ring, rowtab, 1, sg0 - 2, row0, lane);
+                mp.prime(pl, yh, ynb, yisb, sg0, lane);
             }
             __syncthreads();
             for (int it = 0; it < niter; ++it) {
                 const int sg = sg0 - (it - lag);
                 if (live && sg >= 0 && sg <= sg0) {
                     if (sg < sg0) flush(sg + 1, true, true);
-                    mp.run(p, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
+                    mp.run(pl, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
                 }
                 __syncthreads();
             }
             if (live) flush(0, true, true);
         } else if constexpr (KCH == 0) {
             if (live) {
-                generic_block(p, b, ring, 0, sg0 - 1, row0, lane);
-                generic_block(p, b, ring, 1, sg0 - 1, row0, lane);
-                generic_block(p, b, ring, 1, sg0 - 2, row0, lane);
+                generic_block(pl, b, ring, 0, sg0 - 1, row0, lane);
+                generic_block(pl, b, ring, 1, sg0 - 1, row0, lane);
+                generic_block(pl, b, ring, 1, sg0 - 2, row0, lane);
             }
             __syncthreads();
             for (int it = 0; it < niter; ++it) {
                 const int sg = sg0 - (it - lag);
                 if (live && sg >= 0 && sg <= sg0) {
                     if (sg < sg0) flush(sg + 1, true, true);
-                    generic_block(p, b, ring, 0, sg - 2, row0, lane);
-                    generic_block(p, b, ring, 1, sg - 3, row0, lane);
+                    generic_block(pl, b, ring, 0, sg - 2, row0, lane);
+                    generic_block(pl, b, ring, 1, sg - 3, row0, lane);
                 }
                 __syncthreads();
             }
@@ -967,14 +977,14 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
             const float *cost_b = p.cost + (size_t)bb * N * M;
             float4 pre[2][4];
             if (live) {
-                load_cost_block(pre[0], cost_b, 0, sg0 - 1, row0, N, M, p.vec_m != 0, lane);
+                load_cost_block(pre[0], cost_b, 0, sg0 - 1, row0, Nl, Ml, M, p.vec_m != 0, lane);
                 store_cost_block(ring, pre[0], 0, sg0 - 1, lane);
-                load_cost_block(pre[0], cost_b, 1, sg0 - 1, row0, N, M, p.vec_m != 0, lane);
+                load_cost_block(pre[0], cost_b, 1, sg0 - 1, row0, Nl, Ml, M, p.vec_m != 0, lane);
                 store_cost_block(ring, pre[0], 1, sg0 - 1, lane);
-                load_cost_block(pre[0], cost_b, 1, sg0 - 2, row0, N, M, p.vec_m != 0, lane);
+                load_cost_block(pre[0], cost_b, 1, sg0 - 2, row0, Nl, Ml, M, p.vec_m != 0, lane);
                 store_cost_block(ring, pre[0], 1, sg0 - 2, lane);
-                load_cost_block(pre[0], cost_b, 0, sg0 - 2, row0, N, M, p.vec_m != 0, lane);
-                load_cost_block(pre[1], cost_b, 1, sg0 - 3, row0, N, M, p.vec_m != 0, lane);
+                load_cost_block(pre[0], cost_b, 0, sg0 - 2, row0, Nl, Ml, M, p.vec_m != 0, lane);
+                load_cost_block(pre[1], cost_b, 1, sg0 - 3, row0, Nl, Ml, M, p.vec_m != 0, lane);
             }
             __syncthreads();
             for (int it = 0; it < niter; ++it) {
@@ -983,8 +993,8 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
                     if (sg < sg0) flush(sg + 1, true, true);
                     store_cost_block(ring, pre[0], 0, sg - 2, lane);
                     store_cost_block(ring, pre[1], 1, sg - 3, lane);
-                    load_cost_block(pre[0], cost_b, 0, sg - 3, row0, N, M, p.vec_m != 0, lane);
-                    load_cost_block(pre[1], cost_b, 1, sg - 4, row0, N, M, p.vec_m != 0, lane);
+                    load_cost_block(pre[0], cost_b, 0, sg - 3, row0, Nl, Ml, M, p.vec_m != 0, lane);
+                    load_cost_block(pre[1], cost_b, 1, sg - 4, row0, Nl, Ml, M, p.vec_m != 0, lane);
                 }
                 __syncthreads();
             }
@@ -1005,9 +1015,9 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
     double diag = kBig;   // T[i+1][j+1]
     // step at which this lane meets the cell whose diagonal successor is T[N+1,M+1] = 0, and the
     // macro-step in which that happens in this band
-    const int s_corner = (live && row0 + lane == N - 1) ? (M - 1 + lane) : -1;
-    const int t_last = N - 1 - row0;
-    const int sg_corner = (live && t_last < kBandRows) ? (M - 1 + t_last) / kBlk : -1;
+    const int s_corner = (live && row0 + lane == Nl - 1) ? (Ml - 1 + lane) : -1;
+    const int t_last = Nl - 1 - row0;
+    const int sg_corner = (live && t_last >= 0 && t_last < kBandRows) ? (Ml - 1 + t_last) / kBlk : -1;
     const double Rfin = (live && !TSWEEP) ? p.rfinal[b] : 0.0;
     const int kc = live ? k : 0;
     const bool has_below = live && (k + 1 < p.nbands) && CH != 1;  // through memory

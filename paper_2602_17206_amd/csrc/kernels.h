@@ -46,6 +46,8 @@ __global__ __launch_bounds__(256) void forward_prep_kernel(Params p, int64_t xro
         h->gamma_bits = __float_as_uint(p.gamma);
         h->forward_done = 1;
         h->two_sweep = p.two_sweep;
+        h->x_len_ptr = reinterpret_cast<uint64_t>(p.x_len);
+        h->y_len_ptr = reinterpret_cast<uint64_t>(p.y_len);
         h->status = 0;
         h->abort_backward = 0;
         h->fwd_ticket = 0;
@@ -187,6 +189,7 @@ __device__ __forceinline__ bool workspace_matches(const Params &p)
     const Header *h = p.hdr;
     return h->magic == kMagic && h->forward_done == 1 && h->B == p.B && h->N == p.N && h->M == p.M &&
            h->D == p.D && h->mode == p.mode && h->two_sweep == p.two_sweep &&
+           h->x_len_ptr == reinterpret_cast<uint64_t>(p.x_len) && h->y_len_ptr == reinterpret_cast<uint64_t>(p.y_len) &&
            h->gamma_bits == __float_as_uint(p.gamma);
 }
 
@@ -269,6 +272,9 @@ __global__ __launch_bounds__(256) void input_grad_kernel(Params p, const float *
     const int Q = side == 0 ? p.M : p.N;  // reduced positions
     const int m0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
     if (m0 >= P) return;
+    // the pair's own lengths (ragged batches): E is zero beyond them, and neither the reduction nor the
+    // epilogue reads the sequences' padding
+    const int Pl = pair_len(side == 0 ? p.x_len : p.y_len, b, P), Ql = pair_len(side == 0 ? p.y_len : p.x_len, b, Q);
     const float *own = side == 0 ? p.x + b * p.x_stride : p.y + b * p.y_stride;   // sequence of the output side
     const float *oth = side == 0 ? p.y + b * p.y_stride : p.x + b * p.x_stride;   // sequence reduced over
     out += (size_t)b * P * p.D;
@@ -302,7 +308,7 @@ __global__ __launch_bounds__(256) void input_grad_kernel(Params p, const float *
         return live;
     };
     auto next_live = [&](int q0) {
-        while (q0 < Q && !chunk_live(q0)) q0 += kBlk;
+        while (q0 < Ql && !chunk_live(q0)) q0 += kBlk;
         return q0;
     };
     auto load4 = [](const float *q, int first, int limit, bool vec) {
@@ -336,7 +342,7 @@ __global__ __launch_bounds__(256) void input_grad_kernel(Params p, const float *
             }
             const int q = q0 + (e >> 4), n4 = (e & 15) * 4;
             rb[r] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (q < Q) rb[r] = load4(oth + (size_t)q * p.D + n0 + n4, n0 + n4, p.D, p.vec_xy != 0);
+            if (q < Ql) rb[r] = load4(oth + (size_t)q * p.D + n0 + n4, n0 + n4, p.D, p.vec_xy != 0);
         }
     };
     auto stash = [&]() {
@@ -357,13 +363,13 @@ __global__ __launch_bounds__(256) void input_grad_kernel(Params p, const float *
     };
 
     int q0 = next_live(0);
-    if (q0 < Q) fetch(q0);
-    while (q0 < Q) {
+    if (q0 < Ql) fetch(q0);
+    while (q0 < Ql) {
         __syncthreads();  // previous chunk's reads are done
         stash();
         __syncthreads();
         q0 = next_live(q0 + kBlk);
-        if (q0 < Q) fetch(q0);
+        if (q0 < Ql) fetch(q0);
 
         // marginal sums: wavefront w adds rows k = 8w .. 8w+7 of the A tile for output row `lane`
 #pragma unroll
@@ -389,7 +395,8 @@ __global__ __launch_bounds__(256) void input_grad_kernel(Params p, const float *
             const int m = m0 + ml;
             if (m < P) {
                 const float tot = (msum_part[0][ml] + msum_part[1][ml]) + (msum_part[2][ml] + msum_part[3][ml]);
-                out[(size_t)m * p.D + n] = scale * (own[(size_t)m * p.D + n] * tot - acc[i]);
+                const float ov = m < Pl ? own[(size_t)m * p.D + n] : 0.f;
+                out[(size_t)m * p.D + n] = scale * (ov * tot - acc[i]);
             }
         }
     }
@@ -438,6 +445,9 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
     const int Q = side == 0 ? p.M : p.N;  // reduced positions
     const int m0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
     if (m0 >= P) return;
+    // the pair's own lengths (ragged batches): E is zero beyond them, and neither the reduction nor the
+    // epilogue reads the sequences' padding
+    const int Pl = pair_len(side == 0 ? p.x_len : p.y_len, b, P), Ql = pair_len(side == 0 ? p.y_len : p.x_len, b, Q);
     const float *own = side == 0 ? p.x + b * p.x_stride : p.y + b * p.y_stride;   // sequence of the output side
     const float *oth = side == 0 ? p.y + b * p.y_stride : p.x + b * p.x_stride;   // sequence reduced over
     // its rows' 1/scale (positive powers of two: their bit patterns order like the values)
@@ -457,7 +467,7 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
     const float sA = 1024.0f;
     // the largest 1/scale among the chunk's 32 rows: one row per lane (mod 32), then a butterfly
     auto chunk_ismax = [&](int q0) {
-        unsigned mx = oth_is[min(q0 + (lane & 31), Q - 1)];
+        unsigned mx = oth_is[min(q0 + (lane & 31), Ql - 1)];
 #pragma unroll
         for (int o = 16; o > 0; o >>= 1) mx = max(mx, (unsigned)__shfl_xor((int)mx, o));
         return __uint_as_float(mx);
@@ -519,7 +529,7 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
             const int q = q0 + bk + c;
-            bv[c] = (q < Q && n < p.D) ? oth[(size_t)q * p.D + n] : 0.f;
+            bv[c] = (q < Ql && n < p.D) ? oth[(size_t)q * p.D + n] : 0.f;
         }
     };
     auto stash = [&](const float (&ea)[8], const float (&bv)[8], float ismax) {
@@ -559,7 +569,7 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
     // with it the rounding never changes); then the listed chunks are contracted with two of them in
     // flight: while chunk c is contracted, the values of chunk c+1 are arriving and those of chunk
     // c+2 are requested.
-    const int nchunk = (Q + kBlk - 1) / kBlk;
+    const int nchunk = (Ql + kBlk - 1) / kBlk;
     // the output side's own values for the epilogue, requested now so that they are there by then
     float own_v[16];
     {
@@ -567,7 +577,7 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int m = m0 + wr * 32 + acc_row(i, lane);
-            own_v[i] = (m < P && n < p.D) ? own[(size_t)m * p.D + n] : 0.f;
+            own_v[i] = (m < Pl && n < p.D) ? own[(size_t)m * p.D + n] : 0.f;
         }
     }
     float ea0[8], bv0[8], ea1[8], bv1[8], is0 = 1.f, is1 = 1.f;

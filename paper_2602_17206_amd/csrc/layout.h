@@ -27,7 +27,9 @@ struct Header {
     uint32_t fwd_ticket;   // next band task of the forward sweep
     uint32_t bwd_ticket;   // next band task of the backward sweep
     int32_t two_sweep;     // the forward call also ran the reverse sweep
-    uint32_t pad[51];
+    uint32_t pad0;
+    uint64_t x_len_ptr, y_len_ptr;  // the length vectors the forward was run with (0: none)
+    uint32_t pad[46];
 };
 static_assert(sizeof(Header) == 256, "header is 256 bytes");
 
@@ -120,6 +122,7 @@ struct Params {
     int32_t vec_m;                 // 1: M%4==0 -> float4 loads/stores of cost and E rows
     uint32_t spin_limit;           // polls before a band gives up waiting
     const float *x, *y;
+    const int32_t *x_len, *y_len;  // ragged batches: per-pair lengths (device), or nullptr
     Header *hdr;
     double *rfinal;
     float *xn, *yn;

@@ -77,9 +77,12 @@ Layout layout_of(const sdtw_desc *d)
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-Params make_params(const sdtw_desc *d, const Layout &L, const float *x, const float *y, void *ws)
+Params make_params(const sdtw_desc *d, const Layout &L, const float *x, const float *y, void *ws,
+                   const int32_t *x_len = nullptr, const int32_t *y_len = nullptr)
 {
     Params p{};
+    p.x_len = x_len;
+    p.y_len = y_len;
     char *base = static_cast<char *>(ws);
     p.B = d->B; p.N = d->N; p.M = d->M; p.D = d->D; p.mode = d->mode;
     p.nbands = L.nbands; p.nmacro = L.nmacro; p.nrb = L.nrb; p.ncb = L.ncb;
@@ -211,10 +214,11 @@ unsigned prep_grid(const Params &p, int64_t norm_rows)
     return (unsigned)(g < 1 ? 1 : (g > 8192 ? 8192 : g));
 }
 
-int forward_impl(const sdtw_desc *d, const float *x, const float *y, float *value, void *ws, hipStream_t st)
+int forward_impl(const sdtw_desc *d, const float *x, const float *y, float *value, void *ws, hipStream_t st,
+                 const int32_t *x_len = nullptr, const int32_t *y_len = nullptr)
 {
     const Layout L = layout_of(d);
-    const Params p = make_params(d, L, x, y, ws);
+    const Params p = make_params(d, L, x, y, ws, x_len, y_len);
     {
         ProfScope ps("forward_prep", st);
         forward_prep_kernel<<<prep_grid(p, L.xn_count + L.yn_count), 256, 0, st>>>(p, L.xn_count, L.yn_count);
@@ -253,10 +257,11 @@ int forward_impl(const sdtw_desc *d, const float *x, const float *y, float *valu
 }
 
 int backward_impl(const sdtw_desc *d, const float *x, const float *y, const float *grad_value, float *dx,
-                  float *dy, float *E_out, void *ws, hipStream_t st)
+                  float *dy, float *E_out, void *ws, hipStream_t st, const int32_t *x_len = nullptr,
+                  const int32_t *y_len = nullptr)
 {
     const Layout L = layout_of(d);
-    const Params p = make_params(d, L, x, y, ws);
+    const Params p = make_params(d, L, x, y, ws, x_len, y_len);
     if (L.two_sweep) {
         // both tables are there: combine them (the kernel checks the workspace itself)
         ProfScope ps("alignment", st);
@@ -411,6 +416,29 @@ int sdtw_backward(const sdtw_desc *desc, const float *x, const float *y, const f
     if (desc->flags & SDTW_FLAG_VALUE_ONLY) return SDTW_ERR_STATE;
     if (int rc = check_ws(workspace, workspace_bytes, layout_of(desc).total)) return rc;
     return backward_impl(desc, x, y, grad_value, dx, dy, E_out, workspace, static_cast<hipStream_t>(stream));
+}
+
+int sdtw_forward_ragged(const sdtw_desc *desc, const float *x, const float *y, const int32_t *x_len,
+                        const int32_t *y_len, float *value, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!x || !y || !value) return SDTW_ERR_INVALID_ARG;
+    if (int rc = check_ws(workspace, workspace_bytes, layout_of(desc).total)) return rc;
+    return forward_impl(desc, x, y, value, workspace, static_cast<hipStream_t>(stream), x_len, y_len);
+}
+
+int sdtw_backward_ragged(const sdtw_desc *desc, const float *x, const float *y, const int32_t *x_len,
+                         const int32_t *y_len, const float *grad_value, float *dx, float *dy, float *E_out,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    int why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!x || !y) return SDTW_ERR_INVALID_ARG;
+    if (desc->flags & SDTW_FLAG_VALUE_ONLY) return SDTW_ERR_STATE;
+    if (int rc = check_ws(workspace, workspace_bytes, layout_of(desc).total)) return rc;
+    return backward_impl(desc, x, y, grad_value, dx, dy, E_out, workspace, static_cast<hipStream_t>(stream), x_len,
+                         y_len);
 }
 
 size_t sdtw_barycenter_workspace_bytes(const sdtw_bary_desc *desc)

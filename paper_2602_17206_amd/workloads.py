@@ -37,6 +37,17 @@ def walk_pairs(seed, B, N, M, D, step_std=0.1):
     return x, y
 
 
+def ragged_lengths(seed, B, full, shortest=1):
+    """Per-pair lengths for a padded batch: uniform integers in [shortest, full], int32; pair 0 keeps
+    the full length and pair B-1 (if B > 1) the shortest, so both ends are always present."""
+    rng = np.random.default_rng(seed)
+    lens = rng.integers(shortest, full + 1, size=B).astype(np.int32)
+    lens[0] = full
+    if B > 1:
+        lens[-1] = shortest
+    return lens
+
+
 def pair_workload(name, B=None, N=None, M=None, D=None):
     """One of CONFIG_SHAPES by name; B/N/M/D override the shape (same recipe and seed)."""
     b, n, m, d, gamma, modes, kind, seed = CONFIG_SHAPES[name]

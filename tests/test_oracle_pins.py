@@ -308,6 +308,34 @@ def test_thread_count_does_not_change_results():
 
 # ----------------------------------------------------------------------------- barycenter step
 # ----------------------------------------------------------------------------- normalised Soft-DTW
+def test_ragged_batch_is_the_plain_problem_on_each_pair_s_own_prefix():
+    # per pair against path enumeration on the sliced cost matrix; padding must not matter and the
+    # gradients beyond the lengths are zero
+    rng = np.random.default_rng(77)
+    B, N, M, D, gamma = 3, 5, 4, 2, 0.6
+    x = rng.standard_normal((B, N, D)).astype(np.float32).astype(np.float64)
+    y = rng.standard_normal((B, M, D)).astype(np.float32).astype(np.float64)
+    xl, yl = np.array([5, 2, 1]), np.array([3, 4, 1])
+    out = oracle.ragged_batch(x, y, xl, yl, gamma, want_E=True)
+    for b in range(B):
+        n, m = xl[b], yl[b]
+        d = ((x[b, :n, None, :] - y[b, None, :m, :]) ** 2).sum(-1)
+        val, E, _ = brute_force(d, gamma)
+        assert abs(out["value"][b] - val) < 1e-12
+        assert np.abs(out["E"][b, :n, :m] - E).max() < 1e-12
+        assert not out["E"][b, n:].any() and not out["E"][b, :, m:].any()
+        assert not out["dx"][b, n:].any() and not out["dy"][b, m:].any()
+        gx = 2 * (E[:, :, None] * (x[b, :n, None, :] - y[b, None, :m, :])).sum(1)
+        assert np.abs(out["dx"][b, :n] - gx).max() < 1e-12
+    x2, y2 = x.copy(), y.copy()
+    x2[1, 2:] = 1e3
+    y2[0, 3:] = -1e3
+    out2 = oracle.ragged_batch(x2, y2, xl, yl, gamma)
+    assert np.array_equal(out2["value"], out["value"]) and np.array_equal(out2["dy"], out["dy"])
+    full = oracle.ragged_batch(x, y, None, None, gamma)
+    assert np.array_equal(full["value"], oracle.batch(x, y, gamma)["value"])
+
+
 def test_normalized_value_against_enumeration_and_classic_dtw():
     # Sec. 6 (normalisation): sdtw(x,y) - (sdtw(x,x) + sdtw(y,y))/2, each term pinned by path
     # enumeration on its own cost matrix; as gamma -> 0 the self terms vanish (DTW(x,x) = 0)

@@ -254,6 +254,106 @@ def test_backward_twice_after_one_forward_gives_the_same_result():
         assert torch.equal(dx1, dx2) and torch.equal(dy1, dy2)
 
 
+# ------------------------------------------------------------------------------- ragged batches
+def run_gpu_ragged(x, y, xl, yl, gamma, mode, grad_value=None, want_E=True):
+    import torch
+
+    xd, yd = to_dev(x), to_dev(y)
+    xld = to_dev(xl) if xl is not None else None
+    yld = to_dev(yl) if yl is not None else None
+    value, desc, ws = pkg.sdtw_forward_ragged(xd, yd, xld, yld, gamma, mode)
+    gv = to_dev(grad_value.astype(np.float32)) if grad_value is not None else None
+    dx, dy, E = pkg.sdtw_backward_ragged(desc, xd, yd, xld, yld, ws, grad_value=gv, want_E=want_E)
+    torch.cuda.synchronize()
+    assert binding.workspace_status(ws) == 0
+    out = {"value": value.cpu().numpy().astype(np.float64), "dx": dx.cpu().numpy().astype(np.float64),
+           "dy": dy.cpu().numpy().astype(np.float64)}
+    if want_E:
+        out["E"] = E.cpu().numpy().astype(np.float64)
+    return out
+
+
+@pytest.mark.parametrize("shape", [0, 1, 2, 4])
+@pytest.mark.parametrize("mode", ["unfused", "fused"])
+@pytest.mark.parametrize("B,N,M,D,gamma", [(6, 200, 150, 16, 0.1), (4, 130, 257, 128, 0.05), (5, 64, 64, 8, 1.0),
+                                           (3, 300, 90, 200, 0.5)])
+def test_ragged_batches(shape, mode, B, N, M, D, gamma):
+    # every pair with lengths of its own (pair 0 full, the last pair of length 1 on the x side and
+    # full on the y side or the reverse), in each workgroup shape; E and gradients beyond the lengths
+    # must come out as exact zeros
+    say("ragged shape %d %s B=%d N=%d M=%d D=%d" % (shape, mode, B, N, M, D))
+    x, y = workloads.normal_pairs(300 + N + D, B, N, M, D)
+    xl = workloads.ragged_lengths(31 + N, B, N)
+    yl = workloads.ragged_lengths(32 + M, B, M)[::-1].copy()
+    gv = np.linspace(0.5, 2.0, B)
+    ref = oracle.ragged_batch(x, y, xl, yl, gamma, grad_value=gv, want_E=True)
+    binding.debug_force_workgroup_shape(shape)
+    try:
+        got = run_gpu_ragged(x, y, xl, yl, gamma, MODES[mode], grad_value=gv)
+    finally:
+        binding.debug_force_workgroup_shape(0)
+    check_against(ref, got, what="ragged shape %d %s" % (shape, mode))
+    for b in range(B):
+        assert not got["E"][b, xl[b]:].any() and not got["E"][b, :, yl[b]:].any()
+        assert not got["dx"][b, xl[b]:].any() and not got["dy"][b, yl[b]:].any()
+
+
+@pytest.mark.parametrize("mode", ["unfused", "fused"])
+def test_ragged_results_do_not_depend_on_the_padding(mode):
+    import torch
+
+    B, N, M, D, gamma = 4, 150, 210, 12, 0.2
+    x, y = workloads.normal_pairs(81, B, N, M, D)
+    xl = workloads.ragged_lengths(82, B, N, shortest=3)
+    yl = workloads.ragged_lengths(83, B, M, shortest=70)
+    a = run_gpu_ragged(x, y, xl, yl, gamma, MODES[mode])
+    x2, y2 = x.copy(), y.copy()
+    for b in range(B):
+        x2[b, xl[b]:] = 1e4
+        y2[b, yl[b]:] = np.nan
+    c = run_gpu_ragged(x2, y2, xl, yl, gamma, MODES[mode])
+    for key in ("value", "dx", "dy", "E"):
+        assert np.array_equal(a[key], c[key]), key
+    # one length vector only, and none at all (then the plain entry point's result, bit for bit)
+    ref = oracle.ragged_batch(x, y, None, yl, gamma, want_E=True)
+    check_against(ref, run_gpu_ragged(x, y, None, yl, gamma, MODES[mode]), what="y lengths only")
+    plain = run_gpu(x, y, gamma, MODES[mode])
+    none = run_gpu_ragged(x, y, None, None, gamma, MODES[mode])
+    for key in ("value", "dx", "dy", "E"):
+        assert np.array_equal(plain[key], none[key]), key
+    torch.cuda.synchronize()
+
+
+def test_ragged_large_regime_and_state_check():
+    import torch
+
+    # more than 1024 band tasks: 4-band workgroups, stored-table backward and recomputing backward
+    B, N, M, D, gamma = 48, 1500, 400, 24, 0.2
+    say("ragged, large regime B=%d N=%d M=%d" % (B, N, M))
+    x, y = workloads.normal_pairs(52, B, N, M, D)
+    xl = workloads.ragged_lengths(53, B, N)
+    yl = workloads.ragged_lengths(54, B, M)
+    pairs = [0, 1, 20, 47]
+    ref = oracle.ragged_batch(x[pairs], y[pairs], xl[pairs], yl[pairs], gamma)
+    for mode in ("unfused", "fused"):
+        got = run_gpu_ragged(x, y, xl, yl, gamma, MODES[mode], want_E=False)
+        check_against(ref, got, pairs=pairs, what="ragged large " + mode)
+        for b in range(B):
+            assert not got["dx"][b, xl[b]:].any() and not got["dy"][b, yl[b]:].any()
+    # a backward call with other length vectors than the forward's is refused on the device
+    xd, yd, xld, yld = to_dev(x[:2, :100]), to_dev(y[:2, :90]), to_dev(xl[:2] % 100 + 1), to_dev(yl[:2] % 90 + 1)
+    _, desc, ws = pkg.sdtw_forward_ragged(xd, yd, xld, yld, gamma, pkg.FUSED)
+    other = xld.clone()
+    dx, dy, _ = pkg.sdtw_backward_ragged(desc, xd, yd, other, yld, ws)
+    torch.cuda.synchronize()
+    assert binding.workspace_status(ws) == binding.STATUS_STATE
+    assert torch.isnan(dx).all() and torch.isnan(dy).all()
+    _, desc, ws = pkg.sdtw_forward_ragged(xd, yd, xld, yld, gamma, pkg.FUSED)
+    dx, dy, _ = pkg.sdtw_backward(desc, xd, yd, ws)
+    torch.cuda.synchronize()
+    assert binding.workspace_status(ws) == binding.STATUS_STATE
+
+
 # ------------------------------------------------------------------------------- normalised Soft-DTW
 @pytest.mark.parametrize("mode", ["unfused", "fused"])
 @pytest.mark.parametrize("B,N,M,D,gamma,shared", [(3, 40, 40, 8, 0.5, False), (2, 130, 75, 16, 0.1, False),
