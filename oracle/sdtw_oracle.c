@@ -20,6 +20,10 @@
  *                                                            (Sec. 4.3, last two equations)
  *   - barycenter     loss = sum_k sdtw(z, x^(k)), dz = sum_k d/dz, Adam update
  *                                                            (Sec. 4.4)
+ *   - band           Algorithm 1 takes a `bandwidth` the paper does not define; the reading
+ *                    here is the Sakoe-Chiba band: only cells with |i-j| <= w belong to the
+ *                    grid.  The others are never visited: their R stays +inf, their Ebar
+ *                    -inf (E = 0), exactly like the cells of the padding.  w < 0: no band.
  * Cells are visited in row-major order; there is no blocking, fusion or
  * reordering.  OpenMP is used only ACROSS pairs (each pair is independent).
  *
@@ -86,25 +90,40 @@ void sdtw_oracle_cost(const float *x, const float *y, int N, int M, int D, doubl
         }
 }
 
+/* Is cell (i,j) inside the band |i-j| <= w?  (w < 0: there is no band.) */
+static int in_band(int i, int j, int w)
+{
+    if (w < 0) return 1;
+    return (i > j ? i - j : j - i) <= w;
+}
+
 /* Forward table.  R has (N+2) x (M+2) entries (row stride M+2), indices 0..N+1 /
  * 0..M+1 as in Algorithm 1's padded table; row N+1 and column M+1 are left +inf
- * for the backward pass.  Returns R[N,M]. */
-double sdtw_oracle_forward(const double *d, int N, int M, double gamma, double *R)
+ * for the backward pass, and so is every cell outside the band.  Returns R[N,M]. */
+double sdtw_oracle_forward_banded(const double *d, int N, int M, double gamma, int w, double *R)
 {
     const size_t W = (size_t)M + 2;
     for (size_t q = 0; q < ((size_t)N + 2) * W; ++q) R[q] = INFINITY;
     R[0] = 0.0;
     for (int i = 1; i <= N; ++i)
-        for (int j = 1; j <= M; ++j)
-            R[i * W + j] = d[(size_t)(i - 1) * M + (j - 1)] +
-                           softmin3(R[(i - 1) * W + (j - 1)], R[(i - 1) * W + j], R[i * W + (j - 1)], gamma);
+        for (int j = 1; j <= M; ++j) {
+            if (!in_band(i, j, w)) continue;
+            const double a = R[(i - 1) * W + (j - 1)], b = R[(i - 1) * W + j], c = R[i * W + (j - 1)];
+            if (!(a < INFINITY) && !(b < INFINITY) && !(c < INFINITY)) continue;  /* unreachable cell */
+            R[i * W + j] = d[(size_t)(i - 1) * M + (j - 1)] + softmin3(a, b, c, gamma);
+        }
     return R[(size_t)N * W + M];
+}
+
+double sdtw_oracle_forward(const double *d, int N, int M, double gamma, double *R)
+{
+    return sdtw_oracle_forward_banded(d, N, M, gamma, -1, R);
 }
 
 /* Log-space backward.  E is [N,M] (0-based storage of the 1-based matrix).  Ebar is
  * scratch of (N+2) x (M+2).  A successor outside 1..N x 1..M contributes -inf. */
-void sdtw_oracle_backward(const double *d, const double *R, int N, int M, double gamma,
-                          double *Ebar, double *E)
+void sdtw_oracle_backward_banded(const double *d, const double *R, int N, int M, double gamma, int w,
+                                 double *Ebar, double *E)
 {
     const size_t W = (size_t)M + 2;
     for (size_t q = 0; q < ((size_t)N + 2) * W; ++q) Ebar[q] = -INFINITY;
@@ -112,25 +131,32 @@ void sdtw_oracle_backward(const double *d, const double *R, int N, int M, double
     for (int i = N; i >= 1; --i)
         for (int j = M; j >= 1; --j) {
             if (i == N && j == M) continue;
+            if (!in_band(i, j, w)) continue;
             const double r = R[i * W + j];
             double ta = -INFINITY, tb = -INFINITY, tc = -INFINITY;
-            if (i + 1 <= N) {
+            if (i + 1 <= N && in_band(i + 1, j, w)) {
                 double alpha = (R[(i + 1) * W + j] - r - d[(size_t)i * M + (j - 1)]) / gamma;
                 ta = Ebar[(i + 1) * W + j] + alpha;
             }
-            if (j + 1 <= M) {
+            if (j + 1 <= M && in_band(i, j + 1, w)) {
                 double beta = (R[i * W + (j + 1)] - r - d[(size_t)(i - 1) * M + j]) / gamma;
                 tb = Ebar[i * W + (j + 1)] + beta;
             }
-            if (i + 1 <= N && j + 1 <= M) {
+            if (i + 1 <= N && j + 1 <= M && in_band(i + 1, j + 1, w)) {
                 double delta = (R[(i + 1) * W + (j + 1)] - r - d[(size_t)i * M + j]) / gamma;
                 tc = Ebar[(i + 1) * W + (j + 1)] + delta;
             }
-            Ebar[i * W + j] = logsumexp3(ta, tb, tc);
+            if (ta > -INFINITY || tb > -INFINITY || tc > -INFINITY) Ebar[i * W + j] = logsumexp3(ta, tb, tc);
         }
     for (int i = 1; i <= N; ++i)
         for (int j = 1; j <= M; ++j)
             E[(size_t)(i - 1) * M + (j - 1)] = exp(Ebar[i * W + j]);
+}
+
+void sdtw_oracle_backward(const double *d, const double *R, int N, int M, double gamma,
+                          double *Ebar, double *E)
+{
+    sdtw_oracle_backward_banded(d, R, N, M, gamma, -1, Ebar, E);
 }
 
 /* dx[i,:] = g * 2 (x_i sum_j E_ij - sum_j E_ij y_j); dy[j,:] = g * 2 (y_j sum_i E_ij - sum_i E_ij x_i).
@@ -176,7 +202,7 @@ void sdtw_oracle_input_grads(const float *x, const float *y, const double *E, in
 
 /* One pair, start to end.  Any of R_out ((N+2)(M+2)), E_out (N*M), dx, dy, d_out (N*M)
  * may be NULL.  want_backward=0 stops after the value. */
-static int one_pair(const float *x, const float *y, int N, int M, int D, double gamma, double g,
+static int one_pair(const float *x, const float *y, int N, int M, int D, double gamma, int w, double g,
                     int want_backward, double *value, double *dx, double *dy, double *E_out,
                     double *R_out, double *d_out)
 {
@@ -185,14 +211,14 @@ static int one_pair(const float *x, const float *y, int N, int M, int D, double 
     double *R = (double *)malloc(pad * sizeof(double));
     if (!d || !R) { free(d); free(R); return ORACLE_NO_MEM; }
     sdtw_oracle_cost(x, y, N, M, D, d);
-    *value = sdtw_oracle_forward(d, N, M, gamma, R);
+    *value = sdtw_oracle_forward_banded(d, N, M, gamma, w, R);
     if (d_out) memcpy(d_out, d, nm * sizeof(double));
     if (R_out) memcpy(R_out, R, pad * sizeof(double));
     if (want_backward) {
         double *Ebar = (double *)malloc(pad * sizeof(double));
         double *E = E_out ? E_out : (double *)malloc(nm * sizeof(double));
         if (!Ebar || !E) { free(d); free(R); free(Ebar); if (!E_out) free(E); return ORACLE_NO_MEM; }
-        sdtw_oracle_backward(d, R, N, M, gamma, Ebar, E);
+        sdtw_oracle_backward_banded(d, R, N, M, gamma, w, Ebar, E);
         if (dx || dy) {
             double *tx = dx ? dx : (double *)malloc((size_t)N * D * sizeof(double));
             double *ty = dy ? dy : (double *)malloc((size_t)M * D * sizeof(double));
@@ -212,10 +238,10 @@ static int one_pair(const float *x, const float *y, int N, int M, int D, double 
  * pair uses the same x), y likewise.  grad_value (B) may be NULL (= ones).  Outputs:
  * value[B]; dx[B,N,D], dy[B,M,D], E[B,N,M] each optional (NULL).  nthreads<=0: OpenMP default.
  * Returns 0, or the first non-zero per-pair code. */
-int sdtw_oracle_batch(const float *x, const float *y, int B, int N, int M, int D, double gamma,
-                      int64_t x_stride, int64_t y_stride, const double *grad_value,
-                      int want_backward, double *value, double *dx, double *dy, double *E,
-                      int nthreads)
+int sdtw_oracle_batch_banded(const float *x, const float *y, int B, int N, int M, int D, double gamma,
+                             int w, int64_t x_stride, int64_t y_stride, const double *grad_value,
+                             int want_backward, double *value, double *dx, double *dy, double *E,
+                             int nthreads)
 {
     if (!x || !y || !value || B < 1 || N < 1 || M < 1 || D < 1 || !(gamma > 0.0) || !isfinite(gamma))
         return ORACLE_BAD_ARG;
@@ -227,7 +253,7 @@ int sdtw_oracle_batch(const float *x, const float *y, int B, int N, int M, int D
 #endif
 #pragma omp parallel for schedule(dynamic, 1)
     for (int b = 0; b < B; ++b) {
-        int r = one_pair(x + (size_t)b * x_stride, y + (size_t)b * y_stride, N, M, D, gamma,
+        int r = one_pair(x + (size_t)b * x_stride, y + (size_t)b * y_stride, N, M, D, gamma, w,
                          grad_value ? grad_value[b] : 1.0, want_backward, &value[b],
                          dx ? dx + (size_t)b * N * D : NULL, dy ? dy + (size_t)b * M * D : NULL,
                          E ? E + (size_t)b * N * M : NULL, NULL, NULL);
@@ -239,6 +265,15 @@ int sdtw_oracle_batch(const float *x, const float *y, int B, int N, int M, int D
     return rc;
 }
 
+int sdtw_oracle_batch(const float *x, const float *y, int B, int N, int M, int D, double gamma,
+                      int64_t x_stride, int64_t y_stride, const double *grad_value,
+                      int want_backward, double *value, double *dx, double *dy, double *E,
+                      int nthreads)
+{
+    return sdtw_oracle_batch_banded(x, y, B, N, M, D, gamma, -1, x_stride, y_stride, grad_value,
+                                    want_backward, value, dx, dy, E, nthreads);
+}
+
 /* One pair with every intermediate exposed (for the pins). */
 int sdtw_oracle_pair_tables(const float *x, const float *y, int N, int M, int D, double gamma,
                             double *value, double *d_out, double *R_out, double *E_out,
@@ -246,24 +281,30 @@ int sdtw_oracle_pair_tables(const float *x, const float *y, int N, int M, int D,
 {
     if (!x || !y || !value || N < 1 || M < 1 || D < 1 || !(gamma > 0.0) || !isfinite(gamma))
         return ORACLE_BAD_ARG;
-    return one_pair(x, y, N, M, D, gamma, 1.0, 1, value, dx, dy, E_out, R_out, d_out);
+    return one_pair(x, y, N, M, D, gamma, -1, 1.0, 1, value, dx, dy, E_out, R_out, d_out);
 }
 
 /* Forward and backward on a caller-supplied cost matrix d[N,M] (for pins that fix d). */
-int sdtw_oracle_from_cost(const double *d, int N, int M, double gamma, double *value,
-                          double *R_out, double *E_out)
+int sdtw_oracle_from_cost_banded(const double *d, int N, int M, double gamma, int w, double *value,
+                                 double *R_out, double *E_out)
 {
     if (!d || !value || N < 1 || M < 1 || !(gamma > 0.0) || !isfinite(gamma)) return ORACLE_BAD_ARG;
     const size_t pad = ((size_t)N + 2) * ((size_t)M + 2);
     double *R = (double *)malloc(pad * sizeof(double));
     double *Ebar = (double *)malloc(pad * sizeof(double));
     if (!R || !Ebar) { free(R); free(Ebar); return ORACLE_NO_MEM; }
-    *value = sdtw_oracle_forward(d, N, M, gamma, R);
+    *value = sdtw_oracle_forward_banded(d, N, M, gamma, w, R);
     if (R_out) memcpy(R_out, R, pad * sizeof(double));
-    if (E_out) sdtw_oracle_backward(d, R, N, M, gamma, Ebar, E_out);
+    if (E_out) sdtw_oracle_backward_banded(d, R, N, M, gamma, w, Ebar, E_out);
     free(R);
     free(Ebar);
     return ORACLE_OK;
+}
+
+int sdtw_oracle_from_cost(const double *d, int N, int M, double gamma, double *value,
+                          double *R_out, double *E_out)
+{
+    return sdtw_oracle_from_cost_banded(d, N, M, gamma, -1, value, R_out, E_out);
 }
 
 /* Barycenter step (Sec. 4.4): loss = sum_k sdtw_g(z, X_k), dz = sum_k d sdtw/dz, then one

@@ -37,6 +37,13 @@ def _load():
         lib.sdtw_oracle_batch.argtypes = [
             _fp, _fp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double,
             ctypes.c_int64, ctypes.c_int64, _dp, ctypes.c_int, _dp, _dp, _dp, _dp, ctypes.c_int]
+        lib.sdtw_oracle_batch_banded.restype = ctypes.c_int
+        lib.sdtw_oracle_batch_banded.argtypes = [
+            _fp, _fp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_int,
+            ctypes.c_int64, ctypes.c_int64, _dp, ctypes.c_int, _dp, _dp, _dp, _dp, ctypes.c_int]
+        lib.sdtw_oracle_from_cost_banded.restype = ctypes.c_int
+        lib.sdtw_oracle_from_cost_banded.argtypes = [
+            _dp, ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_int, _dp, _dp, _dp]
         lib.sdtw_oracle_pair_tables.restype = ctypes.c_int
         lib.sdtw_oracle_pair_tables.argtypes = [
             _fp, _fp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double,
@@ -68,8 +75,13 @@ def max_threads():
     return int(_load().sdtw_oracle_max_threads())
 
 
-def batch(x, y, gamma, grad_value=None, backward=True, want_E=False, nthreads=0):
-    """x [B,N,D] or [N,D] (shared by every pair), y [B,M,D] or [M,D].
+def _band(bandwidth):
+    return -1 if bandwidth is None else int(bandwidth)
+
+
+def batch(x, y, gamma, grad_value=None, backward=True, want_E=False, nthreads=0, bandwidth=None):
+    """x [B,N,D] or [N,D] (shared by every pair), y [B,M,D] or [M,D].  ``bandwidth`` w: only cells
+    with |i-j| <= w belong to the grid (Sakoe-Chiba band; None = no band).
 
     Returns a dict with ``value`` [B] and, when ``backward``, ``dx`` [B,N,D], ``dy`` [B,M,D]
     (and ``E`` [B,N,M] when ``want_E``), all float64.
@@ -105,14 +117,14 @@ def batch(x, y, gamma, grad_value=None, backward=True, want_E=False, nthreads=0)
         gv = np.ascontiguousarray(grad_value, dtype=np.float64)
         assert gv.shape == (B,)
         gp = gv.ctypes.data_as(_dp)
-    rc = lib.sdtw_oracle_batch(xp, yp, B, N, M, D, float(gamma), xs, ys, gp, int(bool(backward)),
-                               vp, dxp, dyp, Ep, int(nthreads))
+    rc = lib.sdtw_oracle_batch_banded(xp, yp, B, N, M, D, float(gamma), _band(bandwidth), xs, ys, gp,
+                                      int(bool(backward)), vp, dxp, dyp, Ep, int(nthreads))
     if rc != 0:
         raise RuntimeError("sdtw_oracle_batch failed with code %d" % rc)
     return out
 
 
-def ragged_batch(x, y, x_len, y_len, gamma, grad_value=None, want_E=False):
+def ragged_batch(x, y, x_len, y_len, gamma, grad_value=None, want_E=False, bandwidth=None):
     """Pairs of individual lengths inside padded tensors x [B,N,D], y [B,M,D] (Sec. 5: the lengths of
     the two sequences of a pair may differ; here also from pair to pair): pair b is the plain
     problem on x[b, :x_len[b]], y[b, :y_len[b]], one call of :func:`batch` each; gradients and E
@@ -128,7 +140,7 @@ def ragged_batch(x, y, x_len, y_len, gamma, grad_value=None, want_E=False):
         n = N if x_len is None else int(x_len[b])
         m = M if y_len is None else int(y_len[b])
         gv = None if grad_value is None else np.asarray(grad_value, dtype=np.float64)[b:b + 1]
-        o = batch(x[b:b + 1, :n], y[b:b + 1, :m], gamma, grad_value=gv, want_E=want_E)
+        o = batch(x[b:b + 1, :n], y[b:b + 1, :m], gamma, grad_value=gv, want_E=want_E, bandwidth=bandwidth)
         out["value"][b] = o["value"][0]
         out["dx"][b, :n] = o["dx"][0]
         out["dy"][b, :m] = o["dy"][0]
@@ -177,8 +189,8 @@ def pair_tables(x, y, gamma):
     return {"value": val.value, "d": d, "R": R, "E": E, "dx": dx, "dy": dy}
 
 
-def from_cost(d, gamma, want_E=True):
-    """Forward (+ backward) on a given cost matrix d [N,M] (float64)."""
+def from_cost(d, gamma, want_E=True, bandwidth=None):
+    """Forward (+ backward) on a given cost matrix d [N,M] (float64), optionally inside a band."""
     lib = _load()
     d = np.ascontiguousarray(d, dtype=np.float64)
     N, M = d.shape
@@ -187,7 +199,8 @@ def from_cost(d, gamma, want_E=True):
     E = Ep = None
     if want_E:
         E, Ep = _f64_out((N, M))
-    rc = lib.sdtw_oracle_from_cost(d.ctypes.data_as(_dp), N, M, float(gamma), ctypes.byref(val), Rp, Ep)
+    rc = lib.sdtw_oracle_from_cost_banded(d.ctypes.data_as(_dp), N, M, float(gamma), _band(bandwidth),
+                                          ctypes.byref(val), Rp, Ep)
     if rc != 0:
         raise RuntimeError("sdtw_oracle_from_cost failed with code %d" % rc)
     return {"value": val.value, "R": R, "E": E}

@@ -308,6 +308,76 @@ def test_thread_count_does_not_change_results():
 
 # ----------------------------------------------------------------------------- barycenter step
 # ----------------------------------------------------------------------------- normalised Soft-DTW
+# ----------------------------------------------------------------------------- band |i-j| <= w
+@pytest.mark.parametrize("N,M,w", [(5, 5, 1), (6, 6, 2), (4, 7, 3), (7, 5, 2), (6, 6, 0), (3, 6, 4)])
+@pytest.mark.parametrize("gamma", [1.0, 0.05])
+def test_band_matches_enumeration_of_the_paths_inside_it(N, M, w, gamma):
+    # the banded problem is the sum over exactly those alignment paths all of whose cells satisfy
+    # |i-j| <= w: enumerate them
+    rng = np.random.default_rng(10 * N + M + w)
+    d = rng.uniform(0.0, 2.0, size=(N, M))
+    paths = [q for q in all_paths(N, M) if all(abs(i - j) <= w for i, j in q)]
+    assert paths, "the corner must be inside the band"
+    costs = np.array([sum(d[i, j] for i, j in q) for q in paths])
+    wts = np.exp(-(costs - costs.min()) / gamma)
+    value = costs.min() - gamma * math.log(wts.sum())
+    E = np.zeros((N, M))
+    for q, wq in zip(paths, wts):
+        for i, j in q:
+            E[i, j] += wq / wts.sum()
+    o = oracle.from_cost(d, gamma, bandwidth=w)
+    assert o["value"] == pytest.approx(value, rel=1e-12, abs=1e-12)
+    np.testing.assert_allclose(o["E"], E, rtol=1e-9, atol=1e-12)
+    ii, jj = np.indices((N, M))
+    assert not o["E"][np.abs(ii - jj) > w].any()
+
+
+def test_band_special_cases():
+    rng = np.random.default_rng(5)
+    N, M, D, gamma = 9, 11, 3, 0.4
+    x = grid_inputs(rng, (N, D))
+    y = grid_inputs(rng, (M, D))
+    # a band that holds the whole grid changes nothing
+    full = oracle.batch(x, y, gamma, want_E=True)
+    wide = oracle.batch(x, y, gamma, want_E=True, bandwidth=max(N, M))
+    for key in ("value", "dx", "dy", "E"):
+        assert np.array_equal(full[key], wide[key])
+    # w = 0 on a square problem leaves the diagonal path alone: value = sum_i d[i,i], E = identity
+    d = rng.uniform(0.0, 2.0, size=(6, 6))
+    o = oracle.from_cost(d, 0.3, bandwidth=0)
+    assert o["value"] == pytest.approx(np.trace(d), rel=1e-14)
+    np.testing.assert_allclose(o["E"], np.eye(6), rtol=0, atol=1e-14)
+    # narrowing the band removes paths, so the value can only grow; and it is never below classic
+    # DTW restricted to the band minus gamma log(#paths in the band)
+    vals = [oracle.from_cost(d, 0.3, False, bandwidth=w)["value"] for w in (0, 1, 2, 3, 5)]
+    assert all(a >= b - 1e-12 for a, b in zip(vals, vals[1:]))
+    # the corner outside the band: no path, +inf
+    assert oracle.from_cost(rng.uniform(size=(3, 7)), 0.3, False, bandwidth=2)["value"] == np.inf
+
+
+def test_band_gradients_match_central_differences():
+    rng = np.random.default_rng(23)
+    N, M, D, gamma, w = 8, 10, 2, 0.5, 3
+    x = grid_inputs(rng, (N, D))
+    y = grid_inputs(rng, (M, D))
+    base = oracle.batch(x, y, gamma, bandwidth=w)
+    h = 2.0 ** -10
+
+    def val(xx, yy):
+        return oracle.batch(xx, yy, gamma, backward=False, bandwidth=w)["value"][0]
+
+    for (i, k) in [(0, 0), (3, 1), (N - 1, 1)]:
+        xp, xm = x.copy(), x.copy()
+        xp[i, k] += h
+        xm[i, k] -= h
+        assert base["dx"][0, i, k] == pytest.approx((val(xp, y) - val(xm, y)) / (2 * h), rel=2e-5, abs=1e-6)
+    for (j, k) in [(0, 1), (4, 0), (M - 1, 1)]:
+        yp, ym = y.copy(), y.copy()
+        yp[j, k] += h
+        ym[j, k] -= h
+        assert base["dy"][0, j, k] == pytest.approx((val(x, yp) - val(x, ym)) / (2 * h), rel=2e-5, abs=1e-6)
+
+
 def test_ragged_batch_is_the_plain_problem_on_each_pair_s_own_prefix():
     # per pair against path enumeration on the sliced cost matrix; padding must not matter and the
     # gradients beyond the lengths are zero
