@@ -42,9 +42,10 @@ extern "C" {
 
 typedef enum sdtw_status {
     SDTW_OK = 0,
-    SDTW_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, gamma not finite or <= 0, bad mode */
+    SDTW_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, gamma not finite or <= 0, bad mode,
+                                 bandwidth < 0 or 0 < bandwidth < |N-M| */
     SDTW_ERR_WORKSPACE = 2,   /* workspace missing, misaligned or smaller than required */
-    SDTW_ERR_UNSUPPORTED = 3, /* bandwidth != 0 (Algorithm 1 names it, the paper never defines it) */
+    SDTW_ERR_UNSUPPORTED = 3, /* bandwidth != 0 in a normalised Soft-DTW call */
     SDTW_ERR_STATE = 4,       /* device: backward on a workspace not filled by a matching forward;
                                  host: backward with a SDTW_FLAG_VALUE_ONLY descriptor */
     SDTW_ERR_HIP = 5,         /* a HIP runtime call failed (launch, copy) */
@@ -73,7 +74,13 @@ typedef struct sdtw_desc {
     int32_t mode;           /* SDTW_UNFUSED or SDTW_FUSED */
     int64_t x_batch_stride; /* elements between consecutive x sequences: N*D, or 0 = one x shared */
     int64_t y_batch_stride; /* elements between consecutive y sequences: M*D, or 0 = one y shared */
-    int32_t bandwidth;      /* reserved, must be 0 (no band constraint, as in the paper's Sec. 5) */
+    int32_t bandwidth;      /* 0: no band constraint (as in the paper's Sec. 5).  w > 0: Algorithm 1's
+                               `bandwidth`, read as the Sakoe-Chiba band: only cells with |i-j| <= w
+                               (0-based i, j) belong to the grid; the others have cost +inf, E = 0.
+                               Needs w >= |N-M| so that the last cell is inside.  With per-pair
+                               lengths every pair needs |x_len[b]-y_len[b]| <= w, which the device
+                               does not check: such a pair's value and gradients are undefined.  The
+                               sweeps skip the macro-steps outside the band. */
     uint32_t flags;         /* 0 or SDTW_FLAG_VALUE_ONLY */
 } sdtw_desc;
 

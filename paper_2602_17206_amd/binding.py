@@ -202,14 +202,17 @@ def _desc_for(x, y, gamma, mode):
     return make_desc(B, N, M, D, gamma, mode, x_shared, y_shared)
 
 
-def sdtw_forward(x, y, gamma, mode=FUSED, workspace=None, value=None, stream=None, value_only=False):
+def sdtw_forward(x, y, gamma, mode=FUSED, workspace=None, value=None, stream=None, value_only=False,
+                 bandwidth=0):
     """value[b] = sdtw_gamma(x_b, y_b).  Returns (value, desc, workspace); keep the last two for
     :func:`sdtw_backward`.  x [B,N,D] or [N,D]; y [B,M,D] or [M,D]; float32 device tensors.
-    ``value_only=True`` sets SDTW_FLAG_VALUE_ONLY: no backward call will follow."""
+    ``value_only=True`` sets SDTW_FLAG_VALUE_ONLY: no backward call will follow.
+    ``bandwidth`` w > 0: only cells with |i-j| <= w belong to the grid."""
     import torch
 
     lib = load_library()
     desc = _desc_for(x, y, gamma, mode)
+    desc.bandwidth = int(bandwidth)
     if value_only:
         desc.flags = FLAG_VALUE_ONLY
     if workspace is None:
@@ -253,15 +256,20 @@ def sdtw_backward(desc, x, y, workspace, grad_value=None, want_dx=True, want_dy=
     return dx, dy, E
 
 
-def sdtw_forward_ragged(x, y, x_len, y_len, gamma, mode=FUSED, workspace=None, value=None, stream=None):
+def sdtw_forward_ragged(x, y, x_len, y_len, gamma, mode=FUSED, workspace=None, value=None, stream=None,
+                        bandwidth=0):
     """As :func:`sdtw_forward` for pairs of individual lengths: x_len, y_len are int32 device tensors
     [B] (or None).  Returns (value, desc, workspace)."""
     import torch
 
     lib = load_library()
     desc = _desc_for(x, y, gamma, mode)
+    desc.bandwidth = int(bandwidth)
     if workspace is None:
-        workspace = Workspace(sdtw_workspace_bytes(desc), x.device)
+        nbytes = sdtw_workspace_bytes(desc)
+        if nbytes == 0:
+            raise SdtwError(STATUS_INVALID_ARG, "sdtw_workspace_bytes")
+        workspace = Workspace(nbytes, x.device)
     if value is None:
         value = torch.empty(desc.B, dtype=torch.float32, device=x.device)
     rc = lib.sdtw_forward_ragged(ctypes.byref(desc), _ptr(x, torch.float32, name="x"), _ptr(y, torch.float32, name="y"),

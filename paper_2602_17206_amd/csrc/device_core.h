@@ -108,4 +108,36 @@ __device__ __forceinline__ int pair_len(const int32_t *lens, int b, int full)
     return __builtin_amdgcn_readfirstlane(max(1, min(lens[b], full)));
 }
 
+// Macro-steps a band sweep has to run when only cells with |i-j| <= window belong to the grid.
+// The band(s) cover rows [row_a, row_b + 63] (row_a == row_b for one band; a chained pair runs the
+// union).  Lane t meets column j at step j + t, so the cells inside the window lie at steps
+// [row_a - w, row_b + 126 + w]; one more step on either side keeps every predecessor that a cell
+// inside the window reads - itself outside the window - among the computed cells (cost kBigCost)
+// or the initial state (kBig).  Macro-steps [lo, hi] are run; hi_u is hi before it is clipped to
+// the table: a 32x32 block (rb, cb) of the band holds cells of macro-steps cb+rb and cb+rb+1 and is
+// either complete within [lo, hi_u] or entirely outside the window.
+struct SweepRange { int lo, hi, hi_u; };
+
+__device__ __forceinline__ SweepRange sweep_range(const Params &p, int row_a, int row_b)
+{
+    SweepRange r;
+    if (p.window >= kNoWindow) {
+        r.lo = 0;
+        r.hi = p.nmacro - 1;
+        r.hi_u = kNoWindow;
+        return r;
+    }
+    const int first = row_a - p.window - 1;
+    r.lo = first > 0 ? first / kBlk : 0;
+    r.hi_u = (row_b + 2 * kBandRows - 1 + p.window) / kBlk;
+    r.hi = min(r.hi_u, p.nmacro - 1);
+    r.lo = min(r.lo, r.hi);
+    return r;
+}
+
+__device__ __forceinline__ bool in_window(int i, int j, int w)
+{
+    return (unsigned)(j - i + w) <= 2u * (unsigned)w;
+}
+
 }  // namespace sdtw

@@ -59,7 +59,6 @@ constexpr int kHandDoubles = kHandRing + kBandRows + kBlk;
 // (8 bytes per cell written, 8 read).  There the forward keeps only the lane state at the start of
 // every macro-step (1/16 of R) and the backward recomputes each macro-step of R before it uses it.
 constexpr bool dp_recompute(int kch, int slots) { return kch >= 0 && slots == 4; }
-constexpr double kBig = 1e300;     // stands for +inf in the DP tables
 constexpr float kBigCost = 3.0e38f;  // cost of a cell outside the grid
 constexpr int kStatusTimeoutDp = 6;  // SDTW_ERR_TIMEOUT
 
@@ -153,38 +152,43 @@ __device__ __forceinline__ floatx16 zero16()
 
 // Writes a 32x32 cost block given in MFMA accumulator layout (acc[i]: row 8*(i/4)+4*(lane>>5)+(i&3),
 // column lane&31) into the step-indexed ring.  Block rows are band rows 32*rb .., columns 32*cb ..;
-// entries outside the grid become kBigCost, negative round-off is clamped to 0.
+// entries outside the grid (or outside the window |i-j| <= w) become kBigCost, negative round-off is
+// clamped to 0.
 __device__ __forceinline__ void store_block_acc(float *ring, const floatx16 &acc, int rb, int cb, int row0, int N,
-                                                int M, int lane)
+                                                int M, int w, int lane)
 {
     const int h = lane >> 5, c = lane & 31;
     const int sbase = 32 * (cb + rb) + c + 4 * h;
     float *rowbase = ring + (32 * rb + 4 * h) * kRingStride;
     const int i0 = row0 + 32 * rb, j0 = 32 * cb;
-    const bool inside = (i0 + 32 <= N) && (j0 >= 0) && (j0 + 32 <= M);
+    const bool inside = (i0 + 32 <= N) && (j0 >= 0) && (j0 + 32 <= M) && (j0 + 31 - i0 <= w) && (i0 + 31 - j0 <= w);
     const bool col_ok = (unsigned)(j0 + c) < (unsigned)M;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int rr = 8 * (i >> 2) + (i & 3);  // + 4h = row inside the block
         const int pos = (sbase + rr) & (kRingCols - 1);
         float v = fmaxf(acc[i], 0.0f);
-        if (!inside) v = (col_ok && (i0 + 4 * h + rr < N)) ? v : kBigCost;
+        if (!inside) v = (col_ok && (i0 + 4 * h + rr < N) && in_window(i0 + 4 * h + rr, j0 + c, w)) ? v : kBigCost;
         rowbase[rr * kRingStride + pos] = v;
     }
 }
 
 // Unfused mode: the 32x32 block of the stored cost tensor (row length ld) as 4 float4 per lane
-// (lane -> row (lane>>3) + 8*it of the block, columns 4*(lane&7) ..), kBigCost outside the N x M grid.
+// (lane -> row (lane>>3) + 8*it of the block, columns 4*(lane&7) ..), kBigCost outside the N x M grid
+// and outside the window |i-j| <= w (tiles of the cost tensor that lie outside it were never written).
 __device__ __forceinline__ void load_cost_block(float4 (&v)[4], const float *__restrict__ cost_b, int rb, int cb,
-                                                int row0, int N, int M, int ld, bool vec_m, int lane)
+                                                int row0, int N, int M, int ld, int w, bool vec_m, int lane)
 {
     const int c4 = (lane & 7) * 4, j0 = 32 * cb;
+    const int i0 = row0 + 32 * rb;
+    const bool all_in = (j0 + 31 - i0 <= w) && (i0 + 31 - j0 <= w);
+    const bool none_in = (j0 - (i0 + 31) > w) || (i0 - (j0 + 31) > w);
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
         const int row = row0 + 32 * rb + (lane >> 3) + 8 * it;
         const int col = j0 + c4;
         float4 t = make_float4(kBigCost, kBigCost, kBigCost, kBigCost);
-        if (row < N && col >= 0) {
+        if (row < N && col >= 0 && !none_in) {
             const float *q = cost_b + (size_t)row * ld + col;
             if (vec_m && col + 3 < M) {
                 t = *reinterpret_cast<const float4 *>(q);
@@ -193,6 +197,12 @@ __device__ __forceinline__ void load_cost_block(float4 (&v)[4], const float *__r
                 if (col + 1 < M) t.y = q[1];
                 if (col + 2 < M) t.z = q[2];
                 if (col + 3 < M) t.w = q[3];
+            }
+            if (!all_in) {
+                t.x = in_window(row, col + 0, w) ? t.x : kBigCost;
+                t.y = in_window(row, col + 1, w) ? t.y : kBigCost;
+                t.z = in_window(row, col + 2, w) ? t.z : kBigCost;
+                t.w = in_window(row, col + 3, w) ? t.w : kBigCost;
             }
         }
         v[it] = t;
@@ -224,7 +234,7 @@ __device__ __forceinline__ void generic_block(const Params &p, int b, float *rin
     for (int i = 0; i < 16; ++i) acc[i] = out[i];
     // when the block origin had to be clamped the whole block lies outside the grid
     const bool origin_ok = (i0 < p.N) && (j0 >= 0) && (j0 < p.M);
-    store_block_acc(ring, acc, rb, cb, row0, origin_ok ? p.N : 0, p.M, lane);
+    store_block_acc(ring, acc, rb, cb, row0, origin_ok ? p.N : 0, p.M, p.window, lane);
 }
 
 // The two cost blocks a macro-step `sg` must prepare for the following one.
@@ -304,7 +314,7 @@ template <int KG, int DIR, int W0, int NW> struct HalfProducer {
             const float2 t = rowtab[32 * rb + 8 * (i >> 2) + 4 * h + (i & 3)];
             acc[i] = fmaf(acc[i], t.y * yisc, t.x + ync);
         }
-        store_block_acc(ring, acc, rb, cb, row0, p.N, p.M, lane);
+        store_block_acc(ring, acc, rb, cb, row0, p.N, p.M, p.window, lane);
     }
     // one whole block, loads included (start-up only)
     __device__ __forceinline__ void block_now(const Params &p, const uint16_t *yh, const float *ynb,
@@ -406,6 +416,10 @@ __global__ __launch_bounds__(256) void cost_tensor_half_kernel(Params p)
     const float *xnb = p.xn + b * p.xn_stride, *ynb = p.yn + b * p.yn_stride;
     const float *xisb = p.xis + b * p.xn_stride, *yisb = p.yis + b * p.yn_stride;
     const int jbase = blockIdx.x * (32 * CB);
+    {   // no cell of the 128 x 32*CB tile inside the window: nothing to compute (the sweeps never read it)
+        const int ti0 = blockIdx.y * 128;
+        if (jbase - (ti0 + 127) > p.window || ti0 - (jbase + 32 * CB - 1) > p.window) return;
+    }
 
     // y pieces of the tile's columns -> LDS: a column is 4*KG chunks of 16 bytes
     constexpr int kChunks = 4 * KG;
@@ -545,10 +559,6 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
         for (int e = threadIdx.x; e < kHandDoubles; e += kThreads) hand[e] = kBig;
         chain_role(w, producer, slot);
         __syncthreads();
-        if (producer < 0) {  // unused wavefront: only keeps the barrier count (one before the loop, one per iteration)
-            for (int it = 0; it <= p.nmacro + kChainLag; ++it) __syncthreads();
-            return;
-        }
     } else {
         producer = w;
         slot = 0;
@@ -556,19 +566,30 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
     }
     const unsigned ticket = __builtin_amdgcn_readfirstlane(ticket_s);
     int k, b;
+    // The macro-steps to run, [rg.lo, rg.hi], follow from the ticket alone, so that every wavefront
+    // of the workgroup passes the same number of barriers.
+    SweepRange rg;
     if constexpr (SLOTS == 2) {  // ticket -> (pair of bands, pair of sequences); the slot is the band of the pair
         const int kp = ticket / (unsigned)p.B;
         b = ticket - kp * p.B;
-        k = 2 * kp + slot;
+        k = 2 * kp + (slot & 1);
+        rg = sweep_range(p, 2 * kp * kBandRows, min(2 * kp + 1, p.nbands - 1) * kBandRows);
     } else {
         const int ngroups = (p.B + SLOTS - 1) / SLOTS;
         k = ticket / (unsigned)ngroups;
         b = (ticket - k * ngroups) * SLOTS + slot;
+        rg = sweep_range(p, k * kBandRows, k * kBandRows);
     }
     const bool live = (k < p.nbands) && (b < p.B);
-    // chained pair: the second band does macro-step sg in workgroup iteration sg + kChainLag
+    // chained pair: the second band does macro-step sg in workgroup iteration sg - rg.lo + kChainLag
     const int lag = (SLOTS == 2) ? kChainLag * slot : 0;
-    const int niter = p.nmacro + ((SLOTS == 2) ? kChainLag : 0);
+    const int niter = (rg.hi - rg.lo + 1) + ((SLOTS == 2) ? kChainLag : 0);
+    if constexpr (SLOTS == 2) {
+        if (producer < 0) {  // unused wavefront: only keeps the barrier count (one before the loop, one per iteration)
+            for (int it = 0; it <= niter; ++it) __syncthreads();
+            return;
+        }
+    }
 
     const int M = p.M, N = p.N;
     const int row0 = k * kBandRows;
@@ -593,13 +614,13 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
             auto body = [&](auto &mp, bool first_block) {
                 if (live) {
                     mp.init(pl, xh, xnb, xisb, rowtab, row0, lane);
-                    if (first_block) mp.block_now(pl, yh, ynb, yisb, ring, rowtab, 0, 0, row0, lane);
-                    mp.prime(pl, yh, ynb, yisb, 0, lane);
+                    if (first_block) mp.block_now(pl, yh, ynb, yisb, ring, rowtab, 0, rg.lo, row0, lane);
+                    mp.prime(pl, yh, ynb, yisb, rg.lo, lane);
                 }
                 __syncthreads();
                 for (int it = 0; it < niter; ++it) {
-                    const int sg = it - lag;
-                    if (live && sg >= 0 && sg < p.nmacro) mp.run(pl, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
+                    const int sg = rg.lo + it - lag;
+                    if (live && sg >= rg.lo && sg <= rg.hi) mp.run(pl, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
                     __syncthreads();
                 }
             };
@@ -614,21 +635,21 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
             HalfProducer<KCH, +1, 0, 2> mp;
             if (live) {
                 mp.init(pl, xh, xnb, xisb, rowtab, row0, lane);
-                mp.block_now(pl, yh, ynb, yisb, ring, rowtab, 0, 0, row0, lane);  // (upper rows, column block 0)
-                mp.prime(pl, yh, ynb, yisb, 0, lane);
+                mp.block_now(pl, yh, ynb, yisb, ring, rowtab, 0, rg.lo, row0, lane);  // (upper rows, first column block)
+                mp.prime(pl, yh, ynb, yisb, rg.lo, lane);
             }
             __syncthreads();
             for (int it = 0; it < niter; ++it) {
-                const int sg = it - lag;
-                if (live && sg >= 0 && sg < p.nmacro) mp.run(pl, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
+                const int sg = rg.lo + it - lag;
+                if (live && sg >= rg.lo && sg <= rg.hi) mp.run(pl, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
                 __syncthreads();
             }
         } else if constexpr (KCH == 0) {
-            if (live) generic_block(pl, b, ring, 0, 0, row0, lane);
+            if (live) generic_block(pl, b, ring, 0, rg.lo, row0, lane);
             __syncthreads();
             for (int it = 0; it < niter; ++it) {
-                const int sg = it - lag;
-                if (live && sg >= 0 && sg < p.nmacro) {
+                const int sg = rg.lo + it - lag;
+                if (live && sg >= rg.lo && sg <= rg.hi) {
                     generic_block(pl, b, ring, 1, sg, row0, lane);
                     generic_block(pl, b, ring, 0, sg + 1, row0, lane);
                 }
@@ -638,19 +659,19 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
             const float *cost_b = p.cost + (size_t)bb * N * M;
             float4 pre[2][4];
             if (live) {
-                load_cost_block(pre[0], cost_b, 0, 0, row0, Nl, Ml, M, p.vec_m != 0, lane);
-                store_cost_block(ring, pre[0], 0, 0, lane);
-                load_cost_block(pre[0], cost_b, 1, 0, row0, Nl, Ml, M, p.vec_m != 0, lane);
-                load_cost_block(pre[1], cost_b, 0, 1, row0, Nl, Ml, M, p.vec_m != 0, lane);
+                load_cost_block(pre[0], cost_b, 0, rg.lo, row0, Nl, Ml, M, p.window, p.vec_m != 0, lane);
+                store_cost_block(ring, pre[0], 0, rg.lo, lane);
+                load_cost_block(pre[0], cost_b, 1, rg.lo, row0, Nl, Ml, M, p.window, p.vec_m != 0, lane);
+                load_cost_block(pre[1], cost_b, 0, rg.lo + 1, row0, Nl, Ml, M, p.window, p.vec_m != 0, lane);
             }
             __syncthreads();
             for (int it = 0; it < niter; ++it) {
-                const int sg = it - lag;
-                if (live && sg >= 0 && sg < p.nmacro) {
+                const int sg = rg.lo + it - lag;
+                if (live && sg >= rg.lo && sg <= rg.hi) {
                     store_cost_block(ring, pre[0], 1, sg, lane);
                     store_cost_block(ring, pre[1], 0, sg + 1, lane);
-                    load_cost_block(pre[0], cost_b, 1, sg + 1, row0, Nl, Ml, M, p.vec_m != 0, lane);
-                    load_cost_block(pre[1], cost_b, 0, sg + 2, row0, Nl, Ml, M, p.vec_m != 0, lane);
+                    load_cost_block(pre[0], cost_b, 1, sg + 1, row0, Nl, Ml, M, p.window, p.vec_m != 0, lane);
+                    load_cost_block(pre[1], cost_b, 0, sg + 2, row0, Nl, Ml, M, p.window, p.vec_m != 0, lane);
                 }
                 __syncthreads();
             }
@@ -685,20 +706,22 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
     double *top = sh.edge_in[slot];
     double *eo = edge_out[slot];
 
-    // row above the band for macro-step 0: lane l < 32 brings column l
+    // row above the band for the first macro-step: lane l < 32 brings column 32*rg.lo + l
+    // (the cells left of it are outside the grid or outside the window: the lane state starts as kBig)
     if constexpr (CH != 1) {
         double t0 = kBig;
         if (has_above) {
-            const bool need = lane < kBlk && lane < M;
-            t0 = resolve_boundary(p, brow_in, lane, need, lane, gave_up, peek_boundary(brow_in, lane, need));
+            const int j0 = rg.lo * kBlk + lane;
+            const bool need = lane < kBlk && j0 < M;
+            t0 = resolve_boundary(p, brow_in, j0, need, lane, gave_up, peek_boundary(brow_in, j0, need));
         }
         if (lane < kBlk) top[lane] = t0;
     }
     __syncthreads();
 
     for (int it = 0; it < niter; ++it) {
-        const int sg = it - lag;
-        if (live && sg >= 0 && sg < p.nmacro) {
+        const int sg = rg.lo + it - lag;
+        if (live && sg >= rg.lo && sg <= rg.hi) {
             unsigned long long nxt_bits = (unsigned long long)__double_as_longlong(kBig);
             const int jn = (sg + 1) * kBlk + lane;
             const bool need_n = has_above && lane < kBlk && jn < M;
@@ -795,11 +818,22 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
 // E replaces the consumed cost value in the ring; the producers write it out as row-major 32x32
 // blocks, with one flag byte per block saying whether any entry is non-zero.
 // ---------------------------------------------------------------------------------------------
-template <int COLS = kRingCols, int STRIDE = kRingStride>
-__device__ __forceinline__ void flush_E_block(const Params &p, const float *ring, float *__restrict__ Eb,
-                                              unsigned char *__restrict__ nzb, int rb, int cb, int row0, int lane)
+// With a band constraint the sweep runs macro-steps rg.lo .. rg.hi only.  Block (rb, cb) of the band
+// holds cells of macro-steps cb+rb and cb+rb+1: it is written out if both lie in [rg.lo, rg.hi_u];
+// otherwise none of its cells is inside the window, E is zero there, and the block is either left
+// alone with its flag cleared (nobody reads a block whose flag and whose neighbours' flags are
+// clear) or zeroed by zero_fringe.
+__device__ __forceinline__ bool block_in_range(const SweepRange &rg, int rb, int cb)
 {
-    if (cb < 0 || cb >= p.ncb || row0 + 32 * rb >= p.N) return;
+    return cb + rb >= rg.lo && cb + rb + 1 <= rg.hi_u;
+}
+
+template <int COLS = kRingCols, int STRIDE = kRingStride>
+__device__ __forceinline__ void flush_E_block(const Params &p, const SweepRange &rg, const float *ring,
+                                              float *__restrict__ Eb, unsigned char *__restrict__ nzb, int rb, int cb,
+                                              int row0, int lane)
+{
+    if (cb < 0 || cb >= p.ncb || row0 + 32 * rb >= p.N || !block_in_range(rg, rb, cb)) return;
     const int c4 = (lane & 7) * 4, j0 = cb * kBlk;
     bool any = false;
 #pragma unroll
@@ -827,6 +861,44 @@ __device__ __forceinline__ void flush_E_block(const Params &p, const float *ring
     if (lane == 0) nzb[(size_t)(row0 / kBlk + rb) * p.ncb + cb] = blk_any ? 1 : 0;
 }
 
+__device__ __forceinline__ void zero_E_block(const Params &p, float *__restrict__ Eb, unsigned char *__restrict__ nzb,
+                                             int rb, int cb, int row0, int lane)
+{
+    if (cb < 0 || cb >= p.ncb || row0 + 32 * rb >= p.N) return;
+    const int c4 = (lane & 7) * 4, j0 = cb * kBlk;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int row = row0 + rb * 32 + (lane >> 3) + 8 * it;
+        if (row < p.N) {
+            float *q = Eb + (size_t)row * p.M + j0 + c4;
+            if (p.vec_m && j0 + c4 + 3 < p.M) {
+                *reinterpret_cast<float4 *>(q) = make_float4(0.f, 0.f, 0.f, 0.f);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (j0 + c4 + e < p.M) q[e] = 0.f;
+            }
+        }
+    }
+    if (lane == 0) nzb[(size_t)(row0 / kBlk + rb) * p.ncb + cb] = 0;
+}
+
+// The input-gradient kernels read E in chunks of two neighbouring blocks (the two row blocks of a
+// band at one column block; one row block at column blocks 2c and 2c+1) and skip a chunk only when
+// both flags are clear.  So the blocks outside the sweep's range that share a chunk with a block
+// inside it are written as zeros: column blocks (lo-1) & ~1 .. (hi_u-1) | 1 of both row blocks,
+// restricted to [cb_first, cb_last].
+__device__ __forceinline__ void zero_fringe(const Params &p, const SweepRange &rg, float *__restrict__ Eb,
+                                            unsigned char *__restrict__ nzb, int row0, int lane, int cb_first,
+                                            int cb_last)
+{
+    if (p.window >= kNoWindow) return;
+    const int w0 = max((rg.lo - 1) & ~1, cb_first), w1 = min((rg.hi_u - 1) | 1, cb_last);
+    for (int cb = w0; cb <= w1; ++cb)
+        for (int rb = 0; rb < 2; ++rb)
+            if (!block_in_range(rg, rb, cb)) zero_E_block(p, Eb, nzb, rb, cb, row0, lane);
+}
+
 template <int KCH, int SLOTS, int NPROD>
 __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS> &sh, unsigned &ticket_s,
                                                 double (&edge_out)[SLOTS][kEdgeOut], double (&hand)[kHandDoubles])
@@ -850,10 +922,6 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
         for (int e = threadIdx.x; e < kHandDoubles; e += kThreads) hand[e] = kBig;
         chain_role(w, producer, slot);
         __syncthreads();
-        if (producer < 0) {  // unused wavefront: only keeps the barrier count (one before the loop, one per iteration)
-            for (int it = 0; it <= p.nmacro + kChainLag; ++it) __syncthreads();
-            return;
-        }
     } else {
         producer = w;
         slot = 0;
@@ -861,19 +929,29 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
     }
     const unsigned ticket = __builtin_amdgcn_readfirstlane(ticket_s);
     int kk, b;  // kk counts bands from the last one
+    SweepRange rg;  // macro-steps to run, from the ticket alone (the same for every wavefront of the workgroup)
     if constexpr (SLOTS == 2) {
         const int kp = ticket / (unsigned)p.B;
         b = ticket - kp * p.B;
-        kk = 2 * kp + slot;
+        kk = 2 * kp + (slot & 1);
+        const int k_low = p.nbands - 1 - 2 * kp;  // the lower band of the pair (slot 0), the upper one is k_low - 1
+        rg = sweep_range(p, max(k_low - 1, 0) * kBandRows, k_low * kBandRows);
     } else {
         const int ngroups = (p.B + SLOTS - 1) / SLOTS;
         kk = ticket / (unsigned)ngroups;
         b = (ticket - kk * ngroups) * SLOTS + slot;
+        rg = sweep_range(p, (p.nbands - 1 - kk) * kBandRows, (p.nbands - 1 - kk) * kBandRows);
     }
     const int k = p.nbands - 1 - kk;
     const bool live = (kk < p.nbands) && (b < p.B);
     const int lag = (SLOTS == 2) ? kChainLag * slot : 0;
-    const int niter = p.nmacro + ((SLOTS == 2) ? kChainLag : 0);
+    const int niter = (rg.hi - rg.lo + 1) + ((SLOTS == 2) ? kChainLag : 0);
+    if constexpr (SLOTS == 2) {
+        if (producer < 0) {  // unused wavefront: only keeps the barrier count (one before the loop, one per iteration)
+            for (int it = 0; it <= niter; ++it) __syncthreads();
+            return;
+        }
+    }
 
     const int M = p.M, N = p.N;
     const int row0 = (live ? k : 0) * kBandRows;
@@ -888,7 +966,7 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
     const float *xisb = p.xis + bb * p.xn_stride, *yisb = p.yis + bb * p.yn_stride;
     const uint16_t *xh = p.xh + bb * p.xh_stride, *yh = p.yh + bb * p.yh_stride;
     float2 *rowtab = sh.rowtab[slot];
-    const int sg0 = p.nmacro - 1;
+    const int sg0 = rg.hi;  // the sweep's first macro-step
 
     float *Eb = p.E + (size_t)bb * N * M;
     unsigned char *nzb = p.nz + (size_t)bb * p.nrb * p.ncb;
@@ -901,8 +979,8 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
         // (With recomputation the producer is the busier side, so there the consumer keeps this job.)
         auto flush = [&](int done, bool upper, bool lower) {
             if constexpr (kProducerFlush) {
-                if (upper) flush_E_block(p, ring, Eb, nzb, 0, done, row0, lane);
-                if (lower) flush_E_block(p, ring, Eb, nzb, 1, done - 1, row0, lane);
+                if (upper) flush_E_block(p, rg, ring, Eb, nzb, 0, done, row0, lane);
+                if (lower) flush_E_block(p, rg, ring, Eb, nzb, 1, done - 1, row0, lane);
             }
         };
         // blocks the first macro-step reads: (upper rows, sg0-1), (lower rows, sg0-1), (lower rows, sg0-2)
@@ -922,13 +1000,14 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
                 __syncthreads();
                 for (int it = 0; it < niter; ++it) {
                     const int sg = sg0 - (it - lag);
-                    if (live && sg >= 0 && sg <= sg0) {
+                    if (live && sg >= rg.lo && sg <= sg0) {
                         if (sg < sg0) flush(sg + 1, upper, !upper);
                         mp.run(pl, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
                     }
                     __syncthreads();
                 }
-                if (live) flush(0, upper, !upper);
+                if (live) flush(rg.lo, upper, !upper);
+                if (live && kProducerFlush && upper) zero_fringe(p, rg, Eb, nzb, row0, lane, 0, p.ncb - 1);
             };
             if (producer == 1) {
                 HalfProducer<KCH, -1, 0, 1> mp;
@@ -949,13 +1028,14 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
             __syncthreads();
             for (int it = 0; it < niter; ++it) {
                 const int sg = sg0 - (it - lag);
-                if (live && sg >= 0 && sg <= sg0) {
+                if (live && sg >= rg.lo && sg <= sg0) {
                     if (sg < sg0) flush(sg + 1, true, true);
                     mp.run(pl, yh, ynb, yisb, ring, rowtab, sg, row0, lane);
                 }
                 __syncthreads();
             }
-            if (live) flush(0, true, true);
+            if (live) flush(rg.lo, true, true);
+            if (live && kProducerFlush) zero_fringe(p, rg, Eb, nzb, row0, lane, 0, p.ncb - 1);
         } else if constexpr (KCH == 0) {
             if (live) {
                 generic_block(pl, b, ring, 0, sg0 - 1, row0, lane);
@@ -965,40 +1045,42 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
             __syncthreads();
             for (int it = 0; it < niter; ++it) {
                 const int sg = sg0 - (it - lag);
-                if (live && sg >= 0 && sg <= sg0) {
+                if (live && sg >= rg.lo && sg <= sg0) {
                     if (sg < sg0) flush(sg + 1, true, true);
                     generic_block(pl, b, ring, 0, sg - 2, row0, lane);
                     generic_block(pl, b, ring, 1, sg - 3, row0, lane);
                 }
                 __syncthreads();
             }
-            if (live) flush(0, true, true);
+            if (live) flush(rg.lo, true, true);
+            if (live && kProducerFlush) zero_fringe(p, rg, Eb, nzb, row0, lane, 0, p.ncb - 1);
         } else {
             const float *cost_b = p.cost + (size_t)bb * N * M;
             float4 pre[2][4];
             if (live) {
-                load_cost_block(pre[0], cost_b, 0, sg0 - 1, row0, Nl, Ml, M, p.vec_m != 0, lane);
+                load_cost_block(pre[0], cost_b, 0, sg0 - 1, row0, Nl, Ml, M, p.window, p.vec_m != 0, lane);
                 store_cost_block(ring, pre[0], 0, sg0 - 1, lane);
-                load_cost_block(pre[0], cost_b, 1, sg0 - 1, row0, Nl, Ml, M, p.vec_m != 0, lane);
+                load_cost_block(pre[0], cost_b, 1, sg0 - 1, row0, Nl, Ml, M, p.window, p.vec_m != 0, lane);
                 store_cost_block(ring, pre[0], 1, sg0 - 1, lane);
-                load_cost_block(pre[0], cost_b, 1, sg0 - 2, row0, Nl, Ml, M, p.vec_m != 0, lane);
+                load_cost_block(pre[0], cost_b, 1, sg0 - 2, row0, Nl, Ml, M, p.window, p.vec_m != 0, lane);
                 store_cost_block(ring, pre[0], 1, sg0 - 2, lane);
-                load_cost_block(pre[0], cost_b, 0, sg0 - 2, row0, Nl, Ml, M, p.vec_m != 0, lane);
-                load_cost_block(pre[1], cost_b, 1, sg0 - 3, row0, Nl, Ml, M, p.vec_m != 0, lane);
+                load_cost_block(pre[0], cost_b, 0, sg0 - 2, row0, Nl, Ml, M, p.window, p.vec_m != 0, lane);
+                load_cost_block(pre[1], cost_b, 1, sg0 - 3, row0, Nl, Ml, M, p.window, p.vec_m != 0, lane);
             }
             __syncthreads();
             for (int it = 0; it < niter; ++it) {
                 const int sg = sg0 - (it - lag);
-                if (live && sg >= 0 && sg <= sg0) {
+                if (live && sg >= rg.lo && sg <= sg0) {
                     if (sg < sg0) flush(sg + 1, true, true);
                     store_cost_block(ring, pre[0], 0, sg - 2, lane);
                     store_cost_block(ring, pre[1], 1, sg - 3, lane);
-                    load_cost_block(pre[0], cost_b, 0, sg - 3, row0, Nl, Ml, M, p.vec_m != 0, lane);
-                    load_cost_block(pre[1], cost_b, 1, sg - 4, row0, Nl, Ml, M, p.vec_m != 0, lane);
+                    load_cost_block(pre[0], cost_b, 0, sg - 3, row0, Nl, Ml, M, p.window, p.vec_m != 0, lane);
+                    load_cost_block(pre[1], cost_b, 1, sg - 4, row0, Nl, Ml, M, p.window, p.vec_m != 0, lane);
                 }
                 __syncthreads();
             }
-            if (live) flush(0, true, true);
+            if (live) flush(rg.lo, true, true);
+            if (live && kProducerFlush) zero_fringe(p, rg, Eb, nzb, row0, lane, 0, p.ncb - 1);
         }
         return;
     }
@@ -1068,7 +1150,7 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
 
     for (int it = 0; it < niter; ++it) {
         const int sg = sg0 - (it - lag);
-        if (live && sg >= 0 && sg <= sg0) {
+        if (live && sg >= rg.lo && sg <= sg0) {
             unsigned long long nxt_bits = (unsigned long long)__double_as_longlong(kBig);
             const int jn = (sg - 1) * kBlk + lane - kBlk - (kBandRows - 1);
             const bool need_n = has_below && lane >= kBlk && jn >= 0 && jn < M;
@@ -1151,8 +1233,8 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
             // the E blocks this macro-step completed, (upper rows, sg) and (lower rows, sg-1): written
             // out by the producers during the next macro-step, or here
             if constexpr (!kProducerFlush && !TSWEEP) {
-                flush_E_block(p, ring, Eb, nzb, 0, sg, row0, lane);
-                flush_E_block(p, ring, Eb, nzb, 1, sg - 1, row0, lane);
+                flush_E_block(p, rg, ring, Eb, nzb, 0, sg, row0, lane);
+                flush_E_block(p, rg, ring, Eb, nzb, 1, sg - 1, row0, lane);
             }
             if constexpr (CH != 1) {
                 double bn = kBig;
@@ -1161,6 +1243,9 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
             }
         }
         __syncthreads();
+    }
+    if constexpr (!kProducerFlush && !TSWEEP) {
+        if (live) zero_fringe(p, rg, Eb, nzb, row0, lane, 0, p.ncb - 1);
     }
     };
     if constexpr (SLOTS == 2) {
@@ -1215,7 +1300,23 @@ __global__ __launch_bounds__(64) void alignment_kernel(Params p, int seg_blocks)
     const double *Rk = p.R + band_off, *Qk = p.Q + band_off;
     const double Rfin = p.rfinal[b];
     float *my_ring = ring + lane * kAlignRingStride;
-    const int g_end = min(cb1 + 2, p.nmacro);  // macro-steps [cb0, g_end) hold every cell of the run
+    // With a band constraint only macro-steps rg.lo .. rg.hi of the tables exist.  The blocks of the
+    // run that the sweeps did not cover are outside the window: flags cleared, and zeros written
+    // where the gradient kernels may still read them (zero_fringe).
+    const SweepRange rg = sweep_range(p, row0, row0);
+    if (p.window < kNoWindow) {
+        const int w0 = (rg.lo - 1) & ~1, w1 = (rg.hi_u - 1) | 1;
+        for (int cb = cb0 + lane; cb < cb1; cb += kBandRows) {
+            if (cb < w0 || cb > w1) {
+                if (row0 < p.N) nzb[(size_t)(row0 / kBlk) * p.ncb + cb] = 0;
+                if (row0 + kBlk < p.N) nzb[(size_t)(row0 / kBlk + 1) * p.ncb + cb] = 0;
+            }
+        }
+        zero_fringe(p, rg, Eb, nzb, row0, lane, cb0, cb1 - 1);
+    }
+    const int g_first = max(cb0, rg.lo);
+    const int g_end = min(min(cb1 + 2, p.nmacro), rg.hi + 1);  // macro-steps [g_first, g_end) hold every cell of the run
+    if (g_first >= g_end) return;
 
     auto load = [&](int g, double (&r)[kBlk], double (&q)[kBlk]) {
         const size_t o = (size_t)g * kBlk * kBandRows + lane;
@@ -1231,13 +1332,13 @@ __global__ __launch_bounds__(64) void alignment_kernel(Params p, int seg_blocks)
         for (int u = 0; u < kBlk; ++u) wr[u] = __builtin_amdgcn_exp2f((float)((Rfin - r[u]) - q[u]));
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         // complete now: (upper rows, block g-1) and (lower rows, block g-2)
-        if (g - 1 >= cb0 && g - 1 < cb1) flush_E_block<kAlignRingCols, kAlignRingStride>(p, ring, Eb, nzb, 0, g - 1, row0, lane);
-        if (g - 2 >= cb0 && g - 2 < cb1) flush_E_block<kAlignRingCols, kAlignRingStride>(p, ring, Eb, nzb, 1, g - 2, row0, lane);
+        if (g - 1 >= cb0 && g - 1 < cb1) flush_E_block<kAlignRingCols, kAlignRingStride>(p, rg, ring, Eb, nzb, 0, g - 1, row0, lane);
+        if (g - 2 >= cb0 && g - 2 < cb1) flush_E_block<kAlignRingCols, kAlignRingStride>(p, rg, ring, Eb, nzb, 1, g - 2, row0, lane);
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     };
 
     double ra[kBlk], qa[kBlk], rb[kBlk], qb[kBlk];
-    int g = cb0;
+    int g = g_first;
     load(g, ra, qa);
     while (g < g_end) {
         if (g + 1 < g_end) load(g + 1, rb, qb);
@@ -1249,8 +1350,8 @@ __global__ __launch_bounds__(64) void alignment_kernel(Params p, int seg_blocks)
     }
     // blocks whose last macro-steps lie beyond the table (all their cells are already in the ring)
     for (; g < cb1 + 2; ++g) {
-        if (g - 1 >= cb0 && g - 1 < cb1) flush_E_block<kAlignRingCols, kAlignRingStride>(p, ring, Eb, nzb, 0, g - 1, row0, lane);
-        if (g - 2 >= cb0 && g - 2 < cb1) flush_E_block<kAlignRingCols, kAlignRingStride>(p, ring, Eb, nzb, 1, g - 2, row0, lane);
+        if (g - 1 >= cb0 && g - 1 < cb1) flush_E_block<kAlignRingCols, kAlignRingStride>(p, rg, ring, Eb, nzb, 0, g - 1, row0, lane);
+        if (g - 2 >= cb0 && g - 2 < cb1) flush_E_block<kAlignRingCols, kAlignRingStride>(p, rg, ring, Eb, nzb, 1, g - 2, row0, lane);
     }
 }
 

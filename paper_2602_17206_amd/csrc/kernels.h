@@ -27,11 +27,27 @@ __global__ void fill_f32_kernel(float *dst, size_t n, float v)
     for (; i < n; i += stride) dst[i] = v;
 }
 
-__device__ __forceinline__ void fill_boundary_rows(const Params &p, unsigned long long *rows)
+// Boundary rows before a sweep: "not written yet" wherever the band that owns the row will publish a
+// value.  With a band constraint a sweep skips the macro-steps outside the window; the columns it
+// never publishes (forward: the band's last row, columns 32*lo-63 .. 32*hi-32; reverse: its first
+// row, columns 32*lo .. 32*hi+31) lie outside the window and hold kBig from the start.
+__device__ __forceinline__ void fill_boundary_rows(const Params &p, unsigned long long *rows, bool reverse)
 {
     const size_t n = (size_t)p.B * p.nbands * p.M;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) rows[i] = kSentinel;
+    if (p.window >= kNoWindow) {
+        for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) rows[i] = kSentinel;
+        return;
+    }
+    const unsigned long long big = (unsigned long long)__double_as_longlong(kBig);
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const int j = (int)(i % (size_t)p.M);
+        const int k = (int)((i / (size_t)p.M) % (size_t)p.nbands);
+        const SweepRange r = sweep_range(p, k * kBandRows, k * kBandRows);
+        const int first = reverse ? kBlk * r.lo : kBlk * r.lo - (kBandRows - 1);
+        const int last = reverse ? kBlk * r.hi + kBlk - 1 : kBlk * r.hi - kBlk;
+        rows[i] = (j >= first && j <= last) ? kSentinel : big;
+    }
 }
 
 // Start of a forward call, one launch: stamps the header, resets the band tickets, marks every
@@ -46,6 +62,7 @@ __global__ __launch_bounds__(256) void forward_prep_kernel(Params p, int64_t xro
         h->gamma_bits = __float_as_uint(p.gamma);
         h->forward_done = 1;
         h->two_sweep = p.two_sweep;
+        h->window = p.window;
         h->x_len_ptr = reinterpret_cast<uint64_t>(p.x_len);
         h->y_len_ptr = reinterpret_cast<uint64_t>(p.y_len);
         h->status = 0;
@@ -53,8 +70,8 @@ __global__ __launch_bounds__(256) void forward_prep_kernel(Params p, int64_t xro
         h->fwd_ticket = 0;
         h->bwd_ticket = 0;
     }
-    fill_boundary_rows(p, p.brow);
-    if (p.two_sweep) fill_boundary_rows(p, p.brow_b);  // the reverse sweep runs in the same call
+    fill_boundary_rows(p, p.brow, false);
+    if (p.two_sweep) fill_boundary_rows(p, p.brow_b, true);  // the reverse sweep runs in the same call
     const int lane = threadIdx.x & 63;
     const int64_t rows = xrows + yrows;
     const int64_t stride = (int64_t)gridDim.x * 4;
@@ -188,7 +205,7 @@ __device__ __forceinline__ bool workspace_matches(const Params &p)
 {
     const Header *h = p.hdr;
     return h->magic == kMagic && h->forward_done == 1 && h->B == p.B && h->N == p.N && h->M == p.M &&
-           h->D == p.D && h->mode == p.mode && h->two_sweep == p.two_sweep &&
+           h->D == p.D && h->mode == p.mode && h->two_sweep == p.two_sweep && h->window == p.window &&
            h->x_len_ptr == reinterpret_cast<uint64_t>(p.x_len) && h->y_len_ptr == reinterpret_cast<uint64_t>(p.y_len) &&
            h->gamma_bits == __float_as_uint(p.gamma);
 }
@@ -217,7 +234,14 @@ __global__ __launch_bounds__(256) void backward_prep_kernel(Params p)
             h->status = kStatusState;
         }
     }
-    fill_boundary_rows(p, p.brow_b);
+    fill_boundary_rows(p, p.brow_b, true);
+    // with a band constraint the sweep never visits the blocks of E outside the window: their
+    // "any non-zero" flags are cleared here
+    if (p.window < kNoWindow) {
+        const size_t n = (size_t)p.B * p.nrb * p.ncb;
+        const size_t stride = (size_t)gridDim.x * blockDim.x;
+        for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p.nz[i] = 0;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -231,6 +255,7 @@ __global__ __launch_bounds__(256) void cost_tensor_kernel(Params p)
     const int i0 = blockIdx.y * 64 + (w >> 1) * 32;
     const int j0 = blockIdx.x * 64 + (w & 1) * 32;
     if (i0 >= p.N || j0 >= p.M) return;
+    if (j0 - (i0 + 31) > p.window || i0 - (j0 + 31) > p.window) return;  // no cell of the block is inside the window
     float out[16];
     cost_block(p, p.x + b * p.x_stride, p.y + b * p.y_stride, p.xn + b * p.xn_stride,
                p.yn + b * p.yn_stride, i0, j0, lane, out);
@@ -643,15 +668,24 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
     }
 }
 
-// Copies E to the caller's buffer (NaN when the backward call was refused).
+// Copies E to the caller's buffer (NaN when the backward call was refused).  A 32x32 block whose
+// "any non-zero" flag is clear is all zero by definition; with a band constraint the blocks outside
+// the window have never been written.
 __global__ void export_E_kernel(Params p, float *__restrict__ dst)
 {
     const size_t n = (size_t)p.B * p.N * p.M;
     const bool bad = backward_refused(p);
     const float qnan = __builtin_nanf("");
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (; i < n; i += stride) dst[i] = bad ? qnan : p.E[i];
+    for (; e < n; e += stride) {
+        const int j = (int)(e % (size_t)p.M);
+        const size_t bi = e / (size_t)p.M;
+        const int i = (int)(bi % (size_t)p.N);
+        const size_t b = bi / (size_t)p.N;
+        const bool live = p.nz[(b * p.nrb + i / kBlk) * p.ncb + j / kBlk] != 0;
+        dst[e] = bad ? qnan : (live ? p.E[e] : 0.f);
+    }
 }
 
 // Un-skews the step-major DP table into row-major R[b][i][j], in the paper's units (test hook).

@@ -14,6 +14,8 @@ constexpr int kBandRows = 64;    // rows per band == lanes per wavefront
 constexpr int kBlk = 32;         // edge of a cost block (one 32x32 MFMA tile)
 constexpr uint64_t kSentinel = 0xFFFFFFFFFFFFFFFFull;  // "not written yet" in boundary rows
 constexpr uint32_t kMagic = 0x53445457u;               // 'SDTW'
+constexpr double kBig = 1e300;                         // stands for +inf in the DP tables and boundary rows
+constexpr int32_t kNoWindow = 0x3FFFFFFF;              // Params::window when there is no band constraint
 constexpr int kGuardBytes = 512;  // slack before/after regions that are read with clamped indices
 
 // First 256 bytes of a workspace (device memory).
@@ -27,7 +29,7 @@ struct Header {
     uint32_t fwd_ticket;   // next band task of the forward sweep
     uint32_t bwd_ticket;   // next band task of the backward sweep
     int32_t two_sweep;     // the forward call also ran the reverse sweep
-    uint32_t pad0;
+    int32_t window;        // band constraint |i-j| <= window the forward was run with (kNoWindow: none)
     uint64_t x_len_ptr, y_len_ptr;  // the length vectors the forward was run with (0: none)
     uint32_t pad[46];
 };
@@ -123,6 +125,7 @@ struct Params {
     uint32_t spin_limit;           // polls before a band gives up waiting
     const float *x, *y;
     const int32_t *x_len, *y_len;  // ragged batches: per-pair lengths (device), or nullptr
+    int32_t window;                // only cells with |i-j| <= window belong to the grid (kNoWindow: all do)
     Header *hdr;
     double *rfinal;
     float *xn, *yn;

@@ -54,7 +54,9 @@ bool desc_ok(const sdtw_desc *d, int *why)
     if (d->x_batch_stride != 0 && d->x_batch_stride != (int64_t)d->N * d->D) return false;
     if (d->y_batch_stride != 0 && d->y_batch_stride != (int64_t)d->M * d->D) return false;
     if ((int64_t)d->M + 128 > 0x3FFFFFFF || (int64_t)d->N + 128 > 0x3FFFFFFF) return false;
-    if (d->bandwidth != 0) { *why = SDTW_ERR_UNSUPPORTED; return false; }
+    // band constraint |i-j| <= bandwidth: the last cell (N-1, M-1) has to be inside it
+    if (d->bandwidth < 0 || d->bandwidth >= kNoWindow) return false;
+    if (d->bandwidth > 0 && std::abs(d->N - d->M) > d->bandwidth) return false;
     *why = SDTW_OK;
     return true;
 }
@@ -83,6 +85,7 @@ Params make_params(const sdtw_desc *d, const Layout &L, const float *x, const fl
     Params p{};
     p.x_len = x_len;
     p.y_len = y_len;
+    p.window = d->bandwidth > 0 ? d->bandwidth : kNoWindow;
     char *base = static_cast<char *>(ws);
     p.B = d->B; p.N = d->N; p.M = d->M; p.D = d->D; p.mode = d->mode;
     p.nbands = L.nbands; p.nmacro = L.nmacro; p.nrb = L.nrb; p.ncb = L.ncb;
@@ -382,7 +385,7 @@ const char *sdtw_status_string(int status)
         case SDTW_OK: return "ok";
         case SDTW_ERR_INVALID_ARG: return "invalid argument";
         case SDTW_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
-        case SDTW_ERR_UNSUPPORTED: return "unsupported option (bandwidth must be 0)";
+        case SDTW_ERR_UNSUPPORTED: return "unsupported option (normalised Soft-DTW takes no bandwidth)";
         case SDTW_ERR_STATE: return "backward called on a workspace without a matching forward";
         case SDTW_ERR_HIP: return "HIP runtime error";
         case SDTW_ERR_TIMEOUT: return "a band gave up waiting for its neighbour";
@@ -478,7 +481,7 @@ int sdtw_barycenter_step(const sdtw_bary_desc *desc, float *z, const float *X, f
 size_t sdtw_normalized_workspace_bytes(const sdtw_desc *desc)
 {
     int why;
-    if (!desc_ok(desc, &why)) return 0;
+    if (!desc_ok(desc, &why) || desc->bandwidth != 0) return 0;
     return norm_plan(desc).total;
 }
 
@@ -487,6 +490,7 @@ int sdtw_normalized_forward(const sdtw_desc *desc, const float *x, const float *
 {
     int why;
     if (!desc_ok(desc, &why)) return why;
+    if (desc->bandwidth != 0) return SDTW_ERR_UNSUPPORTED;
     if (!x || !y || !value) return SDTW_ERR_INVALID_ARG;
     const NormPlan P = norm_plan(desc);
     if (int rc = check_ws(workspace, workspace_bytes, P.total)) return rc;
@@ -509,6 +513,7 @@ int sdtw_normalized_backward(const sdtw_desc *desc, const float *x, const float 
 {
     int why;
     if (!desc_ok(desc, &why)) return why;
+    if (desc->bandwidth != 0) return SDTW_ERR_UNSUPPORTED;
     if (!x || !y) return SDTW_ERR_INVALID_ARG;
     if (desc->flags & SDTW_FLAG_VALUE_ONLY) return SDTW_ERR_STATE;
     const NormPlan P = norm_plan(desc);

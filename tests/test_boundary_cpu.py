@@ -56,20 +56,32 @@ def test_workspace_sizes():
 
 @pytest.mark.parametrize("kw", [
     dict(B=0), dict(N=0), dict(M=-3), dict(D=0), dict(gamma=0.0), dict(gamma=-1.0), dict(gamma=float("nan")),
-    dict(gamma=float("inf")), dict(mode=2), dict(mode=-1), dict(flags=2), dict(bandwidth=5),
+    dict(gamma=float("inf")), dict(mode=2), dict(mode=-1), dict(flags=2), dict(bandwidth=-1),
+    dict(N=8, M=20, bandwidth=11),  # the last cell (N-1, M-1) would lie outside the band |i-j| <= 11
 ])
 def test_invalid_descriptors_need_zero_bytes_and_are_refused(kw):
     args = dict(B=2, N=8, M=8, D=4, gamma=1.0, mode=pkg.FUSED)
     extra = {k: kw[k] for k in ("flags", "bandwidth") if k in kw}
     args.update({k: v for k, v in kw.items() if k not in extra})
+    assert pkg.sdtw_workspace_bytes(binding.make_desc(2, 8, 20, 4, 1.0, pkg.FUSED, bandwidth=12)) > 0
     d = binding.make_desc(**args, **extra)
     assert pkg.sdtw_workspace_bytes(d) == 0
     lib = pkg.load_library()
     fake = ctypes.c_void_p(0x1000)  # never dereferenced: the descriptor is rejected first
     rc = lib.sdtw_forward(ctypes.byref(d), fake, fake, fake, fake, 1 << 30, None)
-    assert rc == (binding.STATUS_UNSUPPORTED if "bandwidth" in kw else binding.STATUS_INVALID_ARG)
+    assert rc == binding.STATUS_INVALID_ARG
     rc = lib.sdtw_backward(ctypes.byref(d), fake, fake, None, fake, fake, None, fake, 1 << 30, None)
-    assert rc == (binding.STATUS_UNSUPPORTED if "bandwidth" in kw else binding.STATUS_INVALID_ARG)
+    assert rc == binding.STATUS_INVALID_ARG
+
+
+def test_normalized_entry_points_take_no_bandwidth():
+    d = binding.make_desc(2, 8, 8, 4, 1.0, pkg.FUSED, bandwidth=3)
+    assert pkg.sdtw_workspace_bytes(d) > 0
+    assert pkg.sdtw_normalized_workspace_bytes(d) == 0
+    lib = pkg.load_library()
+    fake = ctypes.c_void_p(0x1000)  # never dereferenced
+    assert lib.sdtw_normalized_forward(ctypes.byref(d), fake, fake, fake, fake, 1 << 30, None) == binding.STATUS_UNSUPPORTED
+    assert lib.sdtw_normalized_backward(ctypes.byref(d), fake, fake, None, fake, fake, fake, 1 << 30, None) == binding.STATUS_UNSUPPORTED
 
 
 def test_null_pointers_and_workspace_errors():

@@ -354,6 +354,94 @@ def test_ragged_large_regime_and_state_check():
     assert binding.workspace_status(ws) == binding.STATUS_STATE
 
 
+# ------------------------------------------------------------------------------- band constraint |i-j| <= w
+def run_gpu_band(x, y, gamma, mode, w, want_E=True, xl=None, yl=None):
+    import torch
+
+    xd, yd = to_dev(x), to_dev(y)
+    xld = to_dev(xl) if xl is not None else None
+    yld = to_dev(yl) if yl is not None else None
+    value, desc, ws = pkg.sdtw_forward_ragged(xd, yd, xld, yld, gamma, mode, bandwidth=w)
+    dx, dy, E = pkg.sdtw_backward_ragged(desc, xd, yd, xld, yld, ws, want_E=want_E)
+    torch.cuda.synchronize()
+    assert binding.workspace_status(ws) == 0
+    out = {"value": value.cpu().numpy().astype(np.float64), "dx": dx.cpu().numpy().astype(np.float64),
+           "dy": dy.cpu().numpy().astype(np.float64)}
+    if want_E:
+        out["E"] = E.cpu().numpy().astype(np.float64)
+    return out
+
+
+BAND_CASES = [
+    (3, 200, 150, 16, 0.1, (50, 64, 97, 400)),       # w = |N-M| is the narrowest band that holds the last cell
+    (2, 130, 257, 128, 0.05, (127, 160)),
+    (4, 300, 300, 8, 1.0, (1, 5, 31, 32, 33, 63, 64, 65, 100)),
+    (3, 64, 64, 4, 0.5, (1, 63)),
+    (2, 100, 90, 200, 0.5, (20,)),                    # D above the register-operand limit
+    (5, 500, 520, 40, 0.2, (20, 77)),
+]
+
+
+@pytest.mark.parametrize("shape", [0, 1, 2, 4])
+@pytest.mark.parametrize("mode", ["unfused", "fused"])
+@pytest.mark.parametrize("B,N,M,D,gamma,widths", BAND_CASES)
+def test_band_constraint(shape, mode, B, N, M, D, gamma, widths):
+    x, y = workloads.normal_pairs(700 + N + D, B, N, M, D)
+    ii, jj = np.indices((N, M))
+    for w in widths:
+        say("band w=%d shape %d %s B=%d N=%d M=%d D=%d" % (w, shape, mode, B, N, M, D))
+        ref = oracle.batch(x, y, gamma, want_E=True, bandwidth=w)
+        binding.debug_force_workgroup_shape(shape)
+        try:
+            got = run_gpu_band(x, y, gamma, MODES[mode], w)
+        finally:
+            binding.debug_force_workgroup_shape(0)
+        check_against(ref, got, what="band %d shape %d %s" % (w, shape, mode))
+        assert not got["E"][:, np.abs(ii - jj) > w].any()
+
+
+@pytest.mark.parametrize("mode", ["unfused", "fused"])
+def test_band_constraint_long_and_narrow(mode):
+    # the sweeps skip most macro-steps of every band; small regime
+    B, N, M, D, gamma, w = 3, 4096, 4000, 8, 0.1, 130
+    say("band long %s" % mode)
+    x, y = workloads.walk_pairs(61, B, N, M, D)
+    ref = oracle.batch(x, y, gamma, bandwidth=w)
+    got = run_gpu_band(x, y, gamma, MODES[mode], w, want_E=False)
+    check_against(ref, got, what="band long " + mode)
+
+
+def test_band_constraint_large_regime_ragged_and_state_check():
+    import torch
+
+    # more than 1024 band tasks: 4-band workgroups, stored-table backward and recomputing backward;
+    # per-pair lengths whose difference stays inside the band
+    B, N, M, D, gamma, w = 44, 1600, 1500, 24, 0.2, 230
+    say("band, large regime B=%d N=%d M=%d w=%d" % (B, N, M, w))
+    x, y = workloads.normal_pairs(71, B, N, M, D)
+    xl = workloads.ragged_lengths(72, B, N, shortest=1300)
+    yl = np.minimum(M, np.maximum(1, xl + workloads.ragged_lengths(73, B, 2 * w, shortest=0) - w)).astype(np.int32)
+    assert (np.abs(xl - yl) <= w).all()
+    pairs = [0, 9, 43]
+    ii, jj = np.indices((N, M))
+    for mode in ("unfused", "fused"):
+        ref = oracle.batch(x[pairs], y[pairs], gamma, want_E=True, bandwidth=w)
+        got = run_gpu_band(x, y, gamma, MODES[mode], w)
+        check_against(ref, got, pairs=pairs, what="band large " + mode)
+        assert not got["E"][:, np.abs(ii - jj) > w].any()
+        ref = oracle.ragged_batch(x[pairs], y[pairs], xl[pairs], yl[pairs], gamma, bandwidth=w)
+        got = run_gpu_band(x, y, gamma, MODES[mode], w, want_E=False, xl=xl, yl=yl)
+        check_against(ref, got, pairs=pairs, what="band large ragged " + mode)
+    # a backward call with another bandwidth than the forward's is refused on the device
+    xd, yd = to_dev(x[:2, :100]), to_dev(y[:2, :90])
+    _, desc, ws = pkg.sdtw_forward(xd, yd, gamma, pkg.FUSED, bandwidth=30)
+    desc.bandwidth = 31
+    dx, dy, _ = pkg.sdtw_backward(desc, xd, yd, ws)
+    torch.cuda.synchronize()
+    assert binding.workspace_status(ws) == binding.STATUS_STATE
+    assert torch.isnan(dx).all() and torch.isnan(dy).all()
+
+
 # ------------------------------------------------------------------------------- normalised Soft-DTW
 @pytest.mark.parametrize("mode", ["unfused", "fused"])
 @pytest.mark.parametrize("B,N,M,D,gamma,shared", [(3, 40, 40, 8, 0.5, False), (2, 130, 75, 16, 0.1, False),
