@@ -244,6 +244,39 @@ def bench_normalized(wl, steps, warmup):
             "fwd_bwd_cells_per_s": cells / dt, "workspace_bytes": ws.nbytes}
 
 
+def bench_band(wl, w, steps, warmup):
+    """Band constraint |i-j| <= w on a pair workload, forward+backward per mode; cells counted are
+    those inside the band."""
+    import torch
+
+    import paper_2602_17206_amd as pkg
+
+    xd = torch.from_numpy(wl.x).cuda()
+    yd = torch.from_numpy(wl.y).cuda()
+    dx, dy = torch.empty_like(xd), torch.empty_like(yd)
+    inside = sum(max(0, min(wl.M - 1, i + w) - max(0, i - w) + 1) for i in range(wl.N))
+    out = {"workload": wl.name, "bandwidth": w, "cells_inside_band": wl.B * inside}
+    for name, mode in (("unfused", pkg.UNFUSED), ("fused", pkg.FUSED)):
+        value, desc, ws = pkg.sdtw_forward(xd, yd, wl.gamma, mode, bandwidth=w)
+
+        def step():
+            pkg.sdtw_forward(xd, yd, wl.gamma, mode, workspace=ws, value=value, bandwidth=w)
+            pkg.sdtw_backward(desc, xd, yd, ws, dx=dx, dy=dy)
+
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        out[name] = {"fwd_bwd_ms": dt * 1e3, "fwd_bwd_band_cells_per_s": wl.B * inside / dt}
+        del ws
+        torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(wl, target_wall_s=2.0):
     """The CPU oracle as it stands, forward+backward, all host threads, on whole batches of the
     workload repeated until about target_wall_s has passed."""
@@ -332,6 +365,8 @@ def main():
             torch.cuda.empty_cache()
         others["c5_barycenter"] = bench_barycenter(50, 3)
         others["normalized_c2"] = bench_normalized(wl, 20, 3)
+        others["band_c3_w64"] = bench_band(workloads.pair_workload("c3_b32_l1024_walk"), 64, 20, 3)
+        others["band_c4_w128"] = bench_band(workloads.pair_workload("c4_b32_l8192"), 128, 5, 2)
         line["other_workloads"] = others
     print(json.dumps(line))
 
