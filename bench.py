@@ -27,16 +27,21 @@ if ROOT not in sys.path:
 PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_F32_TFLOPS = 157.3
 PEAK_MFMA_F16_TFLOPS = 2500.0  # dense; the cost and gradient contractions run there for D <= 128 (split operands)
-# Plain (non-packed, non-FMA) vector issue rate: 256 CUs x 64 lanes x 2.4 GHz.  The DP recurrence is
-# a dependent chain of min/sub/convert/exp2/log2 operations that can use neither FMA nor packing,
-# so this, not the 157.3 TFLOP/s packed-FMA figure (= 4x this), is the ceiling of its ALU work.
+# Vector-ALU ceiling of the DP recurrence, in float64-rate lane operations: 256 CUs x 4 SIMDs x 16
+# lanes x 2.4 GHz = 39.3e12/s (the published 78.6 TFLOP/s float64 vector peak counts an FMA as two).
+# At the published rates a float64 add/min/max/fma/convert costs 1 such slot per lane, a float32
+# add or lane shift 0.5 to 1, an exp2/log2 (quarter of the float32 rate) 2.
 PEAK_VALU_TOPS = 256 * 64 * 2.4e9 / 1e12
 
-# Algorithmic work per DP cell: VALU issue slots, a transcendental
-# (exp2/log2, quarter rate) counted as 4 slots.  A sweep (forward, or reverse without E) costs
-# 15 plain operations + 3 transcendentals; the reverse sweep that also forms E 19 + 4.
-SLOTS_SWEEP_CELL = 27.0
-SLOTS_BWD_E_CELL = 35.0
+# Work per DP cell and sweep in those slots, from the instruction mix of the recurrence (Sec. 2
+# Eq. 1-2 with the max-shift of Sec. 4.2): 11 float64 operations (3 min/max, 3 subtractions, 1 fma,
+# 4 conversions), 2 lane-shift moves, 2 float32 additions, 3 transcendentals = 11 + 2 + 1 + 6 = 20
+# (the stand-alone micro-benchmark of the step measures 82 cycles per 64 cells per SIMD = 20.5).
+# The reverse sweep that also forms E adds one exp2, one float64 subtraction, one conversion and one
+# float32 addition: 24.5.  (Recomputing R in the fused backward of large problems is this library's
+# choice, not algorithmic work: it is not counted.)
+SLOTS_SWEEP_CELL = 20.0
+SLOTS_BWD_E_CELL = 24.5
 MODE_NAMES = {0: "unfused", 1: "fused"}
 
 
