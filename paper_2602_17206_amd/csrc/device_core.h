@@ -135,6 +135,15 @@ __device__ __forceinline__ SweepRange sweep_range(const Params &p, int row_a, in
     return r;
 }
 
+// First macro-step held by the tables (R, Q, checkpoints) of band k: that of the widest range the
+// band may run, alone or in a chained pair with the band above it.
+__device__ __forceinline__ int table_base(const Params &p, int k)
+{
+    if (p.window >= kNoWindow) return 0;
+    const int r = max(k - 1, 0) * kBandRows;
+    return sweep_range(p, r, r).lo;
+}
+
 __device__ __forceinline__ bool in_window(int i, int j, int w)
 {
     return (unsigned)(j - i + w) <= 2u * (unsigned)w;

@@ -695,8 +695,10 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
     // RECOMP: the table is not stored; only the lane state at the start of every macro-step is
     // (checkpoints), and the backward kernel recomputes each macro-step of R from it.
     constexpr bool RECOMP = dp_recompute(KCH, SLOTS);
-    double *Rk = RECOMP ? nullptr : p.R + ((size_t)bb * p.nbands + kc) * (size_t)p.nmacro * kBlk * kBandRows;
-    double *Ck = RECOMP ? p.ckpt + ((size_t)bb * p.nbands + kc) * (size_t)p.nmacro * 2 * kBandRows : nullptr;
+    // (table pointers are those of the band's macro-step 0; the table starts at macro-step table_base)
+    const ptrdiff_t tb = table_base(p, kc);
+    double *Rk = RECOMP ? nullptr : p.R + (((size_t)bb * p.nbands + kc) * (size_t)p.nm_tab - tb) * kBlk * kBandRows;
+    double *Ck = RECOMP ? p.ckpt + (((size_t)bb * p.nbands + kc) * (size_t)p.nm_tab - tb) * 2 * kBandRows : nullptr;
     const int s_fin = (live && row0 + lane == Nl - 1) ? (Ml - 1 + lane) : -1;  // step of the pair's last cell
     const bool last_band = live && (k == (Nl - 1) / kBandRows);
     double fin = 0.0;
@@ -1107,10 +1109,12 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
     constexpr bool RECOMP = dp_recompute(KCH, SLOTS);
     const unsigned long long *brow_in = p.brow_b + ((size_t)bb * p.nbands + (has_below ? kc + 1 : kc)) * M;
     unsigned long long *brow_out = p.brow_b + ((size_t)bb * p.nbands + kc) * M;
-    const size_t band_off = ((size_t)bb * p.nbands + kc) * (size_t)p.nmacro * kBlk * kBandRows;
+    // (table pointers are those of the band's macro-step 0; the table starts at macro-step table_base)
+    const ptrdiff_t tb = table_base(p, kc);
+    const ptrdiff_t band_off = (((ptrdiff_t)bb * p.nbands + kc) * (ptrdiff_t)p.nm_tab - tb) * kBlk * kBandRows;
     const double *Rk = (RECOMP || TSWEEP) ? nullptr : p.R + band_off;
     double *Qk = TSWEEP ? p.Q + band_off : nullptr;
-    const double *Ck = RECOMP ? p.ckpt + ((size_t)bb * p.nbands + kc) * (size_t)p.nmacro * 2 * kBandRows : nullptr;
+    const double *Ck = RECOMP ? p.ckpt + (((ptrdiff_t)bb * p.nbands + kc) * (ptrdiff_t)p.nm_tab - tb) * 2 * kBandRows : nullptr;
     // the forward's row above this band (final values, written by the forward call)
     const double *ftop_g = reinterpret_cast<const double *>(p.brow) + ((size_t)bb * p.nbands + (kc > 0 ? kc - 1 : 0)) * M;
     double *ftop = sh.ftop[slot];
@@ -1165,7 +1169,7 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
             // lane 0's values are the band's first row (column 32*sg + u at step u)
             double *my_eo = eo + ((lane == 0) ? 0 : kBlk + lane);
             if constexpr (CH == 0) my_eo = hand + ((lane == 0) ? (sg & 3) * kBlk : kHandRing + lane);
-            const double *Rn = (RECOMP || TSWEEP) ? nullptr : Rk + (size_t)(sg > 0 ? sg - 1 : 0) * kBlk * kBandRows;
+            const double *Rn = (RECOMP || TSWEEP) ? nullptr : Rk + (size_t)(sg > rg.lo ? sg - 1 : sg) * kBlk * kBandRows;
             double *Qs = TSWEEP ? Qk + (size_t)sg * kBlk * kBandRows : nullptr;
             const int sbase = sg * kBlk;
             if constexpr (RECOMP) {
@@ -1173,7 +1177,7 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
                 // cost values, hence the same bits the forward had)
                 double fl = ck_left, fd = ck_diag;
                 if (lane < kBlk) ftop[lane] = ftop_next;
-                if (sg > 0) {  // everything the next macro-step's recomputation needs, one macro-step ahead
+                if (sg > rg.lo) {  // everything the next macro-step's recomputation needs, one macro-step ahead
                     ck_left = __builtin_nontemporal_load(&Ck[((size_t)(sg - 1) * 2 + 0) * kBandRows + lane]);
                     ck_diag = __builtin_nontemporal_load(&Ck[((size_t)(sg - 1) * 2 + 1) * kBandRows + lane]);
                     const int jf = sbase - kBlk + lane;
@@ -1296,7 +1300,7 @@ __global__ __launch_bounds__(64) void alignment_kernel(Params p, int seg_blocks)
 
     float *Eb = p.E + (size_t)b * p.N * p.M;
     unsigned char *nzb = p.nz + (size_t)b * p.nrb * p.ncb;
-    const size_t band_off = ((size_t)b * p.nbands + k) * (size_t)p.nmacro * kBlk * kBandRows;
+    const ptrdiff_t band_off = (((ptrdiff_t)b * p.nbands + k) * (ptrdiff_t)p.nm_tab - table_base(p, k)) * kBlk * kBandRows;
     const double *Rk = p.R + band_off, *Qk = p.Q + band_off;
     const double Rfin = p.rfinal[b];
     float *my_ring = ring + lane * kAlignRingStride;

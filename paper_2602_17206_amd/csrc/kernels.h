@@ -694,14 +694,17 @@ __global__ void export_R_kernel(Params p, double *__restrict__ dst)
     const size_t n = (size_t)p.B * p.N * p.M;
     size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
-    const size_t band_elems = (size_t)p.nmacro * kBlk * kBandRows;
+    const size_t band_elems = (size_t)p.nm_tab * kBlk * kBandRows;
     for (; e < n; e += stride) {
         const int j = (int)(e % p.M);
         const size_t bi = e / p.M;
         const int i = (int)(bi % p.N);
         const int b = (int)(bi / p.N);
         const int k = i / kBandRows, t = i % kBandRows;
-        dst[e] = p.R[((size_t)b * p.nbands + k) * band_elems + (size_t)(j + t) * kBandRows + t] * p.inv_c2d;
+        const int sg = (j + t) / kBlk - table_base(p, k);  // macro-step within the band's table
+        dst[e] = (sg < 0 || sg >= p.nm_tab) ? __builtin_inf()
+                                            : p.R[((size_t)b * p.nbands + k) * band_elems +
+                                                  ((size_t)sg * kBlk + (j + t) % kBlk) * kBandRows + t] * p.inv_c2d;
     }
 }
 

@@ -39,6 +39,7 @@ struct Layout {
     int32_t B, N, M, D, mode;
     int32_t nbands;   // ceil(N/64)
     int32_t nmacro;   // macro-steps per band sweep: ceil((M+63)/32)
+    int32_t nm_tab;   // macro-steps of table (R, Q, checkpoints) kept per band: nmacro, fewer under a band constraint
     int32_t nrb, ncb; // 32x32 block rows / columns: ceil(N/32), ceil(M/32)
     int64_t xn_count, yn_count;  // number of norm entries (1 sequence when the batch stride is 0)
     int32_t Dp;                  // D rounded up to 16, 32, 64 or 128: row length of the split-half operand copies (0: none)
@@ -55,16 +56,28 @@ constexpr int kMaxSplitD = 128;
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// steps per band sweep (multiple of 32, >= M+63)
-inline int64_t steps_of(const Layout &L) { return (int64_t)L.nmacro * kBlk; }
+// table steps kept per band (multiple of 32; without a band constraint all of the sweep's, >= M+63)
+inline int64_t steps_of(const Layout &L) { return (int64_t)L.nm_tab * kBlk; }
+
+// Under a band constraint |i-j| <= window a band only ever runs macro-steps between the first one of
+// the band above it and the last one of the band below it (alone, or as either half of a chained
+// pair): at most (2*window + 256)/32 + 3 of them.  Its tables hold that many, starting at the
+// macro-step table_base() (device_core.h) returns.
+inline int32_t table_macro_steps(int32_t nmacro, int32_t window)
+{
+    if (window >= kNoWindow) return nmacro;
+    const int64_t need = (2 * (int64_t)window + 4 * kBandRows) / kBlk + 3;
+    return need < nmacro ? (int32_t)need : nmacro;
+}
 
 inline Layout make_layout(int32_t B, int32_t N, int32_t M, int32_t D, int32_t mode, bool x_shared,
-                          bool y_shared, bool recompute, bool two_sweep)
+                          bool y_shared, bool recompute, bool two_sweep, int32_t window = kNoWindow)
 {
     Layout L{};
     L.B = B; L.N = N; L.M = M; L.D = D; L.mode = mode;
     L.nbands = (N + kBandRows - 1) / kBandRows;
     L.nmacro = (M + kBandRows - 1 + kBlk - 1) / kBlk;
+    L.nm_tab = table_macro_steps(L.nmacro, window);
     L.nrb = (N + kBlk - 1) / kBlk;
     L.ncb = (M + kBlk - 1) / kBlk;
     L.xn_count = (int64_t)(x_shared ? 1 : B) * N;
@@ -98,7 +111,7 @@ inline Layout make_layout(int32_t B, int32_t N, int32_t M, int32_t D, int32_t mo
     L.off_Q = o;
     if (two_sweep) o = align_up(o + table_bytes, 256);
     L.off_ckpt = o;
-    if (recompute) o = align_up(o + (size_t)B * L.nbands * (size_t)L.nmacro * 2 * kBandRows * sizeof(double), 256);
+    if (recompute) o = align_up(o + (size_t)B * L.nbands * (size_t)L.nm_tab * 2 * kBandRows * sizeof(double), 256);
     o += kGuardBytes;
     L.off_cost = o;
     if (mode == 0) o = align_up(o + (size_t)B * N * (size_t)M * sizeof(float), 256);
@@ -114,6 +127,7 @@ inline Layout make_layout(int32_t B, int32_t N, int32_t M, int32_t D, int32_t mo
 struct Params {
     int32_t B, N, M, D, mode;
     int32_t nbands, nmacro, nrb, ncb;
+    int32_t nm_tab;         // macro-steps of table kept per band (see table_macro_steps)
     float gamma;
     double c2d;             // log2(e)/gamma: paper units -> table units
     double inv_c2d;         // gamma*ln(2): table units -> paper units

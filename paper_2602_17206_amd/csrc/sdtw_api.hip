@@ -61,11 +61,24 @@ bool desc_ok(const sdtw_desc *d, int *why)
     return true;
 }
 
-// Problems of up to 1024 band tasks cannot fill the chip: they run one band per workgroup.
+// Bands of one pair that have work at the same time.  Without a band constraint all of them; with
+// |i-j| <= w a band runs (2w+129)/32 + 2 macro-steps and the band below it starts 5 macro-steps
+// after it (its window begins 64 columns further right), so only a few overlap.
+int64_t busy_bands(const sdtw_desc *d)
+{
+    const int64_t nbands = (d->N + kBandRows - 1) / kBandRows;
+    if (d->bandwidth <= 0) return nbands;
+    const int64_t run = (2 * (int64_t)d->bandwidth + 2 * kBandRows + 1) / kBlk + 2;
+    return std::min<int64_t>(nbands, run / 5 + 2);
+}
+
+// Problems of up to 1024 busy band tasks cannot fill the chip: they run one band per workgroup.
+// (Under a band constraint the estimate of the busy bands is coarse; measured at B = 32, N = M = 8192
+// and B = 128, N = M = 2048 the one-band workgroups win up to about 640.)
 bool small_problem(const sdtw_desc *d)
 {
     if (g_force_slots) return g_force_slots != 4;
-    return (int64_t)d->B * ((d->N + kBandRows - 1) / kBandRows) <= 1024;
+    return (int64_t)d->B * busy_bands(d) <= (d->bandwidth > 0 ? 640 : 1024);
 }
 
 Layout layout_of(const sdtw_desc *d)
@@ -74,7 +87,7 @@ Layout layout_of(const sdtw_desc *d)
     const bool recompute = d->mode == SDTW_FUSED && !small;  // == dp_recompute(KCH >= 0, SLOTS == 4)
     const bool two_sweep = small && !(d->flags & SDTW_FLAG_VALUE_ONLY);
     return make_layout(d->B, d->N, d->M, d->D, d->mode, d->x_batch_stride == 0, d->y_batch_stride == 0, recompute,
-                       two_sweep);
+                       two_sweep, d->bandwidth > 0 ? d->bandwidth : kNoWindow);
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -89,6 +102,7 @@ Params make_params(const sdtw_desc *d, const Layout &L, const float *x, const fl
     char *base = static_cast<char *>(ws);
     p.B = d->B; p.N = d->N; p.M = d->M; p.D = d->D; p.mode = d->mode;
     p.nbands = L.nbands; p.nmacro = L.nmacro; p.nrb = L.nrb; p.ncb = L.ncb;
+    p.nm_tab = L.nm_tab;
     p.gamma = d->gamma;
     p.c2d = 1.4426950408889634 / (double)d->gamma;
     p.inv_c2d = 0.6931471805599453 * (double)d->gamma;
@@ -155,8 +169,9 @@ void launch_dp_kch(const sdtw_desc *d, const Layout &L, const Params &p, float *
         // It also wants a compute unit per workgroup: two chained workgroups on one compute unit put
         // two consumers on one SIMD (measured at N = M = 1024, B = 32: 5 % slower than unchained).
         const bool light = d->mode == SDTW_UNFUSED || d->D <= 64;
-        const bool roomy = (int64_t)d->B * ((L.nbands + 1) / 2) * (L.two_sweep ? 2 : 1) <= 256;
-        const bool chained = g_force_slots ? g_force_slots == 2 : (L.nbands >= 2 && light && roomy);
+        const bool roomy = (int64_t)d->B * ((busy_bands(d) + 1) / 2) * (L.two_sweep ? 2 : 1) <= 256;
+        // (under a band constraint the chain of band hops is all there is: chaining pays there too, 3-4 %)
+        const bool chained = g_force_slots ? g_force_slots == 2 : (L.nbands >= 2 && (light || d->bandwidth > 0) && roomy);
         if constexpr (FWD) {
             if (chained) {
                 const unsigned tasks = (unsigned)d->B * (unsigned)((L.nbands + 1) / 2);

@@ -426,12 +426,19 @@ def test_band_constraint_large_regime_ragged_and_state_check():
     ii, jj = np.indices((N, M))
     for mode in ("unfused", "fused"):
         ref = oracle.batch(x[pairs], y[pairs], gamma, want_E=True, bandwidth=w)
-        got = run_gpu_band(x, y, gamma, MODES[mode], w)
-        check_against(ref, got, pairs=pairs, what="band large " + mode)
-        assert not got["E"][:, np.abs(ii - jj) > w].any()
-        ref = oracle.ragged_batch(x[pairs], y[pairs], xl[pairs], yl[pairs], gamma, bandwidth=w)
-        got = run_gpu_band(x, y, gamma, MODES[mode], w, want_E=False, xl=xl, yl=yl)
-        check_against(ref, got, pairs=pairs, what="band large ragged " + mode)
+        ref_r = oracle.ragged_batch(x[pairs], y[pairs], xl[pairs], yl[pairs], gamma, bandwidth=w)
+        # as the library would run it (few bands of a pair are busy at a time: one band per workgroup)
+        # and in the 4-band workgroups of large problems
+        for shape in (0, 4):
+            binding.debug_force_workgroup_shape(shape)
+            try:
+                got = run_gpu_band(x, y, gamma, MODES[mode], w)
+                got_r = run_gpu_band(x, y, gamma, MODES[mode], w, want_E=False, xl=xl, yl=yl)
+            finally:
+                binding.debug_force_workgroup_shape(0)
+            check_against(ref, got, pairs=pairs, what="band large %s shape %d" % (mode, shape))
+            assert not got["E"][:, np.abs(ii - jj) > w].any()
+            check_against(ref_r, got_r, pairs=pairs, what="band large ragged %s shape %d" % (mode, shape))
     # a backward call with another bandwidth than the forward's is refused on the device
     xd, yd = to_dev(x[:2, :100]), to_dev(y[:2, :90])
     _, desc, ws = pkg.sdtw_forward(xd, yd, gamma, pkg.FUSED, bandwidth=30)
