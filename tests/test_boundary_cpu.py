@@ -52,6 +52,11 @@ def test_workspace_sizes():
     d_l = binding.make_desc(32, 8192, 8192, 64, 0.1, pkg.FUSED)
     assert pkg.sdtw_workspace_bytes(d_l) < 5.0 * 32 * 8192 * 8192
     assert pkg.sdtw_workspace_bytes(binding.make_desc(1, 1, 1, 1, 1.0, pkg.FUSED)) > 0
+    # under a band constraint the tables follow the band, not M: E (4 B per cell of the full grid)
+    # is what remains
+    d_b = binding.make_desc(32, 8192, 8192, 64, 0.1, pkg.FUSED, bandwidth=128)
+    cells = 32 * 8192 * 8192
+    assert 4 * cells < pkg.sdtw_workspace_bytes(d_b) < 6 * cells
 
 
 @pytest.mark.parametrize("kw", [
