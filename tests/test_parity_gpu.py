@@ -449,6 +449,40 @@ def test_band_constraint_large_regime_ragged_and_state_check():
     assert torch.isnan(dx).all() and torch.isnan(dy).all()
 
 
+# ------------------------------------------------------------------------------- random configurations
+@pytest.mark.parametrize("seed", range(24))
+def test_random_configurations(seed):
+    # shapes, gamma, mode, band, per-pair lengths and workgroup shape drawn at random (seeded): every
+    # option of the plain and ragged entry points in combination
+    rng = np.random.default_rng(4000 + seed)
+    B = int(rng.integers(1, 7))
+    N = int(rng.integers(1, 330))
+    M = int(rng.integers(1, 330))
+    D = int(rng.choice([1, 3, 8, 16, 20, 33, 64, 100, 128, 150]))
+    gamma = float(rng.choice([0.02, 0.1, 0.5, 1.0, 3.0]))
+    mode = str(rng.choice(["unfused", "fused"]))
+    shape = int(rng.choice([0, 0, 1, 2, 4]))
+    ragged = bool(rng.integers(0, 2))
+    banded = bool(rng.integers(0, 2))
+    x, y = workloads.normal_pairs(5000 + seed, B, N, M, D)
+    xl = yl = None
+    w = 0
+    if ragged:
+        xl = workloads.ragged_lengths(6000 + seed, B, N)
+        yl = workloads.ragged_lengths(7000 + seed, B, M)
+    if banded:
+        diff = int(np.abs((xl if ragged else N) - (yl if ragged else M)).max())
+        w = max(1, diff + int(rng.integers(0, 40)))
+    say("random %d: B=%d N=%d M=%d D=%d gamma=%g %s shape=%d ragged=%d w=%d" % (seed, B, N, M, D, gamma, mode, shape, ragged, w))
+    ref = oracle.ragged_batch(x, y, xl, yl, gamma, want_E=True, bandwidth=w if banded else None)
+    binding.debug_force_workgroup_shape(shape)
+    try:
+        got = run_gpu_band(x, y, gamma, MODES[mode], w, xl=xl, yl=yl)
+    finally:
+        binding.debug_force_workgroup_shape(0)
+    check_against(ref, got, what="random %d" % seed)
+
+
 # ------------------------------------------------------------------------------- normalised Soft-DTW
 @pytest.mark.parametrize("mode", ["unfused", "fused"])
 @pytest.mark.parametrize("B,N,M,D,gamma,shared", [(3, 40, 40, 8, 0.5, False), (2, 130, 75, 16, 0.1, False),
