@@ -116,23 +116,45 @@ __device__ __forceinline__ int pair_len(const int32_t *lens, int b, int full)
 // or the initial state (kBig).  Macro-steps [lo, hi] are run; hi_u is hi before it is clipped to
 // the table: a 32x32 block (rb, cb) of the band holds cells of macro-steps cb+rb and cb+rb+1 and is
 // either complete within [lo, hi_u] or entirely outside the window.
-struct SweepRange { int lo, hi, hi_u; };
+//
+// Ragged batches: with Nl, Ml the lengths of the pair (the largest ones among the pairs a workgroup
+// serves) the sweep also stops after the macro-step (Ml+63)/32, which still holds every cell of the
+// column blocks 0 .. cb_last = (Ml-1)/32, and bands that start at or below row Nl do not run at all
+// (hi < lo).  Nl = N, Ml = M change nothing.
+struct SweepRange { int lo, hi, hi_u, cb_last; };
 
-__device__ __forceinline__ SweepRange sweep_range(const Params &p, int row_a, int row_b)
+__device__ __forceinline__ SweepRange sweep_range(const Params &p, int row_a, int row_b, int Nl, int Ml)
 {
     SweepRange r;
+    r.cb_last = (Ml - 1) / kBlk;
     if (p.window >= kNoWindow) {
         r.lo = 0;
         r.hi = p.nmacro - 1;
         r.hi_u = kNoWindow;
-        return r;
+    } else {
+        const int first = row_a - p.window - 1;
+        r.lo = first > 0 ? first / kBlk : 0;
+        r.hi_u = (row_b + 2 * kBandRows - 1 + p.window) / kBlk;
+        r.hi = min(r.hi_u, p.nmacro - 1);
+        r.lo = min(r.lo, r.hi);
     }
-    const int first = row_a - p.window - 1;
-    r.lo = first > 0 ? first / kBlk : 0;
-    r.hi_u = (row_b + 2 * kBandRows - 1 + p.window) / kBlk;
-    r.hi = min(r.hi_u, p.nmacro - 1);
-    r.lo = min(r.lo, r.hi);
+    if (Ml < p.M) r.hi = min(r.hi, (Ml + 2 * kBlk - 1) / kBlk);
+    if (row_a >= Nl) {
+        r.lo = 0;
+        r.hi = -1;
+    }
     return r;
+}
+
+__device__ __forceinline__ SweepRange sweep_range(const Params &p, int row_a, int row_b)
+{
+    return sweep_range(p, row_a, row_b, p.N, p.M);
+}
+
+// pair_len without the promise that all lanes ask for the same pair
+__device__ __forceinline__ int pair_len_lane(const int32_t *lens, int b, int full)
+{
+    return lens == nullptr ? full : max(1, min(lens[b], full));
 }
 
 // First macro-step held by the tables (R, Q, checkpoints) of band k: that of the widest range the

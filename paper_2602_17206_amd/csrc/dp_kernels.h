@@ -573,17 +573,26 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
         const int kp = ticket / (unsigned)p.B;
         b = ticket - kp * p.B;
         k = 2 * kp + (slot & 1);
-        rg = sweep_range(p, 2 * kp * kBandRows, min(2 * kp + 1, p.nbands - 1) * kBandRows);
+        rg = sweep_range(p, 2 * kp * kBandRows, min(2 * kp + 1, p.nbands - 1) * kBandRows, pair_len(p.x_len, b, p.N),
+                         pair_len(p.y_len, b, p.M));
     } else {
         const int ngroups = (p.B + SLOTS - 1) / SLOTS;
         k = ticket / (unsigned)ngroups;
-        b = (ticket - k * ngroups) * SLOTS + slot;
-        rg = sweep_range(p, k * kBandRows, k * kBandRows);
+        const int b0 = (ticket - k * ngroups) * SLOTS;
+        b = b0 + slot;
+        int nl = 1, ml = 1;  // the longest sequences among the workgroup's pairs
+        for (int s2 = 0; s2 < SLOTS; ++s2) {
+            if (b0 + s2 < p.B) {
+                nl = max(nl, pair_len(p.x_len, b0 + s2, p.N));
+                ml = max(ml, pair_len(p.y_len, b0 + s2, p.M));
+            }
+        }
+        rg = sweep_range(p, k * kBandRows, k * kBandRows, nl, ml);
     }
-    const bool live = (k < p.nbands) && (b < p.B);
+    const bool live = (k < p.nbands) && (b < p.B) && rg.hi >= rg.lo;
     // chained pair: the second band does macro-step sg in workgroup iteration sg - rg.lo + kChainLag
     const int lag = (SLOTS == 2) ? kChainLag * slot : 0;
-    const int niter = (rg.hi - rg.lo + 1) + ((SLOTS == 2) ? kChainLag : 0);
+    const int niter = max(rg.hi - rg.lo + 1, 0) + ((SLOTS == 2) ? kChainLag : 0);
     if constexpr (SLOTS == 2) {
         if (producer < 0) {  // unused wavefront: only keeps the barrier count (one before the loop, one per iteration)
             for (int it = 0; it <= niter; ++it) __syncthreads();
@@ -827,7 +836,7 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
 // clear) or zeroed by zero_fringe.
 __device__ __forceinline__ bool block_in_range(const SweepRange &rg, int rb, int cb)
 {
-    return cb + rb >= rg.lo && cb + rb + 1 <= rg.hi_u;
+    return cb + rb >= rg.lo && cb + rb + 1 <= rg.hi_u && cb <= rg.cb_last;
 }
 
 template <int COLS = kRingCols, int STRIDE = kRingStride>
@@ -894,8 +903,8 @@ __device__ __forceinline__ void zero_fringe(const Params &p, const SweepRange &r
                                             unsigned char *__restrict__ nzb, int row0, int lane, int cb_first,
                                             int cb_last)
 {
-    if (p.window >= kNoWindow) return;
-    const int w0 = max((rg.lo - 1) & ~1, cb_first), w1 = min((rg.hi_u - 1) | 1, cb_last);
+    if ((p.window >= kNoWindow && p.x_len == nullptr && p.y_len == nullptr) || rg.hi < rg.lo) return;
+    const int w0 = max((rg.lo - 1) & ~1, cb_first), w1 = min(min(rg.hi_u - 1, rg.cb_last) | 1, cb_last);
     for (int cb = w0; cb <= w1; ++cb)
         for (int rb = 0; rb < 2; ++rb)
             if (!block_in_range(rg, rb, cb)) zero_E_block(p, Eb, nzb, rb, cb, row0, lane);
@@ -937,17 +946,26 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
         b = ticket - kp * p.B;
         kk = 2 * kp + (slot & 1);
         const int k_low = p.nbands - 1 - 2 * kp;  // the lower band of the pair (slot 0), the upper one is k_low - 1
-        rg = sweep_range(p, max(k_low - 1, 0) * kBandRows, k_low * kBandRows);
+        rg = sweep_range(p, max(k_low - 1, 0) * kBandRows, k_low * kBandRows, pair_len(p.x_len, b, p.N),
+                         pair_len(p.y_len, b, p.M));
     } else {
         const int ngroups = (p.B + SLOTS - 1) / SLOTS;
         kk = ticket / (unsigned)ngroups;
-        b = (ticket - kk * ngroups) * SLOTS + slot;
-        rg = sweep_range(p, (p.nbands - 1 - kk) * kBandRows, (p.nbands - 1 - kk) * kBandRows);
+        const int b0 = (ticket - kk * ngroups) * SLOTS;
+        b = b0 + slot;
+        int nl = 1, ml = 1;  // the longest sequences among the workgroup's pairs
+        for (int s2 = 0; s2 < SLOTS; ++s2) {
+            if (b0 + s2 < p.B) {
+                nl = max(nl, pair_len(p.x_len, b0 + s2, p.N));
+                ml = max(ml, pair_len(p.y_len, b0 + s2, p.M));
+            }
+        }
+        rg = sweep_range(p, (p.nbands - 1 - kk) * kBandRows, (p.nbands - 1 - kk) * kBandRows, nl, ml);
     }
     const int k = p.nbands - 1 - kk;
-    const bool live = (kk < p.nbands) && (b < p.B);
+    const bool live = (kk < p.nbands) && (b < p.B) && rg.hi >= rg.lo;
     const int lag = (SLOTS == 2) ? kChainLag * slot : 0;
-    const int niter = (rg.hi - rg.lo + 1) + ((SLOTS == 2) ? kChainLag : 0);
+    const int niter = max(rg.hi - rg.lo + 1, 0) + ((SLOTS == 2) ? kChainLag : 0);
     if constexpr (SLOTS == 2) {
         if (producer < 0) {  // unused wavefront: only keeps the barrier count (one before the loop, one per iteration)
             for (int it = 0; it <= niter; ++it) __syncthreads();
@@ -1307,9 +1325,10 @@ __global__ __launch_bounds__(64) void alignment_kernel(Params p, int seg_blocks)
     // With a band constraint only macro-steps rg.lo .. rg.hi of the tables exist.  The blocks of the
     // run that the sweeps did not cover are outside the window: flags cleared, and zeros written
     // where the gradient kernels may still read them (zero_fringe).
-    const SweepRange rg = sweep_range(p, row0, row0);
-    if (p.window < kNoWindow) {
-        const int w0 = (rg.lo - 1) & ~1, w1 = (rg.hi_u - 1) | 1;
+    const SweepRange rg = sweep_range(p, row0, row0, pair_len(p.x_len, b, p.N), pair_len(p.y_len, b, p.M));
+    if (p.window < kNoWindow || p.x_len != nullptr || p.y_len != nullptr) {
+        const bool none = rg.hi < rg.lo;
+        const int w0 = none ? 1 : ((rg.lo - 1) & ~1), w1 = none ? 0 : (min(rg.hi_u - 1, rg.cb_last) | 1);
         for (int cb = cb0 + lane; cb < cb1; cb += kBandRows) {
             if (cb < w0 || cb > w1) {
                 if (row0 < p.N) nzb[(size_t)(row0 / kBlk) * p.ncb + cb] = 0;

@@ -35,7 +35,7 @@ __device__ __forceinline__ void fill_boundary_rows(const Params &p, unsigned lon
 {
     const size_t n = (size_t)p.B * p.nbands * p.M;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
-    if (p.window >= kNoWindow) {
+    if (p.window >= kNoWindow && p.x_len == nullptr && p.y_len == nullptr) {
         for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) rows[i] = kSentinel;
         return;
     }
@@ -43,10 +43,12 @@ __device__ __forceinline__ void fill_boundary_rows(const Params &p, unsigned lon
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
         const int j = (int)(i % (size_t)p.M);
         const int k = (int)((i / (size_t)p.M) % (size_t)p.nbands);
-        const SweepRange r = sweep_range(p, k * kBandRows, k * kBandRows);
+        const int b = (int)(i / ((size_t)p.M * (size_t)p.nbands));
+        const SweepRange r = sweep_range(p, k * kBandRows, k * kBandRows, pair_len_lane(p.x_len, b, p.N),
+                                         pair_len_lane(p.y_len, b, p.M));
         const int first = reverse ? kBlk * r.lo : kBlk * r.lo - (kBandRows - 1);
         const int last = reverse ? kBlk * r.hi + kBlk - 1 : kBlk * r.hi - kBlk;
-        rows[i] = (j >= first && j <= last) ? kSentinel : big;
+        rows[i] = (r.hi >= r.lo && j >= first && j <= last) ? kSentinel : big;
     }
 }
 
@@ -237,7 +239,7 @@ __global__ __launch_bounds__(256) void backward_prep_kernel(Params p)
     fill_boundary_rows(p, p.brow_b, true);
     // with a band constraint the sweep never visits the blocks of E outside the window: their
     // "any non-zero" flags are cleared here
-    if (p.window < kNoWindow) {
+    if (p.window < kNoWindow || p.x_len != nullptr || p.y_len != nullptr) {
         const size_t n = (size_t)p.B * p.nrb * p.ncb;
         const size_t stride = (size_t)gridDim.x * blockDim.x;
         for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p.nz[i] = 0;
