@@ -334,6 +334,9 @@ def main():
     traffic = load_traffic(wl.name)
     dom = max(r["kernels"].items(), key=lambda kv: kv[1]["ms_per_step"])
     roof = roofline_for(dom[0], dom[1]["ms_per_launch"], cells, wl.D, traffic.get(dom[0]))
+    if isinstance(roof.get("traffic"), dict):  # HBM bytes per launch (rocprofv3 counters), split kept beside the total
+        roof["traffic_detail"] = roof["traffic"]
+        roof["traffic"] = roof["traffic"]["total_bytes"]
     roof["kernels_ms_per_step"] = {k: round(v["ms_per_step"], 5) for k, v in sorted(r["kernels"].items())}
 
     line = {
