@@ -162,6 +162,19 @@ __device__ __forceinline__ void store_block_acc(float *ring, const floatx16 &acc
     float *rowbase = ring + (32 * rb + 4 * h) * kRingStride;
     const int i0 = row0 + 32 * rb, j0 = 32 * cb;
     const bool inside = (i0 + 32 <= N) && (j0 >= 0) && (j0 + 32 <= M) && (j0 + 31 - i0 <= w) && (i0 + 31 - j0 <= w);
+    // A lane's 16 entries sit at steps sbase + rr + (0..31); within the 128 ring positions they wrap
+    // only in blocks that start in the last phase.  Everywhere else (and inside the grid and the
+    // window) an entry's address is the lane's base plus a constant: nothing to compute per entry.
+    const int phase = (cb + rb) & 3;
+    if (inside && phase != 3) {
+        float *lane_base = rowbase + (32 * phase + c + 4 * h);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int rr = 8 * (i >> 2) + (i & 3);
+            lane_base[rr * kRingStride + rr] = fmaxf(acc[i], 0.0f);
+        }
+        return;
+    }
     const bool col_ok = (unsigned)(j0 + c) < (unsigned)M;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -212,6 +225,15 @@ __device__ __forceinline__ void load_cost_block(float4 (&v)[4], const float *__r
 __device__ __forceinline__ void store_cost_block(float *ring, const float4 (&v)[4], int rb, int cb, int lane)
 {
     const int c4 = (lane & 7) * 4;
+    const int phase = (cb + rb) & 3;
+    if (phase != 3) {  // no entry of the block wraps around the ring: constant offsets from the lane's base
+        float *lane_base = ring + (32 * rb + (lane >> 3)) * kRingStride + 32 * phase + c4 + (lane >> 3);
+#pragma unroll
+        for (int it = 0; it < 4; ++it)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) lane_base[8 * it * kRingStride + 8 * it + e] = comp4(v[it], e);
+        return;
+    }
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
         const int r = (lane >> 3) + 8 * it;
@@ -846,6 +868,9 @@ __device__ __forceinline__ void flush_E_block(const Params &p, const SweepRange 
 {
     if (cb < 0 || cb >= p.ncb || row0 + 32 * rb >= p.N || !block_in_range(rg, rb, cb)) return;
     const int c4 = (lane & 7) * 4, j0 = cb * kBlk;
+    // the block's steps wrap around the ring only when it starts in the ring's last phase
+    const int phase = (cb + rb) & (COLS / kBlk - 1);
+    const bool nowrap = phase != COLS / kBlk - 1;
     bool any = false;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
@@ -854,8 +879,13 @@ __device__ __forceinline__ void flush_E_block(const Params &p, const SweepRange 
         const float *rowp = ring + (32 * rb + r) * STRIDE;
         const int base = 32 * (cb + rb) + c4 + r;
         float v[4];
+        if (nowrap) {  // constant offsets from the lane's position
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = rowp[(base + e) & (COLS - 1)];
+            for (int e = 0; e < 4; ++e) v[e] = rowp[32 * phase + c4 + r + e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = rowp[(base + e) & (COLS - 1)];
+        }
         if (row < p.N) {
             float *q = Eb + (size_t)row * p.M + j0 + c4;
             if (p.vec_m && j0 + c4 + 3 < p.M) {

@@ -138,6 +138,50 @@ template <int V> __global__ __launch_bounds__(192) void dp_step_mem_kernel(doubl
     if (left == 12345.678) table[0] = left;
 }
 
+// Does matrix-core work of another wavefront on the same SIMD slow the DP step down?  Wavefronts 0-3
+// of a workgroup (one per SIMD) run the DP step; wavefronts 4-7 (same SIMDs) run `mfma_per_32_steps`
+// dependent v_mfma_f32_32x32x16_f16 per 32 steps' worth of iterations (0: they only exist), or, with
+// FP32_PARTNER, a chain of float32 additions instead of the DP step.
+template <bool FP32_PARTNER> __global__ __launch_bounds__(512) void coexec_kernel(double *out, int iters, int mfma_per_iter, double c2d)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    if (w >= 4) {
+        sdtw::half8 a, b;
+        for (int i = 0; i < 8; ++i) { a[i] = (_Float16)(0.001f * (lane + i)); b[i] = (_Float16)(0.002f * (lane - i)); }
+        sdtw::floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int it = 0; it < iters; ++it)
+            for (int m = 0; m < mfma_per_iter; ++m) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc, 0, 0, 0);
+        if (acc[0] == 12345.678f) out[1] = acc[3];
+        return;
+    }
+    if (FP32_PARTNER) {
+        float f = lane * 1e-3f, g = 1.0001f;
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int u = 0; u < 32 * 19; ++u) asm volatile("v_add_f32 %0, %0, %1" : "+v"(f) : "v"(g));
+        }
+        if (f == 12345.678f) out[0] = f;
+        return;
+    }
+    double left = sdtw::kBig, diag = lane == 0 ? 0.0 : sdtw::kBig;
+    float dc[8];
+    for (int i = 0; i < 8; ++i) dc[i] = 0.25f * ((lane * 7 + i * 3) & 15) + 0.5f;
+    const double top = 3.0 + lane;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 32; ++u) {
+            const double up = sdtw::lane_shr1(left, top);
+            double m;
+            float L;
+            sdtw::softmin3_parts(diag, up, left, m, L);
+            const double cur = fma((double)dc[u & 7], c2d, m) - (double)L;
+            diag = up;
+            left = cur;
+        }
+    }
+    if (left == 12345.678) out[0] = left;
+}
+
 static float timed(void (*launch)(int, int, double *), int waves_per_simd, int iters, double *d)
 {
     hipEvent_t e0, e1;
@@ -157,6 +201,8 @@ static float timed(void (*launch)(int, int, double *), int waves_per_simd, int i
 template <int OP> static void launch_rate(int w, int iters, double *d) { rate_kernel<OP><<<256, 256 * w>>>(d, iters); }
 template <int OP> static void launch_lat(int, int iters, double *d) { latency_kernel<OP><<<256, 256>>>(d, iters); }
 static void launch_dp(int w, int iters, double *d) { dp_step_kernel<<<256, 256 * w>>>(d, iters, 14.4); }
+static int g_mfma = 0;
+template <bool F> static void launch_coexec(int, int iters, double *d) { coexec_kernel<F><<<256, 512>>>(d, iters, g_mfma, 14.4); }
 static double *g_table = nullptr;
 template <int V> static void launch_mem(int, int iters, double *) { dp_step_mem_kernel<V><<<256, 192>>>(g_table, iters, 14.4); }
 
@@ -188,6 +234,14 @@ int main()
     for (int w = 1; w <= 4; w *= 2) {
         const double cyc = timed(launch_dp, w, iters, d) * 1e-3 * ghz * 1e9 / ((double)iters * 32);
         printf("  %d wavefront(s) per SIMD: %.1f per step of one wavefront, %.1f per step per SIMD\n", w, cyc, cyc / w);
+        fflush(stdout);
+    }
+    printf("DP step of one wavefront with a matrix-core wavefront on the same SIMD (v_mfma_f32_32x32x16_f16 per 32 steps):\n");
+    for (int m : {0, 12, 24, 48, 96}) {
+        g_mfma = m;
+        const double dp = timed(launch_coexec<false>, 1, iters / 4, d) * 1e-3 * ghz * 1e9 / ((double)(iters / 4) * 32);
+        const double f32 = timed(launch_coexec<true>, 1, iters / 4, d) * 1e-3 * ghz * 1e9 / ((double)(iters / 4) * 32);
+        printf("  %3d MFMA per 32 steps: DP step %.1f cycles; 19 dependent float32 additions instead: %.1f cycles\n", m, dp, f32);
         fflush(stdout);
     }
     CHECK(hipMalloc(&g_table, (size_t)256 * 4 * 32 * 64 * sizeof(double)));
