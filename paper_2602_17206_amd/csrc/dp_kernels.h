@@ -7,13 +7,14 @@
 // value one step earlier, so the dependent chain never leaves the registers.  Steps come in
 // macro-steps of 32.
 //
-// Workgroup.  512 threads = 8 wavefronts = 4 bands (the same band index of 4 consecutive pairs):
-// per band one consumer (the DP chain, pure VALU) and one PRODUCER that prepares the cost blocks
-// of the next macro-step in LDS - on the fp32 matrix cores in fused mode, by copying from the
-// stored cost tensor in unfused mode.  The matrix cores only run concurrently with VALU work of a
-// DIFFERENT wavefront on the same SIMD, so the roles are separate wavefronts and the two
-// wavefronts that share a SIMD are paired (elected at run time from the hardware SIMD id; any
-// pairing is correct, this one is fast).  One workgroup barrier per macro-step keeps them in step.
+// Workgroup (large problems).  4 bands (the same band index of 4 consecutive pairs): per band one
+// consumer (the DP chain, pure VALU) and one or two PRODUCERS that prepare the cost blocks of the
+// next macro-step in LDS - on the matrix cores in fused mode, by copying from the stored cost
+// tensor in unfused mode.  The roles are separate wavefronts, so that the producers' loads and
+// their latency never sit in the consumer's instruction stream; the wavefronts of a band are
+// placed on one SIMD (elected at run time from the hardware SIMD id; any placement is correct,
+// this one keeps one consumer per SIMD).  One workgroup barrier per macro-step keeps them in step.
+// Small problems use one band, or two consecutive bands of a pair, per workgroup (see below).
 //
 // Cells outside the N x M grid are not masked.  They are fed a huge finite cost (kBigCost) and the
 // table boundary is a huge finite value (kBig) instead of +inf: a cell whose three neighbours are
@@ -270,9 +271,9 @@ template <int DIR> __device__ __forceinline__ int blk_cb(int sg, int which)
 
 // Matrix-core producer for D <= 16*KG (KG = 1, 2, 4, 8 groups of 16 features).
 //
-// The inner products run on the fp16 matrix cores (v_mfma_f32_32x32x16_f16, float32 accumulate),
-// which - unlike the fp32 MFMA, which shares the vector ALUs - execute beside the consumer's VALU
-// work.  Float32 accuracy is kept by the split-half copies the prep kernel made: each scaled
+// The inner products run on the fp16 matrix cores (v_mfma_f32_32x32x16_f16, float32 accumulate:
+// 16 features per pass against 2 for the float32 matrix instruction, so three of them cost far
+// less).  Float32 accuracy is kept by the split-half copies the prep kernel made: each scaled
 // element is h1 + h2 (two float16), and <x_i,y_j> = (h1.k1 + h1.k2 + h2.k1) / (s_i s_j) up to
 // ~2^-22 relative (Sec. 4.3 Eq. 8 supplies the norms; they are added in float32 afterwards).
 // Lane (r = lane&31, h = lane>>5) holds features 16g+8h .. 16g+8h+7 of its row for group g; the
