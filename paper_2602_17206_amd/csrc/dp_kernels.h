@@ -1021,13 +1021,16 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
 
     float *Eb = p.E + (size_t)bb * N * M;
     unsigned char *nzb = p.nz + (size_t)bb * p.nrb * p.ncb;
-    constexpr bool kProducerFlush = !dp_recompute(KCH, SLOTS) && !TSWEEP;
+    // Who writes the finished E blocks out: the producer, whose loads and stores then wait beside the
+    // consumer's chain instead of in it (measured with recomputation at the L = 8192 shape: 6.3 -> 5.3 ms
+    // at D = 16, 6.5 -> 6.1 ms at D = 64) - except where the producer has no registers left for it
+    // (recomputation with D > 64: the x pieces fill them, the flush would spill).
+    constexpr bool kProducerFlush = !TSWEEP && !(dp_recompute(KCH, SLOTS) && KCH > 4);
 
     if (producer) {
         // Besides the cost blocks, the producers write out the E blocks the consumer finished in the
         // previous macro-step `done`: (upper rows, done) and (lower rows, done-1).  Each producer
         // touches only the rows it owns and flushes before it overwrites the same ring phase.
-        // (With recomputation the producer is the busier side, so there the consumer keeps this job.)
         auto flush = [&](int done, bool upper, bool lower) {
             if constexpr (kProducerFlush) {
                 if (upper) flush_E_block(p, rg, ring, Eb, nzb, 0, done, row0, lane);
