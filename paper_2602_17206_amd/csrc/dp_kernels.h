@@ -425,13 +425,21 @@ template <int KG, int DIR, int W0, int NW> struct HalfProducer {
 // LDS column stride 512+16 bytes: the 16-byte operand reads of 8 consecutive columns hit all banks.
 // ---------------------------------------------------------------------------------------------
 template <int KG> constexpr int cost_col_halfs() { return 32 * KG + 8; }
+// floats per row of a wavefront's 32 x (32*CB) output tile while it waits in LDS to be stored row by row
+template <int CB> constexpr int cost_stage_stride() { return 32 * CB + 4; }
+template <int KG, int CB> constexpr int cost_lds_bytes()
+{
+    constexpr int operands = 32 * CB * cost_col_halfs<KG>() * 2, stage = 4 * 32 * cost_stage_stride<CB>() * 4;
+    return operands > stage ? operands : stage;
+}
 
 template <int KG, int CB>
 __global__ __launch_bounds__(256) void cost_tensor_half_kernel(Params p)
 {
     constexpr int kCol = cost_col_halfs<KG>();
-    __shared__ __attribute__((aligned(16))) _Float16 ys[32 * CB * kCol];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[cost_lds_bytes<KG, CB>()];
     __shared__ float2 ytab[32 * CB];  // (||y_j||^2, 1/scale_j)
+    _Float16 *ys = reinterpret_cast<_Float16 *>(lds);
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, h = lane >> 5;
     const int b = blockIdx.z;
     const int i0 = blockIdx.y * 128 + w * 32;
@@ -476,34 +484,65 @@ __global__ __launch_bounds__(256) void cost_tensor_half_kernel(Params p)
         }
     }
     __syncthreads();
-    if (!rows_live) return;
 
     float *dst = p.cost + (size_t)b * p.N * p.M;
+    floatx16 acc[CB];
 #pragma unroll
     for (int cbk = 0; cbk < CB; ++cbk) {
-        const int j0 = jbase + cbk * 32;
-        if (j0 >= p.M) break;
-        const int col = j0 + (lane & 31);
         const _Float16 *yc = ys + (cbk * 32 + (lane & 31)) * kCol + 8 * h;
-        floatx16 acc = zero16();
+        acc[cbk] = zero16();
+        if (rows_live && jbase + cbk * 32 < p.M) {
 #pragma unroll
-        for (int g = 0; g < KG; ++g) {
-            const half8 k1 = *reinterpret_cast<const half8 *>(yc + 32 * g);
-            const half8 k2 = *reinterpret_cast<const half8 *>(yc + 32 * g + 16);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0][g], k1, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0][g], k2, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[1][g], k1, acc, 0, 0, 0);
+            for (int g = 0; g < KG; ++g) {
+                const half8 k1 = *reinterpret_cast<const half8 *>(yc + 32 * g);
+                const half8 k2 = *reinterpret_cast<const half8 *>(yc + 32 * g + 16);
+                acc[cbk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0][g], k1, acc[cbk], 0, 0, 0);
+                acc[cbk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0][g], k2, acc[cbk], 0, 0, 0);
+                acc[cbk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[1][g], k1, acc[cbk], 0, 0, 0);
+            }
+            const float2 yt = ytab[cbk * 32 + (lane & 31)];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[cbk][i] = fmaxf(fmaf(acc[cbk][i], m2is_r[i] * yt.y, xn_r[i] + yt.x), 0.0f);
         }
-        const float2 yt = ytab[cbk * 32 + (lane & 31)];
-        if (col < p.M) {
+    }
+    if (!p.vec_m) {  // rows of the tensor are not 16-byte aligned: element stores straight from the accumulators
+        if (rows_live) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int row = i0 + acc_row(i, lane);
-                if (row < p.N)
-                    __builtin_nontemporal_store(fmaxf(fmaf(acc[i], m2is_r[i] * yt.y, xn_r[i] + yt.x), 0.0f),
-                                                &dst[(size_t)row * p.M + col]);
+            for (int cbk = 0; cbk < CB; ++cbk) {
+                const int col = jbase + cbk * 32 + (lane & 31);
+                if (col < p.M) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int row = i0 + acc_row(i, lane);
+                        if (row < p.N) __builtin_nontemporal_store(acc[cbk][i], &dst[(size_t)row * p.M + col]);
+                    }
+                }
             }
         }
+        return;
+    }
+    // An accumulator holds one column of 16 rows per lane; stored like that, an instruction touches 32
+    // rows with 4 bytes each.  The wavefront's 32 x (32*CB) tile goes through LDS instead (the operand
+    // area, once every wavefront has finished reading it) and leaves as whole rows, 16 bytes per lane.
+    __syncthreads();
+    constexpr int kStage = cost_stage_stride<CB>();
+    float *stage = reinterpret_cast<float *>(lds) + w * (32 * kStage);
+#pragma unroll
+    for (int cbk = 0; cbk < CB; ++cbk)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) stage[acc_row(i, lane) * kStage + cbk * 32 + (lane & 31)] = acc[cbk][i];
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    if (!rows_live) return;
+    constexpr int kVecPerRow = 8 * CB;  // float4 per tile row
+#pragma unroll
+    for (int k = 0; k < (32 * kVecPerRow) / 64; ++k) {
+        const int idx = k * 64 + lane;
+        const int r = idx / kVecPerRow, c4 = (idx % kVecPerRow) * 4;
+        typedef float floatx4 __attribute__((ext_vector_type(4)));
+        const floatx4 v = *reinterpret_cast<const floatx4 *>(stage + r * kStage + c4);
+        const int row = i0 + r, col = jbase + c4;
+        if (row < p.N && col < p.M)
+            __builtin_nontemporal_store(v, reinterpret_cast<floatx4 *>(&dst[(size_t)row * p.M + col]));
     }
 }
 
