@@ -77,7 +77,8 @@ typedef struct sdtw_desc {
     int32_t bandwidth;      /* 0: no band constraint (as in the paper's Sec. 5).  w > 0: Algorithm 1's
                                `bandwidth`, read as the Sakoe-Chiba band: only cells with |i-j| <= w
                                (0-based i, j) belong to the grid; the others have cost +inf, E = 0.
-                               Needs w >= |N-M| so that the last cell is inside.  With per-pair
+                               Needs w >= |N-M| so that the last cell is inside; w >= max(N,M)
+                               constrains nothing and is the same as 0.  With per-pair
                                lengths every pair needs |x_len[b]-y_len[b]| <= w, which the device
                                does not check: such a pair's value and gradients are undefined.  The
                                sweeps skip the macro-steps outside the band. */

@@ -61,14 +61,21 @@ bool desc_ok(const sdtw_desc *d, int *why)
     return true;
 }
 
+// A band at least as wide as the grid constrains nothing: treated as no band at all.
+int32_t effective_window(const sdtw_desc *d)
+{
+    return (d->bandwidth > 0 && d->bandwidth < std::max(d->N, d->M)) ? d->bandwidth : kNoWindow;
+}
+
 // Bands of one pair that have work at the same time.  Without a band constraint all of them; with
 // |i-j| <= w a band runs (2w+129)/32 + 2 macro-steps and the band below it starts 5 macro-steps
 // after it (its window begins 64 columns further right), so only a few overlap.
 int64_t busy_bands(const sdtw_desc *d)
 {
     const int64_t nbands = (d->N + kBandRows - 1) / kBandRows;
-    if (d->bandwidth <= 0) return nbands;
-    const int64_t run = (2 * (int64_t)d->bandwidth + 2 * kBandRows + 1) / kBlk + 2;
+    const int32_t w = effective_window(d);
+    if (w >= kNoWindow) return nbands;
+    const int64_t run = (2 * (int64_t)w + 2 * kBandRows + 1) / kBlk + 2;
     return std::min<int64_t>(nbands, run / 5 + 2);
 }
 
@@ -78,7 +85,7 @@ int64_t busy_bands(const sdtw_desc *d)
 bool small_problem(const sdtw_desc *d)
 {
     if (g_force_slots) return g_force_slots != 4;
-    return (int64_t)d->B * busy_bands(d) <= (d->bandwidth > 0 ? 640 : 1024);
+    return (int64_t)d->B * busy_bands(d) <= (effective_window(d) < kNoWindow ? 640 : 1024);
 }
 
 Layout layout_of(const sdtw_desc *d)
@@ -87,7 +94,7 @@ Layout layout_of(const sdtw_desc *d)
     const bool recompute = d->mode == SDTW_FUSED && !small;  // == dp_recompute(KCH >= 0, SLOTS == 4)
     const bool two_sweep = small && !(d->flags & SDTW_FLAG_VALUE_ONLY);
     return make_layout(d->B, d->N, d->M, d->D, d->mode, d->x_batch_stride == 0, d->y_batch_stride == 0, recompute,
-                       two_sweep, d->bandwidth > 0 ? d->bandwidth : kNoWindow);
+                       two_sweep, effective_window(d));
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -98,7 +105,7 @@ Params make_params(const sdtw_desc *d, const Layout &L, const float *x, const fl
     Params p{};
     p.x_len = x_len;
     p.y_len = y_len;
-    p.window = d->bandwidth > 0 ? d->bandwidth : kNoWindow;
+    p.window = effective_window(d);
     char *base = static_cast<char *>(ws);
     p.B = d->B; p.N = d->N; p.M = d->M; p.D = d->D; p.mode = d->mode;
     p.nbands = L.nbands; p.nmacro = L.nmacro; p.nrb = L.nrb; p.ncb = L.ncb;
@@ -171,7 +178,7 @@ void launch_dp_kch(const sdtw_desc *d, const Layout &L, const Params &p, float *
         const bool light = d->mode == SDTW_UNFUSED || d->D <= 64;
         const bool roomy = (int64_t)d->B * ((busy_bands(d) + 1) / 2) * (L.two_sweep ? 2 : 1) <= 256;
         // (under a band constraint the chain of band hops is all there is: chaining pays there too, 3-4 %)
-        const bool chained = g_force_slots ? g_force_slots == 2 : (L.nbands >= 2 && (light || d->bandwidth > 0) && roomy);
+        const bool chained = g_force_slots ? g_force_slots == 2 : (L.nbands >= 2 && (light || effective_window(d) < kNoWindow) && roomy);
         if constexpr (FWD) {
             if (chained) {
                 const unsigned tasks = (unsigned)d->B * (unsigned)((L.nbands + 1) / 2);
