@@ -971,9 +971,9 @@ __device__ __forceinline__ void zero_E_block(const Params &p, float *__restrict_
 // restricted to [cb_first, cb_last].
 __device__ __forceinline__ void zero_fringe(const Params &p, const SweepRange &rg, float *__restrict__ Eb,
                                             unsigned char *__restrict__ nzb, int row0, int lane, int cb_first,
-                                            int cb_last)
+                                            int cb_last, bool narrowed = false)
 {
-    if ((p.window >= kNoWindow && p.x_len == nullptr && p.y_len == nullptr) || rg.hi < rg.lo) return;
+    if ((p.window >= kNoWindow && p.x_len == nullptr && p.y_len == nullptr && !narrowed) || rg.hi < rg.lo) return;
     const int w0 = max((rg.lo - 1) & ~1, cb_first), w1 = min(min(rg.hi_u - 1, rg.cb_last) | 1, cb_last);
     for (int cb = w0; cb <= w1; ++cb)
         for (int rb = 0; rb < 2; ++rb)
@@ -1371,6 +1371,52 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
 // ---------------------------------------------------------------------------------------------
 constexpr int kAlignRingCols = 64, kAlignRingStride = 65;
 
+// Which columns of band k can hold a non-zero E (in float32)?  Every alignment path through a cell
+// (i,j) of the band enters the band at a column <= j and leaves it at a column >= j, so
+//   E[i,j] <= P(enter at a column <= j)  and  E[i,j] <= P(leave at a column >= j).
+// Both probabilities follow from the boundary rows the two sweeps left behind: the path's first
+// cell in row r+1 is (r+1,j) with probability
+//   2^(R[N,M] - T[r+1,j] - softmin2(R[r,j], R[r,j-1]))          (r = the last row of the band above),
+// and its last cell in row r is (r,j) with probability
+//   2^(R[N,M] - R[r,j] - softmin2(T[r+1,j], T[r+1,j+1]))        (r = the band's own last row),
+// in table units, softmin2 >= min - 1.  With thr = -(156 + log2 M) every column left of the first one
+// whose entering term exceeds thr has E < M * 2^thr, which float32 cannot tell from 0, and likewise
+// right of the last column whose leaving term exceeds thr.  Returns that column range (the whole row
+// for the first band's left end and for the right end of the band that holds the pair's last row).
+__device__ __forceinline__ void live_columns(const Params &p, int b, int k, int Nl, int Ml, double Rfin, int lane,
+                                             int &first, int &last)
+{
+    const double thr = -(157.0 + (double)(32 - __builtin_clz((unsigned)p.M)));
+    auto row = [&](const unsigned long long *rows, int band, int j) {
+        return __longlong_as_double((long long)rows[((size_t)b * p.nbands + band) * p.M + j]);
+    };
+    first = 0;
+    if (k > 0) {
+        int f = Ml;
+        for (int j = lane; j < Ml; j += kBandRows) {
+            const double ra = row(p.brow, k - 1, j), rb = j > 0 ? row(p.brow, k - 1, j - 1) : kBig;
+            const double term = (Rfin - row(p.brow_b, k, j)) - min_f64(ra, rb) + 1.0;
+            if (term > thr) f = min(f, j);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) f = min(f, __shfl_xor(f, o));
+        first = f;
+    }
+    last = Ml - 1;
+    if (k != (Nl - 1) / kBandRows && k + 1 < p.nbands) {
+        int l = -1;
+        for (int j = lane; j < Ml; j += kBandRows) {
+            const double ta = row(p.brow_b, k + 1, j), tb = j + 1 < Ml ? row(p.brow_b, k + 1, j + 1) : kBig;
+            const double term = (Rfin - row(p.brow, k, j)) - min_f64(ta, tb) + 1.0;
+            if (term > thr) l = max(l, j);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) l = max(l, __shfl_xor(l, o));
+        last = l;
+    }
+}
+
+template <bool LOOK_FIRST>  // find the columns that can hold a non-zero E before reading the tables
 __global__ __launch_bounds__(64) void alignment_kernel(Params p, int seg_blocks)
 {
     __shared__ float ring[kBandRows * kAlignRingStride];
@@ -1398,8 +1444,28 @@ __global__ __launch_bounds__(64) void alignment_kernel(Params p, int seg_blocks)
     // With a band constraint only macro-steps rg.lo .. rg.hi of the tables exist.  The blocks of the
     // run that the sweeps did not cover are outside the window: flags cleared, and zeros written
     // where the gradient kernels may still read them (zero_fringe).
-    const SweepRange rg = sweep_range(p, row0, row0, pair_len(p.x_len, b, p.N), pair_len(p.y_len, b, p.M));
-    if (p.window < kNoWindow || p.x_len != nullptr || p.y_len != nullptr) {
+    const int Nl = pair_len(p.x_len, b, p.N), Ml = pair_len(p.y_len, b, p.M);
+    SweepRange rg = sweep_range(p, row0, row0, Nl, Ml);
+    // ... and of those, only the blocks between the first and the last column that can hold a
+    // non-zero E are formed; the rest is zero without looking (most of the grid when gamma is small).
+    // (Looking costs one pass over four boundary rows before the first table row can be asked for:
+    // worth it from 16 column blocks on - 138 -> 40 us at N = M = 1024, B = 32 - not at 8.
+    // The host asks for it from 16 column blocks on.)
+    if constexpr (LOOK_FIRST) {
+        if (rg.hi >= rg.lo) {
+            int first, last;
+            live_columns(p, b, k, Nl, Ml, Rfin, lane, first, last);
+            first = __builtin_amdgcn_readfirstlane(first);  // the same in every lane: keep them scalar
+            last = __builtin_amdgcn_readfirstlane(last);
+            if (first <= last) {
+                rg.lo = max(rg.lo, first / kBlk);
+                rg.hi = min(rg.hi, last / kBlk + 2);
+                rg.hi_u = min(rg.hi_u, last / kBlk + 2);
+                rg.cb_last = min(rg.cb_last, last / kBlk);
+            }
+        }
+    }
+    if (LOOK_FIRST || p.window < kNoWindow || p.x_len != nullptr || p.y_len != nullptr) {
         const bool none = rg.hi < rg.lo;
         const int w0 = none ? 1 : ((rg.lo - 1) & ~1), w1 = none ? 0 : (min(rg.hi_u - 1, rg.cb_last) | 1);
         for (int cb = cb0 + lane; cb < cb1; cb += kBandRows) {
@@ -1408,7 +1474,7 @@ __global__ __launch_bounds__(64) void alignment_kernel(Params p, int seg_blocks)
                 if (row0 + kBlk < p.N) nzb[(size_t)(row0 / kBlk + 1) * p.ncb + cb] = 0;
             }
         }
-        zero_fringe(p, rg, Eb, nzb, row0, lane, cb0, cb1 - 1);
+        zero_fringe(p, rg, Eb, nzb, row0, lane, cb0, cb1 - 1, LOOK_FIRST);
     }
     const int g_first = max(cb0, rg.lo);
     const int g_end = min(min(cb1 + 2, p.nmacro), rg.hi + 1);  // macro-steps [g_first, g_end) hold every cell of the run

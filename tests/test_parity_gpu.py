@@ -159,6 +159,25 @@ def test_all_workgroup_shapes(shape, mode, B, N, M, D, gamma):
     check_against(ref, got, what="shape %d %s" % (shape, mode))
 
 
+@pytest.mark.parametrize("mode", ["unfused", "fused"])
+@pytest.mark.parametrize("gamma", [0.01, 1.0, 50.0])
+@pytest.mark.parametrize("kind", ["normal", "walk"])
+def test_alignment_only_looks_where_E_can_be_non_zero(mode, gamma, kind):
+    # 600 x 700: from 16 column blocks on the backward call of small problems first finds, per band,
+    # the columns that can hold a non-zero E (from the boundary rows) and forms E only there.  Sparse
+    # E (small gamma), dense E (gamma = 50: every cell non-zero) and both input recipes; E is compared
+    # everywhere, so a block wrongly taken for zero would show.
+    B, N, M, D = 3, 600, 700, 12
+    x, y = (workloads.normal_pairs if kind == "normal" else workloads.walk_pairs)(77, B, N, M, D)
+    say("alignment pruning %s gamma=%g %s" % (mode, gamma, kind))
+    ref = oracle.batch(x, y, gamma, want_E=True)
+    got = run_gpu(x, y, gamma, MODES[mode])
+    check_against(ref, got, what="alignment pruning %s gamma=%g %s" % (mode, gamma, kind))
+    # float32 cannot hold anything the pruning may have dropped: wherever the oracle's E is above the
+    # smallest normal float32 by a margin (the hardware exp2 flushes denormal results), the library's E is non-zero
+    assert (got["E"][ref["E"] > 1e-36] > 0).all()
+
+
 def test_config1_tiny_oracle_case():
     wl = workloads.pair_workload("c1_tiny")
     say("config 1")
