@@ -21,6 +21,25 @@ __device__ __forceinline__ int lane_shl1_i32(int v, int fill)
 {
     return __builtin_amdgcn_update_dpp(fill, v, 0x130, 0xf, 0xf, false);
 }
+// Minimum of a float over the 64 lanes (the same value in every lane's result): row-wise scan with
+// row_shr 1, 2, 4, 8, then lane 15 of a row to the next row (row_bcast:15) and lane 31 to the upper
+// half (row_bcast:31); lane 63 holds the minimum.
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ float dpp_min_step(float v)
+{
+    const int moved = __builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, ROW_MASK, 0xf, false);
+    return fminf(v, __int_as_float(moved));
+}
+__device__ __forceinline__ float wave_min_f32(float v)
+{
+    v = dpp_min_step<0x111, 0xf>(v);
+    v = dpp_min_step<0x112, 0xf>(v);
+    v = dpp_min_step<0x114, 0xf>(v);
+    v = dpp_min_step<0x118, 0xf>(v);
+    v = dpp_min_step<0x142, 0xa>(v);
+    v = dpp_min_step<0x143, 0xc>(v);
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
 __device__ __forceinline__ double lane_shr1(double v, double fill)
 {
     int lo = lane_shr1_i32(__double2loint(v), __double2loint(fill));
@@ -142,6 +161,7 @@ __device__ __forceinline__ SweepRange sweep_range(const Params &p, int row_a, in
     if (row_a >= Nl) {
         r.lo = 0;
         r.hi = -1;
+        r.hi_u = -1;
     }
     return r;
 }

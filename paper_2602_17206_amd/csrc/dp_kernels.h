@@ -891,11 +891,11 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
 // E replaces the consumed cost value in the ring; the producers write it out as row-major 32x32
 // blocks, with one flag byte per block saying whether any entry is non-zero.
 // ---------------------------------------------------------------------------------------------
-// With a band constraint the sweep runs macro-steps rg.lo .. rg.hi only.  Block (rb, cb) of the band
-// holds cells of macro-steps cb+rb and cb+rb+1: it is written out if both lie in [rg.lo, rg.hi_u];
-// otherwise none of its cells is inside the window, E is zero there, and the block is either left
-// alone with its flag cleared (nobody reads a block whose flag and whose neighbours' flags are
-// clear) or zeroed by zero_fringe.
+// A sweep may run macro-steps rg.lo .. rg.hi only (band constraint, per-pair lengths, or the columns
+// alignment_kernel found to matter).  Block (rb, cb) of the band holds cells of macro-steps cb+rb and
+// cb+rb+1: it is written out if both lie in [rg.lo, rg.hi_u] and it has a column inside the pair's
+// grid; otherwise E is zero in all of it and the block is left alone with its flag cleared (nobody
+// reads a block whose flag is clear).
 __device__ __forceinline__ bool block_in_range(const SweepRange &rg, int rb, int cb)
 {
     return cb + rb >= rg.lo && cb + rb + 1 <= rg.hi_u && cb <= rg.cb_last;
@@ -911,73 +911,51 @@ __device__ __forceinline__ void flush_E_block(const Params &p, const SweepRange 
     // the block's steps wrap around the ring only when it starts in the ring's last phase
     const int phase = (cb + rb) & (COLS / kBlk - 1);
     const bool nowrap = phase != COLS / kBlk - 1;
-    bool any = false;
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
+    auto read4 = [&](int it, float (&v)[4]) {
         const int r = (lane >> 3) + 8 * it;
-        const int row = row0 + rb * 32 + r;
         const float *rowp = ring + (32 * rb + r) * STRIDE;
-        const int base = 32 * (cb + rb) + c4 + r;
-        float v[4];
         if (nowrap) {  // constant offsets from the lane's position
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] = rowp[32 * phase + c4 + r + e];
         } else {
+            const int base = 32 * (cb + rb) + c4 + r;
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] = rowp[(base + e) & (COLS - 1)];
         }
-        if (row < p.N) {
-            float *q = Eb + (size_t)row * p.M + j0 + c4;
-            if (p.vec_m && j0 + c4 + 3 < p.M) {
-                *reinterpret_cast<float4 *>(q) = make_float4(v[0], v[1], v[2], v[3]);
-                any |= (v[0] != 0.f) | (v[1] != 0.f) | (v[2] != 0.f) | (v[3] != 0.f);
-            } else {
+    };
+    // First: does the block hold a non-zero inside the grid?  If not, only its flag is written: a
+    // block with a clear flag is all zero by definition and is never read (for small gamma that is
+    // almost every block).
+    bool any = false;
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (j0 + c4 + e < p.M) { q[e] = v[e]; any |= v[e] != 0.f; }
-            }
+    for (int it = 0; it < 4; ++it) {
+        float v[4];
+        read4(it, v);
+        const int row = row0 + rb * 32 + (lane >> 3) + 8 * it;
+        if (row < p.N) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) any |= (j0 + c4 + e < p.M) && v[e] != 0.f;
         }
     }
     const bool blk_any = __any(any);
     if (lane == 0) nzb[(size_t)(row0 / kBlk + rb) * p.ncb + cb] = blk_any ? 1 : 0;
-}
-
-__device__ __forceinline__ void zero_E_block(const Params &p, float *__restrict__ Eb, unsigned char *__restrict__ nzb,
-                                             int rb, int cb, int row0, int lane)
-{
-    if (cb < 0 || cb >= p.ncb || row0 + 32 * rb >= p.N) return;
-    const int c4 = (lane & 7) * 4, j0 = cb * kBlk;
+    if (!blk_any) return;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
+        float v[4];
+        read4(it, v);
         const int row = row0 + rb * 32 + (lane >> 3) + 8 * it;
         if (row < p.N) {
             float *q = Eb + (size_t)row * p.M + j0 + c4;
             if (p.vec_m && j0 + c4 + 3 < p.M) {
-                *reinterpret_cast<float4 *>(q) = make_float4(0.f, 0.f, 0.f, 0.f);
+                *reinterpret_cast<float4 *>(q) = make_float4(v[0], v[1], v[2], v[3]);
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    if (j0 + c4 + e < p.M) q[e] = 0.f;
+                    if (j0 + c4 + e < p.M) q[e] = v[e];
             }
         }
     }
-    if (lane == 0) nzb[(size_t)(row0 / kBlk + rb) * p.ncb + cb] = 0;
-}
-
-// The input-gradient kernels read E in chunks of two neighbouring blocks (the two row blocks of a
-// band at one column block; one row block at column blocks 2c and 2c+1) and skip a chunk only when
-// both flags are clear.  So the blocks outside the sweep's range that share a chunk with a block
-// inside it are written as zeros: column blocks (lo-1) & ~1 .. (hi_u-1) | 1 of both row blocks,
-// restricted to [cb_first, cb_last].
-__device__ __forceinline__ void zero_fringe(const Params &p, const SweepRange &rg, float *__restrict__ Eb,
-                                            unsigned char *__restrict__ nzb, int row0, int lane, int cb_first,
-                                            int cb_last, bool narrowed = false)
-{
-    if ((p.window >= kNoWindow && p.x_len == nullptr && p.y_len == nullptr && !narrowed) || rg.hi < rg.lo) return;
-    const int w0 = max((rg.lo - 1) & ~1, cb_first), w1 = min(min(rg.hi_u - 1, rg.cb_last) | 1, cb_last);
-    for (int cb = w0; cb <= w1; ++cb)
-        for (int rb = 0; rb < 2; ++rb)
-            if (!block_in_range(rg, rb, cb)) zero_E_block(p, Eb, nzb, rb, cb, row0, lane);
 }
 
 template <int KCH, int SLOTS, int NPROD>
@@ -1100,7 +1078,6 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
                     __syncthreads();
                 }
                 if (live) flush(rg.lo, upper, !upper);
-                if (live && kProducerFlush && upper) zero_fringe(p, rg, Eb, nzb, row0, lane, 0, p.ncb - 1);
             };
             if (producer == 1) {
                 HalfProducer<KCH, -1, 0, 1> mp;
@@ -1128,7 +1105,6 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
                 __syncthreads();
             }
             if (live) flush(rg.lo, true, true);
-            if (live && kProducerFlush) zero_fringe(p, rg, Eb, nzb, row0, lane, 0, p.ncb - 1);
         } else if constexpr (KCH == 0) {
             if (live) {
                 generic_block(pl, b, ring, 0, sg0 - 1, row0, lane);
@@ -1146,7 +1122,6 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
                 __syncthreads();
             }
             if (live) flush(rg.lo, true, true);
-            if (live && kProducerFlush) zero_fringe(p, rg, Eb, nzb, row0, lane, 0, p.ncb - 1);
         } else {
             const float *cost_b = p.cost + (size_t)bb * N * M;
             float4 pre[2][4];
@@ -1173,7 +1148,6 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
                 __syncthreads();
             }
             if (live) flush(rg.lo, true, true);
-            if (live && kProducerFlush) zero_fringe(p, rg, Eb, nzb, row0, lane, 0, p.ncb - 1);
         }
         return;
     }
@@ -1263,6 +1237,24 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
             const double *Rn = (RECOMP || TSWEEP) ? nullptr : Rk + (size_t)(sg > rg.lo ? sg - 1 : sg) * kBlk * kBandRows;
             double *Qs = TSWEEP ? Qk + (size_t)sg * kBlk * kBandRows : nullptr;
             const int sbase = sg * kBlk;
+            // Can any cell of this macro-step have a non-zero E (in float32)?  Every R of the macro-step
+            // is at least the smallest value entering it (the lanes' forward state at its start, the
+            // row above) minus 32 log2(3), since a cell is its non-negative cost plus a soft-minimum
+            // of its predecessors; likewise every Q = T - d and the reverse state (the lanes' values,
+            // the row below).  If R[N,M] - min R - min Q is far below the smallest float32 exponent,
+            // E is zero throughout: the macro-step only continues T (no recomputation, no exp2).
+            bool dead = false;
+            if constexpr (RECOMP) {
+                float rmin = (float)min_f64(ck_left, ck_diag), qmin = (float)min_f64(right, diag);
+                if (lane < kBlk) {
+                    rmin = fminf(rmin, (float)ftop_next);
+                    qmin = fminf(qmin, (float)bot[lane]);
+                }
+                rmin = wave_min_f32(rmin);
+                qmin = wave_min_f32(qmin);
+                // 157 (float32), 2 x 32 log2(3) = 102, rounding of the two minima to float32 (<= 2 x 16)
+                dead = __builtin_amdgcn_readfirstlane((int)(((double)rmin + (double)qmin > Rfin + 300.0) && sg != sg_corner)) != 0;
+            }
             if constexpr (RECOMP) {
                 // recompute R of this macro-step from the forward's checkpoint (same arithmetic, same
                 // cost values, hence the same bits the forward had)
@@ -1275,20 +1267,22 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
                     ftop_next = kBig;
                     if (k > 0 && lane < kBlk && jf < M) ftop_next = __builtin_nontemporal_load(&ftop_g[jf]);
                 }
+                if (!dead) {
 #pragma unroll
-                for (int u = 0; u < kBlk; ++u) {
-                    const double up = lane_shr1(fl, ftop[u]);
-                    const float dcf = rd[u];
-                    double mf;
-                    float Lf;
-                    softmin3_parts(fd, up, fl, mf, Lf);
-                    const double cur = fma((double)dcf, c2d, mf) - (double)Lf;
-                    Rq[u] = Rfin - cur;
-                    fd = up;
-                    fl = cur;
+                    for (int u = 0; u < kBlk; ++u) {
+                        const double up = lane_shr1(fl, ftop[u]);
+                        const float dcf = rd[u];
+                        double mf;
+                        float Lf;
+                        softmin3_parts(fd, up, fl, mf, Lf);
+                        const double cur = fma((double)dcf, c2d, mf) - (double)Lf;
+                        Rq[u] = Rfin - cur;
+                        fd = up;
+                        fl = cur;
+                    }
                 }
             }
-            auto steps = [&](auto corner) {
+            auto steps = [&](auto corner, auto alive) {
 #pragma unroll
             for (int u = kBlk - 1; u >= 0; --u) {
                 if (u == kBlk - 1 - kPeekStep && has_below) nxt_bits = peek_boundary(brow_in, jn, need_n);
@@ -1306,9 +1300,13 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
                     cur = fma((double)dc, c2d, q);
                 } else {
                     cur = fma((double)dc, c2d, m) - (double)L;
-                    // log2 E = R[N,M] - R[i,j] - (m - L) in table units
-                    rd[u] = __builtin_amdgcn_exp2f((float)(Rq[u] - m) + L);
-                    if constexpr (!RECOMP) Rq[u] = Rfin - __builtin_nontemporal_load(&Rn[u * kBandRows + lane]);
+                    if constexpr (decltype(alive)::value) {
+                        // log2 E = R[N,M] - R[i,j] - (m - L) in table units
+                        rd[u] = __builtin_amdgcn_exp2f((float)(Rq[u] - m) + L);
+                        if constexpr (!RECOMP) Rq[u] = Rfin - __builtin_nontemporal_load(&Rn[u * kBandRows + lane]);
+                    } else {
+                        rd[u] = 0.0f;
+                    }
                 }
                 my_eo[u] = cur;  // lane 0: value of column 32*sg + u for the band above
                 diag = down;
@@ -1316,9 +1314,11 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
             }
             };
             if (sg == sg_corner)
-                steps(std::true_type{});
+                steps(std::true_type{}, std::true_type{});
+            else if (RECOMP && dead)
+                steps(std::false_type{}, std::false_type{});
             else
-                steps(std::false_type{});
+                steps(std::false_type{}, std::true_type{});
             // first row of the band, columns 32*sg .. 32*sg+31, for the band above
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             if (emit_top && lane < kBlk) {
@@ -1338,9 +1338,6 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
             }
         }
         __syncthreads();
-    }
-    if constexpr (!kProducerFlush && !TSWEEP) {
-        if (live) zero_fringe(p, rg, Eb, nzb, row0, lane, 0, p.ncb - 1);
     }
     };
     if constexpr (SLOTS == 2) {
@@ -1441,9 +1438,8 @@ __global__ __launch_bounds__(64) void alignment_kernel(Params p, int seg_blocks)
     const double *Rk = p.R + band_off, *Qk = p.Q + band_off;
     const double Rfin = p.rfinal[b];
     float *my_ring = ring + lane * kAlignRingStride;
-    // With a band constraint only macro-steps rg.lo .. rg.hi of the tables exist.  The blocks of the
-    // run that the sweeps did not cover are outside the window: flags cleared, and zeros written
-    // where the gradient kernels may still read them (zero_fringe).
+    // With a band constraint (or per-pair lengths) only macro-steps rg.lo .. rg.hi of the tables exist.
+    // The blocks of the run that the sweeps did not cover are outside the window: flags cleared.
     const int Nl = pair_len(p.x_len, b, p.N), Ml = pair_len(p.y_len, b, p.M);
     SweepRange rg = sweep_range(p, row0, row0, Nl, Ml);
     // ... and of those, only the blocks between the first and the last column that can hold a
@@ -1466,15 +1462,10 @@ __global__ __launch_bounds__(64) void alignment_kernel(Params p, int seg_blocks)
         }
     }
     if (LOOK_FIRST || p.window < kNoWindow || p.x_len != nullptr || p.y_len != nullptr) {
-        const bool none = rg.hi < rg.lo;
-        const int w0 = none ? 1 : ((rg.lo - 1) & ~1), w1 = none ? 0 : (min(rg.hi_u - 1, rg.cb_last) | 1);
         for (int cb = cb0 + lane; cb < cb1; cb += kBandRows) {
-            if (cb < w0 || cb > w1) {
-                if (row0 < p.N) nzb[(size_t)(row0 / kBlk) * p.ncb + cb] = 0;
-                if (row0 + kBlk < p.N) nzb[(size_t)(row0 / kBlk + 1) * p.ncb + cb] = 0;
-            }
+            if (row0 < p.N && !block_in_range(rg, 0, cb)) nzb[(size_t)(row0 / kBlk) * p.ncb + cb] = 0;
+            if (row0 + kBlk < p.N && !block_in_range(rg, 1, cb)) nzb[(size_t)(row0 / kBlk + 1) * p.ncb + cb] = 0;
         }
-        zero_fringe(p, rg, Eb, nzb, row0, lane, cb0, cb1 - 1, LOOK_FIRST);
     }
     const int g_first = max(cb0, rg.lo);
     const int g_end = min(min(cb1 + 2, p.nmacro), rg.hi + 1);  // macro-steps [g_first, g_end) hold every cell of the run

@@ -321,21 +321,25 @@ __global__ __launch_bounds__(256) void input_grad_kernel(Params p, const float *
     floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     float msum = 0.f;  // thread (w, lane): partial sum of E over the reduced index for output row m0+lane
 
-    // is any of the two 32x32 E blocks of the chunk at q0 non-zero?
-    auto chunk_live = [&](int q0) {
+    // which of the two 32x32 E blocks of the chunk at q0 have a non-zero?  (bit 0: the first 32 output
+    // positions, bit 1: the other 32.)  A block whose flag is clear is never read: it is all zero by
+    // definition, and nobody may have written it.
+    auto chunk_flags = [&](int q0) {
         const int qb = q0 / kBlk, mb = m0 / kBlk;
-        bool live;
+        int bits;
         if (side == 0) {
-            live = nzb[(size_t)mb * p.ncb + qb] != 0;
-            if (mb + 1 < p.nrb) live |= nzb[(size_t)(mb + 1) * p.ncb + qb] != 0;
+            bits = nzb[(size_t)mb * p.ncb + qb] != 0 ? 1 : 0;
+            if (mb + 1 < p.nrb && nzb[(size_t)(mb + 1) * p.ncb + qb] != 0) bits |= 2;
         } else {
-            live = nzb[(size_t)qb * p.ncb + mb] != 0;
-            if (mb + 1 < p.ncb) live |= nzb[(size_t)qb * p.ncb + mb + 1] != 0;
+            bits = nzb[(size_t)qb * p.ncb + mb] != 0 ? 1 : 0;
+            if (mb + 1 < p.ncb && nzb[(size_t)qb * p.ncb + mb + 1] != 0) bits |= 2;
         }
-        return live;
+        return bits;
     };
+    int live_bits = 0;  // flags of the chunk next_live stopped at
     auto next_live = [&](int q0) {
-        while (q0 < Ql && !chunk_live(q0)) q0 += kBlk;
+        live_bits = 0;
+        while (q0 < Ql && (live_bits = chunk_flags(q0)) == 0) q0 += kBlk;
         return q0;
     };
     auto load4 = [](const float *q, int first, int limit, bool vec) {
@@ -356,16 +360,17 @@ __global__ __launch_bounds__(256) void input_grad_kernel(Params p, const float *
     //   side 1: E rows i = q0+k (32), columns j = m0+m (64): element e -> k = e/16, m = 4*(e%16)
     float4 ra[2], rb[2];
     auto fetch = [&](int q0) {
+        const int bits = live_bits;
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
             const int e = tid + 256 * r;
             ra[r] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (side == 0) {
-                const int i = m0 + (e >> 3), k4 = (e & 7) * 4;
-                if (i < p.N) ra[r] = load4(Eb + (size_t)i * p.M + q0 + k4, q0 + k4, p.M, p.vec_m != 0);
+                const int i = m0 + (e >> 3), k4 = (e & 7) * 4;  // rows m0 .. m0+31 for r = 0, the other 32 for r = 1
+                if (i < p.N && ((bits >> r) & 1)) ra[r] = load4(Eb + (size_t)i * p.M + q0 + k4, q0 + k4, p.M, p.vec_m != 0);
             } else {
-                const int i = q0 + (e >> 4), m4 = (e & 15) * 4;
-                if (i < p.N) ra[r] = load4(Eb + (size_t)i * p.M + m0 + m4, m0 + m4, p.M, p.vec_m != 0);
+                const int i = q0 + (e >> 4), m4 = (e & 15) * 4;  // columns m0 .. m0+31 for m4 < 32
+                if (i < p.N && ((bits >> (m4 >> 5)) & 1)) ra[r] = load4(Eb + (size_t)i * p.M + m0 + m4, m0 + m4, p.M, p.vec_m != 0);
             }
             const int q = q0 + (e >> 4), n4 = (e & 15) * 4;
             rb[r] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -506,18 +511,20 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
     const floatx16 zero = acc;
     float msum = 0.f;  // partial sum of E over the reduced index for one output row (which: see stash)
 
-    // is any of the two 32x32 E blocks of the chunk at q0 non-zero?
-    auto chunk_live = [&](int q0) {
+    // which of the two 32x32 E blocks of the chunk at q0 have a non-zero?  (bit 0: the first 32 output
+    // positions, bit 1: the other 32.)  A block whose flag is clear is never read: it is all zero by
+    // definition, and nobody may have written it.
+    auto chunk_flags = [&](int q0) {
         const int qb = q0 / kBlk, mb = m0 / kBlk;
-        bool live;
+        unsigned bits;
         if (side == 0) {
-            live = nzb[(size_t)mb * p.ncb + qb] != 0;
-            if (mb + 1 < p.nrb) live |= nzb[(size_t)(mb + 1) * p.ncb + qb] != 0;
+            bits = nzb[(size_t)mb * p.ncb + qb] != 0 ? 1u : 0u;
+            if (mb + 1 < p.nrb && nzb[(size_t)(mb + 1) * p.ncb + qb] != 0) bits |= 2u;
         } else {
-            live = nzb[(size_t)qb * p.ncb + mb] != 0;
-            if (mb + 1 < p.ncb) live |= nzb[(size_t)qb * p.ncb + mb + 1] != 0;
+            bits = nzb[(size_t)qb * p.ncb + mb] != 0 ? 1u : 0u;
+            if (mb + 1 < p.ncb && nzb[(size_t)qb * p.ncb + mb + 1] != 0) bits |= 2u;
         }
-        return live;
+        return bits;
     };
 
     // Per thread and chunk: 8 values of E and 8 of the reduced sequence, each run along the reduced
@@ -527,13 +534,16 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
     //   sequence rows q0+k, features n0+n:      n = tid%64, k = 8*(tid/64) .. +7
     const int am = side == 0 ? (tid >> 2) : lane, ak = side == 0 ? (tid & 3) * 8 : w * 8;
     const int bn = lane, bk = w * 8;
-    auto fetch = [&](int q0, float (&ea)[8], float (&bv)[8], float &ismax) {
+    // (a list entry is the chunk's first reduced position with the two block flags in bits 30 and 31)
+    auto fetch = [&](int entry, float (&ea)[8], float (&bv)[8], float &ismax) {
+        const int q0 = entry & 0x3FFFFFFF;
+        const bool blk_live = (((unsigned)entry >> (30 + (am >> 5))) & 1u) != 0;  // the block this thread's output position is in
         ismax = chunk_ismax(q0);
         if (side == 0) {
             const int i = m0 + am;
 #pragma unroll
             for (int c = 0; c < 8; ++c) ea[c] = 0.f;
-            if (i < p.N) {
+            if (i < p.N && blk_live) {
                 const float *q = Eb + (size_t)i * p.M + q0 + ak;
                 if (p.vec_m && q0 + ak + 7 < p.M) {
                     const float4 t0 = *reinterpret_cast<const float4 *>(q), t1 = *reinterpret_cast<const float4 *>(q + 4);
@@ -549,7 +559,7 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
                 const int i = q0 + ak + c;
-                ea[c] = (i < p.N && j < p.M) ? Eb[(size_t)i * p.M + j] : 0.f;
+                ea[c] = (i < p.N && j < p.M && blk_live) ? Eb[(size_t)i * p.M + j] : 0.f;
             }
         }
         const int n = n0 + bn;
@@ -613,7 +623,8 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
         int nlive = 0;
         for (int g = base, round = 0; g < lim; g += 256, ++round) {
             const int c = g + tid;
-            const bool lv = c < lim && chunk_live(c * kBlk);
+            const unsigned bits = c < lim ? chunk_flags(c * kBlk) : 0u;
+            const bool lv = bits != 0;
             const unsigned long long m = __ballot(lv);
             if (lane == 0) wave_mask[round & 1][w] = m;
             __syncthreads();
@@ -624,7 +635,7 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
                 if (ww < w) off += cnt;
                 total += cnt;
             }
-            if (lv) live_list[off + __popcll(m & ((1ull << lane) - 1ull))] = c * kBlk;
+            if (lv) live_list[off + __popcll(m & ((1ull << lane) - 1ull))] = (int)((unsigned)(c * kBlk) | (bits << 30));
             nlive += total;
         }
         __syncthreads();
