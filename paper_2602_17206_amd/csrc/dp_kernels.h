@@ -555,6 +555,7 @@ template <int SLOTS> struct WgShared {
     double ftop[SLOTS][kBlk];     // backward with recomputation: the forward's row above the band
     float2 rowtab[SLOTS][kBandRows];  // per band row: (||x_r||^2, -2/scale_r) for the cost epilogue
     int simd_count[4];
+    int blk_dead[SLOTS][2];  // reverse sweep: the E blocks completed by macro-step sg hold no non-zero (indexed by sg & 1)
 };
 
 // Values the band's edge row (last row in the forward sweep, first in the reverse sweep) produced
@@ -904,9 +905,13 @@ __device__ __forceinline__ bool block_in_range(const SweepRange &rg, int rb, int
 template <int COLS = kRingCols, int STRIDE = kRingStride>
 __device__ __forceinline__ void flush_E_block(const Params &p, const SweepRange &rg, const float *ring,
                                               float *__restrict__ Eb, unsigned char *__restrict__ nzb, int rb, int cb,
-                                              int row0, int lane)
+                                              int row0, int lane, bool known_zero = false)
 {
     if (cb < 0 || cb >= p.ncb || row0 + 32 * rb >= p.N || !block_in_range(rg, rb, cb)) return;
+    if (known_zero) {  // the consumer found that no cell of the block's two macro-steps can be non-zero
+        if (lane == 0) nzb[(size_t)(row0 / kBlk + rb) * p.ncb + cb] = 0;
+        return;
+    }
     const int c4 = (lane & 7) * 4, j0 = cb * kBlk;
     // the block's steps wrap around the ring only when it starts in the ring's last phase
     const int phase = (cb + rb) & (COLS / kBlk - 1);
@@ -1050,8 +1055,9 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
         // touches only the rows it owns and flushes before it overwrites the same ring phase.
         auto flush = [&](int done, bool upper, bool lower) {
             if constexpr (kProducerFlush) {
-                if (upper) flush_E_block(p, rg, ring, Eb, nzb, 0, done, row0, lane);
-                if (lower) flush_E_block(p, rg, ring, Eb, nzb, 1, done - 1, row0, lane);
+                const bool dead = sh.blk_dead[slot][done & 1] != 0;  // written by the consumer before the last barrier
+                if (upper) flush_E_block(p, rg, ring, Eb, nzb, 0, done, row0, lane, dead);
+                if (lower) flush_E_block(p, rg, ring, Eb, nzb, 1, done - 1, row0, lane, dead);
             }
         };
         // blocks the first macro-step reads: (upper rows, sg0-1), (lower rows, sg0-1), (lower rows, sg0-2)
@@ -1187,6 +1193,7 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
     double *bot = sh.edge_in[slot];
     double *eo = edge_out[slot];
 
+    bool dead_prev = true;  // the macro-step before the first one: beyond the table, nothing there
     // R of the first macro-step; afterwards each value is reloaded one macro-step ahead, right after use
     double Rq[kBlk];
     double ck_left = kBig, ck_diag = kBig;  // RECOMP: forward lane state at the start of the coming macro-step
@@ -1327,9 +1334,14 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
             }
             // the E blocks this macro-step completed, (upper rows, sg) and (lower rows, sg-1): written
             // out by the producers during the next macro-step, or here
+            // (both hold cells of this macro-step and the one before it only)
+            const bool blocks_dead = dead && dead_prev;
+            dead_prev = dead;
             if constexpr (!kProducerFlush && !TSWEEP) {
-                flush_E_block(p, rg, ring, Eb, nzb, 0, sg, row0, lane);
-                flush_E_block(p, rg, ring, Eb, nzb, 1, sg - 1, row0, lane);
+                flush_E_block(p, rg, ring, Eb, nzb, 0, sg, row0, lane, blocks_dead);
+                flush_E_block(p, rg, ring, Eb, nzb, 1, sg - 1, row0, lane, blocks_dead);
+            } else if constexpr (!TSWEEP) {
+                if (lane == 0) sh.blk_dead[slot][sg & 1] = blocks_dead ? 1 : 0;
             }
             if constexpr (CH != 1) {
                 double bn = kBig;
