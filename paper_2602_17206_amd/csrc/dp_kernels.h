@@ -1399,10 +1399,14 @@ __device__ __forceinline__ void live_columns(const Params &p, int b, int k, int 
     auto row = [&](const unsigned long long *rows, int band, int j) {
         return __longlong_as_double((long long)rows[((size_t)b * p.nbands + band) * p.M + j]);
     };
-    first = 0;
+    // under a band constraint only the columns within the window of the band's rows can matter
+    const int row0 = k * kBandRows;
+    const int jlo = p.window < kNoWindow ? max(0, row0 - p.window - 1) : 0;
+    const int jhi = p.window < kNoWindow ? min(Ml - 1, row0 + kBandRows + p.window) : Ml - 1;
+    first = jlo;
     if (k > 0) {
         int f = Ml;
-        for (int j = lane; j < Ml; j += kBandRows) {
+        for (int j = jlo + lane; j <= jhi; j += kBandRows) {
             const double ra = row(p.brow, k - 1, j), rb = j > 0 ? row(p.brow, k - 1, j - 1) : kBig;
             const double term = (Rfin - row(p.brow_b, k, j)) - min_f64(ra, rb) + 1.0;
             if (term > thr) f = min(f, j);
@@ -1411,10 +1415,10 @@ __device__ __forceinline__ void live_columns(const Params &p, int b, int k, int 
         for (int o = 32; o > 0; o >>= 1) f = min(f, __shfl_xor(f, o));
         first = f;
     }
-    last = Ml - 1;
+    last = jhi;
     if (k != (Nl - 1) / kBandRows && k + 1 < p.nbands) {
         int l = -1;
-        for (int j = lane; j < Ml; j += kBandRows) {
+        for (int j = jlo + lane; j <= jhi; j += kBandRows) {
             const double ta = row(p.brow_b, k + 1, j), tb = j + 1 < Ml ? row(p.brow_b, k + 1, j + 1) : kBig;
             const double term = (Rfin - row(p.brow, k, j)) - min_f64(ta, tb) + 1.0;
             if (term > thr) l = max(l, j);
