@@ -611,10 +611,15 @@ def test_rectangular_large_regime():
     say("rectangular, large regime B=%d N=%d M=%d" % (B, N, M))
     x, y = workloads.normal_pairs(51, B, N, M, D)
     pairs = [0, 17, 39]
-    ref = oracle.batch(x[pairs], y[pairs], gamma)
-    for mode in ("unfused", "fused"):
-        got = run_gpu(x, y, gamma, MODES[mode], want_E=False)
-        check_against(ref, got, pairs=pairs, what="rectangular large " + mode)
+    for gamma in (0.2, 0.01, 20.0):
+        # sparse to dense E: the recomputing backward skips the macro-steps whose E it can prove to be
+        # zero (most of them at gamma = 0.01, none at gamma = 20); E itself is compared everywhere
+        ref = oracle.batch(x[pairs], y[pairs], gamma, want_E=True)
+        for mode in ("unfused", "fused"):
+            got = run_gpu(x, y, gamma, MODES[mode], want_E=True)
+            check_against(ref, got, pairs=pairs, what="rectangular large %s gamma=%g" % (mode, gamma))
+            for r, b in enumerate(pairs):
+                assert (got["E"][b][ref["E"][r] > 1e-36] > 0).all()
 
 
 # ------------------------------------------------------------------------------- benchmark configurations
