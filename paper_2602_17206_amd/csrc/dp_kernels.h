@@ -56,10 +56,11 @@ constexpr int kChainLag = 3;  // macro-steps the second band of a chained pair r
 // write to (see kEdgeOut below)
 constexpr int kHandRing = 4 * kBlk;
 constexpr int kHandDoubles = kHandRing + kBandRows + kBlk;
-// Large fused problems are bound by HBM traffic, of which the float64 table R is the largest part
-// (8 bytes per cell written, 8 read).  There the forward keeps only the lane state at the start of
-// every macro-step (1/16 of R) and the backward recomputes each macro-step of R before it uses it.
-constexpr bool dp_recompute(int kch, int slots) { return kch >= 0 && slots == 4; }
+// Large problems (the 4-band workgroups) are bound by HBM traffic, of which the float64 table R would
+// be the largest part (8 bytes per cell written, 8 read).  There the forward keeps only the lane
+// state at the start of every macro-step (1/16 of R) and the backward recomputes each macro-step of
+// R before it uses it - from the cost block that is in the ring anyway, in either mode.
+constexpr bool dp_recompute(int /*kch*/, int slots) { return slots == 4; }
 constexpr float kBigCost = 3.0e38f;  // cost of a cell outside the grid
 constexpr int kStatusTimeoutDp = 6;  // SDTW_ERR_TIMEOUT
 
@@ -1178,12 +1179,12 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
     const bool has_below = live && (k + 1 < p.nbands) && CH != 1;  // through memory
     const bool emit_top = live && k > 0 && CH != 0;                // through memory
     constexpr bool RECOMP = dp_recompute(KCH, SLOTS);
+    static_assert(RECOMP != TSWEEP, "a reverse sweep either stores its own table or recomputes R and forms E");
     const unsigned long long *brow_in = p.brow_b + ((size_t)bb * p.nbands + (has_below ? kc + 1 : kc)) * M;
     unsigned long long *brow_out = p.brow_b + ((size_t)bb * p.nbands + kc) * M;
     // (table pointers are those of the band's macro-step 0; the table starts at macro-step table_base)
     const ptrdiff_t tb = table_base(p, kc);
     const ptrdiff_t band_off = (((ptrdiff_t)bb * p.nbands + kc) * (ptrdiff_t)p.nm_tab - tb) * kBlk * kBandRows;
-    const double *Rk = (RECOMP || TSWEEP) ? nullptr : p.R + band_off;
     double *Qk = TSWEEP ? p.Q + band_off : nullptr;
     const double *Ck = RECOMP ? p.ckpt + (((ptrdiff_t)bb * p.nbands + kc) * (ptrdiff_t)p.nm_tab - tb) * 2 * kBandRows : nullptr;
     // the forward's row above this band (final values, written by the forward call)
@@ -1205,10 +1206,6 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
             const int jf = sg0 * kBlk + lane;
             if (k > 0 && lane < kBlk && jf < M) ftop_next = ftop_g[jf];
         }
-    } else if constexpr (!TSWEEP) {
-#pragma unroll
-        for (int u = 0; u < kBlk; ++u)  // (Rk points at a valid band also for an idle slot: no branch per load)
-            Rq[u] = Rfin - Rk[((size_t)sg0 * kBlk + u) * kBandRows + lane];
     }
 
     // row below the band for the first macro-step: lane l >= 32 brings column 32*sg - 63 + (l - 32),
@@ -1241,7 +1238,6 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
             // lane 0's values are the band's first row (column 32*sg + u at step u)
             double *my_eo = eo + ((lane == 0) ? 0 : kBlk + lane);
             if constexpr (CH == 0) my_eo = hand + ((lane == 0) ? (sg & 3) * kBlk : kHandRing + lane);
-            const double *Rn = (RECOMP || TSWEEP) ? nullptr : Rk + (size_t)(sg > rg.lo ? sg - 1 : sg) * kBlk * kBandRows;
             double *Qs = TSWEEP ? Qk + (size_t)sg * kBlk * kBandRows : nullptr;
             const int sbase = sg * kBlk;
             // Can any cell of this macro-step have a non-zero E (in float32)?  Every R of the macro-step
@@ -1310,7 +1306,6 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
                     if constexpr (decltype(alive)::value) {
                         // log2 E = R[N,M] - R[i,j] - (m - L) in table units
                         rd[u] = __builtin_amdgcn_exp2f((float)(Rq[u] - m) + L);
-                        if constexpr (!RECOMP) Rq[u] = Rfin - __builtin_nontemporal_load(&Rn[u * kBandRows + lane]);
                     } else {
                         rd[u] = 0.0f;
                     }

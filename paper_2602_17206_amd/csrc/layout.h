@@ -43,7 +43,7 @@ struct Layout {
     int32_t nrb, ncb; // 32x32 block rows / columns: ceil(N/32), ceil(M/32)
     int64_t xn_count, yn_count;  // number of norm entries (1 sequence when the batch stride is 0)
     int32_t Dp;                  // D rounded up to 16, 32, 64 or 128: row length of the split-half operand copies (0: none)
-    int32_t recompute;           // 1: checkpoints instead of the R table (large fused problems)
+    int32_t recompute;           // 1: checkpoints instead of the R table (large problems)
     int32_t two_sweep;           // 1: the forward call also runs the reverse sweep and stores its table Q
     size_t off_hdr, off_rfinal, off_xn, off_yn, off_xis, off_yis, off_xh, off_yh, off_brow, off_brow_b, off_R,
         off_Q, off_ckpt, off_cost, off_E, off_nz, total;
@@ -148,7 +148,7 @@ struct Params {
     uint16_t *xh, *yh;             // [rows][Dp/16][2 pieces][16] float16 bit patterns
     int64_t xh_stride, yh_stride;  // batch strides of the split copies (0 when shared)
     unsigned long long *brow;      // boundary rows of the forward sweep
-    unsigned long long *brow_b;    // boundary rows of the backward sweep (== brow unless recompute)
+    unsigned long long *brow_b;    // boundary rows of the backward sweep (rows of its own whenever a backward can follow)
     double *R;
     double *Q;                     // two_sweep: table of the reverse sweep (soft-minimum part), ordered like R
     double *ckpt;                  // recompute: forward lane state per macro-step

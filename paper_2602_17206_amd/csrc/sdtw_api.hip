@@ -91,7 +91,7 @@ bool small_problem(const sdtw_desc *d)
 Layout layout_of(const sdtw_desc *d)
 {
     const bool small = small_problem(d);
-    const bool recompute = d->mode == SDTW_FUSED && !small;  // == dp_recompute(KCH >= 0, SLOTS == 4)
+    const bool recompute = !small;  // the 4-band workgroups keep checkpoints instead of R (dp_recompute)
     const bool two_sweep = small && !(d->flags & SDTW_FLAG_VALUE_ONLY);
     return make_layout(d->B, d->N, d->M, d->D, d->mode, d->x_batch_stride == 0, d->y_batch_stride == 0, recompute,
                        two_sweep, effective_window(d));

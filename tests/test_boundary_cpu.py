@@ -48,7 +48,7 @@ def test_workspace_sizes():
     d_v = binding.make_desc(32, 1024, 1024, 128, 0.1, pkg.FUSED, flags=pkg.FLAG_VALUE_ONLY)
     wv = pkg.sdtw_workspace_bytes(d_v)
     assert 8 * cells < wf - wv < 9 * cells
-    # large fused problems keep checkpoints instead of the table
+    # large problems keep checkpoints instead of the table
     d_l = binding.make_desc(32, 8192, 8192, 64, 0.1, pkg.FUSED)
     assert pkg.sdtw_workspace_bytes(d_l) < 5.0 * 32 * 8192 * 8192
     assert pkg.sdtw_workspace_bytes(binding.make_desc(1, 1, 1, 1, 1.0, pkg.FUSED)) > 0

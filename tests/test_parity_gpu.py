@@ -346,7 +346,7 @@ def test_ragged_results_do_not_depend_on_the_padding(mode):
 def test_ragged_large_regime_and_state_check():
     import torch
 
-    # more than 1024 band tasks: 4-band workgroups, stored-table backward and recomputing backward
+    # more than 1024 band tasks: 4-band workgroups, recomputing backward in both modes
     B, N, M, D, gamma = 48, 1500, 400, 24, 0.2
     say("ragged, large regime B=%d N=%d M=%d" % (B, N, M))
     x, y = workloads.normal_pairs(52, B, N, M, D)
@@ -433,7 +433,7 @@ def test_band_constraint_long_and_narrow(mode):
 def test_band_constraint_large_regime_ragged_and_state_check():
     import torch
 
-    # more than 1024 band tasks: 4-band workgroups, stored-table backward and recomputing backward;
+    # more than 1024 band tasks: 4-band workgroups, recomputing backward in both modes;
     # per-pair lengths whose difference stays inside the band
     B, N, M, D, gamma, w = 44, 1600, 1500, 24, 0.2, 230
     say("band, large regime B=%d N=%d M=%d w=%d" % (B, N, M, w))
