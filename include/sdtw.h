@@ -209,7 +209,7 @@ int sdtw_debug_lane_shift(int32_t *out, void *stream);
 int sdtw_debug_set_spin_limit(uint32_t polls);
 
 /*
- * Test hook: the DP kernels run either one band per workgroup (problems of up to 1024 band tasks)
+ * Test hook: the DP kernels run either one band per workgroup (problems of up to about 1536 band tasks)
  * or four bands per workgroup (larger ones).  1 or 4 forces that shape for later calls whatever the
  * size, 0 restores the choice by size.  Results do not depend on the shape.  Process-wide; host only.
  */

@@ -79,13 +79,14 @@ int64_t busy_bands(const sdtw_desc *d)
     return std::min<int64_t>(nbands, run / 5 + 2);
 }
 
-// Problems of up to 1024 busy band tasks cannot fill the chip: they run one band per workgroup.
+// Problems of up to about 1536 busy band tasks cannot fill the chip: they run one band per workgroup
+// (measured: 19 % faster than the 4-band workgroups at 1536 tasks, equal at 2048, 40 % slower at 4096).
 // (Under a band constraint the estimate of the busy bands is coarse; measured at B = 32, N = M = 8192
 // and B = 128, N = M = 2048 the one-band workgroups win up to about 640.)
 bool small_problem(const sdtw_desc *d)
 {
     if (g_force_slots) return g_force_slots != 4;
-    return (int64_t)d->B * busy_bands(d) <= (effective_window(d) < kNoWindow ? 640 : 1024);
+    return (int64_t)d->B * busy_bands(d) <= (effective_window(d) < kNoWindow ? 640 : 1536);
 }
 
 Layout layout_of(const sdtw_desc *d)
@@ -158,7 +159,7 @@ int fused_variant(int D)
     return 0;
 }
 
-// Launches the DP kernels in the workgroup shape that suits the problem.  Up to 1024 band tasks
+// Launches the DP kernels in the workgroup shape that suits the problem.  Up to about 1536 band tasks
 // cannot fill the chip: each band gets a small workgroup of its own (consumer and producers on
 // different SIMDs), and the forward call runs the reverse sweep in the same launch (FWD, unless
 // only the value is wanted); its backward call launches no DP kernel.  Larger problems use 4-band

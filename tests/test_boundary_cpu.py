@@ -36,7 +36,7 @@ def test_struct_sizes_match_the_header_layout():
 
 
 def test_workspace_sizes():
-    # small problems (up to 1024 band tasks): float64 tables of both sweeps, float32 E
+    # small problems (up to 1536 band tasks): float64 tables of both sweeps, float32 E
     d_f = binding.make_desc(32, 1024, 1024, 128, 0.1, pkg.FUSED)
     d_u = binding.make_desc(32, 1024, 1024, 128, 0.1, pkg.UNFUSED)
     wf, wu = pkg.sdtw_workspace_bytes(d_f), pkg.sdtw_workspace_bytes(d_u)

@@ -145,7 +145,7 @@ def test_value_E_and_gradients(mode, B, N, M, D, gamma):
                                            (3, 100, 90, 200, 0.5), (2, 300, 40, 8, 0.3), (3, 50, 70, 4, 1.0)])
 def test_all_workgroup_shapes(shape, mode, B, N, M, D, gamma):
     # one band per workgroup, a chained pair of bands per workgroup (normally for 2 or more bands),
-    # or 4 bands of 4 pairs (normally only for > 1024 band tasks): force each on small inputs
+    # or 4 bands of 4 pairs (normally only for > 1536 band tasks): force each on small inputs
     # (odd numbers of bands, a single band, B not a multiple of 4, D above the register-operand
     # limit of 128 included)
     say("shape %d %s B=%d N=%d M=%d D=%d gamma=%g" % (shape, mode, B, N, M, D, gamma))
@@ -346,8 +346,8 @@ def test_ragged_results_do_not_depend_on_the_padding(mode):
 def test_ragged_large_regime_and_state_check():
     import torch
 
-    # more than 1024 band tasks: 4-band workgroups, recomputing backward in both modes
-    B, N, M, D, gamma = 48, 1500, 400, 24, 0.2
+    # more than 1536 band tasks: 4-band workgroups, recomputing backward in both modes
+    B, N, M, D, gamma = 72, 1500, 400, 24, 0.2
     say("ragged, large regime B=%d N=%d M=%d" % (B, N, M))
     x, y = workloads.normal_pairs(52, B, N, M, D)
     xl = workloads.ragged_lengths(53, B, N)
@@ -433,7 +433,7 @@ def test_band_constraint_long_and_narrow(mode):
 def test_band_constraint_large_regime_ragged_and_state_check():
     import torch
 
-    # more than 1024 band tasks: 4-band workgroups, recomputing backward in both modes;
+    # more than 1536 band tasks would be: 4-band workgroups, recomputing backward in both modes;
     # per-pair lengths whose difference stays inside the band
     B, N, M, D, gamma, w = 44, 1600, 1500, 24, 0.2, 230
     say("band, large regime B=%d N=%d M=%d w=%d" % (B, N, M, w))
@@ -606,8 +606,8 @@ def test_rectangular_at_scale(mode, B, N, M, D, gamma):
 
 
 def test_rectangular_large_regime():
-    # more than 1024 band tasks with N != M: the 4-band workgroups, recomputing fused backward
-    B, N, M, D, gamma = 40, 1700, 300, 24, 0.2
+    # more than 1536 band tasks with N != M: the 4-band workgroups, recomputing backward
+    B, N, M, D, gamma = 64, 1700, 300, 24, 0.2
     say("rectangular, large regime B=%d N=%d M=%d" % (B, N, M))
     x, y = workloads.normal_pairs(51, B, N, M, D)
     pairs = [0, 17, 39]
