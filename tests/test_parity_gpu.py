@@ -205,6 +205,32 @@ def test_zero_cost_gives_delannoy_table(mode):
     np.testing.assert_allclose(R, -gamma * logdel, rtol=1e-5, atol=1e-4)
 
 
+@pytest.mark.parametrize("shape", [1, 4])
+@pytest.mark.parametrize("mode", ["unfused", "fused"])
+def test_zero_cost_alignment_matrix_is_the_delannoy_ratio(shape, mode):
+    # identical constant sequences: every cost is 0, R is negative throughout and
+    # E[i,j] = Del(i,j) Del(N-1-i, M-1-j) / Del(N-1, M-1) (0-based): nowhere near zero around the
+    # diagonal, vanishing towards the far corners - also in the 4-band workgroups, whose backward
+    # decides per macro-step whether E can be non-zero at all
+    N, M, gamma = 200, 170, 1.0
+    say("delannoy E shape %d %s" % (shape, mode))
+    x = np.full((2, N, 4), 0.25, dtype=np.float32)
+    y = np.full((2, M, 4), 0.25, dtype=np.float32)
+    logdel = np.zeros((N, M))
+    for i in range(1, N):
+        for j in range(1, M):
+            logdel[i, j] = np.logaddexp(np.logaddexp(logdel[i - 1, j], logdel[i, j - 1]), logdel[i - 1, j - 1])
+    E_exact = np.exp(logdel + logdel[::-1, ::-1] - logdel[N - 1, M - 1])
+    binding.debug_force_workgroup_shape(shape)
+    try:
+        got = run_gpu(x, y, gamma, MODES[mode])
+    finally:
+        binding.debug_force_workgroup_shape(0)
+    assert np.abs(got["E"][0] - E_exact).max() <= E_ATOL
+    assert np.abs(got["E"][1] - E_exact).max() <= E_ATOL
+    assert abs(got["value"][0] + gamma * logdel[N - 1, M - 1]) <= 1e-4 * gamma * logdel[N - 1, M - 1]
+
+
 @pytest.mark.parametrize("mode", ["unfused", "fused"])
 def test_upstream_gradient_and_shared_x(mode):
     say("grad_value / shared x %s" % mode)
