@@ -10,23 +10,6 @@ namespace sdtw {
 constexpr int kStatusState = 4;    // SDTW_ERR_STATE
 constexpr int kStatusTimeout = 6;  // SDTW_ERR_TIMEOUT
 
-// ---------------------------------------------------------------------------------------------
-// Small utility kernels
-// ---------------------------------------------------------------------------------------------
-__global__ void fill_u64_kernel(unsigned long long *dst, size_t n, unsigned long long v)
-{
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (; i < n; i += stride) dst[i] = v;
-}
-
-__global__ void fill_f32_kernel(float *dst, size_t n, float v)
-{
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (; i < n; i += stride) dst[i] = v;
-}
-
 // Boundary rows before a sweep: "not written yet" wherever the band that owns the row will publish a
 // value.  With a band constraint a sweep skips the macro-steps outside the window; the columns it
 // never publishes (forward: the band's last row, columns 32*lo-63 .. 32*hi-32; reverse: its first

@@ -151,8 +151,7 @@ struct Params {
     unsigned long long *brow_b;    // boundary rows of the backward sweep (rows of its own whenever a backward can follow)
     double *R;
     double *Q;                     // two_sweep: table of the reverse sweep (soft-minimum part), ordered like R
-    double *ckpt;                  // recompute: forward lane state per macro-step
-    int32_t recompute;
+    double *ckpt;                  // large problems: forward lane state per macro-step instead of R
     int32_t two_sweep;
     float *cost;
     float *E;

@@ -141,7 +141,6 @@ Params make_params(const sdtw_desc *d, const Layout &L, const float *x, const fl
     p.Q = reinterpret_cast<double *>(base + L.off_Q);
     p.two_sweep = L.two_sweep;
     p.ckpt = reinterpret_cast<double *>(base + L.off_ckpt);
-    p.recompute = L.recompute;
     p.cost = reinterpret_cast<float *>(base + L.off_cost);
     p.E = reinterpret_cast<float *>(base + L.off_E);
     p.nz = reinterpret_cast<unsigned char *>(base + L.off_nz);
