@@ -121,7 +121,9 @@ int sdtw_forward(const sdtw_desc *desc, const float *x, const float *y, float *v
  *   grad_value [B]: device, upstream dL/dvalue per pair, or NULL for ones.
  *   dx [B,N,D], dy [B,M,D]: device, out; either may be NULL if not wanted.  With
  *        x_batch_stride 0 dx still has one [N,D] slab per pair (the caller sums them).
- *   E_out [B,N,M]: device, out, optional (NULL): the alignment matrix E.
+ *   E_out [B,N,M]: device, out, optional (NULL): the alignment matrix E (entries that underflow
+ *        float32 are exact zeros; inside the workspace E exists only block-wise where it is
+ *        non-zero).
  */
 int sdtw_backward(const sdtw_desc *desc, const float *x, const float *y, const float *grad_value,
                   float *dx, float *dy, float *E_out, void *workspace, size_t workspace_bytes,
@@ -209,9 +211,11 @@ int sdtw_debug_lane_shift(int32_t *out, void *stream);
 int sdtw_debug_set_spin_limit(uint32_t polls);
 
 /*
- * Test hook: the DP kernels run either one band per workgroup (problems of up to about 1536 band tasks)
- * or four bands per workgroup (larger ones).  1 or 4 forces that shape for later calls whatever the
- * size, 0 restores the choice by size.  Results do not depend on the shape.  Process-wide; host only.
+ * Test hook: the DP kernels run one band per workgroup or two consecutive bands of a pair per
+ * workgroup (problems of up to about 1536 band tasks), or four bands per workgroup (larger ones).
+ * 1, 2 or 4 forces that shape for later calls whatever the size, 0 restores the choice by size.
+ * Results agree across shapes to rounding.  The forced shape also decides the workspace layout, so
+ * set it before sdtw_workspace_bytes.  Process-wide; host only.
  */
 int sdtw_debug_force_workgroup_shape(int bands_per_workgroup);
 
