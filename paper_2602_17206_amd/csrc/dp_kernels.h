@@ -906,8 +906,9 @@ __device__ __forceinline__ bool block_in_range(const SweepRange &rg, int rb, int
 template <int COLS = kRingCols, int STRIDE = kRingStride>
 __device__ __forceinline__ void flush_E_block(const Params &p, const SweepRange &rg, const float *ring,
                                               float *__restrict__ Eb, unsigned char *__restrict__ nzb, int rb, int cb,
-                                              int row0, int lane, bool known_zero = false)
+                                              int row0, int lane, bool known_zero = false, int ring_row0 = 0)
 {
+    // ring_row0: the band row that the ring's first row holds (0, or 32 for a ring of the lower block row alone)
     if (cb < 0 || cb >= p.ncb || row0 + 32 * rb >= p.N || !block_in_range(rg, rb, cb)) return;
     if (known_zero) {  // the consumer found that no cell of the block's two macro-steps can be non-zero
         if (lane == 0) nzb[(size_t)(row0 / kBlk + rb) * p.ncb + cb] = 0;
@@ -919,7 +920,7 @@ __device__ __forceinline__ void flush_E_block(const Params &p, const SweepRange 
     const bool nowrap = phase != COLS / kBlk - 1;
     auto read4 = [&](int it, float (&v)[4]) {
         const int r = (lane >> 3) + 8 * it;
-        const float *rowp = ring + (32 * rb + r) * STRIDE;
+        const float *rowp = ring + (32 * rb + r - ring_row0) * STRIDE;
         if (nowrap) {  // constant offsets from the lane's position
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] = rowp[32 * phase + c4 + r + e];
@@ -1517,6 +1518,87 @@ __global__ __launch_bounds__(64) void alignment_kernel(Params p, int seg_blocks)
         if (g - 1 >= cb0 && g - 1 < cb1) flush_E_block<kAlignRingCols, kAlignRingStride>(p, rg, ring, Eb, nzb, 0, g - 1, row0, lane);
         if (g - 2 >= cb0 && g - 2 < cb1) flush_E_block<kAlignRingCols, kAlignRingStride>(p, rg, ring, Eb, nzb, 1, g - 2, row0, lane);
     }
+}
+
+// The same for short rows (at most NM - 2 column blocks): one workgroup of NW wavefronts per block
+// row (32 rows: half a band).  The block row's E fits in LDS (32 rows x 32*NM steps), so every
+// table entry is read exactly once - a wavefront takes a macro-step, its two half-waves alternate
+// steps - and after one barrier the ncb blocks are written out, one per wavefront at a time.  (The
+// run-per-wavefront kernel above re-reads two macro-steps per run, which at 8 column blocks and
+// runs of 2 is 60 % more table traffic, and it has a quarter of the wavefronts in flight.)
+constexpr int kAlignRowMacro = 12;  // macro-steps of E that alignment_row_kernel keeps (49 KB of LDS)
+template <int NM, int NW>
+__global__ __launch_bounds__(64 * NW) void alignment_row_kernel(Params p)
+{
+    constexpr int kStride = kBlk * NM + 1, kCols = 512;  // kCols: a power of two >= 32*NM, so no index ever wraps
+    static_assert(kBlk * NM <= kCols, "the steps must fit below the wrap-around of flush_E_block");
+    __shared__ float ring[kBlk * kStride + 2 * kBlk];  // the last block of a row is read up to step 32*NM + 30
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int rb = blockIdx.x, k = blockIdx.y, b = blockIdx.z;
+    const int row0 = k * kBandRows;
+
+    if (backward_refused(p)) {
+        // record why (the status word keeps a time-out of the sweeps), leave NaN to the later kernels
+        if (threadIdx.x == 0 && rb == 0 && k == 0 && b == 0 && p.hdr->status == 0) {
+            p.hdr->magic = kMagic;
+            p.hdr->status = kStatusState;
+            p.hdr->abort_backward = 1;
+        }
+        return;
+    }
+    if (row0 + kBlk * rb >= p.N) return;
+
+    float *Eb = p.E + (size_t)b * p.N * p.M;
+    unsigned char *nzb = p.nz + (size_t)b * p.nrb * p.ncb;
+    const ptrdiff_t band_off = (((ptrdiff_t)b * p.nbands + k) * (ptrdiff_t)p.nm_tab - table_base(p, k)) * kBlk * kBandRows;
+    const double *Rk = p.R + band_off, *Qk = p.Q + band_off;
+    const double Rfin = p.rfinal[b];
+    const SweepRange rg = sweep_range(p, row0, row0, pair_len(p.x_len, b, p.N), pair_len(p.y_len, b, p.M));
+    if (p.window < kNoWindow || p.x_len != nullptr || p.y_len != nullptr) {
+        // blocks the sweeps did not cover are outside the window or the pair's lengths: flags cleared
+        for (int cb = threadIdx.x; cb < p.ncb; cb += 64 * NW)
+            if (!block_in_range(rg, rb, cb)) nzb[(size_t)(row0 / kBlk + rb) * p.ncb + cb] = 0;
+    }
+    // this block row's cells lie in macro-steps rb ... ncb + rb
+    const int g_begin = max(rg.lo, rb), g_end = min(min(rg.hi, p.ncb + rb) + 1, min(p.nmacro, NM));
+    const int half = lane >> 5, r = lane & 31;
+    float *my_ring = ring + r * kStride + half;
+    auto load = [&](int g, double (&rr)[kBlk / 2], double (&qq)[kBlk / 2]) {
+        const size_t o = ((size_t)g * kBlk + half) * kBandRows + kBlk * rb + r;
+#pragma unroll
+        for (int u = 0; u < kBlk / 2; ++u) {
+            rr[u] = __builtin_nontemporal_load(&Rk[o + (size_t)(2 * u) * kBandRows]);
+            qq[u] = __builtin_nontemporal_load(&Qk[o + (size_t)(2 * u) * kBandRows]);
+        }
+    };
+    auto process = [&](int g, const double (&rr)[kBlk / 2], const double (&qq)[kBlk / 2]) {
+        float *wr = my_ring + g * kBlk;  // step s = 32g + 2u + half sits at position s of the row
+#pragma unroll
+        for (int u = 0; u < kBlk / 2; ++u) wr[2 * u] = __builtin_amdgcn_exp2f((float)((Rfin - rr[u]) - qq[u]));
+    };
+    // macro-steps of this block row that the sweeps left out hold no cell of the grid: zero
+    for (int g = rb + w; g <= min(p.ncb + rb, NM - 1); g += NW) {
+        if (g >= g_begin && g < g_end) continue;
+#pragma unroll
+        for (int u = 0; u < kBlk / 2; ++u) my_ring[g * kBlk + 2 * u] = 0.f;
+    }
+    {
+        double ra[kBlk / 2], qa[kBlk / 2], rc[kBlk / 2], qc[kBlk / 2];
+        int g = g_begin + w;
+        if (g < g_end) load(g, ra, qa);
+        while (g < g_end) {
+            if (g + NW < g_end) load(g + NW, rc, qc);
+            process(g, ra, qa);
+            g += NW;
+            if (g >= g_end) break;
+            if (g + NW < g_end) load(g + NW, ra, qa);
+            process(g, rc, qc);
+            g += NW;
+        }
+    }
+    __syncthreads();
+    for (int cb = w; cb < p.ncb; cb += NW)
+        flush_E_block<kCols, kStride>(p, rg, ring, Eb, nzb, rb, cb, row0, lane, false, kBlk * rb);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -296,7 +296,9 @@ int backward_impl(const sdtw_desc *d, const float *x, const float *y, const floa
         const int nseg = (int)std::max<int64_t>(1, std::min<int64_t>(L.ncb, (512 + bands - 1) / bands));
         const int seg_blocks = (L.ncb + nseg - 1) / nseg;
         dim3 g((L.ncb + seg_blocks - 1) / seg_blocks, L.nbands, d->B);
-        if (L.ncb >= 16)
+        if (L.ncb + 2 <= kAlignRowMacro)  // short rows: a block row's E fits in LDS, one workgroup for each
+            alignment_row_kernel<kAlignRowMacro, 8><<<dim3(2, L.nbands, d->B), 512, 0, st>>>(p);
+        else if (L.ncb >= 16)
             alignment_kernel<true><<<g, 64, 0, st>>>(p, seg_blocks);
         else
             alignment_kernel<false><<<g, 64, 0, st>>>(p, seg_blocks);

@@ -298,6 +298,28 @@ def test_backward_twice_after_one_forward_gives_the_same_result():
         assert binding.workspace_status(ws) == 0
         assert torch.equal(dx1, dx2) and torch.equal(dy1, dy2)
 
+@pytest.mark.parametrize("ragged", [False, True])
+@pytest.mark.parametrize("N,M", [(33, 257), (97, 288), (64, 289), (130, 320), (65, 321), (32, 225)])
+def test_alignment_at_the_row_length_limits(N, M, ragged):
+    # Small problems with up to 10 column blocks form E per block row with the whole row in LDS,
+    # longer rows in runs of blocks per wavefront: the last lengths of the one (M = 320), the first
+    # of the other (321), rows that end one past a block (257, 289: the sweep then has one macro-step
+    # fewer beyond the last block), and band counts that leave half a band empty (N = 33, 97, 32)
+    say("row limits N=%d M=%d ragged=%s" % (N, M, ragged))
+    B, D, gamma = 3, 8, 0.3
+    x, y = workloads.normal_pairs(4100 + N + M, B, N, M, D)
+    if ragged:
+        xl = workloads.ragged_lengths(5 + N, B, N)
+        yl = workloads.ragged_lengths(6 + M, B, M, shortest=M - 40)[::-1].copy()
+        ref = oracle.ragged_batch(x, y, xl, yl, gamma, want_E=True)
+        got = run_gpu_ragged(x, y, xl, yl, gamma, MODES["fused"])
+        for b in range(B):
+            assert not got["E"][b, xl[b]:].any() and not got["E"][b, :, yl[b]:].any()
+    else:
+        ref = oracle.batch(x, y, gamma, want_E=True)
+        got = run_gpu(x, y, gamma, MODES["fused"])
+    check_against(ref, got, what="row limits %d x %d" % (N, M))
+
 
 # ------------------------------------------------------------------------------- ragged batches
 def run_gpu_ragged(x, y, xl, yl, gamma, mode, grad_value=None, want_E=True):
