@@ -1537,15 +1537,9 @@ __global__ __launch_bounds__(64 * NW) void alignment_row_kernel(Params p)
     const int rb = blockIdx.x, k = blockIdx.y, b = blockIdx.z;
     const int row0 = k * kBandRows;
 
-    if (backward_refused(p)) {
-        // record why (the status word keeps a time-out of the sweeps), leave NaN to the later kernels
-        if (threadIdx.x == 0 && rb == 0 && k == 0 && b == 0 && p.hdr->status == 0) {
-            p.hdr->magic = kMagic;
-            p.hdr->status = kStatusState;
-            p.hdr->abort_backward = 1;
-        }
-        return;
-    }
+    // (the header is asked for now and looked at once the first table rows have been asked for:
+    // the kernel is a few memory round trips long, this keeps it from being one longer)
+    const bool refused = backward_refused(p);
     if (row0 + kBlk * rb >= p.N) return;
 
     float *Eb = p.E + (size_t)b * p.N * p.M;
@@ -1554,11 +1548,6 @@ __global__ __launch_bounds__(64 * NW) void alignment_row_kernel(Params p)
     const double *Rk = p.R + band_off, *Qk = p.Q + band_off;
     const double Rfin = p.rfinal[b];
     const SweepRange rg = sweep_range(p, row0, row0, pair_len(p.x_len, b, p.N), pair_len(p.y_len, b, p.M));
-    if (p.window < kNoWindow || p.x_len != nullptr || p.y_len != nullptr) {
-        // blocks the sweeps did not cover are outside the window or the pair's lengths: flags cleared
-        for (int cb = threadIdx.x; cb < p.ncb; cb += 64 * NW)
-            if (!block_in_range(rg, rb, cb)) nzb[(size_t)(row0 / kBlk + rb) * p.ncb + cb] = 0;
-    }
     // this block row's cells lie in macro-steps rb ... ncb + rb
     const int g_begin = max(rg.lo, rb), g_end = min(min(rg.hi, p.ncb + rb) + 1, min(p.nmacro, NM));
     const int half = lane >> 5, r = lane & 31;
@@ -1576,16 +1565,30 @@ __global__ __launch_bounds__(64 * NW) void alignment_row_kernel(Params p)
 #pragma unroll
         for (int u = 0; u < kBlk / 2; ++u) wr[2 * u] = __builtin_amdgcn_exp2f((float)((Rfin - rr[u]) - qq[u]));
     };
-    // macro-steps of this block row that the sweeps left out hold no cell of the grid: zero
-    for (int g = rb + w; g <= min(p.ncb + rb, NM - 1); g += NW) {
-        if (g >= g_begin && g < g_end) continue;
-#pragma unroll
-        for (int u = 0; u < kBlk / 2; ++u) my_ring[g * kBlk + 2 * u] = 0.f;
-    }
     {
         double ra[kBlk / 2], qa[kBlk / 2], rc[kBlk / 2], qc[kBlk / 2];
         int g = g_begin + w;
         if (g < g_end) load(g, ra, qa);
+        if (refused) {
+            // record why (the status word keeps a time-out of the sweeps), leave NaN to the later kernels
+            if (threadIdx.x == 0 && rb == 0 && k == 0 && b == 0 && p.hdr->status == 0) {
+                p.hdr->magic = kMagic;
+                p.hdr->status = kStatusState;
+                p.hdr->abort_backward = 1;
+            }
+            return;
+        }
+        if (p.window < kNoWindow || p.x_len != nullptr || p.y_len != nullptr) {
+            // blocks the sweeps did not cover are outside the window or the pair's lengths: flags cleared
+            for (int cb = threadIdx.x; cb < p.ncb; cb += 64 * NW)
+                if (!block_in_range(rg, rb, cb)) nzb[(size_t)(row0 / kBlk + rb) * p.ncb + cb] = 0;
+        }
+        // macro-steps of this block row that the sweeps left out hold no cell of the grid: zero
+        for (int gz = rb + w; gz <= min(p.ncb + rb, NM - 1); gz += NW) {
+            if (gz >= g_begin && gz < g_end) continue;
+#pragma unroll
+            for (int u = 0; u < kBlk / 2; ++u) my_ring[gz * kBlk + 2 * u] = 0.f;
+        }
         while (g < g_end) {
             if (g + NW < g_end) load(g + NW, rc, qc);
             process(g, ra, qa);

@@ -185,20 +185,31 @@ __global__ __launch_bounds__(256) void forward_prep_kernel(Params p, int64_t xro
     }
 }
 
-// Does the workspace hold the forward of this descriptor?
+// Does the workspace hold the forward of this descriptor?  Every field is read before any is
+// compared, and the comparisons are combined without branches: the header costs one memory round
+// trip (short-circuit comparisons would take one per field, a microsecond each, at the start of
+// kernels that run for ten).
 __device__ __forceinline__ bool workspace_matches(const Params &p)
 {
     const Header *h = p.hdr;
-    return h->magic == kMagic && h->forward_done == 1 && h->B == p.B && h->N == p.N && h->M == p.M &&
-           h->D == p.D && h->mode == p.mode && h->two_sweep == p.two_sweep && h->window == p.window &&
-           h->x_len_ptr == reinterpret_cast<uint64_t>(p.x_len) && h->y_len_ptr == reinterpret_cast<uint64_t>(p.y_len) &&
-           h->gamma_bits == __float_as_uint(p.gamma);
+    const uint32_t magic = h->magic, gamma_bits = h->gamma_bits;
+    const int32_t B = h->B, N = h->N, M = h->M, D = h->D, mode = h->mode, done = h->forward_done;
+    const int32_t two_sweep = h->two_sweep, window = h->window;
+    const uint64_t xl = h->x_len_ptr, yl = h->y_len_ptr;
+    const uint32_t diff = (magic ^ kMagic) | (uint32_t)(done ^ 1) | (uint32_t)(B ^ p.B) | (uint32_t)(N ^ p.N) |
+                          (uint32_t)(M ^ p.M) | (uint32_t)(D ^ p.D) | (uint32_t)(mode ^ p.mode) |
+                          (uint32_t)(two_sweep ^ p.two_sweep) | (uint32_t)(window ^ p.window) |
+                          (gamma_bits ^ __float_as_uint(p.gamma));
+    const uint64_t diff_ptr = (xl ^ reinterpret_cast<uint64_t>(p.x_len)) | (yl ^ reinterpret_cast<uint64_t>(p.y_len));
+    return (diff == 0) & (diff_ptr == 0);
 }
 
 // A backward call's outputs are NaN when the workspace does not match or a sweep gave up waiting.
 __device__ __forceinline__ bool backward_refused(const Params &p)
 {
-    return p.hdr->abort_backward != 0 || !workspace_matches(p) || p.hdr->status != 0;
+    const int32_t aborted = p.hdr->abort_backward, status = p.hdr->status;
+    const bool ok = workspace_matches(p);
+    return ((aborted | status) != 0) | !ok;
 }
 
 // Start of a backward call that runs the reverse sweep itself, one launch: checks that the
@@ -446,8 +457,8 @@ __device__ __forceinline__ void split8(const float (&v)[8], float scale, half8 &
 __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const float *__restrict__ grad_value,
                                                              float *__restrict__ dx, float *__restrict__ dy)
 {
-    __shared__ __attribute__((aligned(16))) _Float16 Ah[2][64 * kGradHalfRow];  // [piece][m][k]
-    __shared__ __attribute__((aligned(16))) _Float16 Bh[2][64 * kGradHalfRow];  // [piece][n][k]
+    __shared__ __attribute__((aligned(16))) _Float16 Ah[2][2][64 * kGradHalfRow];  // [buffer][piece][m][k]
+    __shared__ __attribute__((aligned(16))) _Float16 Bh[2][2][64 * kGradHalfRow];  // [buffer][piece][n][k]
     __shared__ float msum_part[4][64];
     __shared__ int live_list[kLiveCap];          // first reduced position of every chunk that has a non-zero
     __shared__ unsigned long long wave_mask[2][4];
@@ -470,14 +481,9 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
     out += (size_t)b * P * p.D;
     const int wr = w >> 1, wc = w & 1;
 
-    if (backward_refused(p)) {
-        const float qnan = __builtin_nanf("");
-        for (int e = tid; e < 64 * 64; e += 256) {
-            const int m = m0 + (e >> 6), n = n0 + (e & 63);
-            if (m < P && n < p.D) out[(size_t)m * p.D + n] = qnan;
-        }
-        return;
-    }
+    // (the header is asked for now and looked at below, once the first flags and the output side's
+    // own values have been asked for as well: one wait for all three)
+    const bool refused = backward_refused(p);
 
     const float sA = 1024.0f;
     // the largest 1/scale among the chunk's 32 rows: one row per lane (mod 32), then a butterfly
@@ -552,29 +558,29 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
             bv[c] = (q < Ql && n < p.D) ? oth[(size_t)q * p.D + n] : 0.f;
         }
     };
-    auto stash = [&](const float (&ea)[8], const float (&bv)[8], float ismax) {
+    auto stash = [&](int buf, const float (&ea)[8], const float (&bv)[8], float ismax) {
         half8 h1, h2;
         const float sB = 1.0f / ismax;  // exact: a power of two
         split8(ea, sA, h1, h2);
-        *reinterpret_cast<half8 *>(&Ah[0][am * kGradHalfRow + ak]) = h1;
-        *reinterpret_cast<half8 *>(&Ah[1][am * kGradHalfRow + ak]) = h2;
+        *reinterpret_cast<half8 *>(&Ah[buf][0][am * kGradHalfRow + ak]) = h1;
+        *reinterpret_cast<half8 *>(&Ah[buf][1][am * kGradHalfRow + ak]) = h2;
         split8(bv, sB, h1, h2);
-        *reinterpret_cast<half8 *>(&Bh[0][bn * kGradHalfRow + bk]) = h1;
-        *reinterpret_cast<half8 *>(&Bh[1][bn * kGradHalfRow + bk]) = h2;
+        *reinterpret_cast<half8 *>(&Bh[buf][0][bn * kGradHalfRow + bk]) = h1;
+        *reinterpret_cast<half8 *>(&Bh[buf][1][bn * kGradHalfRow + bk]) = h2;
         // marginal sums from the unsplit values: this thread's 8 entries of output row `am`
         msum += ((ea[0] + ea[1]) + (ea[2] + ea[3])) + ((ea[4] + ea[5]) + (ea[6] + ea[7]));
     };
     // the matrix-core work of one chunk, added to the total with the chunk's scale undone
-    auto contract = [&](float ismax) {
+    auto contract = [&](int buf, float ismax) {
         const int ar = (wr * 32 + (lane & 31)) * kGradHalfRow, br = (wc * 32 + (lane & 31)) * kGradHalfRow;
         const int kh = (lane >> 5) * 8;
         floatx16 part = zero;
 #pragma unroll
         for (int ks = 0; ks < kBlk; ks += 16) {
-            const half8 a1 = *reinterpret_cast<const half8 *>(&Ah[0][ar + ks + kh]);
-            const half8 a2 = *reinterpret_cast<const half8 *>(&Ah[1][ar + ks + kh]);
-            const half8 b1 = *reinterpret_cast<const half8 *>(&Bh[0][br + ks + kh]);
-            const half8 b2 = *reinterpret_cast<const half8 *>(&Bh[1][br + ks + kh]);
+            const half8 a1 = *reinterpret_cast<const half8 *>(&Ah[buf][0][ar + ks + kh]);
+            const half8 a2 = *reinterpret_cast<const half8 *>(&Ah[buf][1][ar + ks + kh]);
+            const half8 b1 = *reinterpret_cast<const half8 *>(&Bh[buf][0][br + ks + kh]);
+            const half8 b2 = *reinterpret_cast<const half8 *>(&Bh[buf][1][br + ks + kh]);
             part = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, b1, part, 0, 0, 0);
             part = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, b2, part, 0, 0, 0);
             part = __builtin_amdgcn_mfma_f32_32x32x16_f16(a2, b1, part, 0, 0, 0);
@@ -600,13 +606,22 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
             own_v[i] = (m < Pl && n < p.D) ? own[(size_t)m * p.D + n] : 0.f;
         }
     }
+    const unsigned first_bits = tid < min(nchunk, kLiveCap) ? chunk_flags(tid * kBlk) : 0u;
+    if (refused) {
+        const float qnan = __builtin_nanf("");
+        for (int e = tid; e < 64 * 64; e += 256) {
+            const int m = m0 + (e >> 6), n = n0 + (e & 63);
+            if (m < P && n < p.D) out[(size_t)m * p.D + n] = qnan;
+        }
+        return;
+    }
     float ea0[8], bv0[8], ea1[8], bv1[8], is0 = 1.f, is1 = 1.f;
     for (int base = 0; base < nchunk; base += kLiveCap) {
         const int lim = min(nchunk, base + kLiveCap);
         int nlive = 0;
         for (int g = base, round = 0; g < lim; g += 256, ++round) {
             const int c = g + tid;
-            const unsigned bits = c < lim ? chunk_flags(c * kBlk) : 0u;
+            const unsigned bits = g == 0 ? first_bits : (c < lim ? chunk_flags(c * kBlk) : 0u);
             const bool lv = bits != 0;
             const unsigned long long m = __ballot(lv);
             if (lane == 0) wave_mask[round & 1][w] = m;
@@ -626,21 +641,21 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
         int i = 0;
         if (nlive > 0) fetch(live_list[0], ea0, bv0, is0);
         if (nlive > 1) fetch(live_list[1], ea1, bv1, is1);
+        // (two LDS buffers, one barrier per chunk: a buffer is written again two chunks later, after
+        // the barrier of the chunk in between, by when every wavefront is done reading it)
         while (i < nlive) {
-            __syncthreads();  // previous chunk's reads are done
-            stash(ea0, bv0, is0);
+            stash(0, ea0, bv0, is0);
             const float isc0 = is0;
             __syncthreads();
             if (i + 2 < nlive) fetch(live_list[i + 2], ea0, bv0, is0);
-            contract(isc0);
+            contract(0, isc0);
             if (++i >= nlive) break;
 
-            __syncthreads();
-            stash(ea1, bv1, is1);
+            stash(1, ea1, bv1, is1);
             const float isc1 = is1;
             __syncthreads();
             if (i + 2 < nlive) fetch(live_list[i + 2], ea1, bv1, is1);
-            contract(isc1);
+            contract(1, isc1);
             ++i;
         }
         __syncthreads();  // the list is rebuilt next
