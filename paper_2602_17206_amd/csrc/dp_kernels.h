@@ -801,6 +801,11 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
             const int jn = (sg + 1) * kBlk + lane;
             const bool need_n = has_above && lane < kBlk && jn < M;
             const float *rd = my_ring + (sg & 3) * kBlk;
+            // the macro-step's 32 cost values, read in one batch: read one per step they sit between the
+            // steps' LDS stores, which they may not overtake, and each costs the chain a wait
+            float dcv[kBlk];
+#pragma unroll
+            for (int u = 0; u < kBlk; ++u) dcv[u] = rd[u];
             // The row above, column 32*sg + u at step u: from the incoming boundary values, or from
             // the hand-over ring, where the band above put column c at slot (c + 63) mod 128.
             const double *top0 = top, *top1 = top + 1;  // step 0, steps 1..31
@@ -824,7 +829,7 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
                     // is needed: asked earlier, the answer would be "not written yet" too often
                     if (u == kPeekStep && has_above) nxt_bits = peek_boundary(brow_in, jn, need_n);
                     const double up = lane_shr1(left, u == 0 ? top0[0] : top1[u - 1]);  // R[i-1][j]; lane 0 takes the row above the band
-                    const float dc = rd[u];
+                    const float dc = dcv[u];
                     double m;
                     float L;
                     softmin3_parts(diag, up, left, m, L);
@@ -1286,12 +1291,22 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
                     }
                 }
             }
+            // (small problems: the macro-step's 32 cost values in one batch, as in the forward sweep)
+            [[maybe_unused]] float dcv[TSWEEP ? kBlk : 1];
+            if constexpr (TSWEEP) {
+#pragma unroll
+                for (int u = 0; u < kBlk; ++u) dcv[u] = rd[u];
+            }
             auto steps = [&](auto corner, auto alive) {
 #pragma unroll
             for (int u = kBlk - 1; u >= 0; --u) {
                 if (u == kBlk - 1 - kPeekStep && has_below) nxt_bits = peek_boundary(brow_in, jn, need_n);
                 const double down = lane_shl1(right, u == kBlk - 1 ? bot31[0] : bot0[u]);  // T[i+1][j]; lane 63 takes the row below the band
-                const float dc = rd[u];
+                float dc;
+                if constexpr (TSWEEP)
+                    dc = dcv[u];
+                else
+                    dc = rd[u];
                 const double dg = (decltype(corner)::value && sbase + u == s_corner) ? 0.0 : diag;
                 double m;
                 float L;
