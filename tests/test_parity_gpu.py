@@ -298,6 +298,27 @@ def test_backward_twice_after_one_forward_gives_the_same_result():
         assert binding.workspace_status(ws) == 0
         assert torch.equal(dx1, dx2) and torch.equal(dy1, dy2)
 
+@pytest.mark.parametrize("mode", ["unfused", "fused"])
+@pytest.mark.parametrize("B,N,M,D,gamma,scale", [
+    (2, 1, 5000, 8, 0.1, 1.0),        # a single row, 157 macro-steps
+    (2, 5000, 1, 8, 0.1, 1.0),        # a single column, 79 bands
+    (1, 3000, 7, 1, 1.0, 1.0),        # one feature
+    (2, 200, 200, 16, 1e-3, 1.0),     # gamma far below the costs: E is a single path
+    (2, 200, 200, 16, 100.0, 1.0),    # gamma far above them: E spreads over the whole grid
+    (2, 128, 128, 128, 0.1, 100.0),   # inputs of magnitude 100 (costs ~ 2.5e6) ...
+    (2, 128, 128, 128, 0.1, 1e-3),    # ... and of magnitude 0.001
+    (70, 64, 64, 128, 0.1, 1.0),      # more pairs than fit one round of workgroups of a band
+])
+def test_extreme_shapes_and_magnitudes(mode, B, N, M, D, gamma, scale):
+    say("extreme %s B=%d N=%d M=%d D=%d gamma=%g scale=%g" % (mode, B, N, M, D, gamma, scale))
+    x, y = workloads.normal_pairs(777 + N + M + D, B, N, M, D)
+    x, y = (x * scale).astype(np.float32), (y * scale).astype(np.float32)
+    ref = oracle.batch(x, y, gamma, want_E=False)
+    got = run_gpu(x, y, gamma, MODES[mode], want_E=False)
+    check_against(ref, got, what="extreme %s" % mode)
+    assert np.all(np.isfinite(got["dx"])) and np.all(np.isfinite(got["dy"]))
+
+
 @pytest.mark.parametrize("ragged", [False, True])
 @pytest.mark.parametrize("N,M", [(33, 257), (97, 288), (64, 289), (130, 320), (65, 321), (32, 225)])
 def test_alignment_at_the_row_length_limits(N, M, ragged):
