@@ -753,6 +753,9 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
     }
 
     // ---------------------------------------------------------------------- consumer wavefront
+    // The chain of dependent steps is what everything waits for: where this wavefront shares its SIMD
+    // with producers, its instructions go first.
+    __builtin_amdgcn_s_setprio(3);
     // CH: -1 = both neighbouring bands are reached through memory; 0 = the band below is the other
     // band of this workgroup (edge values go to the LDS hand-over ring); 1 = the band above is.
     // (Separate instances, so that each one reads and writes distinct LDS objects.)
@@ -1166,6 +1169,9 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
     }
 
     // ---------------------------------------------------------------------- consumer wavefront
+    // The chain of dependent steps is what everything waits for: where this wavefront shares its SIMD
+    // with producers, its instructions go first.
+    __builtin_amdgcn_s_setprio(3);
     // CH: -1 = both neighbouring bands are reached through memory; 0 = the band above is the other
     // band of this workgroup (this band's first row goes to the LDS hand-over ring); 1 = the band
     // below is.
