@@ -1420,13 +1420,27 @@ __device__ __forceinline__ void live_columns(const Params &p, int b, int k, int 
     const int row0 = k * kBandRows;
     const int jlo = p.window < kNoWindow ? max(0, row0 - p.window - 1) : 0;
     const int jhi = p.window < kNoWindow ? min(Ml - 1, row0 + kBandRows + p.window) : Ml - 1;
+    // (kScan iterations' loads are asked for together: one memory round trip per 64*kScan columns, not per 64)
+    constexpr int kScan = 8;
     first = jlo;
     if (k > 0) {
         int f = Ml;
-        for (int j = jlo + lane; j <= jhi; j += kBandRows) {
-            const double ra = row(p.brow, k - 1, j), rb = j > 0 ? row(p.brow, k - 1, j - 1) : kBig;
-            const double term = (Rfin - row(p.brow_b, k, j)) - min_f64(ra, rb) + 1.0;
-            if (term > thr) f = min(f, j);
+        for (int j0 = jlo + lane; j0 <= jhi; j0 += kBandRows * kScan) {
+            double ra[kScan], rb[kScan], tq[kScan];
+#pragma unroll
+            for (int i = 0; i < kScan; ++i) {
+                const int j = j0 + i * kBandRows;
+                const bool in = j <= jhi;
+                ra[i] = in ? row(p.brow, k - 1, j) : kBig;
+                rb[i] = (in && j > 0) ? row(p.brow, k - 1, j - 1) : kBig;
+                tq[i] = in ? row(p.brow_b, k, j) : kBig;
+            }
+#pragma unroll
+            for (int i = 0; i < kScan; ++i) {
+                const int j = j0 + i * kBandRows;
+                const double term = (Rfin - tq[i]) - min_f64(ra[i], rb[i]) + 1.0;
+                if (j <= jhi && term > thr) f = min(f, j);
+            }
         }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) f = min(f, __shfl_xor(f, o));
@@ -1435,10 +1449,22 @@ __device__ __forceinline__ void live_columns(const Params &p, int b, int k, int 
     last = jhi;
     if (k != (Nl - 1) / kBandRows && k + 1 < p.nbands) {
         int l = -1;
-        for (int j = jlo + lane; j <= jhi; j += kBandRows) {
-            const double ta = row(p.brow_b, k + 1, j), tb = j + 1 < Ml ? row(p.brow_b, k + 1, j + 1) : kBig;
-            const double term = (Rfin - row(p.brow, k, j)) - min_f64(ta, tb) + 1.0;
-            if (term > thr) l = max(l, j);
+        for (int j0 = jlo + lane; j0 <= jhi; j0 += kBandRows * kScan) {
+            double ta[kScan], tb[kScan], rq[kScan];
+#pragma unroll
+            for (int i = 0; i < kScan; ++i) {
+                const int j = j0 + i * kBandRows;
+                const bool in = j <= jhi;
+                ta[i] = in ? row(p.brow_b, k + 1, j) : kBig;
+                tb[i] = (in && j + 1 < Ml) ? row(p.brow_b, k + 1, j + 1) : kBig;
+                rq[i] = in ? row(p.brow, k, j) : kBig;
+            }
+#pragma unroll
+            for (int i = 0; i < kScan; ++i) {
+                const int j = j0 + i * kBandRows;
+                const double term = (Rfin - rq[i]) - min_f64(ta[i], tb[i]) + 1.0;
+                if (j <= jhi && term > thr) l = max(l, j);
+            }
         }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) l = max(l, __shfl_xor(l, o));
