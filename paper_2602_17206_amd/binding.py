@@ -73,6 +73,11 @@ def load_library():
         raise RuntimeError(
             "libsdtw_hip.so is missing at %s: run `python -c 'import __graft_entry__ as g; g.build()'` "
             "from the repository root" % _LIB_PATH)
+    # PyTorch first: its wheel brings a HIP runtime of its own, and the tensors this binding hands over
+    # live in that runtime.  Loaded after it, this library binds to the same one; loaded before it, the
+    # process would end up with two (the calls then fail with a HIP runtime error).
+    import torch  # noqa: F401
+
     lib = ctypes.CDLL(_LIB_PATH)
     vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
     lib.sdtw_version.restype = i32

@@ -30,6 +30,20 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert "bandwidth" in pkg.sdtw_status_string(binding.STATUS_UNSUPPORTED)
 
 
+def test_the_binding_loads_pytorch_before_the_library():
+    # PyTorch's wheel carries a HIP runtime of its own; the library must bind to that one (the one the
+    # tensors live in), which it does when it is loaded second.  A fresh interpreter that touches the
+    # binding first must therefore find torch imported by the time the library is.
+    import subprocess
+    import sys
+
+    code = ("import sys; import paper_2602_17206_amd as pkg; assert 'torch' not in sys.modules; "
+            "pkg.sdtw_version(); assert 'torch' in sys.modules; print('ok')")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, "-c", code], cwd=root, capture_output=True, text=True, timeout=300)
+    assert out.returncode == 0 and out.stdout.strip() == "ok", out.stderr[-2000:]
+
+
 def test_struct_sizes_match_the_header_layout():
     assert ctypes.sizeof(binding.Desc) == 48
     assert ctypes.sizeof(binding.BaryDesc) == 48
