@@ -434,58 +434,18 @@ template <int KG, int CB> constexpr int cost_lds_bytes()
     return operands > stage ? operands : stage;
 }
 
+// Second half of both cost-tensor kernels: the tile's inner products on the matrix cores, the cost
+// from them (Sec. 4.3 Eq. 8), and the stores.  xa: the wavefront's 32 rows of x as operand pieces,
+// xn_r / m2is_r: ||x||^2 and -2/scale of the 16 rows a lane's accumulator entries belong to, ys /
+// ytab: the tile's columns of y in LDS (pieces; norm and 1/scale), lds: the same memory, reused for
+// the stores once every wavefront has passed the barrier in here.
 template <int KG, int CB>
-__global__ __launch_bounds__(256) void cost_tensor_half_kernel(Params p)
+__device__ __forceinline__ void cost_tile_finish(const Params &p, const half8 (&xa)[2][KG], const float (&xn_r)[16],
+                                                 const float (&m2is_r)[16], const _Float16 *ys, const float2 *ytab,
+                                                 unsigned char *lds, int b, int i0, int jbase, bool rows_live, int lane,
+                                                 int w, int h)
 {
     constexpr int kCol = cost_col_halfs<KG>();
-    __shared__ __attribute__((aligned(16))) unsigned char lds[cost_lds_bytes<KG, CB>()];
-    __shared__ float2 ytab[32 * CB];  // (||y_j||^2, 1/scale_j)
-    _Float16 *ys = reinterpret_cast<_Float16 *>(lds);
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, h = lane >> 5;
-    const int b = blockIdx.z;
-    const int i0 = blockIdx.y * 128 + w * 32;
-    const uint16_t *xh = p.xh + b * p.xh_stride, *yh = p.yh + b * p.yh_stride;
-    const float *xnb = p.xn + b * p.xn_stride, *ynb = p.yn + b * p.yn_stride;
-    const float *xisb = p.xis + b * p.xn_stride, *yisb = p.yis + b * p.yn_stride;
-    const int jbase = blockIdx.x * (32 * CB);
-    {   // no cell of the 128 x 32*CB tile inside the window: nothing to compute (the sweeps never read it)
-        const int ti0 = blockIdx.y * 128;
-        if (jbase - (ti0 + 127) > p.window || ti0 - (jbase + 32 * CB - 1) > p.window) return;
-    }
-
-    // y pieces of the tile's columns -> LDS: a column is 4*KG chunks of 16 bytes
-    constexpr int kChunks = 4 * KG;
-    for (int e = tid; e < 32 * CB * kChunks; e += 256) {
-        const int c = e / kChunks, ch = e % kChunks;
-        const int colc = min(jbase + c, p.M - 1);
-        const half8 v = *reinterpret_cast<const half8 *>(yh + (size_t)colc * (2 * p.Dp) + 8 * ch);
-        *reinterpret_cast<half8 *>(&ys[c * kCol + 8 * ch]) = v;
-    }
-    if (tid < 32 * CB) {
-        const int colc = min(jbase + tid, p.M - 1);
-        ytab[tid] = make_float2(ynb[colc], yisb[colc]);
-    }
-    // own rows' pieces -> registers
-    half8 xa[2][KG];
-    float xn_r[16], m2is_r[16];
-    const bool rows_live = i0 < p.N;
-    {
-        const int row = min(i0 + (lane & 31), p.N - 1);
-        const uint16_t *r = xh + (size_t)row * (2 * p.Dp) + 8 * h;
-#pragma unroll
-        for (int g = 0; g < KG; ++g) {
-            xa[0][g] = *reinterpret_cast<const half8 *>(r + 32 * g);
-            xa[1][g] = *reinterpret_cast<const half8 *>(r + 32 * g + 16);
-        }
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int rr = min(i0 + acc_row(i, lane), p.N - 1);
-            xn_r[i] = xnb[rr];
-            m2is_r[i] = -2.0f * xisb[rr];
-        }
-    }
-    __syncthreads();
-
     float *dst = p.cost + (size_t)b * p.N * p.M;
     floatx16 acc[CB];
 #pragma unroll
@@ -545,6 +505,200 @@ __global__ __launch_bounds__(256) void cost_tensor_half_kernel(Params p)
         if (row < p.N && col < p.M)
             __builtin_nontemporal_store(v, reinterpret_cast<floatx4 *>(&dst[(size_t)row * p.M + col]));
     }
+}
+
+template <int KG, int CB>
+__global__ __launch_bounds__(256) void cost_tensor_half_kernel(Params p)
+{
+    constexpr int kCol = cost_col_halfs<KG>();
+    __shared__ __attribute__((aligned(16))) unsigned char lds[cost_lds_bytes<KG, CB>()];
+    __shared__ float2 ytab[32 * CB];  // (||y_j||^2, 1/scale_j)
+    _Float16 *ys = reinterpret_cast<_Float16 *>(lds);
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, h = lane >> 5;
+    const int b = blockIdx.z;
+    const int i0 = blockIdx.y * 128 + w * 32;
+    const uint16_t *xh = p.xh + b * p.xh_stride, *yh = p.yh + b * p.yh_stride;
+    const float *xnb = p.xn + b * p.xn_stride, *ynb = p.yn + b * p.yn_stride;
+    const float *xisb = p.xis + b * p.xn_stride, *yisb = p.yis + b * p.yn_stride;
+    const int jbase = blockIdx.x * (32 * CB);
+    {   // no cell of the 128 x 32*CB tile inside the window: nothing to compute (the sweeps never read it)
+        const int ti0 = blockIdx.y * 128;
+        if (jbase - (ti0 + 127) > p.window || ti0 - (jbase + 32 * CB - 1) > p.window) return;
+    }
+
+    // y pieces of the tile's columns -> LDS: a column is 4*KG chunks of 16 bytes
+    constexpr int kChunks = 4 * KG;
+    for (int e = tid; e < 32 * CB * kChunks; e += 256) {
+        const int c = e / kChunks, ch = e % kChunks;
+        const int colc = min(jbase + c, p.M - 1);
+        const half8 v = *reinterpret_cast<const half8 *>(yh + (size_t)colc * (2 * p.Dp) + 8 * ch);
+        *reinterpret_cast<half8 *>(&ys[c * kCol + 8 * ch]) = v;
+    }
+    if (tid < 32 * CB) {
+        const int colc = min(jbase + tid, p.M - 1);
+        ytab[tid] = make_float2(ynb[colc], yisb[colc]);
+    }
+    // own rows' pieces -> registers
+    half8 xa[2][KG];
+    float xn_r[16], m2is_r[16];
+    const bool rows_live = i0 < p.N;
+    {
+        const int row = min(i0 + (lane & 31), p.N - 1);
+        const uint16_t *r = xh + (size_t)row * (2 * p.Dp) + 8 * h;
+#pragma unroll
+        for (int g = 0; g < KG; ++g) {
+            xa[0][g] = *reinterpret_cast<const half8 *>(r + 32 * g);
+            xa[1][g] = *reinterpret_cast<const half8 *>(r + 32 * g + 16);
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int rr = min(i0 + acc_row(i, lane), p.N - 1);
+            xn_r[i] = xnb[rr];
+            m2is_r[i] = -2.0f * xisb[rr];
+        }
+    }
+    __syncthreads();
+
+    cost_tile_finish<KG, CB>(p, xa, xn_r, m2is_r, ys, ytab, lds, b, i0, jbase, rows_live, lane, w, h);
+}
+
+// The same with the start of the forward call folded in (unfused mode without band constraint or
+// length vectors, rows of 16-byte aligned float4): one launch instead of forward_prep_kernel and
+// cost_tensor_half_kernel, which for small problems are two chains of memory round trips of about
+// equal length.  Every workgroup makes the norms, scales and split-half pieces of its own 128 rows
+// of x (in registers, already in the layout of the matrix operand) and of its 32*CB rows of y (into
+// LDS) from x and y themselves - the rows of a tile are split again by every tile that shares them,
+// which costs less than the launch it saves - and the workgroups of the first tile column / row also
+// leave them in the workspace for the later kernels.  Header, tickets and the "not written yet"
+// marks of the boundary rows are spread over all workgroups.
+template <int KG, int CB>
+__global__ __launch_bounds__(256) void cost_tensor_prep_kernel(Params p)
+{
+    constexpr int kCol = cost_col_halfs<KG>();
+    constexpr int kDp = 16 * KG;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[cost_lds_bytes<KG, CB>()];
+    __shared__ float2 ytab[32 * CB];  // (||y_j||^2, 1/scale_j)
+    __shared__ float2 xtab[128];      // (||x_i||^2, -2/scale_i) of the tile's rows
+    _Float16 *ys = reinterpret_cast<_Float16 *>(lds);
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, h = lane >> 5;
+    const int b = blockIdx.z;
+    const int i0 = blockIdx.y * 128 + w * 32;
+    const int jbase = blockIdx.x * (32 * CB);
+    const float *xb = p.x + b * p.x_stride, *yb = p.y + b * p.y_stride;
+
+    // start of the call
+    const size_t nblk = (size_t)gridDim.x * gridDim.y * gridDim.z;
+    const size_t blk = ((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+    if (tid == 0 && blk == 0) stamp_header(p);
+    fill_boundary_rows(p, p.brow, false, blk, nblk);
+    if (p.two_sweep) fill_boundary_rows(p, p.brow_b, true, blk, nblk);
+
+    // (the loads of the x rows are asked for together with those of the y rows: one round trip for both)
+    const int xr_row = min(i0 + (lane & 31), p.N - 1);
+    float xv[KG][8];
+    {
+        const float *xr = xb + (size_t)xr_row * p.D;
+#pragma unroll
+        for (int g = 0; g < KG; ++g) {
+            const int k = 16 * g + 8 * h;
+            float4 a = make_float4(0.f, 0.f, 0.f, 0.f), c = a;
+            if (k < p.D) a = *reinterpret_cast<const float4 *>(xr + k);
+            if (k + 4 < p.D) c = *reinterpret_cast<const float4 *>(xr + k + 4);
+            xv[g][0] = a.x; xv[g][1] = a.y; xv[g][2] = a.z; xv[g][3] = a.w;
+            xv[g][4] = c.x; xv[g][5] = c.y; xv[g][6] = c.z; xv[g][7] = c.w;
+        }
+    }
+    // y rows of the tile's columns, one block of 32 per wavefront (wavefront w takes blocks w, w+4, ...):
+    // like the x rows, half a row per lane, so that a row's maximum and norm take one exchange
+    for (int cbk = w; cbk < CB; cbk += 4) {
+        const int c = cbk * 32 + (lane & 31);
+        const int col = min(jbase + c, p.M - 1);
+        const float *yr = yb + (size_t)col * p.D;
+        float yv[KG][8];
+#pragma unroll
+        for (int g = 0; g < KG; ++g) {
+            const int k = 16 * g + 8 * h;
+            float4 a = make_float4(0.f, 0.f, 0.f, 0.f), c2 = a;
+            if (k < p.D) a = *reinterpret_cast<const float4 *>(yr + k);
+            if (k + 4 < p.D) c2 = *reinterpret_cast<const float4 *>(yr + k + 4);
+            yv[g][0] = a.x; yv[g][1] = a.y; yv[g][2] = a.z; yv[g][3] = a.w;
+            yv[g][4] = c2.x; yv[g][5] = c2.y; yv[g][6] = c2.z; yv[g][7] = c2.w;
+        }
+        float acc = 0.f, mx = 0.f;
+#pragma unroll
+        for (int g = 0; g < KG; ++g)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                acc = fmaf(yv[g][e], yv[g][e], acc);
+                mx = fmaxf(mx, fabsf(yv[g][e]));
+            }
+        acc += __shfl_xor(acc, 32);  // the other half of the row
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        float sc, inv;
+        split_scale(mx, sc, inv);
+        if (h == 0) ytab[c] = make_float2(acc, inv);
+        const bool owner = blockIdx.y == 0 && jbase + c < p.M;  // leaves them in the workspace
+        if (owner && h == 0) {
+            p.yn[b * p.yn_stride + col] = acc;
+            p.yis[b * p.yn_stride + col] = inv;
+        }
+        uint16_t *dsth = p.yh + b * p.yh_stride + (size_t)col * (2 * kDp) + 8 * h;
+#pragma unroll
+        for (int g = 0; g < KG; ++g) {
+            half8 h1, h2;
+            split8(yv[g], sc, h1, h2);
+            *reinterpret_cast<half8 *>(&ys[c * kCol + 32 * g + 8 * h]) = h1;  // [group of 16 features][piece][16]
+            *reinterpret_cast<half8 *>(&ys[c * kCol + 32 * g + 8 * h + 16]) = h2;
+            if (owner) {
+                *reinterpret_cast<half8 *>(dsth + 32 * g) = h1;
+                *reinterpret_cast<half8 *>(dsth + 32 * g + 16) = h2;
+            }
+        }
+    }
+    // own rows of x, straight into the operand layout: lane (r, h) holds features 16g+8h .. +7 of row r
+    half8 xa[2][KG];
+    const bool rows_live = i0 < p.N;
+    {
+        const int r = lane & 31;
+        const int row = xr_row;
+        float acc = 0.f, mx = 0.f;
+#pragma unroll
+        for (int g = 0; g < KG; ++g)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                acc = fmaf(xv[g][e], xv[g][e], acc);
+                mx = fmaxf(mx, fabsf(xv[g][e]));
+            }
+        acc += __shfl_xor(acc, 32);  // the other half of the row
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        float sc, inv;
+        split_scale(mx, sc, inv);
+#pragma unroll
+        for (int g = 0; g < KG; ++g) split8(xv[g], sc, xa[0][g], xa[1][g]);
+        if (h == 0) xtab[w * 32 + r] = make_float2(acc, -2.0f * inv);
+        if (blockIdx.x == 0 && i0 + r < p.N) {  // this tile column leaves them in the workspace
+            if (h == 0) {
+                p.xn[b * p.xn_stride + row] = acc;
+                p.xis[b * p.xn_stride + row] = inv;
+            }
+            uint16_t *dsth = p.xh + b * p.xh_stride + (size_t)row * (2 * kDp) + 8 * h;
+#pragma unroll
+            for (int g = 0; g < KG; ++g) {
+                *reinterpret_cast<half8 *>(dsth + 32 * g) = xa[0][g];
+                *reinterpret_cast<half8 *>(dsth + 32 * g + 16) = xa[1][g];
+            }
+        }
+    }
+    __syncthreads();
+    float xn_r[16], m2is_r[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const float2 t = xtab[w * 32 + acc_row(i, lane)];
+        xn_r[i] = t.x;
+        m2is_r[i] = t.y;
+    }
+
+    cost_tile_finish<KG, CB>(p, xa, xn_r, m2is_r, ys, ytab, lds, b, i0, jbase, rows_live, lane, w, h);
 }
 
 // ---------------------------------------------------------------------------------------------

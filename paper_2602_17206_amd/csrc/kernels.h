@@ -14,16 +14,18 @@ constexpr int kStatusTimeout = 6;  // SDTW_ERR_TIMEOUT
 // value.  With a band constraint a sweep skips the macro-steps outside the window; the columns it
 // never publishes (forward: the band's last row, columns 32*lo-63 .. 32*hi-32; reverse: its first
 // row, columns 32*lo .. 32*hi+31) lie outside the window and hold kBig from the start.
-__device__ __forceinline__ void fill_boundary_rows(const Params &p, unsigned long long *rows, bool reverse)
+// (blk of nblk: this workgroup's number among those of the launch that share the filling)
+__device__ __forceinline__ void fill_boundary_rows(const Params &p, unsigned long long *rows, bool reverse, size_t blk,
+                                                   size_t nblk)
 {
     const size_t n = (size_t)p.B * p.nbands * p.M;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    const size_t stride = nblk * blockDim.x;
     if (p.window >= kNoWindow && p.x_len == nullptr && p.y_len == nullptr) {
-        for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) rows[i] = kSentinel;
+        for (size_t i = blk * blockDim.x + threadIdx.x; i < n; i += stride) rows[i] = kSentinel;
         return;
     }
     const unsigned long long big = (unsigned long long)__double_as_longlong(kBig);
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+    for (size_t i = blk * blockDim.x + threadIdx.x; i < n; i += stride) {
         const int j = (int)(i % (size_t)p.M);
         const int k = (int)((i / (size_t)p.M) % (size_t)p.nbands);
         const int b = (int)(i / ((size_t)p.M * (size_t)p.nbands));
@@ -38,25 +40,40 @@ __device__ __forceinline__ void fill_boundary_rows(const Params &p, unsigned lon
 // Start of a forward call, one launch: stamps the header, resets the band tickets, marks every
 // boundary value "not written yet", and computes the squared row norms ||x_i||^2, ||y_j||^2
 // (Sec. 4.3: the norms are computed once; one wavefront per row, lanes stride over the features).
+// The header of a workspace at the start of a forward call (one thread).
+__device__ __forceinline__ void stamp_header(const Params &p)
+{
+    Header *h = p.hdr;
+    h->magic = kMagic;
+    h->B = p.B; h->N = p.N; h->M = p.M; h->D = p.D; h->mode = p.mode;
+    h->gamma_bits = __float_as_uint(p.gamma);
+    h->forward_done = 1;
+    h->two_sweep = p.two_sweep;
+    h->window = p.window;
+    h->x_len_ptr = reinterpret_cast<uint64_t>(p.x_len);
+    h->y_len_ptr = reinterpret_cast<uint64_t>(p.y_len);
+    h->status = 0;
+    h->abort_backward = 0;
+    h->fwd_ticket = 0;
+    h->bwd_ticket = 0;
+}
+
+// The power of two a row is scaled by before it is split into float16 pieces (largest element in
+// [2^13, 2^14)), and its reciprocal.
+__device__ __forceinline__ void split_scale(float mx, float &sc, float &inv)
+{
+    int ex = 0;
+    if (mx > 0.f) (void)frexpf(mx, &ex);
+    ex = max(-100, min(ex, 120));
+    sc = ldexpf(1.0f, 14 - ex);
+    inv = ldexpf(1.0f, ex - 14);
+}
+
 __global__ __launch_bounds__(256) void forward_prep_kernel(Params p, int64_t xrows, int64_t yrows)
 {
-    if (threadIdx.x == 0 && blockIdx.x == 0) {
-        Header *h = p.hdr;
-        h->magic = kMagic;
-        h->B = p.B; h->N = p.N; h->M = p.M; h->D = p.D; h->mode = p.mode;
-        h->gamma_bits = __float_as_uint(p.gamma);
-        h->forward_done = 1;
-        h->two_sweep = p.two_sweep;
-        h->window = p.window;
-        h->x_len_ptr = reinterpret_cast<uint64_t>(p.x_len);
-        h->y_len_ptr = reinterpret_cast<uint64_t>(p.y_len);
-        h->status = 0;
-        h->abort_backward = 0;
-        h->fwd_ticket = 0;
-        h->bwd_ticket = 0;
-    }
-    fill_boundary_rows(p, p.brow, false);
-    if (p.two_sweep) fill_boundary_rows(p, p.brow_b, true);  // the reverse sweep runs in the same call
+    if (threadIdx.x == 0 && blockIdx.x == 0) stamp_header(p);
+    fill_boundary_rows(p, p.brow, false, blockIdx.x, gridDim.x);
+    if (p.two_sweep) fill_boundary_rows(p, p.brow_b, true, blockIdx.x, gridDim.x);  // the reverse sweep runs in the same call
     const int lane = threadIdx.x & 63;
     const int64_t rows = xrows + yrows;
     const int64_t stride = (int64_t)gridDim.x * 4;
@@ -230,7 +247,7 @@ __global__ __launch_bounds__(256) void backward_prep_kernel(Params p)
             h->status = kStatusState;
         }
     }
-    fill_boundary_rows(p, p.brow_b, true);
+    fill_boundary_rows(p, p.brow_b, true, blockIdx.x, gridDim.x);
     // with a band constraint the sweep never visits the blocks of E outside the window: their
     // "any non-zero" flags are cleared here
     if (p.window < kNoWindow || p.x_len != nullptr || p.y_len != nullptr) {

@@ -244,19 +244,28 @@ int forward_impl(const sdtw_desc *d, const float *x, const float *y, float *valu
 {
     const Layout L = layout_of(d);
     const Params p = make_params(d, L, x, y, ws, x_len, y_len);
-    {
+    // Unfused mode, small problems: the start of the call is folded into the cost-tensor kernel (one
+    // launch instead of two).  Not with a band constraint or length vectors (tiles outside them are
+    // skipped), not without 16-byte rows, and only where the tiles are few (fewer than 512 of 128 x 128):
+    // with more, splitting the rows again in every tile costs more than the launch (measured at
+    // N = M = 1024, B = 32: 89 us against 19 + 65).
+    const size_t tiles128 = (size_t)((d->M + 127) / 128) * ((d->N + 127) / 128) * d->B;
+    const bool folded = d->mode == SDTW_UNFUSED && L.Dp > 0 && p.vec_d4 && p.window >= kNoWindow && !x_len && !y_len &&
+                        tiles128 < 512;
+    if (!folded) {
         ProfScope ps("forward_prep", st);
         forward_prep_kernel<<<prep_grid(p, L.xn_count + L.yn_count), 256, 0, st>>>(p, L.xn_count, L.yn_count);
     }
     if (d->mode == SDTW_UNFUSED) {
         ProfScope ps("cost_tensor", st);
         // 128 x 128 tiles, or 128 x 64 when those would leave most of the chip idle
-        const size_t tiles128 = (size_t)((d->M + 127) / 128) * ((d->N + 127) / 128) * d->B;
         const bool narrow = tiles128 < 512;
         dim3 gh(narrow ? (d->M + 63) / 64 : (d->M + 127) / 128, (d->N + 127) / 128, d->B);
         auto launch = [&](auto kg) {
             constexpr int KG = decltype(kg)::value;
-            if (narrow)
+            if (folded)
+                cost_tensor_prep_kernel<KG, 2><<<gh, 256, 0, st>>>(p);
+            else if (narrow)
                 cost_tensor_half_kernel<KG, 2><<<gh, 256, 0, st>>>(p);
             else
                 cost_tensor_half_kernel<KG, 4><<<gh, 256, 0, st>>>(p);

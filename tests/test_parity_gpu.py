@@ -249,8 +249,10 @@ def test_fused_equals_unfused_to_rounding():
     x, y = workloads.normal_pairs(5, 4, 120, 140, 32)
     a = run_gpu(x, y, 0.1, pkg.UNFUSED)
     b = run_gpu(x, y, 0.1, pkg.FUSED)
+    # (the two modes sum the squared norms in different orders: the costs differ by an ulp here and
+    # there, 4e-6 at d ~ 64, which over gamma = 0.1 is a few 1e-5 relative in E)
     np.testing.assert_allclose(a["value"], b["value"], rtol=1e-6)
-    np.testing.assert_allclose(a["E"], b["E"], atol=1e-5)
+    np.testing.assert_allclose(a["E"], b["E"], atol=5e-5)
     np.testing.assert_allclose(a["dx"], b["dx"], atol=1e-4 * np.abs(a["dx"]).max())
 
 
