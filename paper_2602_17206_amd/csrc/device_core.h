@@ -40,6 +40,23 @@ __device__ __forceinline__ float wave_min_f32(float v)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
+// the same for the maximum
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ float dpp_max_step(float v)
+{
+    const int moved = __builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, ROW_MASK, 0xf, false);
+    return fmaxf(v, __int_as_float(moved));
+}
+__device__ __forceinline__ float wave_max_f32(float v)
+{
+    v = dpp_max_step<0x111, 0xf>(v);
+    v = dpp_max_step<0x112, 0xf>(v);
+    v = dpp_max_step<0x114, 0xf>(v);
+    v = dpp_max_step<0x118, 0xf>(v);
+    v = dpp_max_step<0x142, 0xa>(v);
+    v = dpp_max_step<0x143, 0xc>(v);
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
 __device__ __forceinline__ double lane_shr1(double v, double fill)
 {
     int lo = lane_shr1_i32(__double2loint(v), __double2loint(fill));

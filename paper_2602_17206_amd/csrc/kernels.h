@@ -503,13 +503,9 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
     const bool refused = backward_refused(p);
 
     const float sA = 1024.0f;
-    // the largest 1/scale among the chunk's 32 rows: one row per lane (mod 32), then a butterfly
-    auto chunk_ismax = [&](int q0) {
-        unsigned mx = oth_is[min(q0 + (lane & 31), Ql - 1)];
-#pragma unroll
-        for (int o = 16; o > 0; o >>= 1) mx = max(mx, (unsigned)__shfl_xor((int)mx, o));
-        return __uint_as_float(mx);
-    };
+    // the largest 1/scale among the chunk's 32 rows: one row per lane (mod 32; both halves of the
+    // wavefront hold the same 32), then the maximum over the wavefront by lane shifts
+    auto chunk_ismax = [&](int q0) { return wave_max_f32(__uint_as_float(oth_is[min(q0 + (lane & 31), Ql - 1)])); };
 
     const float *Eb = p.E + (size_t)b * p.N * p.M;
     const unsigned char *nzb = p.nz + (size_t)b * p.nrb * p.ncb;
