@@ -256,6 +256,38 @@ def test_fused_equals_unfused_to_rounding():
     np.testing.assert_allclose(a["dx"], b["dx"], atol=1e-4 * np.abs(a["dx"]).max())
 
 
+def test_calls_run_on_the_callers_stream():
+    # Two different problems enqueued on two side streams (default priority), nothing on the default
+    # stream, no synchronisation until both are enqueued: each call's kernels must all be on its own
+    # stream, or they would overtake the copies and each other.  Results as from one call at a time.
+    import torch
+
+    x1, y1 = workloads.normal_pairs(61, 6, 200, 170, 32)
+    x2, y2 = workloads.normal_pairs(62, 3, 90, 310, 128)
+    ref1 = oracle.batch(x1, y1, 0.1, want_E=False)
+    ref2 = oracle.batch(x2, y2, 0.5, want_E=False)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    hx1, hy1, hx2, hy2 = (torch.from_numpy(a).pin_memory() for a in (x1, y1, x2, y2))
+    out = {}
+    for rep in range(3):
+        with torch.cuda.stream(s1):
+            xd1, yd1 = hx1.cuda(non_blocking=True), hy1.cuda(non_blocking=True)
+            v1, d1, w1 = pkg.sdtw_forward(xd1, yd1, 0.1, pkg.FUSED)
+            dx1, dy1, _ = pkg.sdtw_backward(d1, xd1, yd1, w1)
+        with torch.cuda.stream(s2):
+            xd2, yd2 = hx2.cuda(non_blocking=True), hy2.cuda(non_blocking=True)
+            v2, d2, w2 = pkg.sdtw_forward(xd2, yd2, 0.5, pkg.UNFUSED)
+            dx2, dy2, _ = pkg.sdtw_backward(d2, xd2, yd2, w2)
+        s1.synchronize()
+        s2.synchronize()
+        assert binding.workspace_status(w1) == 0 and binding.workspace_status(w2) == 0
+        out[rep] = [t.cpu().numpy().astype(np.float64) for t in (v1, dx1, dy1, v2, dx2, dy2)]
+        check_against(ref1, {"value": out[rep][0], "dx": out[rep][1], "dy": out[rep][2]}, what="stream 1")
+        check_against(ref2, {"value": out[rep][3], "dx": out[rep][4], "dy": out[rep][5]}, what="stream 2")
+    for a, b in zip(out[0], out[2]):
+        np.testing.assert_array_equal(a, b)  # and the same bits every time
+
+
 def test_symmetry():
     x, y = workloads.normal_pairs(6, 2, 90, 75, 8)
     a = run_gpu(x, y, 0.5, pkg.FUSED)
