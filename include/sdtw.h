@@ -48,7 +48,8 @@ typedef enum sdtw_status {
     SDTW_ERR_UNSUPPORTED = 3, /* bandwidth != 0 in a normalised Soft-DTW call */
     SDTW_ERR_STATE = 4,       /* device: backward on a workspace not filled by a matching forward;
                                  host: backward with a SDTW_FLAG_VALUE_ONLY descriptor */
-    SDTW_ERR_HIP = 5,         /* a HIP runtime call failed (launch, copy) */
+    SDTW_ERR_HIP = 5,         /* a HIP runtime call of this call failed (launch, copy); an error that an
+                                 earlier, unrelated HIP call left pending is discarded at entry */
     SDTW_ERR_TIMEOUT = 6      /* device: a band gave up waiting for the band it depends on */
 } sdtw_status;
 

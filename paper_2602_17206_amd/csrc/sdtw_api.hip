@@ -242,6 +242,7 @@ unsigned prep_grid(const Params &p, int64_t norm_rows)
 int forward_impl(const sdtw_desc *d, const float *x, const float *y, float *value, void *ws, hipStream_t st,
                  const int32_t *x_len = nullptr, const int32_t *y_len = nullptr)
 {
+    (void)hipGetLastError();  // what an earlier, unrelated call left behind is not this call's error
     const Layout L = layout_of(d);
     const Params p = make_params(d, L, x, y, ws, x_len, y_len);
     // Unfused mode, small problems: the start of the call is folded into the cost-tensor kernel (one
@@ -294,6 +295,7 @@ int backward_impl(const sdtw_desc *d, const float *x, const float *y, const floa
                   float *dy, float *E_out, void *ws, hipStream_t st, const int32_t *x_len = nullptr,
                   const int32_t *y_len = nullptr)
 {
+    (void)hipGetLastError();  // see forward_impl
     const Layout L = layout_of(d);
     const Params p = make_params(d, L, x, y, ws, x_len, y_len);
     if (L.two_sweep) {
