@@ -173,6 +173,11 @@ int sdtw_barycenter_step(const sdtw_bary_desc *desc, float *z, const float *X, f
  * first argument alone.  Arguments as for sdtw_forward / sdtw_backward (no E output); the
  * workspace holds the three plain workspaces and the self terms' gradients, and its status word
  * (sdtw_workspace_status) reports the worst of the three.
+ * With N == M, no shared sequence and a batch small enough to leave the chip idle, the three terms
+ * run as ONE batch of 3B pairs - (x_b,y_b), (x_b,x_b), (y_b,y_b) - on copies of x and y that the
+ * forward call gathers into the workspace (which then holds one plain workspace of 3B pairs, the
+ * copies and the batch's gradients): fewer, fuller launches.  The backward call uses those copies,
+ * so, as for the plain calls, x and y must not change between the two.
  */
 size_t sdtw_normalized_workspace_bytes(const sdtw_desc *desc);
 int sdtw_normalized_forward(const sdtw_desc *desc, const float *x, const float *y, float *value,

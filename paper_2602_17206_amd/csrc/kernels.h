@@ -759,6 +759,53 @@ __global__ void normalized_grad_kernel(float *__restrict__ g, const float *__res
     }
 }
 
+// Normalised Soft-DTW as one batch of 3B pairs (equal lengths, nothing shared): pairs 0..B-1 are
+// (x_b, y_b), B..2B-1 are (x_b, x_b), 2B..3B-1 are (y_b, y_b).  This kernel lays the operands out
+// that way (per sequence `per` floats, a multiple of 4 or copied one by one).
+__global__ void normalized_gather_kernel(const float *__restrict__ x, const float *__restrict__ y, int64_t x_stride,
+                                         int64_t y_stride, float *__restrict__ xs, float *__restrict__ ys, int B,
+                                         int64_t per, int vec)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    if (vec) {
+        const int64_t per4 = per / 4, n = 3 * (int64_t)B * per4;
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+            const int64_t q = i / per4, e = i - q * per4;
+            const int kind = (int)(q / B), b = (int)(q - (int64_t)kind * B);
+            const float4 xv = reinterpret_cast<const float4 *>(x + b * x_stride)[e];
+            const float4 yv = reinterpret_cast<const float4 *>(y + b * y_stride)[e];
+            reinterpret_cast<float4 *>(xs)[i] = kind == 2 ? yv : xv;
+            reinterpret_cast<float4 *>(ys)[i] = kind == 1 ? xv : yv;
+        }
+    } else {
+        const int64_t n = 3 * (int64_t)B * per;
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+            const int64_t q = i / per, e = i - q * per;
+            const int kind = (int)(q / B), b = (int)(q - (int64_t)kind * B);
+            const float xv = x[b * x_stride + e], yv = y[b * y_stride + e];
+            xs[i] = kind == 2 ? yv : xv;
+            ys[i] = kind == 1 ? xv : yv;
+        }
+    }
+}
+
+// ... and this one forms the gradients from the batch's (computed with upstream gradient 1):
+// dx_b = g_b (d/dx of the cross term - d/d(first argument) of the (x,x) term), dy_b alike with (y,y):
+// the self terms are symmetric, so the gradient of half of one is its first-argument gradient.
+__global__ void normalized_batched_grad_kernel(float *__restrict__ dx, float *__restrict__ dy,
+                                               const float *__restrict__ dxs, const float *__restrict__ dys,
+                                               const float *__restrict__ grad_value, int B, int64_t per)
+{
+    const int64_t n = (int64_t)B * per;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const int64_t b = i / per;
+        const float gv = grad_value ? grad_value[b] : 1.0f;
+        if (dx) dx[i] = gv * (dxs[i] - dxs[n + i]);
+        if (dy) dy[i] = gv * (dys[i] - dxs[2 * n + i]);
+    }
+}
+
 // the cross term's header reports the worst status of the three workspaces
 __global__ void merge_status_kernel(Header *xy, const Header *xx, const Header *yy)
 {

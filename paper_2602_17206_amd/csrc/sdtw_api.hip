@@ -389,6 +389,13 @@ struct NormPlan {
     sdtw_desc xy, xx, yy;
     bool x_shared, y_shared;
     size_t off_xy, off_xx, off_yy, off_vals, off_gx, off_gy, total;
+    // One batch of 3B pairs instead of three passes: equal lengths, nothing shared, and small enough
+    // that one pass leaves the chip idle (and the host, at about 5 us per launch, would otherwise be
+    // what the three passes wait for).  The operands are gathered into xs, ys; dxs, dys take the
+    // batch's gradients.  (all's workspace comes first: its header carries the status word.)
+    bool batched;
+    sdtw_desc all;
+    size_t off_all, off_xs, off_ys, off_dxs, off_dys;
 };
 
 NormPlan norm_plan(const sdtw_desc *d)
@@ -396,6 +403,23 @@ NormPlan norm_plan(const sdtw_desc *d)
     NormPlan P{};
     P.x_shared = d->x_batch_stride == 0;
     P.y_shared = d->y_batch_stride == 0;
+    P.all = *d;
+    P.all.B = 3 * d->B;
+    P.all.x_batch_stride = (int64_t)d->N * d->D;
+    P.all.y_batch_stride = (int64_t)d->M * d->D;
+    P.batched = d->N == d->M && !P.x_shared && !P.y_shared && (int64_t)d->B * 3 <= 0x7fffffff / 4 && small_problem(&P.all);
+    if (P.batched) {
+        const size_t seq = 3 * (size_t)d->B * d->N * (size_t)d->D * sizeof(float);
+        size_t o = 0;
+        P.off_all = o; o = align_up(o + layout_of(&P.all).total, 256);
+        P.off_xs = o; o = align_up(o + seq, 256);
+        P.off_ys = o; o = align_up(o + seq, 256);
+        P.off_dxs = o; o = align_up(o + seq, 256);
+        P.off_dys = o; o = align_up(o + seq, 256);
+        P.off_vals = o; o = align_up(o + 3 * (size_t)d->B * sizeof(float), 256);
+        P.total = o;
+        return P;
+    }
     P.xy = *d;
     P.xx = *d;
     P.xx.B = P.x_shared ? 1 : d->B;
@@ -541,6 +565,17 @@ int sdtw_normalized_forward(const sdtw_desc *desc, const float *x, const float *
     char *base = static_cast<char *>(workspace);
     float *vals = reinterpret_cast<float *>(base + P.off_vals);
     float *vxy = vals, *vxx = vals + desc->B, *vyy = vals + 2 * (size_t)desc->B;
+    if (P.batched) {
+        float *xs = reinterpret_cast<float *>(base + P.off_xs), *ys = reinterpret_cast<float *>(base + P.off_ys);
+        const int64_t per = (int64_t)desc->N * desc->D;
+        const int vec = per % 4 == 0 && desc->x_batch_stride % 4 == 0 && desc->y_batch_stride % 4 == 0 && aligned16(x) &&
+                        aligned16(y);
+        normalized_gather_kernel<<<fill_grid(3 * (size_t)desc->B * per / (vec ? 4 : 1)), 256, 0, st>>>(
+            x, y, desc->x_batch_stride, desc->y_batch_stride, xs, ys, desc->B, per, vec);
+        if (int rc = forward_impl(&P.all, xs, ys, vals, base + P.off_all, st)) return rc;
+        normalized_value_kernel<<<(desc->B + 255) / 256, 256, 0, st>>>(value, vxy, vxx, vyy, desc->B, 0, 0);
+        return hip_ok();
+    }
     if (int rc = forward_impl(&P.xy, x, y, vxy, base + P.off_xy, st)) return rc;
     if (int rc = forward_impl(&P.xx, x, x, vxx, base + P.off_xx, st)) return rc;
     if (int rc = forward_impl(&P.yy, y, y, vyy, base + P.off_yy, st)) return rc;
@@ -563,6 +598,16 @@ int sdtw_normalized_backward(const sdtw_desc *desc, const float *x, const float 
     if (int rc = check_ws(workspace, workspace_bytes, P.total)) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *base = static_cast<char *>(workspace);
+    if (P.batched) {
+        const float *xs = reinterpret_cast<const float *>(base + P.off_xs), *ys = reinterpret_cast<const float *>(base + P.off_ys);
+        float *dxs = reinterpret_cast<float *>(base + P.off_dxs), *dys = reinterpret_cast<float *>(base + P.off_dys);
+        // (the operands are the copies the forward call gathered: the caller must not have changed x, y since)
+        if (int rc = backward_impl(&P.all, xs, ys, nullptr, dxs, dy ? dys : nullptr, nullptr, base + P.off_all, st)) return rc;
+        const int64_t per = (int64_t)desc->N * desc->D;
+        normalized_batched_grad_kernel<<<fill_grid((size_t)desc->B * per), 256, 0, st>>>(dx, dy, dxs, dys, grad_value,
+                                                                                      desc->B, per);
+        return hip_ok();
+    }
     float *gx = reinterpret_cast<float *>(base + P.off_gx), *gy = reinterpret_cast<float *>(base + P.off_gy);
     if (int rc = backward_impl(&P.xy, x, y, grad_value, dx, dy, nullptr, base + P.off_xy, st)) return rc;
     if (dx) {
