@@ -643,7 +643,12 @@ def test_random_configurations(seed):
 # ------------------------------------------------------------------------------- normalised Soft-DTW
 @pytest.mark.parametrize("mode", ["unfused", "fused"])
 @pytest.mark.parametrize("B,N,M,D,gamma,shared", [(3, 40, 40, 8, 0.5, False), (2, 130, 75, 16, 0.1, False),
-                                                  (4, 70, 200, 12, 1.0, True)])
+                                                  (4, 70, 200, 12, 1.0, True),
+                                                  # equal lengths, nothing shared: the three terms as one batch
+                                                  # (several bands, a ragged last block, D not a multiple of 4 / of 16)
+                                                  (5, 150, 150, 21, 0.2, False), (7, 257, 257, 128, 0.1, False),
+                                                  # equal lengths but a shared x: three passes
+                                                  (3, 96, 96, 8, 0.5, True)])
 def test_normalized_value_and_gradients(mode, B, N, M, D, gamma, shared):
     import torch
 
@@ -668,6 +673,21 @@ def test_normalized_value_and_gradients(mode, B, N, M, D, gamma, shared):
         for b in range(B):
             scale = np.abs(plain[key][b]).max()
             assert np.abs(g[b] - ref[key][b]).max() <= GRAD_RTOL * scale, (key, b)
+
+
+def test_normalized_batch_gives_one_gradient_alone():
+    # the one-batch path with only dx or only dy asked for: same values as with both
+    import torch
+
+    x, y = workloads.normal_pairs(21, 4, 100, 100, 16)
+    xd, yd = to_dev(x), to_dev(y)
+    value, desc, ws = pkg.sdtw_normalized_forward(xd, yd, 0.3, pkg.FUSED)
+    dx, dy = pkg.sdtw_normalized_backward(desc, xd, yd, ws)
+    dx1, none1 = pkg.sdtw_normalized_backward(desc, xd, yd, ws, want_dy=False)
+    none2, dy2 = pkg.sdtw_normalized_backward(desc, xd, yd, ws, want_dx=False)
+    torch.cuda.synchronize()
+    assert none1 is None and none2 is None
+    assert torch.equal(dx, dx1) and torch.equal(dy, dy2)
 
 
 def test_normalized_of_identical_sequences_is_zero():
