@@ -188,10 +188,10 @@ void launch_dp_kch(const sdtw_desc *d, const Layout &L, const Params &p, float *
                     forward_dp_kernel<KCH, 2, NP><<<tasks, wg_threads(2, NP), 0, st>>>(p, value);
             } else {
                 const unsigned tasks = (unsigned)d->B * (unsigned)L.nbands;
-                // more than two workgroups per compute unit: the wavefronts share SIMDs anyway, and one
+                // about four workgroups per compute unit: the wavefronts share SIMDs anyway, and one
                 // producer per band (two wavefronts per workgroup instead of three) leaves the consumers
                 // more of them (3 % at N = M = 1024, B = 32)
-                if (L.two_sweep && KCH > 0 && 2 * tasks > 512)
+                if (L.two_sweep && KCH > 0 && 2 * tasks > 900)
                     both_sweeps_kernel<KCH, 1, 1><<<2 * tasks, wg_threads(1, 1), 0, st>>>(p, value);
                 else if (L.two_sweep)
                     both_sweeps_kernel<KCH, 1, NP><<<2 * tasks, wg_threads(1, NP), 0, st>>>(p, value);
