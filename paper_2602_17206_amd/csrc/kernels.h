@@ -558,17 +558,21 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
             }
         } else {
             const int j = m0 + am;
+            const float *e = Eb + (size_t)(q0 + ak) * p.M + j;
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
                 const int i = q0 + ak + c;
-                ea[c] = (i < p.N && j < p.M && blk_live) ? Eb[(size_t)i * p.M + j] : 0.f;
+                ea[c] = (i < p.N && j < p.M && blk_live) ? *e : 0.f;
+                e += p.M;
             }
         }
         const int n = n0 + bn;
+        const float *o = oth + (size_t)(q0 + bk) * p.D + n;
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
             const int q = q0 + bk + c;
-            bv[c] = (q < Ql && n < p.D) ? oth[(size_t)q * p.D + n] : 0.f;
+            bv[c] = (q < Ql && n < p.D) ? *o : 0.f;
+            o += p.D;
         }
     };
     auto stash = [&](int buf, const float (&ea)[8], const float (&bv)[8], float ismax) {
@@ -612,11 +616,21 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
     // the output side's own values for the epilogue, requested now so that they are there by then
     float own_v[16];
     {
+        // (addresses by adding the row length up: a multiplication per element would cost a lone
+        // wavefront more than the loads themselves)
         const int n = n0 + wc * 32 + (lane & 31);
+        const int mb = m0 + wr * 32 + 4 * (lane >> 5);
+        const float *og = own + (size_t)mb * p.D + n;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int m = m0 + wr * 32 + acc_row(i, lane);
-            own_v[i] = (m < Pl && n < p.D) ? own[(size_t)m * p.D + n] : 0.f;
+        for (int g4 = 0; g4 < 4; ++g4) {
+            const float *o = og;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int m = mb + 8 * g4 + k;  // == m0 + wr*32 + acc_row(4*g4 + k, lane)
+                own_v[4 * g4 + k] = (m < Pl && n < p.D) ? *o : 0.f;
+                o += p.D;
+            }
+            og += 8 * (size_t)p.D;
         }
     }
     const unsigned first_bits = tid < min(nchunk, kLiveCap) ? chunk_flags(tid * kBlk) : 0u;
@@ -680,14 +694,21 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
     const float scale = 2.0f * (grad_value ? grad_value[b] : 1.0f);
     const int n = n0 + wc * 32 + (lane & 31);
     if (n < p.D) {
+        const int mlb = wr * 32 + 4 * (lane >> 5);
+        float *og = out + (size_t)(m0 + mlb) * p.D + n;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int ml = wr * 32 + acc_row(i, lane);
-            const int m = m0 + ml;
-            if (m < P) {
-                const float tot = (msum_part[0][ml] + msum_part[1][ml]) + (msum_part[2][ml] + msum_part[3][ml]);
-                out[(size_t)m * p.D + n] = scale * (own_v[i] * tot - acc[i]);
+        for (int g4 = 0; g4 < 4; ++g4) {
+            float *o = og;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int i = 4 * g4 + k, ml = mlb + 8 * g4 + k;  // ml == wr*32 + acc_row(i, lane)
+                if (m0 + ml < P) {
+                    const float tot = (msum_part[0][ml] + msum_part[1][ml]) + (msum_part[2][ml] + msum_part[3][ml]);
+                    *o = scale * (own_v[i] * tot - acc[i]);
+                }
+                o += p.D;
             }
+            og += 8 * (size_t)p.D;
         }
     }
 }
