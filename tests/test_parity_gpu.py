@@ -647,6 +647,7 @@ def test_random_configurations(seed):
                                                   # equal lengths, nothing shared: the three terms as one batch
                                                   # (several bands, a ragged last block, D not a multiple of 4 / of 16)
                                                   (5, 150, 150, 21, 0.2, False), (7, 257, 257, 128, 0.1, False),
+                                                  (2, 1, 1, 4, 1.0, False), (3, 2, 2, 3, 0.5, False),
                                                   # equal lengths but a shared x: three passes
                                                   (3, 96, 96, 8, 0.5, True)])
 def test_normalized_value_and_gradients(mode, B, N, M, D, gamma, shared):
