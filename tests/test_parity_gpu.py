@@ -691,6 +691,35 @@ def test_normalized_batch_gives_one_gradient_alone():
     assert torch.equal(dx, dx1) and torch.equal(dy, dy2)
 
 
+def test_normalized_calls_replay_from_a_captured_graph():
+    # the one-batch path (gather, forward, combine; backward, combine) captured once, replayed on new inputs
+    import torch
+
+    B, N, D, gamma = 4, 120, 16, 0.3
+    xs, ys = torch.empty(B, N, D, device="cuda"), torch.empty(B, N, D, device="cuda")
+    value = torch.empty(B, device="cuda")
+    dx, dy = torch.empty(B, N, D, device="cuda"), torch.empty(B, N, D, device="cuda")
+    x0, y0 = workloads.normal_pairs(80, B, N, N, D)
+    xs.copy_(to_dev(x0)); ys.copy_(to_dev(y0))
+    _, desc, ws = pkg.sdtw_normalized_forward(xs, ys, gamma, pkg.FUSED, value=value)
+    pkg.sdtw_normalized_backward(desc, xs, ys, ws, dx=dx, dy=dy)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        pkg.sdtw_normalized_forward(xs, ys, gamma, pkg.FUSED, workspace=ws, value=value)
+        pkg.sdtw_normalized_backward(desc, xs, ys, ws, dx=dx, dy=dy)
+    for rep in range(3):
+        x, y = workloads.normal_pairs(81 + rep, B, N, N, D)
+        xe, ye = to_dev(x), to_dev(y)
+        ve, de, we = pkg.sdtw_normalized_forward(xe, ye, gamma, pkg.FUSED)
+        dxe, dye = pkg.sdtw_normalized_backward(de, xe, ye, we)
+        xs.copy_(xe); ys.copy_(ye)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert binding.workspace_status(ws) == 0
+        assert torch.equal(value, ve) and torch.equal(dx, dxe) and torch.equal(dy, dye), "replay %d" % rep
+
+
 def test_normalized_of_identical_sequences_is_zero():
     import torch
 
