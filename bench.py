@@ -297,8 +297,19 @@ def cpu_baseline(wl, target_wall_s=2.0):
         if dt >= target_wall_s or reps >= 200:
             break
     cells = wl.B * wl.N * wl.M * reps
+    # ... and on one thread, on a few pairs of the same batch, for about a second
+    nb = min(wl.B, 4)
+    reps1, t1 = 0, time.perf_counter()
+    while True:
+        oracle.batch(wl.x[:nb], wl.y[:nb], wl.gamma, nthreads=1)
+        reps1 += 1
+        dt1 = time.perf_counter() - t1
+        if dt1 >= 1.0 or reps1 >= 200:
+            break
     return {"value": cells / dt, "unit": "DP cells/s (forward+backward)", "cores": threads, "kind": "oracle",
-            "sample": "%d repetitions of the full %s batch (B=%d), %.1f s wall, float64" % (reps, wl.name, wl.B, dt)}
+            "sample": "%d repetitions of the full %s batch (B=%d), %.1f s wall, float64" % (reps, wl.name, wl.B, dt),
+            "value_one_core": nb * wl.N * wl.M * reps1 / dt1,
+            "sample_one_core": "%d repetitions of %d pairs of the same batch on one thread, %.1f s" % (reps1, nb, dt1)}
 
 
 def main():
