@@ -158,6 +158,8 @@ size_t sdtw_barycenter_workspace_bytes(const sdtw_bary_desc *desc);
  *   z [Lz,D]: device, in/out.  X [K,Lx,D]: device, read only.
  *   adam_m, adam_v [Lz,D]: device, in/out, caller-owned optimiser state (zeros before step 1).
  *   loss [1]: device, out.  dz_out [Lz,D]: device, out, optional (NULL).
+ * If the device reports an error for this step (sdtw_workspace_status: a band gave up waiting),
+ * loss and dz_out are NaN and z, adam_m and adam_v are left unchanged.
  */
 int sdtw_barycenter_step(const sdtw_bary_desc *desc, float *z, const float *X, float *adam_m,
                          float *adam_v, float *loss, float *dz_out, void *workspace,
@@ -211,6 +213,12 @@ int sdtw_debug_export(const sdtw_desc *desc, const void *workspace, size_t works
 int sdtw_debug_lane_shift(int32_t *out, void *stream);
 
 /*
+ * The sdtw_debug_set_spin_limit, sdtw_debug_force_workgroup_shape and sdtw_debug_profile hooks below
+ * set process-wide switches (the only state this library keeps between calls).  They are for tests
+ * and benchmarks: call them while no other thread is inside a call of this library, and do not
+ * change the forced workgroup shape between sdtw_workspace_bytes, the forward and the backward call
+ * of one problem (the shape decides the workspace layout).
+ *
  * Test hook: number of polls after which a band that waits for its neighbouring band gives up
  * and records SDTW_ERR_TIMEOUT (default 2^23, several seconds).  Process-wide; host only.
  */
@@ -236,6 +244,27 @@ int sdtw_debug_force_workgroup_shape(int bands_per_workgroup);
  */
 int sdtw_debug_profile(int enable);
 int sdtw_debug_profile_read(char *names, size_t names_bytes, float *ms, int max_entries, int *count);
+
+/*
+ * Benchmark hook: calibration of the vector-ALU figures the DP sweeps are priced against.  Runs one
+ * micro-kernel on 256 workgroups (one per compute unit), `iters` iterations of 32 instructions or
+ * DP steps each after a short warm-up launch, waits, and writes the duration in milliseconds to
+ * *ms (host).  Creates two HIP events per call.
+ *   probe 0: issue rate of one instruction (variant 0..9: v_add_f32, v_fma_f32, v_add_f64, v_min_f64,
+ *            v_fma_f64, v_exp_f32, v_log_f32, v_cvt_f32_f64, v_cvt_f64_f32, v_mov_b32_dpp), eight
+ *            independent chains per wavefront, waves_per_simd (1, 2, 4) wavefronts per SIMD
+ *   probe 1: the same instruction as one dependent chain (variants 0..6, 9), one wavefront per SIMD
+ *   probe 2: the bare DP step of Sec. 2 Eq. 1-2 (one row per lane), waves_per_simd wavefronts per SIMD
+ *   probe 3: the bare DP step with two rows per lane (128 cells per step and wavefront)
+ *   probe 4: the DP step of one wavefront per SIMD beside a wavefront that issues `variant`
+ *            v_mfma_f32_32x32x16_f16 per 32 steps (variant + 1000: two rows per lane)
+ *   probe 5: the DP step of one wavefront per compute unit with the consumer's memory traffic;
+ *            variant = bit set (1: cost from LDS, 2: edge value to LDS, 4: table store to HBM,
+ *            8: a workgroup barrier per 32 steps); supported: 0, 1, 3, 7, 15, 4, 8
+ *   scratch: device, 256-byte aligned, at least 16 MiB.
+ */
+int sdtw_debug_rate_probe(int probe, int variant, int waves_per_simd, int iters, void *scratch,
+                          size_t scratch_bytes, float *ms, void *stream);
 
 #ifdef __cplusplus
 }

@@ -27,6 +27,9 @@
  * Cells are visited in row-major order; there is no blocking, fusion or
  * reordering.  OpenMP is used only ACROSS pairs (each pair is independent).
  *
+ * Out of memory: every function that allocates returns ORACLE_NO_MEM and leaves its outputs
+ * unspecified; one_pair passes the code of the gradient step on, the batch returns the first one.
+ *
  * Pins (tests/test_oracle_*.py, none needs a GPU): brute-force enumeration of all
  * monotone paths for N,M<=6 (value and E), the Delannoy closed form for zero
  * cost, the hard-DTW sandwich as gamma->0, central finite differences of the
@@ -162,12 +165,12 @@ void sdtw_oracle_backward(const double *d, const double *R, int N, int M, double
 /* dx[i,:] = g * 2 (x_i sum_j E_ij - sum_j E_ij y_j); dy[j,:] = g * 2 (y_j sum_i E_ij - sum_i E_ij x_i).
  * Every sum runs over its index in increasing order; the feature loop is innermost only so that
  * memory is walked along rows (the terms of each sum and their order are those of the formula). */
-void sdtw_oracle_input_grads(const float *x, const float *y, const double *E, int N, int M, int D,
-                             double g, double *dx, double *dy)
+int sdtw_oracle_input_grads(const float *x, const float *y, const double *E, int N, int M, int D,
+                            double g, double *dx, double *dy)
 {
     double *acc = (double *)malloc((size_t)(N > M ? N : M) * D * sizeof(double));
     double *marg = (double *)malloc((size_t)(N > M ? N : M) * sizeof(double));
-    if (!acc || !marg) { free(acc); free(marg); return; }
+    if (!acc || !marg) { free(acc); free(marg); return ORACLE_NO_MEM; }
     /* dx: for each i, sum over j */
     for (int i = 0; i < N; ++i) {
         double rs = 0.0;
@@ -198,6 +201,7 @@ void sdtw_oracle_input_grads(const float *x, const float *y, const double *E, in
             dy[(size_t)j * D + k] = g * 2.0 * ((double)y[(size_t)j * D + k] * marg[j] - acc[(size_t)j * D + k]);
     free(acc);
     free(marg);
+    return ORACLE_OK;
 }
 
 /* One pair, start to end.  Any of R_out ((N+2)(M+2)), E_out (N*M), dx, dy, d_out (N*M)
@@ -219,15 +223,17 @@ static int one_pair(const float *x, const float *y, int N, int M, int D, double 
         double *E = E_out ? E_out : (double *)malloc(nm * sizeof(double));
         if (!Ebar || !E) { free(d); free(R); free(Ebar); if (!E_out) free(E); return ORACLE_NO_MEM; }
         sdtw_oracle_backward_banded(d, R, N, M, gamma, w, Ebar, E);
+        int rc = ORACLE_OK;
         if (dx || dy) {
             double *tx = dx ? dx : (double *)malloc((size_t)N * D * sizeof(double));
             double *ty = dy ? dy : (double *)malloc((size_t)M * D * sizeof(double));
-            if (tx && ty) sdtw_oracle_input_grads(x, y, E, N, M, D, g, tx, ty);
+            rc = (tx && ty) ? sdtw_oracle_input_grads(x, y, E, N, M, D, g, tx, ty) : ORACLE_NO_MEM;
             if (!dx) free(tx);
             if (!dy) free(ty);
         }
         free(Ebar);
         if (!E_out) free(E);
+        if (rc != ORACLE_OK) { free(d); free(R); return rc; }
     }
     free(d);
     free(R);

@@ -1,8 +1,16 @@
 """ctypes front end of the float64 CPU oracle (``sdtw_oracle.c``).
 
 TEST INFRASTRUCTURE ONLY: imported by ``tests/``, the smoke check and the benchmark's
-``cpu_baseline`` leg.  Argument marshalling only; every formula lives in the C file,
-where each function names the passage of the paper it writes out.
+``cpu_baseline`` leg.  The recurrences, the cost and the gradient formulas live in the C
+file, where each function names the passage of the paper it writes out; this module marshals
+arguments for them.  Two combinations of plain calls are written here, in numpy, because they
+are nothing but that: :func:`normalized` (the difference of three plain values and of their
+gradients) and :func:`ragged_batch` (one plain call per sliced pair).
+
+``SDTW_ORACLE_SANITIZE=1`` in the environment builds and loads the oracle with
+``-fsanitize=address,undefined`` instead (``libsdtw_oracle_san.so``); the process then needs the
+sanitizer runtime preloaded, which ``tests/test_oracle_sanitized.py`` arranges for a child
+process that re-runs the pins.
 """
 import ctypes
 import os
@@ -12,20 +20,27 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "sdtw_oracle.c")
-_LIB = os.path.join(_HERE, "libsdtw_oracle.so")
+_SANITIZE = os.environ.get("SDTW_ORACLE_SANITIZE", "") not in ("", "0")
+_LIB = os.path.join(_HERE, "libsdtw_oracle_san.so" if _SANITIZE else "libsdtw_oracle.so")
 _lib = None
 
 _dp = ctypes.POINTER(ctypes.c_double)
 _fp = ctypes.POINTER(ctypes.c_float)
 
 
-def build(force=False):
-    """Compile the oracle with gcc (-O2, OpenMP across pairs).  Returns the library path."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(
-            ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-o", _LIB, _SRC, "-lm"]
-        )
-    return _LIB
+SANITIZE_FLAGS = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+                  "-fno-sanitize-recover=undefined"]
+
+
+def build(force=False, sanitize=None):
+    """Compile the oracle with gcc (-O2, OpenMP across pairs; or, with ``sanitize``, -O1 with the
+    address and undefined-behaviour sanitizers).  Returns the library path."""
+    sanitize = _SANITIZE if sanitize is None else bool(sanitize)
+    lib = os.path.join(_HERE, "libsdtw_oracle_san.so" if sanitize else "libsdtw_oracle.so")
+    if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(_SRC):
+        flags = SANITIZE_FLAGS if sanitize else ["-O2"]
+        subprocess.check_call(["gcc"] + flags + ["-std=c99", "-fopenmp", "-fPIC", "-shared", "-o", lib, _SRC, "-lm"])
+    return lib
 
 
 def _load():

@@ -57,6 +57,7 @@ EXPORTED_SYMBOLS = (
     "sdtw_forward_ragged", "sdtw_backward_ragged",
     "sdtw_debug_export", "sdtw_debug_lane_shift", "sdtw_debug_set_spin_limit",
     "sdtw_debug_profile", "sdtw_debug_profile_read", "sdtw_debug_force_workgroup_shape",
+    "sdtw_debug_rate_probe",
 )
 
 
@@ -118,6 +119,8 @@ def load_library():
     lib.sdtw_debug_profile_read.restype = i32
     lib.sdtw_debug_profile_read.argtypes = [ctypes.c_char_p, sz, ctypes.POINTER(ctypes.c_float), i32,
                                             ctypes.POINTER(ctypes.c_int)]
+    lib.sdtw_debug_rate_probe.restype = i32
+    lib.sdtw_debug_rate_probe.argtypes = [i32, i32, i32, i32, vp, sz, ctypes.POINTER(ctypes.c_float), vp]
     _lib = lib
     return lib
 
@@ -233,6 +236,18 @@ def sdtw_forward(x, y, gamma, mode=FUSED, workspace=None, value=None, stream=Non
     if rc != 0:
         raise SdtwError(rc, "sdtw_forward")
     return value, desc, workspace
+
+
+def sdtw_forward_desc(desc, x, y, workspace, value, stream=None):
+    """sdtw_forward with a descriptor the caller made (make_desc): nothing is allocated here."""
+    import torch
+
+    rc = load_library().sdtw_forward(ctypes.byref(desc), _ptr(x, torch.float32, name="x"), _ptr(y, torch.float32, name="y"),
+                                     _ptr(value, torch.float32, (desc.B,), "value"), workspace.ptr, workspace.nbytes,
+                                     _stream_ptr(stream))
+    if rc != 0:
+        raise SdtwError(rc, "sdtw_forward")
+    return value
 
 
 def sdtw_backward(desc, x, y, workspace, grad_value=None, want_dx=True, want_dy=True, want_E=False,
@@ -448,3 +463,16 @@ def debug_force_workgroup_shape(bands_per_workgroup):
     rc = load_library().sdtw_debug_force_workgroup_shape(int(bands_per_workgroup))
     if rc != 0:
         raise SdtwError(rc, "sdtw_debug_force_workgroup_shape")
+
+
+RATE_PROBE_SCRATCH_BYTES = 16 << 20
+
+
+def debug_rate_probe(probe, variant, waves_per_simd, iters, scratch, stream=None):
+    """Milliseconds one calibration micro-kernel took (see sdtw_debug_rate_probe in sdtw.h)."""
+    ms = ctypes.c_float(0.0)
+    rc = load_library().sdtw_debug_rate_probe(int(probe), int(variant), int(waves_per_simd), int(iters), scratch.ptr,
+                                              scratch.nbytes, ctypes.byref(ms), _stream_ptr(stream))
+    if rc != 0:
+        raise SdtwError(rc, "sdtw_debug_rate_probe")
+    return float(ms.value)

@@ -933,7 +933,7 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
     const bool last_band = live && (k == (Nl - 1) / kBandRows);
     double fin = 0.0;
     const bool has_above = live && k > 0 && CH != 1;                // through memory
-    const bool emit_bottom = live && (k + 1 < p.nbands) && CH != 0;  // through memory
+    const bool emit_bottom = live && (k + 1 < p.nbands);             // the band's last row goes to memory
     const float *my_ring = ring + lane * kRingStride;
     double *top = sh.edge_in[slot];
     double *eo = edge_out[slot];
@@ -1009,7 +1009,10 @@ __device__ __forceinline__ void forward_dp_body(const Params &p, float *__restri
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             if (emit_bottom && lane >= kBlk) {
                 const int j = sg * kBlk + lane - kBlk - (kBandRows - 1);
-                if (j >= 0 && j < M) publish_boundary(brow_out, j, eo[lane - kBlk]);
+                // (a chained pair's upper band hands the row over through LDS; it still leaves it in
+                // memory, where alignment_kernel looks for the columns that can hold a non-zero E)
+                const double *src = (CH == 0) ? hand + (sg & 3) * kBlk : eo;
+                if (j >= 0 && j < M) publish_boundary(brow_out, j, src[lane - kBlk]);
             }
             if constexpr (CH != 1) {
                 double tn = kBig;
@@ -1343,7 +1346,7 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
     const double Rfin = (live && !TSWEEP) ? p.rfinal[b] : 0.0;
     const int kc = live ? k : 0;
     const bool has_below = live && (k + 1 < p.nbands) && CH != 1;  // through memory
-    const bool emit_top = live && k > 0 && CH != 0;                // through memory
+    const bool emit_top = live && k > 0;                           // the band's first row goes to memory
     constexpr bool RECOMP = dp_recompute(KCH, SLOTS);
     static_assert(RECOMP != TSWEEP, "a reverse sweep either stores its own table or recomputes R and forms E");
     const unsigned long long *brow_in = p.brow_b + ((size_t)bb * p.nbands + (has_below ? kc + 1 : kc)) * M;
@@ -1501,7 +1504,9 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             if (emit_top && lane < kBlk) {
                 const int j = sg * kBlk + lane;
-                if (j < M) publish_boundary(brow_out, j, eo[lane]);
+                // (also from a chained pair's lower band, whose first row travels through LDS: see the forward sweep)
+                const double *src = (CH == 0) ? hand + (sg & 3) * kBlk : eo;
+                if (j < M) publish_boundary(brow_out, j, src[lane]);
             }
             // the E blocks this macro-step completed, (upper rows, sg) and (lower rows, sg-1): written
             // out by the producers during the next macro-step, or here

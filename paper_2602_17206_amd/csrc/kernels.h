@@ -848,12 +848,17 @@ struct AdamParams {
     float corr1, corr2;  // 1-beta1^step, 1-beta2^step
 };
 
-__global__ void barycenter_update_kernel(AdamParams a, const float *__restrict__ dxk /*[K][n]*/,
+// When the pair workspace reports an error (a band gave up waiting, or the workspace did not match),
+// the gradients are NaN: loss and dz_out receive them, but z and the optimiser state are left as
+// they were, so that the caller can read the status word and retry.
+__global__ void barycenter_update_kernel(AdamParams a, const Header *__restrict__ hdr,
+                                         const float *__restrict__ dxk /*[K][n]*/,
                                          const float *__restrict__ values /*[K]*/, float *__restrict__ z,
                                          float *__restrict__ m, float *__restrict__ v,
                                          float *__restrict__ loss, float *__restrict__ dz_out)
 {
     const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const bool failed = (hdr->status | hdr->abort_backward) != 0;
     // sums over k in index order; the loads of 16 terms are asked for together (one memory round trip
     // per 16 sequences instead of one per sequence)
     constexpr int kBatch = 16;
@@ -878,6 +883,7 @@ __global__ void barycenter_update_kernel(AdamParams a, const float *__restrict__
         for (int i = 0; i < kBatch; ++i) g += t[i];
     }
     if (dz_out) dz_out[q] = g;
+    if (failed) return;
     const float mq = a.beta1 * m[q] + (1.0f - a.beta1) * g;
     const float vq = a.beta2 * v[q] + (1.0f - a.beta2) * g * g;
     m[q] = mq;

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -14,13 +15,16 @@
 #include "kernels.h"
 #include "dp_kernels.h"
 #include "layout.h"
+#include "rate_probe.h"
 
 namespace {
 
 using namespace sdtw;
 
-uint32_t g_spin_limit = 1u << 23;  // ~10 s of polling before a band gives up
-int g_force_slots = 0;             // test hook: 0 = choose by problem size, 1, 2 or 4 = force that workgroup shape
+// Test hooks (process-wide; a change while another thread is inside a call of this library may be seen
+// by part of that call only: set them between calls).
+std::atomic<uint32_t> g_spin_limit{1u << 23};  // ~10 s of polling before a band gives up
+std::atomic<int> g_force_slots{0};             // 0 = choose by problem size, 1, 2 or 4 = force that workgroup shape
 
 // Optional per-kernel timing (test/benchmark hook): when switched on, every kernel launch of the
 // library is bracketed by two HIP events on the caller's stream.
@@ -540,7 +544,8 @@ int sdtw_barycenter_step(const sdtw_bary_desc *desc, float *z, const float *X, f
     a.corr2 = (float)(1.0 - std::pow((double)desc->beta2, (double)desc->step));
     {
         ProfScope ps("barycenter_update", st);
-        barycenter_update_kernel<<<(unsigned)((a.n + 255) / 256), 256, 0, st>>>(a, dxk, values, z, adam_m, adam_v, loss, dz_out);
+        barycenter_update_kernel<<<(unsigned)((a.n + 255) / 256), 256, 0, st>>>(
+            a, reinterpret_cast<const Header *>(pair_ws), dxk, values, z, adam_m, adam_v, loss, dz_out);
     }
     return hip_ok();
 }
@@ -685,6 +690,35 @@ int sdtw_debug_force_workgroup_shape(int bands_per_workgroup)
         return SDTW_ERR_INVALID_ARG;
     g_force_slots = bands_per_workgroup;
     return SDTW_OK;
+}
+
+int sdtw_debug_rate_probe(int probe, int variant, int waves_per_simd, int iters, void *scratch, size_t scratch_bytes,
+                          float *ms, void *stream)
+{
+    if (!ms || iters < 1 || iters > (1 << 20)) return SDTW_ERR_INVALID_ARG;
+    if (waves_per_simd != 1 && waves_per_simd != 2 && waves_per_simd != 4) return SDTW_ERR_INVALID_ARG;
+    if (int rc = check_ws(scratch, scratch_bytes, probe::kScratchBytes)) return rc;
+    (void)hipGetLastError();
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    double *d = static_cast<double *>(scratch);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
+        if (e0) (void)hipEventDestroy(e0);
+        return SDTW_ERR_HIP;
+    }
+    int rc = SDTW_OK;
+    if (!probe::launch(probe, variant, waves_per_simd, 10, d, st)) {  // warm-up (instruction cache, clocks)
+        rc = SDTW_ERR_INVALID_ARG;
+    } else {
+        (void)hipEventRecord(e0, st);
+        probe::launch(probe, variant, waves_per_simd, iters, d, st);
+        (void)hipEventRecord(e1, st);
+        if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(ms, e0, e1) != hipSuccess) rc = SDTW_ERR_HIP;
+        if (rc == SDTW_OK) rc = hip_ok();
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return rc;
 }
 
 int sdtw_debug_profile(int enable)

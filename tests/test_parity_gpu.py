@@ -162,16 +162,23 @@ def test_all_workgroup_shapes(shape, mode, B, N, M, D, gamma):
 @pytest.mark.parametrize("mode", ["unfused", "fused"])
 @pytest.mark.parametrize("gamma", [0.01, 1.0, 50.0])
 @pytest.mark.parametrize("kind", ["normal", "walk"])
-def test_alignment_only_looks_where_E_can_be_non_zero(mode, gamma, kind):
+@pytest.mark.parametrize("shape", [1, 2])
+def test_alignment_only_looks_where_E_can_be_non_zero(shape, mode, gamma, kind):
     # 600 x 700: from 16 column blocks on the backward call of small problems first finds, per band,
     # the columns that can hold a non-zero E (from the boundary rows) and forms E only there.  Sparse
     # E (small gamma), dense E (gamma = 50: every cell non-zero) and both input recipes; E is compared
     # everywhere, so a block wrongly taken for zero would show.
     B, N, M, D = 3, 600, 700, 12
     x, y = (workloads.normal_pairs if kind == "normal" else workloads.walk_pairs)(77, B, N, M, D)
-    say("alignment pruning %s gamma=%g %s" % (mode, gamma, kind))
+    # Both workgroup shapes of small problems: the look needs every band's edge rows in memory, also
+    # those a chained pair hands over through LDS.
+    say("alignment pruning shape %d %s gamma=%g %s" % (shape, mode, gamma, kind))
     ref = oracle.batch(x, y, gamma, want_E=True)
-    got = run_gpu(x, y, gamma, MODES[mode])
+    binding.debug_force_workgroup_shape(shape)
+    try:
+        got = run_gpu(x, y, gamma, MODES[mode])
+    finally:
+        binding.debug_force_workgroup_shape(0)
     check_against(ref, got, what="alignment pruning %s gamma=%g %s" % (mode, gamma, kind))
     # float32 cannot hold anything the pruning may have dropped: wherever the oracle's E is above the
     # smallest normal float32 by a margin (the hardware exp2 flushes denormal results), the library's E is non-zero
@@ -820,15 +827,32 @@ def test_config2_full(mode):
     check_against(ref, got, what="c2 " + mode)
 
 
+# E has no bar of its own in the task.  Its error is that of the float32 cost: d is off by about
+# eps32 * (||x||^2 + ||y||^2) per cell, which moves the exponent of the weight of an alignment by that
+# over gamma for every cell in which two competing alignments differ (a handful of cells, since
+# longer detours are exponentially suppressed), and E(1 - E) <= 1/4 turns a relative weight error into
+# an absolute error of E.  With eps32 = 6e-8 and four differing cells:
+def e_tolerance(x, y, gamma):
+    norms = float((x.astype(np.float64) ** 2).sum(-1).mean() + (y.astype(np.float64) ** 2).sum(-1).mean())
+    return max(E_ATOL, 0.25 * 2.0 * 6e-8 * norms / gamma)
+
+
 @pytest.mark.parametrize("mode", ["unfused", "fused"])
 def test_config3_full_size_sampled_pairs(mode):
     wl = workloads.pair_workload("c3_b32_l1024_walk")
     say("config 3 %s" % mode)
     pairs = [0, 13, 31]
-    ref = oracle.batch(wl.x[pairs], wl.y[pairs], wl.gamma)
-    got = run_gpu(wl.x, wl.y, wl.gamma, MODES[mode], want_E=False)
-    check_against(ref, got, pairs=pairs, what="c3 " + mode)
+    ref = oracle.batch(wl.x[pairs], wl.y[pairs], wl.gamma, want_E=True)
+    got = run_gpu(wl.x, wl.y, wl.gamma, MODES[mode], want_E=True)
+    check_against({k: v for k, v in ref.items() if k != "E"}, got, pairs=pairs, what="c3 " + mode)
     assert np.all(np.isfinite(got["dx"])) and np.all(np.isfinite(got["dy"]))
+    # the whole alignment matrix of the sampled pairs, through the E output of the backward call
+    tol = e_tolerance(wl.x[pairs], wl.y[pairs], wl.gamma)
+    for r, b in enumerate(pairs):
+        err = np.abs(got["E"][b] - ref["E"][r]).max()
+        say("  c3 %s pair %d: max |E - oracle| = %.3e (bar %.3e)" % (mode, b, err, tol))
+        assert err <= tol
+        assert (got["E"][b][ref["E"][r] > 1e-36] > 0).all()
 
 
 def test_config4_full_size_sampled_pairs():
@@ -838,7 +862,7 @@ def test_config4_full_size_sampled_pairs():
     say("config 4 fused: GPU")
     xd, yd = to_dev(wl.x), to_dev(wl.y)
     value, desc, ws = pkg.sdtw_forward(xd, yd, wl.gamma, pkg.FUSED)
-    dx, dy, _ = pkg.sdtw_backward(desc, xd, yd, ws)
+    dx, dy, E = pkg.sdtw_backward(desc, xd, yd, ws, want_E=True)
     torch.cuda.synchronize()
     assert binding.workspace_status(ws) == 0
     got = {"value": value.cpu().numpy().astype(np.float64), "dx": dx.cpu().numpy().astype(np.float64),
@@ -847,68 +871,108 @@ def test_config4_full_size_sampled_pairs():
     # E summed over a row is at least 1 and dx_i = 2 sum_j E_ij (x_i - y_j): translation invariance
     tot = got["dx"].sum(axis=1) + got["dy"].sum(axis=1)
     assert np.abs(tot).max() <= 2e-2 * np.abs(got["dx"]).max()
-    del ws
-    torch.cuda.empty_cache()
     pairs = [3, 28]
+    E3 = E[pairs[0]].cpu().numpy()
+    # the same backward without the E output (the gradients are then formed where E is produced)
+    dx2, dy2, _ = pkg.sdtw_backward(desc, xd, yd, ws)
+    torch.cuda.synchronize()
+    for a, b2 in ((dx, dx2), (dy, dy2)):
+        assert (a - b2).abs().max().item() <= 1e-4 * a.abs().max().item()
+    del ws, E, dx2, dy2
+    torch.cuda.empty_cache()
     say("config 4 fused: oracle on pairs %s" % pairs)
-    ref = oracle.batch(wl.x[pairs], wl.y[pairs], wl.gamma, nthreads=2)
-    check_against(ref, got, pairs=pairs, what="c4")
+    ref = oracle.batch(wl.x[pairs], wl.y[pairs], wl.gamma, nthreads=2, want_E=True)
+    check_against({k: v for k, v in ref.items() if k != "E"}, got, pairs=pairs, what="c4")
+    # pair 3's whole alignment matrix: 96 % of the macro-steps of this configuration are skipped as
+    # provably zero, so a wrongly skipped one would show here
+    tol = e_tolerance(wl.x[pairs[:1]], wl.y[pairs[:1]], wl.gamma)
+    err = np.abs(E3 - ref["E"][0]).max()
+    say("  c4 pair %d: max |E - oracle| = %.3e (bar %.3e)" % (pairs[0], err, tol))
+    assert err <= tol
+    assert (E3[ref["E"][0] > 1e-36] > 0).all()
+    assert abs(E3.sum() - ref["E"][0].sum()) <= 1e-3 * ref["E"][0].sum()
 
 
 # ------------------------------------------------------------------------------- barycenter
+def teacher_forced_step(bw, mode, z, X, m, v, step, ws, consts):
+    """One library step on (z, m, v) and the oracle's step from the same state; returns the workspace."""
+    import torch
+
+    lr, b1, b2, eps = consts
+    z_in = z.cpu().numpy().astype(np.float64)
+    m_o, v_o = m.cpu().numpy().astype(np.float64), v.cpu().numpy().astype(np.float64)
+    loss, dz, ws = pkg.sdtw_barycenter_step(z, X, m, v, bw.gamma, step, lr, b1, b2, eps, mode, workspace=ws, want_dz=True)
+    torch.cuda.synchronize()
+    z_o = z_in.copy()
+    lo, dzo = oracle.barycenter_step(z_o, bw.X, bw.gamma, lr, b1, b2, eps, step, m_o, v_o)
+    assert abs(loss.item() - lo) <= VALUE_RTOL * max(abs(lo), 1.0), "step %d loss %r vs %r" % (step, loss.item(), lo)
+    g = dz.cpu().numpy().astype(np.float64)
+    err = np.abs(g - dzo).max() / np.abs(dzo).max()
+    say("  step %d: loss %.6g, max|dz| %.4g, rel err dz %.3e" % (step, lo, np.abs(dzo).max(), err))
+    assert err <= GRAD_RTOL, "step %d dz rel err %.3e" % (step, err)
+    # Adam's moments after the step, from the same moments before it
+    mm, vv = m.cpu().numpy().astype(np.float64), v.cpu().numpy().astype(np.float64)
+    assert np.abs(mm - m_o).max() <= GRAD_RTOL * np.abs(m_o).max(), "step %d m" % step
+    assert np.abs(vv - v_o).max() <= 2 * GRAD_RTOL * np.abs(v_o).max(), "step %d v" % step
+    # the update itself, given the library's own moments (Adam divides by |g| where g ~ 0,
+    # so the comparison through the oracle's gradient would amplify rounding there)
+    expect = z_in - lr * (mm / (1 - b1 ** step)) / (np.sqrt(vv / (1 - b2 ** step)) + eps)
+    np.testing.assert_allclose(z.cpu().numpy(), expect, rtol=1e-5, atol=1e-6)
+    return ws
+
+
 @pytest.mark.parametrize("mode", ["unfused", "fused"])
 def test_barycenter_steps_teacher_forced(mode):
     import torch
 
     bw = workloads.barycenter_workload(K=8, L=96, D=6, seed=5)
     say("barycenter %s" % mode)
-    lr, b1, b2, eps, gamma = 0.05, 0.9, 0.999, 1e-8, 1.0
+    consts = (0.05, 0.9, 0.999, 1e-8)
     z = to_dev(bw.z0.copy())
     X = to_dev(bw.X)
     m = torch.zeros_like(z)
     v = torch.zeros_like(z)
     ws = None
     for step in (1, 2, 3):
-        z_in = z.cpu().numpy()
-        m_in, v_in = m.cpu().numpy().astype(np.float64), v.cpu().numpy().astype(np.float64)
-        loss, dz, ws = pkg.sdtw_barycenter_step(z, X, m, v, gamma, step, lr, b1, b2, eps, MODES[mode],
-                                                workspace=ws, want_dz=True)
-        torch.cuda.synchronize()
-        zo = z_in.astype(np.float64)
-        lo, dzo = oracle.barycenter_step(zo, bw.X, gamma, lr, b1, b2, eps, step, m_in, v_in)
-        assert abs(loss.item() - lo) <= VALUE_RTOL * max(abs(lo), 1.0)
-        g = dz.cpu().numpy().astype(np.float64)
-        assert np.abs(g - dzo).max() <= GRAD_RTOL * np.abs(dzo).max()
-        np.testing.assert_allclose(m.cpu().numpy(), m_in, rtol=2e-3, atol=2e-3 * np.abs(m_in).max())
-        # the update itself, given the library's own gradient (Adam divides by |g| where g ~ 0,
-        # so the comparison through the oracle's gradient would amplify rounding there)
-        mm = m.cpu().numpy().astype(np.float64)
-        vv = v.cpu().numpy().astype(np.float64)
-        expect = z_in.astype(np.float64) - lr * (mm / (1 - b1 ** step)) / (np.sqrt(vv / (1 - b2 ** step)) + eps)
-        np.testing.assert_allclose(z.cpu().numpy(), expect, rtol=1e-5, atol=1e-6)
+        ws = teacher_forced_step(bw, MODES[mode], z, X, m, v, step, ws, consts)
 
 
-def test_config5_barycenter_loss_decreases_and_first_step_matches():
+def test_config5_barycenter_teacher_forced_and_trajectory():
+    # K = 64, L = 512, D = 32, gamma = 1, fused, 50 Adam steps.  The library runs freely; at steps 1, 10,
+    # 25 and 50 the oracle takes the same step from the library's state (z, m, v) and loss, gradient and
+    # both moments are compared.  Late steps have z close to the sequences, where the norm expansion of
+    # the cost cancels most.  The oracle also runs the 50 steps on its own: the two trajectories are
+    # compared loosely at the end (Adam divides by sqrt(v), which amplifies rounding where dz ~ 0).
     import torch
 
     bw = workloads.barycenter_workload()
-    say("config 5")
+    say("config 5: K=%d L=%d D=%d gamma=%g, %d steps" % (bw.K, bw.L, bw.D, bw.gamma, bw.steps))
+    consts = (bw.lr, 0.9, 0.999, 1e-8)
     z = to_dev(bw.z0.copy())
     X = to_dev(bw.X)
     m = torch.zeros_like(z)
     v = torch.zeros_like(z)
-    z_np = bw.z0.astype(np.float64)
-    lo, dzo = oracle.barycenter_step(z_np, bw.X, bw.gamma, bw.lr, 0.9, 0.999, 1e-8, 1,
-                                     np.zeros_like(z_np), np.zeros_like(z_np))
     ws = None
-    losses = []
-    for step in range(1, 11):
-        loss, dz, ws = pkg.sdtw_barycenter_step(z, X, m, v, bw.gamma, step, bw.lr, workspace=ws, want_dz=(step == 1))
-        if step == 1:
-            torch.cuda.synchronize()
-            assert abs(loss.item() - lo) <= VALUE_RTOL * max(abs(lo), 1.0)
-            assert np.abs(dz.cpu().numpy() - dzo).max() <= GRAD_RTOL * np.abs(dzo).max()
-        losses.append(loss.item())
+    z_o = bw.z0.astype(np.float64)
+    m_o, v_o = np.zeros_like(z_o), np.zeros_like(z_o)
+    losses, losses_o = [], []
+    for step in range(1, bw.steps + 1):
+        lo, _ = oracle.barycenter_step(z_o, bw.X, bw.gamma, consts[0], consts[1], consts[2], consts[3], step, m_o, v_o)
+        losses_o.append(lo)
+        if step in (1, 10, 25, 50):
+            ws = teacher_forced_step(bw, pkg.FUSED, z, X, m, v, step, ws, consts)
+            losses.append(None)
+        else:
+            loss, _, ws = pkg.sdtw_barycenter_step(z, X, m, v, bw.gamma, step, *consts, mode=pkg.FUSED, workspace=ws)
+            losses.append(loss)
     torch.cuda.synchronize()
     assert binding.workspace_status(ws) == 0
-    assert losses[-1] < losses[0]
+    got = [None if l is None else l.item() for l in losses]
+    assert got[-2] < got[1]
+    # free-running trajectories: final point and the loss along the way
+    zz = z.cpu().numpy().astype(np.float64)
+    dev = np.abs(zz - z_o).max() / np.abs(z_o).max()
+    say("  after %d free steps: max |z - oracle z| / max |z| = %.3e" % (bw.steps, dev))
+    assert dev <= 1e-2
+    for step in (2, 9, 24, 49):
+        assert abs(got[step - 1] - losses_o[step - 1]) <= 1e-3 * max(abs(losses_o[step - 1]), 1.0), step
