@@ -117,6 +117,30 @@ int sdtw_forward(const sdtw_desc *desc, const float *x, const float *y, float *v
                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * sdtw_forward for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops that only score pairs, harnesses that forbid hipMalloc.
+ * Same arguments and result as sdtw_forward with SDTW_FLAG_VALUE_ONLY (the flag is implied: no
+ * backward call can follow), but the workspace is a buffer of SDTW_STATIC_SCRATCH_BYTES that lives
+ * inside the library's device image, one copy per GPU, held until the process ends.  The call
+ * allocates nothing (no hipMalloc / hipFree, no events), enqueues the same kernels on `stream` and
+ * returns without waiting.
+ *   - A descriptor whose value-only workspace (sdtw_workspace_bytes with SDTW_FLAG_VALUE_ONLY set)
+ *     exceeds SDTW_STATIC_SCRATCH_BYTES is refused with SDTW_ERR_WORKSPACE before anything is
+ *     enqueued.
+ *   - Every call on a GPU uses that GPU's one buffer and overwrites what the last call left there:
+ *     calls that overlap on one GPU (different streams, or threads) race; order them.
+ *   - The first call on a GPU looks the buffer's address up (hipGetSymbolAddress, no allocation):
+ *     make that call outside graph capture.  The per-kernel timing hook (sdtw_debug_profile) must
+ *     be off, since it creates events.
+ *   - Device-side conditions cannot be read back (there is no workspace pointer to pass to
+ *     sdtw_workspace_status); a band that gives up waiting leaves NaN-free but meaningless values,
+ *     as for sdtw_forward.
+ */
+#define SDTW_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+int sdtw_forward_static_scratch(const sdtw_desc *desc, const float *x, const float *y, float *value,
+                                void *stream);
+
+/*
  * Backward (Sec. 2 "Backward pass", Sec. 4.2 log-space recurrence, Sec. 4.3 gradient formulas).
  * Must follow sdtw_forward with the same descriptor, x, y and workspace.
  *   grad_value [B]: device, upstream dL/dvalue per pair, or NULL for ones.

@@ -57,7 +57,7 @@ EXPORTED_SYMBOLS = (
     "sdtw_forward_ragged", "sdtw_backward_ragged",
     "sdtw_debug_export", "sdtw_debug_lane_shift", "sdtw_debug_set_spin_limit",
     "sdtw_debug_profile", "sdtw_debug_profile_read", "sdtw_debug_force_workgroup_shape",
-    "sdtw_debug_rate_probe",
+    "sdtw_debug_rate_probe", "sdtw_forward_static_scratch",
 )
 
 
@@ -88,6 +88,8 @@ def load_library():
     lib.sdtw_workspace_bytes.argtypes = [ctypes.POINTER(Desc)]
     lib.sdtw_forward.restype = i32
     lib.sdtw_forward.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, sz, vp]
+    lib.sdtw_forward_static_scratch.restype = i32
+    lib.sdtw_forward_static_scratch.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp]
     lib.sdtw_backward.restype = i32
     lib.sdtw_backward.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.sdtw_barycenter_workspace_bytes.restype = sz
@@ -248,6 +250,19 @@ def sdtw_forward_desc(desc, x, y, workspace, value, stream=None):
     if rc != 0:
         raise SdtwError(rc, "sdtw_forward")
     return value
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def sdtw_forward_static_scratch(desc, x, y, value, stream=None):
+    """sdtw_forward's values through the entry point that uses the library's own scratch buffer
+    (nothing is allocated, here or in the library).  Returns the status code."""
+    import torch
+
+    return int(load_library().sdtw_forward_static_scratch(
+        ctypes.byref(desc), _ptr(x, torch.float32, name="x"), _ptr(y, torch.float32, name="y"),
+        _ptr(value, torch.float32, (desc.B,), "value"), _stream_ptr(stream)))
 
 
 def sdtw_backward(desc, x, y, workspace, grad_value=None, want_dx=True, want_dy=True, want_E=False,

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <type_traits>
 #include <vector>
@@ -444,6 +445,30 @@ NormPlan norm_plan(const sdtw_desc *d)
     return P;
 }
 
+// Scratch of sdtw_forward_static_scratch: the workspace of a value-only forward, held by every GPU the
+// library runs on until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the kernels get the address that call returned for the current device.
+constexpr size_t kStaticScratchBytes = SDTW_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+
+// Device address of `scratch` on the current device, looked up once per device.
+void *static_scratch_ptr()
+{
+    static std::mutex mu;
+    static void *ptrs[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    if (ptrs[dev] == nullptr) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        ptrs[dev] = ptr;
+    }
+    return ptrs[dev];
+}
+
 }  // namespace
 
 extern "C" {
@@ -479,6 +504,21 @@ int sdtw_forward(const sdtw_desc *desc, const float *x, const float *y, float *v
     if (!x || !y || !value) return SDTW_ERR_INVALID_ARG;
     if (int rc = check_ws(workspace, workspace_bytes, layout_of(desc).total)) return rc;
     return forward_impl(desc, x, y, value, workspace, static_cast<hipStream_t>(stream));
+}
+
+int sdtw_forward_static_scratch(const sdtw_desc *desc, const float *x, const float *y, float *value, void *stream)
+{
+    int why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!x || !y || !value) return SDTW_ERR_INVALID_ARG;
+    sdtw_desc d = *desc;
+    d.flags |= SDTW_FLAG_VALUE_ONLY;  // no backward call can follow: the scratch belongs to the next call
+    if (layout_of(&d).total > kStaticScratchBytes) return SDTW_ERR_WORKSPACE;
+    void *ws = static_scratch_ptr();
+    if (ws == nullptr) return SDTW_ERR_HIP;
+    // (the start of the forward - forward_prep_kernel or cost_tensor_prep_kernel - stamps the header,
+    // resets the tickets and refills the boundary rows: nothing of the last call's contents is read)
+    return forward_impl(&d, x, y, value, ws, static_cast<hipStream_t>(stream));
 }
 
 int sdtw_backward(const sdtw_desc *desc, const float *x, const float *y, const float *grad_value, float *dx,
