@@ -308,7 +308,7 @@ def bench_barycenter(with_cpu):
     if with_cpu:
         import oracle
 
-        threads = oracle.max_threads()
+        threads = host_threads()
         z = bw.z0.astype(np.float64)
         m, v = np.zeros_like(z), np.zeros_like(z)
         oracle.barycenter_step(z.copy(), bw.X[:2], bw.gamma, bw.lr, 0.9, 0.999, 1e-8, 1, m.copy(), v.copy())
@@ -323,13 +323,26 @@ def bench_barycenter(with_cpu):
     return out
 
 
+_HOST_THREADS = None
+
+
+def host_threads():
+    """Threads the oracle may use, read once (a call with an explicit thread count changes OpenMP's default)."""
+    global _HOST_THREADS
+    if _HOST_THREADS is None:
+        import oracle
+
+        _HOST_THREADS = oracle.max_threads()
+    return _HOST_THREADS
+
+
 def cpu_baseline(wl, max_pairs=None, target_wall_s=2.0):
     """The CPU oracle as it stands, forward+backward, all host threads.  Small workloads: whole batches
     repeated for about target_wall_s.  max_pairs: one pass over the first max_pairs pairs of the batch
     (a pair of the N = M = 8192 configuration keeps about 2.1 GB of float64 tables in flight)."""
     import oracle
 
-    threads = oracle.max_threads()
+    threads = host_threads()
     oracle.batch(wl.x[:1, :64], wl.y[:1, :64], wl.gamma)  # load the library, touch memory
     if max_pairs is not None:
         nb = min(wl.B, max_pairs)

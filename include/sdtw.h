@@ -63,7 +63,16 @@ enum { SDTW_UNFUSED = 0, SDTW_FUSED = 1 };
  *   beside the forward sweep (it does not depend on the forward's table), so that sdtw_backward
  *   only has to combine the two tables.  The flag changes the workspace size.
  */
-enum { SDTW_FLAG_VALUE_ONLY = 1 };
+/*
+ *   SDTW_FLAG_MIN_MEMORY: trade time for memory on problems too small to fill the chip.  Those
+ *   normally keep both DP tables (16 bytes per cell) and E in the workspace and run the two sweeps side
+ *   by side; with this flag they run like large problems: the forward keeps checkpoints (0.5 bytes
+ *   per cell), the backward call runs the reverse sweep, recomputes R from the checkpoints and
+ *   contracts E into the gradients block by block without storing it.  Results agree to rounding.
+ *   The flag changes the workspace size; give the same flags to sdtw_workspace_bytes, the forward
+ *   and the backward call.  Also accepted in sdtw_bary_desc.flags.
+ */
+enum { SDTW_FLAG_VALUE_ONLY = 1, SDTW_FLAG_MIN_MEMORY = 2 };
 
 /* What sdtw_debug_export copies out of a workspace. */
 enum { SDTW_EXPORT_COST = 0, SDTW_EXPORT_R = 1, SDTW_EXPORT_E = 2 };
@@ -83,7 +92,7 @@ typedef struct sdtw_desc {
                                lengths every pair needs |x_len[b]-y_len[b]| <= w, which the device
                                does not check: such a pair's value and gradients are undefined.  The
                                sweeps skip the macro-steps outside the band. */
-    uint32_t flags;         /* 0 or SDTW_FLAG_VALUE_ONLY */
+    uint32_t flags;         /* 0 or an OR of SDTW_FLAG_VALUE_ONLY, SDTW_FLAG_MIN_MEMORY */
 } sdtw_desc;
 
 /* One barycenter step: K sequences X_k [Lx,D] against the current barycenter z [Lz,D]. */
@@ -93,7 +102,7 @@ typedef struct sdtw_bary_desc {
     int32_t mode;           /* SDTW_UNFUSED or SDTW_FUSED */
     float lr, beta1, beta2, eps; /* Adam: lr > 0, 0 <= beta < 1, eps > 0 */
     int32_t step;           /* 1-based index of this step (bias correction) */
-    uint32_t flags;         /* reserved, must be 0 */
+    uint32_t flags;         /* 0 or SDTW_FLAG_MIN_MEMORY */
 } sdtw_bary_desc;
 
 int sdtw_version(void);
@@ -147,8 +156,12 @@ int sdtw_forward_static_scratch(const sdtw_desc *desc, const float *x, const flo
  *   dx [B,N,D], dy [B,M,D]: device, out; either may be NULL if not wanted.  With
  *        x_batch_stride 0 dx still has one [N,D] slab per pair (the caller sums them).
  *   E_out [B,N,M]: device, out, optional (NULL): the alignment matrix E (entries that underflow
- *        float32 are exact zeros; inside the workspace E exists only block-wise where it is
- *        non-zero).
+ *        float32 are exact zeros).  For large problems with D <= 128 (and with
+ *        SDTW_FLAG_MIN_MEMORY) the workspace holds no E at all: without E_out the reverse sweep
+ *        contracts every 32x32 block of E into dx and dy while the block is still on the chip
+ *        (Sec. 4.3: the gradients "without ever materializing" a B x N x M tensor); with E_out the
+ *        blocks are written to the caller's memory and the gradients are formed from there.
+ *        Both routes give the same dx, dy to rounding.
  */
 int sdtw_backward(const sdtw_desc *desc, const float *x, const float *y, const float *grad_value,
                   float *dx, float *dy, float *E_out, void *workspace, size_t workspace_bytes,
@@ -224,7 +237,8 @@ int sdtw_workspace_status(const void *workspace, size_t workspace_bytes, void *s
  * Test hook: copies an intermediate out of a workspace as a plain row-major tensor.
  *   SDTW_EXPORT_COST: out = float32 [B,N,M], the cost tensor d (unfused mode, after forward)
  *   SDTW_EXPORT_R:    out = float64 [B,N,M], the DP table R[1..N,1..M] (after forward)
- *   SDTW_EXPORT_E:    out = float32 [B,N,M], the alignment matrix (after backward)
+ *   SDTW_EXPORT_E:    out = float32 [B,N,M], the alignment matrix (after backward; SDTW_ERR_UNSUPPORTED
+ *                     where the workspace keeps no E: use sdtw_backward's E_out there)
  * `out` is a device pointer with room for B*N*M elements of that type.
  */
 int sdtw_debug_export(const sdtw_desc *desc, const void *workspace, size_t workspace_bytes,

@@ -15,6 +15,7 @@ _lib = None
 UNFUSED = 0
 FUSED = 1
 FLAG_VALUE_ONLY = 1
+FLAG_MIN_MEMORY = 2
 EXPORT_COST, EXPORT_R, EXPORT_E = 0, 1, 2
 
 STATUS_OK = 0
@@ -213,7 +214,7 @@ def _desc_for(x, y, gamma, mode):
 
 
 def sdtw_forward(x, y, gamma, mode=FUSED, workspace=None, value=None, stream=None, value_only=False,
-                 bandwidth=0):
+                 bandwidth=0, min_memory=False):
     """value[b] = sdtw_gamma(x_b, y_b).  Returns (value, desc, workspace); keep the last two for
     :func:`sdtw_backward`.  x [B,N,D] or [N,D]; y [B,M,D] or [M,D]; float32 device tensors.
     ``value_only=True`` sets SDTW_FLAG_VALUE_ONLY: no backward call will follow.
@@ -224,7 +225,9 @@ def sdtw_forward(x, y, gamma, mode=FUSED, workspace=None, value=None, stream=Non
     desc = _desc_for(x, y, gamma, mode)
     desc.bandwidth = int(bandwidth)
     if value_only:
-        desc.flags = FLAG_VALUE_ONLY
+        desc.flags |= FLAG_VALUE_ONLY
+    if min_memory:
+        desc.flags |= FLAG_MIN_MEMORY
     if workspace is None:
         nbytes = sdtw_workspace_bytes(desc)
         if nbytes == 0:
@@ -292,7 +295,7 @@ def sdtw_backward(desc, x, y, workspace, grad_value=None, want_dx=True, want_dy=
 
 
 def sdtw_forward_ragged(x, y, x_len, y_len, gamma, mode=FUSED, workspace=None, value=None, stream=None,
-                        bandwidth=0):
+                        bandwidth=0, min_memory=False):
     """As :func:`sdtw_forward` for pairs of individual lengths: x_len, y_len are int32 device tensors
     [B] (or None).  Returns (value, desc, workspace)."""
     import torch
@@ -300,6 +303,8 @@ def sdtw_forward_ragged(x, y, x_len, y_len, gamma, mode=FUSED, workspace=None, v
     lib = load_library()
     desc = _desc_for(x, y, gamma, mode)
     desc.bandwidth = int(bandwidth)
+    if min_memory:
+        desc.flags |= FLAG_MIN_MEMORY
     if workspace is None:
         nbytes = sdtw_workspace_bytes(desc)
         if nbytes == 0:
@@ -389,20 +394,20 @@ def sdtw_normalized_backward(desc, x, y, workspace, grad_value=None, want_dx=Tru
     return dx, dy
 
 
-def make_bary_desc(K, Lz, Lx, D, gamma, mode, lr, beta1, beta2, eps, step):
+def make_bary_desc(K, Lz, Lx, D, gamma, mode, lr, beta1, beta2, eps, step, flags=0):
     return BaryDesc(K, Lz, Lx, D, float(gamma), int(mode), float(lr), float(beta1), float(beta2), float(eps),
-                    int(step), 0)
+                    int(step), int(flags))
 
 
 def sdtw_barycenter_step(z, X, adam_m, adam_v, gamma, step, lr=0.05, beta1=0.9, beta2=0.999, eps=1e-8,
-                         mode=FUSED, workspace=None, loss=None, dz=None, want_dz=False, stream=None):
+                         mode=FUSED, workspace=None, loss=None, dz=None, want_dz=False, stream=None, min_memory=False):
     """One in-place Adam step on z [Lz,D] against X [K,Lx,D].  Returns (loss [1], dz or None, workspace)."""
     import torch
 
     lib = load_library()
     K, Lx, D = X.shape
     Lz = z.shape[0]
-    bdesc = make_bary_desc(K, Lz, Lx, D, gamma, mode, lr, beta1, beta2, eps, step)
+    bdesc = make_bary_desc(K, Lz, Lx, D, gamma, mode, lr, beta1, beta2, eps, step, FLAG_MIN_MEMORY if min_memory else 0)
     if workspace is None:
         nbytes = sdtw_barycenter_workspace_bytes(bdesc)
         if nbytes == 0:

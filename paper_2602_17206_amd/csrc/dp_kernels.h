@@ -1130,7 +1130,199 @@ __device__ __forceinline__ void flush_E_block(const Params &p, const SweepRange 
     }
 }
 
-template <int KCH, int SLOTS, int NPROD>
+// ---------------------------------------------------------------------------------------------
+// Input gradients where E is produced (Sec. 4.3, last two equations):
+//   dx_i = 2 (x_i sum_j E_ij - sum_j E_ij y_j),     dy_j = 2 (y_j sum_i E_ij - sum_i E_ij x_i).
+// One wavefront contracts a finished 32x32 block of E (in the ring, skewed) against the 32 rows of y
+// and of x it meets, on the fp16 matrix cores with both operands split into two float16 pieces
+// (E * 2^10; the sequence rows times one power-of-two scale per block, the largest of the rows'
+// scales, from the per-row scales the forward call stored): a1*b1 + a1*b2 + a2*b1, float32
+// accumulate, the same arithmetic as input_grad_half_kernel.  gradient_finish_kernel applies the
+// rest of the formula afterwards.  A block whose entries are all below 2^-40 adds nothing (what that
+// drops is below 2^-40 M max|y| per gradient entry) and is left after one look at its entries.
+//
+// Where the sums go.  Rows i0.. of the x side belong to this band alone: sum_j E_ij y_j and sum_j E_ij
+// are added to p.gdx (the caller's dx) and p.rsum in float32, block after block in the order of the
+// sweep.  Columns j0.. of the y side receive a term from every band of the pair, and the bands of a
+// pair run at the same time: their terms are added with integer atomics to a fixed-point number per
+// entry, so that the sum does not depend on who comes first (integer addition commutes exactly; a
+// float32 atomic would not).  The number has unit 2^(e_b - prec), e_b = exponent bound of pair b's x
+// (|x| < 2^e_b, p.pair_exp), and two 32-bit words: the low p.fx_lo_bits bits of every term are added
+// to one word (p.gdy, the caller's dy, as unsigned), the rest to the other (p.gdy_hi); neither can
+// overflow with as many terms as the pair has blocks in a column (the host chooses the widths).
+// ---------------------------------------------------------------------------------------------
+constexpr float kGradLive = 9.094947e-13f;  // 2^-40
+constexpr int kMargBits = 24;               // fixed-point digits of the column sums of E (terms <= 33)
+
+__device__ __forceinline__ void fixed_point_add(unsigned *lo_word, int *hi_word, float v, int shift, int lo_bits)
+{
+    const long long q = __float2ll_rn(ldexpf(v, shift));
+    const unsigned lo = (unsigned)(q & ((1ll << lo_bits) - 1));
+    const int hi = (int)(q >> lo_bits);
+    if (lo != 0u) atomicAdd(lo_word, lo);
+    if (hi != 0) atomicAdd(hi_word, hi);
+}
+
+template <int NFT, int COLS = kRingCols, int STRIDE = kRingStride>
+__device__ __attribute__((noinline)) void grad_E_block(const Params &p, const SweepRange &rg, const float *ring, int rb, int cb,
+                                                       int row0, int b, int Nl, int Ml, int lane)
+{
+    if (cb < 0 || cb >= p.ncb || row0 + 32 * rb >= p.N || !block_in_range(rg, rb, cb)) return;
+    const int r = lane & 31, h = lane >> 5;
+    const int i0 = row0 + 32 * rb, j0 = cb * kBlk;
+    const int sb = 32 * (cb + rb);  // step at which band row 32*rb meets column j0
+    // E[i0 + r][j0 + 16 ks + 8 h + c]: the A operand of the product with y, and every entry of the
+    // block once over the wavefront
+    float ea[2][8];
+    {
+        const float *rowp = ring + (32 * rb + r) * STRIDE;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                // (ring positions of cells beyond the pair's grid may belong to macro-steps that never ran)
+                const float v = rowp[(sb + r + 16 * ks + 8 * h + c) & (COLS - 1)];
+                ea[ks][c] = (i0 + r < Nl && j0 + 16 * ks + 8 * h + c < Ml) ? v : 0.f;
+            }
+    }
+    bool any = false;
+    float rs = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            any |= ea[ks][c] >= kGradLive;
+            rs += ea[ks][c];
+        }
+    if (!__any(any)) return;
+    rs += __shfl_xor(rs, 32);
+    if (h == 0 && i0 + r < p.N) p.rsum[(size_t)b * p.N + i0 + r] += rs;
+
+    const float sA = 1024.0f;
+    if (p.gdx != nullptr) {
+        const unsigned *yis = reinterpret_cast<const unsigned *>(p.yis + b * p.yn_stride);
+        // (positive powers of two: their bit patterns order like the values)
+        const float ismax = wave_max_f32(__uint_as_float(yis[min(j0 + r, Ml - 1)]));
+        const float sB = 1.0f / ismax, unscale = ismax * (1.0f / 1024.0f);
+        half8 a1[2], a2[2];
+        split8(ea[0], sA, a1[0], a2[0]);
+        split8(ea[1], sA, a1[1], a2[1]);
+        const float *yb = p.y + b * p.y_stride;
+        float *g = p.gdx + ((size_t)b * p.N + i0) * p.D;
+        // all operand values and all sums so far are asked for before the first is used
+        float bv[NFT][2][8], old[NFT][16];
+#pragma unroll
+        for (int t = 0; t < NFT; ++t) {
+            const int f = 32 * t + r;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                const int jb = j0 + 16 * ks + 8 * h;
+                const float *src = yb + (size_t)jb * p.D + f;
+#pragma unroll
+                for (int c = 0; c < 8; ++c) bv[t][ks][c] = (jb + c < Ml && f < p.D) ? src[(size_t)c * p.D] : 0.f;
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < NFT; ++t) {
+            const int f = 32 * t + r;
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int rr = 8 * (q >> 2) + 4 * h + (q & 3);
+                old[t][q] = (i0 + rr < p.N && f < p.D) ? g[(size_t)rr * p.D + f] : 0.f;
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < NFT; ++t) {
+            const int f = 32 * t + r;
+            floatx16 acc = zero16();
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                half8 b1, b2;
+                split8(bv[t][ks], sB, b1, b2);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1[ks], b1, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1[ks], b2, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a2[ks], b1, acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int rr = 8 * (q >> 2) + 4 * h + (q & 3);
+                if (i0 + rr < p.N && f < p.D) g[(size_t)rr * p.D + f] = fmaf(acc[q], unscale, old[t][q]);
+            }
+        }
+    }
+    if (p.gdy != nullptr) {
+        // E[i0 + 16 ks + 8 h + c][j0 + r]: the A operand of the product with x
+        float et[2][8];
+        float cs = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                const int rr = 16 * ks + 8 * h + c;
+                const float v = ring[(32 * rb + rr) * STRIDE + ((sb + r + rr) & (COLS - 1))];
+                et[ks][c] = (i0 + rr < Nl && j0 + r < Ml) ? v : 0.f;
+                cs += et[ks][c];
+            }
+        cs += __shfl_xor(cs, 32);
+        if (h == 0 && j0 + r < p.M)
+            fixed_point_add(p.csum_lo + (size_t)b * p.M + j0 + r, p.csum_hi + (size_t)b * p.M + j0 + r, cs, kMargBits, p.fx_lo_bits);
+        const unsigned *xis = reinterpret_cast<const unsigned *>(p.xis + b * p.xn_stride);
+        const float ismax = wave_max_f32(__uint_as_float(xis[min(i0 + r, Nl - 1)]));
+        const float sB = 1.0f / ismax, unscale = ismax * (1.0f / 1024.0f);
+        half8 a1[2], a2[2];
+        split8(et[0], sA, a1[0], a2[0]);
+        split8(et[1], sA, a1[1], a2[1]);
+        const float *xb = p.x + b * p.x_stride;
+        const int shift = p.fx_prec - p.pair_exp[b];
+        unsigned *glo = reinterpret_cast<unsigned *>(p.gdy) + ((size_t)b * p.M + j0) * p.D;
+        int *ghi = p.gdy_hi + ((size_t)b * p.M + j0) * p.D;
+        float bv[NFT][2][8];
+#pragma unroll
+        for (int t = 0; t < NFT; ++t) {
+            const int f = 32 * t + r;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                const int ib = i0 + 16 * ks + 8 * h;
+                const float *src = xb + (size_t)ib * p.D + f;
+#pragma unroll
+                for (int c = 0; c < 8; ++c) bv[t][ks][c] = (ib + c < Nl && f < p.D) ? src[(size_t)c * p.D] : 0.f;
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < NFT; ++t) {
+            const int f = 32 * t + r;
+            floatx16 acc = zero16();
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                half8 b1, b2;
+                split8(bv[t][ks], sB, b1, b2);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1[ks], b1, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1[ks], b2, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a2[ks], b1, acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int cc = 8 * (q >> 2) + 4 * h + (q & 3);
+                if (j0 + cc < p.M && f < p.D)
+                    fixed_point_add(glo + (size_t)cc * p.D + f, ghi + (size_t)cc * p.D + f, acc[q] * unscale, shift, p.fx_lo_bits);
+            }
+        }
+    }
+}
+
+// the same for any D <= 128: 32 features per pass of the matrix cores
+__device__ __forceinline__ void grad_E_block_any(const Params &p, const SweepRange &rg, const float *ring, int rb, int cb,
+                                                 int row0, int b, int Nl, int Ml, int lane)
+{
+    if (p.D <= 32)
+        grad_E_block<1>(p, rg, ring, rb, cb, row0, b, Nl, Ml, lane);
+    else if (p.D <= 64)
+        grad_E_block<2>(p, rg, ring, rb, cb, row0, b, Nl, Ml, lane);
+    else
+        grad_E_block<4>(p, rg, ring, rb, cb, row0, b, Nl, Ml, lane);
+}
+
+template <int KCH, int SLOTS, int NPROD, bool GRAD = false>
 __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS> &sh, unsigned &ticket_s,
                                                 double (&edge_out)[SLOTS][kEdgeOut], double (&hand)[kHandDoubles])
 {
@@ -1214,7 +1406,10 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
     // consumer's chain instead of in it (measured with recomputation at the L = 8192 shape: 6.3 -> 5.3 ms
     // at D = 16, 6.5 -> 6.1 ms at D = 64) - except where the producer has no registers left for it
     // (recomputation with D > 64: the x pieces fill them, the flush would spill).
-    constexpr bool kProducerFlush = !TSWEEP && !(dp_recompute(KCH, SLOTS) && KCH > 4);
+    // GRAD: E is not written out at all; the consumer contracts each finished block into the gradients
+    // (grad_E_block) right after it has published the macro-step's boundary values.
+    static_assert(!GRAD || dp_recompute(KCH, SLOTS), "the contracting sweep is the recomputing one");
+    constexpr bool kProducerFlush = !GRAD && !TSWEEP && !(dp_recompute(KCH, SLOTS) && KCH > 4);
 
     if (producer) {
         // Besides the cost blocks, the producers write out the E blocks the consumer finished in the
@@ -1500,8 +1695,8 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
                 steps(std::false_type{}, std::false_type{});
             else
                 steps(std::false_type{}, std::true_type{});
-            // first row of the band, columns 32*sg .. 32*sg+31, for the band above
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            // first row of the band, columns 32*sg .. 32*sg+31, for the band above
             if (emit_top && lane < kBlk) {
                 const int j = sg * kBlk + lane;
                 // (also from a chained pair's lower band, whose first row travels through LDS: see the forward sweep)
@@ -1513,7 +1708,13 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
             // (both hold cells of this macro-step and the one before it only)
             const bool blocks_dead = dead && dead_prev;
             dead_prev = dead;
-            if constexpr (!kProducerFlush && !TSWEEP) {
+            if constexpr (GRAD) {
+                // into the gradients, once the band above has what it waits for
+                if (!blocks_dead) {
+                    grad_E_block_any(p, rg, ring, 0, sg, row0, bb, Nl, Ml, lane);
+                    grad_E_block_any(p, rg, ring, 1, sg - 1, row0, bb, Nl, Ml, lane);
+                }
+            } else if constexpr (!kProducerFlush && !TSWEEP) {
                 flush_E_block(p, rg, ring, Eb, nzb, 0, sg, row0, lane, blocks_dead);
                 flush_E_block(p, rg, ring, Eb, nzb, 1, sg - 1, row0, lane, blocks_dead);
             } else if constexpr (!TSWEEP) {
@@ -1825,14 +2026,14 @@ __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void forward_dp_kernel(Pa
     forward_dp_body<KCH, SLOTS, NPROD>(p, value, sh, ticket_s, edge_out, hand);
 }
 
-template <int KCH, int SLOTS, int NPROD>
+template <int KCH, int SLOTS, int NPROD, bool GRAD = false>
 __global__ __launch_bounds__(wg_threads(SLOTS, NPROD)) void backward_dp_kernel(Params p)
 {
     __shared__ WgShared<SLOTS> sh;
     __shared__ unsigned ticket_s;
     __shared__ double edge_out[SLOTS][kEdgeOut];
     __shared__ double hand[kHandDoubles];
-    reverse_dp_body<KCH, SLOTS, NPROD>(p, sh, ticket_s, edge_out, hand);
+    reverse_dp_body<KCH, SLOTS, NPROD, GRAD>(p, sh, ticket_s, edge_out, hand);
 }
 
 template <int KCH, int SLOTS, int NPROD>

@@ -248,6 +248,24 @@ __global__ __launch_bounds__(256) void backward_prep_kernel(Params p)
         }
     }
     fill_boundary_rows(p, p.brow_b, true, blockIdx.x, gridDim.x);
+    // a sweep that contracts E into the gradients itself adds to these: they start at zero
+    if (p.rsum != nullptr) {
+        const size_t stride = (size_t)gridDim.x * blockDim.x, first = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+        const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
+        auto clear = [&](float *dst, size_t n) {  // dst is 16-byte aligned (caller's tensors, workspace regions)
+            if (dst == nullptr) return;
+            for (size_t i = first; i < n / 4; i += stride) reinterpret_cast<float4 *>(dst)[i] = z4;
+            for (size_t i = (n / 4) * 4 + first; i < n; i += stride) dst[i] = 0.f;
+        };
+        clear(p.gdx, (size_t)p.B * p.N * p.D);
+        clear(p.rsum, (size_t)p.B * p.N);
+        if (p.gdy != nullptr) {  // (integer words: all bits zero, like 0.f)
+            clear(p.gdy, (size_t)p.B * p.M * p.D);
+            clear(reinterpret_cast<float *>(p.gdy_hi), (size_t)p.B * p.M * p.D);
+            clear(reinterpret_cast<float *>(p.csum_lo), (size_t)p.B * p.M);
+            clear(reinterpret_cast<float *>(p.csum_hi), (size_t)p.B * p.M);
+        }
+    }
     // with a band constraint the sweep never visits the blocks of E outside the window: their
     // "any non-zero" flags are cleared here
     if (p.window < kNoWindow || p.x_len != nullptr || p.y_len != nullptr) {
@@ -710,6 +728,97 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
             }
             og += 8 * (size_t)p.D;
         }
+    }
+}
+
+// Exponent bound of every pair's x for the fixed-point sums of the y side (Params::gdy_hi):
+// pair_exp[b] = e with |x_b[i][k]| < 2^e for all rows of the pair, read off the per-row scales
+// 2^(e_row - 14) that the forward call stored with the split copies.  One workgroup per pair.
+__global__ __launch_bounds__(256) void pair_exponent_kernel(Params p, int32_t *__restrict__ pair_exp)
+{
+    __shared__ unsigned part[4];
+    const int b = blockIdx.x;
+    const int Nl = pair_len(p.x_len, b, p.N);
+    const unsigned *is = reinterpret_cast<const unsigned *>(p.xis + b * p.xn_stride);
+    unsigned m = 0u;  // positive powers of two: their bit patterns order like the values
+    for (int i = threadIdx.x; i < Nl; i += 256) m = max(m, is[i]);
+    const float mw = wave_max_f32(__uint_as_float(m));
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = __float_as_uint(mw);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned bits = max(max(part[0], part[1]), max(part[2], part[3]));
+        pair_exp[b] = (int32_t)((bits >> 23) & 255u) - 127 + 14;
+    }
+}
+
+// After a reverse sweep that contracted E into the gradients itself: gdx holds sum_j E_ij y_j, rsum
+// sum_j E_ij; gdy / gdy_hi and csum_lo / csum_hi hold sum_i E_ij x_i and sum_i E_ij in fixed point
+// (see Params).  The formulas of Sec. 4.3 are completed in place,
+//   dx_i = 2 g (x_i sum_j E_ij - sum_j E_ij y_j),   dy_j = 2 g (y_j sum_i E_ij - sum_i E_ij x_i),
+// with zeros beyond a pair's own lengths (the sequences' padding is not read) and NaN when the
+// backward call was refused.  One thread per W consecutive features (W = 4 needs D % 4 == 0 and
+// 16-byte aligned tensors).
+template <int W>
+__global__ __launch_bounds__(256) void gradient_finish_kernel(Params p, const float *__restrict__ grad_value)
+{
+    const bool bad = backward_refused(p);
+    const float qnan = __builtin_nanf("");
+    const size_t nx = (size_t)p.B * p.N * p.D, ny = (size_t)p.B * p.M * p.D;
+    const size_t stride = (size_t)gridDim.x * blockDim.x * W;
+    const double lo_unit = (double)(1ll << p.fx_lo_bits);
+    for (size_t e = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * W; e < nx + ny; e += stride) {
+        const bool isx = e < nx;
+        float *g = isx ? p.gdx : p.gdy;
+        if (g == nullptr) continue;
+        const size_t q = isx ? e : e - nx;           // element of [B, P, D]
+        const int P = isx ? p.N : p.M;
+        const size_t row = q / (size_t)p.D;          // b * P + position
+        const int b = (int)(row / (size_t)P), pos = (int)(row - (size_t)b * P);
+        const int len = pair_len_lane(isx ? p.x_len : p.y_len, b, P);
+        const float *seq = (isx ? p.x + b * p.x_stride : p.y + b * p.y_stride) + (size_t)pos * p.D + (q - row * p.D);
+        const float scale = 2.0f * (grad_value ? grad_value[b] : 1.0f);
+        const bool in = pos < len;
+        float acc[W], sv[W], marg;
+        if (isx) {
+            marg = p.rsum[row];
+#pragma unroll
+            for (int c = 0; c < W; ++c) acc[c] = g[q + c];
+        } else {
+            marg = (float)ldexp((double)p.csum_hi[row] * lo_unit + (double)p.csum_lo[row], -24);
+            const unsigned *lo = reinterpret_cast<const unsigned *>(g);
+            const int ex = p.pair_exp[b] - p.fx_prec;
+#pragma unroll
+            for (int c = 0; c < W; ++c) acc[c] = (float)ldexp((double)p.gdy_hi[q + c] * lo_unit + (double)lo[q + c], ex);
+        }
+#pragma unroll
+        for (int c = 0; c < W; ++c) sv[c] = in ? seq[c] : 0.f;
+#pragma unroll
+        for (int c = 0; c < W; ++c) {
+            const float o = in ? scale * (sv[c] * marg - acc[c]) : 0.f;
+            g[q + c] = bad ? qnan : o;
+        }
+    }
+}
+
+// Where the caller supplied the memory for E (large problems, E_out): the sweep wrote the blocks that
+// hold a non-zero straight into it; this fills in the rest (zeros; NaN when the call was refused).
+__global__ void complete_E_kernel(Params p)
+{
+    const size_t n = (size_t)p.B * p.N * p.M;
+    const bool bad = backward_refused(p);
+    const float qnan = __builtin_nanf("");
+    size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; e < n; e += stride) {
+        const int j = (int)(e % (size_t)p.M);
+        const size_t bi = e / (size_t)p.M;
+        const int i = (int)(bi % (size_t)p.N);
+        const size_t b = bi / (size_t)p.N;
+        const bool live = p.nz[(b * p.nrb + i / kBlk) * p.ncb + j / kBlk] != 0;
+        if (bad)
+            p.E[e] = qnan;
+        else if (!live)
+            p.E[e] = 0.f;
     }
 }
 

@@ -45,8 +45,9 @@ struct Layout {
     int32_t Dp;                  // D rounded up to 16, 32, 64 or 128: row length of the split-half operand copies (0: none)
     int32_t recompute;           // 1: checkpoints instead of the R table (large problems)
     int32_t two_sweep;           // 1: the forward call also runs the reverse sweep and stores its table Q
+    int32_t sweep_grad;          // 1: the reverse sweep contracts E into the gradients itself, E is not stored (see make_layout)
     size_t off_hdr, off_rfinal, off_xn, off_yn, off_xis, off_yis, off_xh, off_yh, off_brow, off_brow_b, off_R,
-        off_Q, off_ckpt, off_cost, off_E, off_nz, total;
+        off_Q, off_ckpt, off_cost, off_E, off_nz, off_rsum, off_csum, off_dyhi, off_pexp, total;
 };
 
 // With D <= 128 the workspace keeps a copy of x and y split into two float16 pieces per element
@@ -116,9 +117,23 @@ inline Layout make_layout(int32_t B, int32_t N, int32_t M, int32_t D, int32_t mo
     L.off_cost = o;
     if (mode == 0) o = align_up(o + (size_t)B * N * (size_t)M * sizeof(float), 256);
     o += kGuardBytes;
-    L.off_E = o;        o = align_up(o + (size_t)B * N * (size_t)M * sizeof(float), 256);
+    // The alignment matrix E [B,N,M] float32 - unless the reverse sweep contracts every finished block
+    // of it into the gradients on the spot (large problems with split operand copies, i.e. D <= 128):
+    // then E exists only block by block in LDS, the workspace holds the marginal sums of E instead,
+    // and a caller who wants E itself supplies the memory for it (the E_out argument).
+    L.sweep_grad = (recompute && L.Dp > 0) ? 1 : 0;
+    L.off_E = o;
+    if (!L.sweep_grad) o = align_up(o + (size_t)B * N * (size_t)M * sizeof(float), 256);
     o += kGuardBytes;
     L.off_nz = o;       o = align_up(o + (size_t)B * L.nrb * (size_t)L.ncb, 256);
+    L.off_rsum = o;
+    if (L.sweep_grad) o = align_up(o + (size_t)B * N * sizeof(float), 256);
+    L.off_csum = o;  // two 32-bit words per column (see Params::gdy_hi)
+    if (L.sweep_grad) o += 2 * align_up((size_t)B * M * sizeof(uint32_t), 256);
+    L.off_dyhi = o;
+    if (L.sweep_grad) o = align_up(o + (size_t)B * M * (size_t)D * sizeof(int32_t), 256);
+    L.off_pexp = o;
+    if (L.sweep_grad) o = align_up(o + (size_t)B * sizeof(int32_t), 256);
     L.total = o;
     return L;
 }
@@ -154,8 +169,21 @@ struct Params {
     double *ckpt;                  // large problems: forward lane state per macro-step instead of R
     int32_t two_sweep;
     float *cost;
-    float *E;
+    float *E;                      // alignment matrix: in the workspace, or the caller's E_out where the workspace has none
     unsigned char *nz;
+    // Reverse sweep that contracts E into the gradients itself (Layout::sweep_grad, no E_out wanted):
+    // gdx [B,N,D] / gdy [B,M,D] accumulate sum_j E_ij y_j / sum_i E_ij x_i (the caller's dx, dy buffers,
+    // either may be null), rsum [B,N] / csum [B,M] the marginal sums of E; gradient_finish_kernel
+    // turns them into dx, dy.
+    // The y side is summed over all bands of a pair at once, in fixed point with integer atomics (exact
+    // in any order): unit 2^(pair_exp[b] - fx_prec), low fx_lo_bits bits of every term into gdy (as
+    // unsigned), the rest into gdy_hi; the column sums of E likewise (unit 2^-24) in csum_lo / csum_hi.
+    float *gdx, *gdy;
+    float *rsum;
+    unsigned *csum_lo;
+    int32_t *csum_hi, *gdy_hi;
+    const int32_t *pair_exp;       // [B]: |x_b| < 2^pair_exp[b] (from the per-row scales of the split copies)
+    int32_t fx_prec, fx_lo_bits;
 };
 
 }  // namespace sdtw

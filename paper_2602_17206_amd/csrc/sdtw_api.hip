@@ -55,7 +55,7 @@ bool desc_ok(const sdtw_desc *d, int *why)
     if (d->B > 32767) return false;
     if (!(d->gamma > 0.0f) || !std::isfinite(d->gamma)) return false;
     if (d->mode != SDTW_UNFUSED && d->mode != SDTW_FUSED) return false;
-    if ((d->flags & ~(uint32_t)SDTW_FLAG_VALUE_ONLY) != 0) return false;
+    if ((d->flags & ~(uint32_t)(SDTW_FLAG_VALUE_ONLY | SDTW_FLAG_MIN_MEMORY)) != 0) return false;
     if (d->x_batch_stride != 0 && d->x_batch_stride != (int64_t)d->N * d->D) return false;
     if (d->y_batch_stride != 0 && d->y_batch_stride != (int64_t)d->M * d->D) return false;
     if ((int64_t)d->M + 128 > 0x3FFFFFFF || (int64_t)d->N + 128 > 0x3FFFFFFF) return false;
@@ -91,6 +91,7 @@ int64_t busy_bands(const sdtw_desc *d)
 bool small_problem(const sdtw_desc *d)
 {
     if (g_force_slots) return g_force_slots != 4;
+    if (d->flags & SDTW_FLAG_MIN_MEMORY) return false;  // checkpoints instead of tables, no stored E
     return (int64_t)d->B * busy_bands(d) <= (effective_window(d) < kNoWindow ? 640 : 1536);
 }
 
@@ -147,8 +148,14 @@ Params make_params(const sdtw_desc *d, const Layout &L, const float *x, const fl
     p.two_sweep = L.two_sweep;
     p.ckpt = reinterpret_cast<double *>(base + L.off_ckpt);
     p.cost = reinterpret_cast<float *>(base + L.off_cost);
-    p.E = reinterpret_cast<float *>(base + L.off_E);
+    p.E = L.sweep_grad ? nullptr : reinterpret_cast<float *>(base + L.off_E);  // (sweep_grad: the caller's E_out, if any)
     p.nz = reinterpret_cast<unsigned char *>(base + L.off_nz);
+    // (the accumulators of a reverse sweep that forms the gradients itself: set by that backward call)
+    p.gdx = p.gdy = p.rsum = nullptr;
+    p.csum_lo = nullptr;
+    p.csum_hi = p.gdy_hi = nullptr;
+    p.pair_exp = nullptr;
+    p.fx_prec = p.fx_lo_bits = 0;
     return p;
 }
 
@@ -172,6 +179,7 @@ int fused_variant(int D)
 template <bool FWD, int KCH>
 void launch_dp_kch(const sdtw_desc *d, const Layout &L, const Params &p, float *value, hipStream_t st)
 {
+    [[maybe_unused]] const bool grad = p.rsum != nullptr;  // the reverse sweep contracts E into the gradients itself
     constexpr int NP = KCH > 0 ? 2 : 1;
     if (small_problem(d)) {
         // Pairs of consecutive bands share a workgroup (the hand-over between them stays in LDS)
@@ -211,8 +219,14 @@ void launch_dp_kch(const sdtw_desc *d, const Layout &L, const Params &p, float *
         // long macro-steps leave a single producer enough time.
         if constexpr (FWD)
             forward_dp_kernel<KCH, 4, NP><<<tasks, wg_threads(4, NP), 0, st>>>(p, value);
-        else
-            backward_dp_kernel<KCH, 4, 1><<<tasks, wg_threads(4, 1), 0, st>>>(p);
+        else if constexpr (KCH != 0) {
+            if (grad)
+                backward_dp_kernel<KCH, 4, 1, true><<<tasks, wg_threads(4, 1), 0, st>>>(p);
+            else
+                backward_dp_kernel<KCH, 4, 1><<<tasks, wg_threads(4, 1), 0, st>>>(p);
+        } else {
+            backward_dp_kernel<KCH, 4, 1><<<tasks, wg_threads(4, 1), 0, st>>>(p);  // D > 128: no split copies, E is stored
+        }
     }
 }
 
@@ -307,7 +321,31 @@ int backward_impl(const sdtw_desc *d, const float *x, const float *y, const floa
 {
     (void)hipGetLastError();  // see forward_impl
     const Layout L = layout_of(d);
-    const Params p = make_params(d, L, x, y, ws, x_len, y_len);
+    Params p = make_params(d, L, x, y, ws, x_len, y_len);
+    // Large problems with D <= 128 keep no E in the workspace.  Without E_out the reverse sweep contracts
+    // every finished block of E into the gradients where it stands (dx, dy serve as accumulators); with
+    // E_out the blocks go to the caller's memory and the gradients are formed from there, as for small
+    // problems.
+    const bool sweep_grad = L.sweep_grad && E_out == nullptr;
+    if (L.sweep_grad && E_out != nullptr) p.E = E_out;
+    if (sweep_grad) {
+        char *base = static_cast<char *>(ws);
+        p.gdx = dx;
+        p.gdy = dy;
+        p.rsum = reinterpret_cast<float *>(base + L.off_rsum);
+        p.csum_lo = reinterpret_cast<unsigned *>(base + L.off_csum);
+        p.csum_hi = reinterpret_cast<int32_t *>(base + L.off_csum + align_up((size_t)d->B * d->M * sizeof(uint32_t), 256));
+        p.gdy_hi = reinterpret_cast<int32_t *>(base + L.off_dyhi);
+        p.pair_exp = reinterpret_cast<const int32_t *>(base + L.off_pexp);
+        // Fixed-point format of the y-side sums: a column receives at most two terms per band (one per
+        // 32-row block), each below 2^(prec + 6) units.  With nb bits for their number, the low word
+        // takes lo_bits = 32 - nb bits of every term and the high word the other prec + 6 - lo_bits,
+        // which have to fit 31 bits nb times over: prec <= 57 - 2 nb (26 is plenty).
+        int nb = 1;
+        while ((1ll << nb) < 2ll * L.nbands + 1) ++nb;
+        p.fx_lo_bits = 32 - nb;
+        p.fx_prec = std::min(26, 57 - 2 * nb);
+    }
     if (L.two_sweep) {
         // both tables are there: combine them (the kernel checks the workspace itself)
         ProfScope ps("alignment", st);
@@ -326,12 +364,26 @@ int backward_impl(const sdtw_desc *d, const float *x, const float *y, const floa
     } else {
         {
             ProfScope ps("backward_prep", st);
+            if (sweep_grad && dy)
+                pair_exponent_kernel<<<d->B, 256, 0, st>>>(p, reinterpret_cast<int32_t *>(static_cast<char *>(ws) + L.off_pexp));
             backward_prep_kernel<<<prep_grid(p, 0), 256, 0, st>>>(p);
         }
         {
             ProfScope ps(d->mode == SDTW_UNFUSED ? "backward_dp_unfused" : "backward_dp_fused", st);
             launch_dp<false>(d, L, p, nullptr, st);
         }
+    }
+    if (sweep_grad) {
+        if (dx || dy) {
+            const bool vec = (d->D % 4 == 0) && aligned16(x) && aligned16(y) && (!dx || aligned16(dx)) && (!dy || aligned16(dy));
+            const size_t n = (size_t)d->B * ((size_t)d->N + d->M) * d->D / (vec ? 4 : 1);
+            ProfScope ps("gradient_finish", st);
+            if (vec)
+                gradient_finish_kernel<4><<<fill_grid(n), 256, 0, st>>>(p, grad_value);
+            else
+                gradient_finish_kernel<1><<<fill_grid(n), 256, 0, st>>>(p, grad_value);
+        }
+        return hip_ok();
     }
     if (dx || dy) {
         const int P = std::max(dx ? d->N : 0, dy ? d->M : 0);
@@ -344,7 +396,10 @@ int backward_impl(const sdtw_desc *d, const float *x, const float *y, const floa
     }
     if (E_out) {
         const size_t n = (size_t)d->B * d->N * d->M;
-        export_E_kernel<<<fill_grid(n), 256, 0, st>>>(p, E_out);
+        if (L.sweep_grad)
+            complete_E_kernel<<<fill_grid(n), 256, 0, st>>>(p);  // the sweep wrote the non-zero blocks into E_out itself
+        else
+            export_E_kernel<<<fill_grid(n), 256, 0, st>>>(p, E_out);
     }
     return hip_ok();
 }
@@ -358,7 +413,7 @@ bool bary_ok(const sdtw_bary_desc *d)
     if (!(d->lr > 0.0f) || !std::isfinite(d->lr)) return false;
     if (!(d->beta1 >= 0.0f && d->beta1 < 1.0f) || !(d->beta2 >= 0.0f && d->beta2 < 1.0f)) return false;
     if (!(d->eps > 0.0f) || !std::isfinite(d->eps)) return false;
-    if (d->flags != 0) return false;
+    if ((d->flags & ~(uint32_t)SDTW_FLAG_MIN_MEMORY) != 0) return false;
     return true;
 }
 
@@ -369,7 +424,7 @@ sdtw_desc bary_pair_desc(const sdtw_bary_desc *d)
     s.gamma = d->gamma; s.mode = d->mode;
     s.x_batch_stride = 0;
     s.y_batch_stride = (int64_t)d->Lx * d->D;
-    s.bandwidth = 0; s.flags = 0;
+    s.bandwidth = 0; s.flags = d->flags & SDTW_FLAG_MIN_MEMORY;
     return s;
 }
 
@@ -704,6 +759,7 @@ int sdtw_debug_export(const sdtw_desc *desc, const void *workspace, size_t works
             export_R_kernel<<<fill_grid(n), 256, 0, st>>>(p, static_cast<double *>(out));
             return hip_ok();
         case SDTW_EXPORT_E:
+            if (L.sweep_grad) return SDTW_ERR_UNSUPPORTED;  // no E in this workspace: ask sdtw_backward for E_out
             export_E_kernel<<<fill_grid(n), 256, 0, st>>>(p, static_cast<float *>(out));
             return hip_ok();
         default:

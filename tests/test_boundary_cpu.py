@@ -62,20 +62,27 @@ def test_workspace_sizes():
     d_v = binding.make_desc(32, 1024, 1024, 128, 0.1, pkg.FUSED, flags=pkg.FLAG_VALUE_ONLY)
     wv = pkg.sdtw_workspace_bytes(d_v)
     assert 8 * cells < wf - wv < 9 * cells
-    # large problems keep checkpoints instead of the table
-    d_l = binding.make_desc(32, 8192, 8192, 64, 0.1, pkg.FUSED)
-    assert pkg.sdtw_workspace_bytes(d_l) < 5.0 * 32 * 8192 * 8192
+    # large problems keep checkpoints instead of the tables and no E at all (fused: under a byte per cell)
+    d_l = binding.make_desc(32, 8192, 8192, 128, 0.01, pkg.FUSED)
+    assert pkg.sdtw_workspace_bytes(d_l) < 1.0 * 32 * 8192 * 8192
+    d_lu = binding.make_desc(32, 8192, 8192, 128, 0.01, pkg.UNFUSED)
+    assert 4.0 * 32 * 8192 * 8192 < pkg.sdtw_workspace_bytes(d_lu) < 5.0 * 32 * 8192 * 8192
+    # ... and so do small ones on request
+    d_m = binding.make_desc(32, 1024, 1024, 128, 0.1, pkg.FUSED, flags=pkg.FLAG_MIN_MEMORY)
+    assert pkg.sdtw_workspace_bytes(d_m) < 2.5 * 32 * 1024 * 1024
     assert pkg.sdtw_workspace_bytes(binding.make_desc(1, 1, 1, 1, 1.0, pkg.FUSED)) > 0
     # under a band constraint the tables follow the band, not M: E (4 B per cell of the full grid)
     # is what remains
     d_b = binding.make_desc(32, 8192, 8192, 64, 0.1, pkg.FUSED, bandwidth=128)
     cells = 32 * 8192 * 8192
     assert 4 * cells < pkg.sdtw_workspace_bytes(d_b) < 6 * cells
+    d_bm = binding.make_desc(32, 8192, 8192, 64, 0.1, pkg.FUSED, bandwidth=128, flags=pkg.FLAG_MIN_MEMORY)
+    assert pkg.sdtw_workspace_bytes(d_bm) < 0.6 * cells
 
 
 @pytest.mark.parametrize("kw", [
     dict(B=0), dict(N=0), dict(M=-3), dict(D=0), dict(gamma=0.0), dict(gamma=-1.0), dict(gamma=float("nan")),
-    dict(gamma=float("inf")), dict(mode=2), dict(mode=-1), dict(flags=2), dict(bandwidth=-1),
+    dict(gamma=float("inf")), dict(mode=2), dict(mode=-1), dict(flags=4), dict(bandwidth=-1),
     dict(N=8, M=20, bandwidth=11),  # the last cell (N-1, M-1) would lie outside the band |i-j| <= 11
 ])
 def test_invalid_descriptors_need_zero_bytes_and_are_refused(kw):
@@ -130,7 +137,7 @@ def test_barycenter_descriptor_checks():
     assert need > 4 * 16 * 2 * 4
     fake = ctypes.c_void_p(0x10000)
     for field, bad in [("K", 0), ("Lz", 0), ("gamma", 0.0), ("lr", 0.0), ("beta1", 1.0), ("beta2", -0.1),
-                       ("eps", 0.0), ("step", 0), ("mode", 7), ("flags", 3)]:
+                       ("eps", 0.0), ("step", 0), ("mode", 7), ("flags", 1), ("flags", 4)]:
         d = binding.make_bary_desc(4, 16, 16, 2, 1.0, pkg.FUSED, 0.05, 0.9, 0.999, 1e-8, 1)
         setattr(d, field, bad)
         assert pkg.sdtw_barycenter_workspace_bytes(d) == 0, field

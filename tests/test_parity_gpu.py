@@ -32,20 +32,37 @@ def to_dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def run_gpu(x, y, gamma, mode, grad_value=None, want_E=True):
+def run_gpu(x, y, gamma, mode, grad_value=None, want_E=True, min_memory=False):
     import torch
 
     xd, yd = to_dev(x), to_dev(y)
-    value, desc, ws = pkg.sdtw_forward(xd, yd, gamma, mode)
+    value, desc, ws = pkg.sdtw_forward(xd, yd, gamma, mode, min_memory=min_memory)
     gv = to_dev(grad_value.astype(np.float32)) if grad_value is not None else None
-    dx, dy, E = pkg.sdtw_backward(desc, xd, yd, ws, grad_value=gv, want_E=want_E)
+    # The gradients come from the call without E output: where the workspace keeps no E (large problems,
+    # SDTW_FLAG_MIN_MEMORY) that is the reverse sweep that contracts E block by block.  E comes from a
+    # second backward call on the same workspace, whose gradients (formed from the stored E there) must agree.
+    dx, dy, _ = pkg.sdtw_backward(desc, xd, yd, ws, grad_value=gv)
     torch.cuda.synchronize()
     assert binding.workspace_status(ws) == 0
     out = {"value": value.cpu().numpy().astype(np.float64), "dx": dx.cpu().numpy().astype(np.float64),
            "dy": dy.cpu().numpy().astype(np.float64), "desc": desc, "ws": ws}
     if want_E:
+        dx2, dy2, E = pkg.sdtw_backward(desc, xd, yd, ws, grad_value=gv, want_E=True)
+        torch.cuda.synchronize()
+        assert binding.workspace_status(ws) == 0
         out["E"] = E.cpu().numpy().astype(np.float64)
+        assert_same_gradients(dx, dx2, dy, dy2, xd, yd)
     return out
+
+
+def assert_same_gradients(dx, dx2, dy, dy2, xd, yd):
+    """Two routes to the same gradients agree to rounding.  Each is 2 g (x_i sum E - sum E y_j) in float32,
+    so besides a relative part the difference has a floor of a few ulps of the terms that cancel."""
+    floor = 4e-6 * max(xd.abs().max().item(), yd.abs().max().item())
+    for a, b2, name in ((dx, dx2, "dx"), (dy, dy2, "dy")):
+        for b in range(a.shape[0]):
+            err = (a[b] - b2[b]).abs().max().item()
+            assert err <= 2e-5 * a[b].abs().max().item() + floor, "%s of pair %d with and without E output: %g" % (name, b, err)
 
 
 def check_against(ref, got, pairs=None, what=""):
@@ -183,6 +200,23 @@ def test_alignment_only_looks_where_E_can_be_non_zero(shape, mode, gamma, kind):
     # float32 cannot hold anything the pruning may have dropped: wherever the oracle's E is above the
     # smallest normal float32 by a margin (the hardware exp2 flushes denormal results), the library's E is non-zero
     assert (got["E"][ref["E"] > 1e-36] > 0).all()
+
+
+@pytest.mark.parametrize("mode", ["unfused", "fused"])
+@pytest.mark.parametrize("B,N,M,D,gamma", [(5, 200, 150, 16, 0.1), (2, 130, 257, 128, 0.05), (3, 64, 64, 8, 1.0),
+                                           (2, 100, 90, 200, 0.5), (4, 300, 333, 33, 20.0), (1, 1, 1, 1, 1.0),
+                                           (3, 31, 700, 64, 0.01)])
+def test_min_memory_flag(mode, B, N, M, D, gamma):
+    # SDTW_FLAG_MIN_MEMORY: small problems on the route of large ones - checkpoints instead of tables, and
+    # (D <= 128) no stored E: the reverse sweep contracts every block of E into dx, dy where it stands.
+    # Sparse to dense E, D that is no multiple of 32, D above 128 (E stays in the workspace there).
+    say("min memory %s B=%d N=%d M=%d D=%d gamma=%g" % (mode, B, N, M, D, gamma))
+    x, y = workloads.normal_pairs(300 + N + D, B, N, M, D)
+    ref = oracle.batch(x, y, gamma, want_E=True)
+    got = run_gpu(x, y, gamma, MODES[mode], min_memory=True)
+    check_against(ref, got, what="min memory %s %dx%d" % (mode, N, M))
+    plain = binding.make_desc(B, N, M, D, gamma, MODES[mode])
+    assert pkg.sdtw_workspace_bytes(got["desc"]) < pkg.sdtw_workspace_bytes(plain) or N * M < 4096
 
 
 def test_config1_tiny_oracle_case():
@@ -427,13 +461,24 @@ def run_gpu_ragged(x, y, xl, yl, gamma, mode, grad_value=None, want_E=True):
     yld = to_dev(yl) if yl is not None else None
     value, desc, ws = pkg.sdtw_forward_ragged(xd, yd, xld, yld, gamma, mode)
     gv = to_dev(grad_value.astype(np.float32)) if grad_value is not None else None
-    dx, dy, E = pkg.sdtw_backward_ragged(desc, xd, yd, xld, yld, ws, grad_value=gv, want_E=want_E)
+    return ragged_backward_both_routes(value, desc, ws, xd, yd, xld, yld, gv, want_E)
+
+
+def ragged_backward_both_routes(value, desc, ws, xd, yd, xld, yld, gv, want_E):
+    """Gradients from the backward call without E output, E from a second call (see run_gpu)."""
+    import torch
+
+    dx, dy, _ = pkg.sdtw_backward_ragged(desc, xd, yd, xld, yld, ws, grad_value=gv)
     torch.cuda.synchronize()
     assert binding.workspace_status(ws) == 0
     out = {"value": value.cpu().numpy().astype(np.float64), "dx": dx.cpu().numpy().astype(np.float64),
            "dy": dy.cpu().numpy().astype(np.float64)}
     if want_E:
+        dx2, dy2, E = pkg.sdtw_backward_ragged(desc, xd, yd, xld, yld, ws, grad_value=gv, want_E=True)
+        torch.cuda.synchronize()
+        assert binding.workspace_status(ws) == 0
         out["E"] = E.cpu().numpy().astype(np.float64)
+        assert_same_gradients(dx, dx2, dy, dy2, xd, yd)
     return out
 
 
@@ -526,14 +571,7 @@ def run_gpu_band(x, y, gamma, mode, w, want_E=True, xl=None, yl=None):
     xld = to_dev(xl) if xl is not None else None
     yld = to_dev(yl) if yl is not None else None
     value, desc, ws = pkg.sdtw_forward_ragged(xd, yd, xld, yld, gamma, mode, bandwidth=w)
-    dx, dy, E = pkg.sdtw_backward_ragged(desc, xd, yd, xld, yld, ws, want_E=want_E)
-    torch.cuda.synchronize()
-    assert binding.workspace_status(ws) == 0
-    out = {"value": value.cpu().numpy().astype(np.float64), "dx": dx.cpu().numpy().astype(np.float64),
-           "dy": dy.cpu().numpy().astype(np.float64)}
-    if want_E:
-        out["E"] = E.cpu().numpy().astype(np.float64)
-    return out
+    return ragged_backward_both_routes(value, desc, ws, xd, yd, xld, yld, None, want_E)
 
 
 BAND_CASES = [
@@ -894,14 +932,15 @@ def test_config4_full_size_sampled_pairs():
 
 
 # ------------------------------------------------------------------------------- barycenter
-def teacher_forced_step(bw, mode, z, X, m, v, step, ws, consts):
+def teacher_forced_step(bw, mode, z, X, m, v, step, ws, consts, min_memory=False):
     """One library step on (z, m, v) and the oracle's step from the same state; returns the workspace."""
     import torch
 
     lr, b1, b2, eps = consts
     z_in = z.cpu().numpy().astype(np.float64)
     m_o, v_o = m.cpu().numpy().astype(np.float64), v.cpu().numpy().astype(np.float64)
-    loss, dz, ws = pkg.sdtw_barycenter_step(z, X, m, v, bw.gamma, step, lr, b1, b2, eps, mode, workspace=ws, want_dz=True)
+    loss, dz, ws = pkg.sdtw_barycenter_step(z, X, m, v, bw.gamma, step, lr, b1, b2, eps, mode, workspace=ws, want_dz=True,
+                                            min_memory=min_memory)
     torch.cuda.synchronize()
     z_o = z_in.copy()
     lo, dzo = oracle.barycenter_step(z_o, bw.X, bw.gamma, lr, b1, b2, eps, step, m_o, v_o)
@@ -921,12 +960,13 @@ def teacher_forced_step(bw, mode, z, X, m, v, step, ws, consts):
     return ws
 
 
+@pytest.mark.parametrize("min_memory", [False, True])
 @pytest.mark.parametrize("mode", ["unfused", "fused"])
-def test_barycenter_steps_teacher_forced(mode):
+def test_barycenter_steps_teacher_forced(mode, min_memory):
     import torch
 
     bw = workloads.barycenter_workload(K=8, L=96, D=6, seed=5)
-    say("barycenter %s" % mode)
+    say("barycenter %s min_memory=%s" % (mode, min_memory))
     consts = (0.05, 0.9, 0.999, 1e-8)
     z = to_dev(bw.z0.copy())
     X = to_dev(bw.X)
@@ -934,7 +974,7 @@ def test_barycenter_steps_teacher_forced(mode):
     v = torch.zeros_like(z)
     ws = None
     for step in (1, 2, 3):
-        ws = teacher_forced_step(bw, MODES[mode], z, X, m, v, step, ws, consts)
+        ws = teacher_forced_step(bw, MODES[mode], z, X, m, v, step, ws, consts, min_memory=min_memory)
 
 
 def test_config5_barycenter_teacher_forced_and_trajectory():
