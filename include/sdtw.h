@@ -64,15 +64,26 @@ enum { SDTW_UNFUSED = 0, SDTW_FUSED = 1 };
  *   only has to combine the two tables.  The flag changes the workspace size.
  */
 /*
- *   SDTW_FLAG_MIN_MEMORY: trade time for memory on problems too small to fill the chip.  Those
- *   normally keep both DP tables (16 bytes per cell) and E in the workspace and run the two sweeps side
- *   by side; with this flag they run like large problems: the forward keeps checkpoints (0.5 bytes
- *   per cell), the backward call runs the reverse sweep, recomputes R from the checkpoints and
- *   contracts E into the gradients block by block without storing it.  Results agree to rounding.
- *   The flag changes the workspace size; give the same flags to sdtw_workspace_bytes, the forward
- *   and the backward call.  Also accepted in sdtw_bary_desc.flags.
+ * How the alignment matrix E is kept between the reverse sweep and the gradient kernel.
+ *   Problems too small to fill the chip keep both DP tables (16 bytes per cell) and a dense E.
+ *   Large problems keep checkpoints of the forward sweep (0.5 bytes per cell) and
+ *     - with fewer than 2^22 cells per pair: a dense float32 E [B,N,M] (4 bytes per cell);
+ *     - with 2^22 cells per pair or more, D <= 128: a COMPACT E - only the 32x32 blocks that hold a
+ *       non-zero, in a pool with room for 1/64 of all blocks (at least 2 (N/32 + M/32) per pair).  For
+ *       the small gamma long alignments are run with, E is a few blocks wide around the alignment
+ *       path and fits many times over.  If it does not fit, the backward call notices on the device
+ *       and forms the gradients with a second reverse sweep that contracts every block of E into
+ *       dx, dy while the block is on the chip: same result to rounding, several times slower.
+ *   SDTW_FLAG_MIN_MEMORY: checkpoints and the compact E for any problem, however small or short
+ *     (a fused workspace is then about 1 byte per cell or less).  Trades time for memory: small
+ *     problems lose the two sweeps running side by side.
+ *   SDTW_FLAG_DENSE_E: never the compact E: for long sequences whose E is known to be dense (large
+ *     gamma), where the second sweep would cost more than the memory is worth.
+ *   The two exclude each other.  Both change the workspace size; give the same flags to
+ *   sdtw_workspace_bytes, the forward and the backward call.  SDTW_FLAG_MIN_MEMORY is also accepted in
+ *   sdtw_bary_desc.flags.
  */
-enum { SDTW_FLAG_VALUE_ONLY = 1, SDTW_FLAG_MIN_MEMORY = 2 };
+enum { SDTW_FLAG_VALUE_ONLY = 1, SDTW_FLAG_MIN_MEMORY = 2, SDTW_FLAG_DENSE_E = 4 };
 
 /* What sdtw_debug_export copies out of a workspace. */
 enum { SDTW_EXPORT_COST = 0, SDTW_EXPORT_R = 1, SDTW_EXPORT_E = 2 };
@@ -92,7 +103,7 @@ typedef struct sdtw_desc {
                                lengths every pair needs |x_len[b]-y_len[b]| <= w, which the device
                                does not check: such a pair's value and gradients are undefined.  The
                                sweeps skip the macro-steps outside the band. */
-    uint32_t flags;         /* 0 or an OR of SDTW_FLAG_VALUE_ONLY, SDTW_FLAG_MIN_MEMORY */
+    uint32_t flags;         /* 0 or an OR of SDTW_FLAG_VALUE_ONLY, SDTW_FLAG_MIN_MEMORY, SDTW_FLAG_DENSE_E */
 } sdtw_desc;
 
 /* One barycenter step: K sequences X_k [Lx,D] against the current barycenter z [Lz,D]. */
@@ -156,12 +167,10 @@ int sdtw_forward_static_scratch(const sdtw_desc *desc, const float *x, const flo
  *   dx [B,N,D], dy [B,M,D]: device, out; either may be NULL if not wanted.  With
  *        x_batch_stride 0 dx still has one [N,D] slab per pair (the caller sums them).
  *   E_out [B,N,M]: device, out, optional (NULL): the alignment matrix E (entries that underflow
- *        float32 are exact zeros).  For large problems with D <= 128 (and with
- *        SDTW_FLAG_MIN_MEMORY) the workspace holds no E at all: without E_out the reverse sweep
- *        contracts every 32x32 block of E into dx and dy while the block is still on the chip
- *        (Sec. 4.3: the gradients "without ever materializing" a B x N x M tensor); with E_out the
- *        blocks are written to the caller's memory and the gradients are formed from there.
- *        Both routes give the same dx, dy to rounding.
+ *        float32 are exact zeros).  Where the workspace keeps E compactly (see the flags) the
+ *        reverse sweep writes the non-zero blocks straight into E_out and the gradients are formed
+ *        from there; without E_out nothing of size B x N x M exists anywhere (Sec. 4.3: the gradients
+ *        "without ever materializing" such a tensor).  Both routes give the same dx, dy to rounding.
  */
 int sdtw_backward(const sdtw_desc *desc, const float *x, const float *y, const float *grad_value,
                   float *dx, float *dy, float *E_out, void *workspace, size_t workspace_bytes,
@@ -238,7 +247,7 @@ int sdtw_workspace_status(const void *workspace, size_t workspace_bytes, void *s
  *   SDTW_EXPORT_COST: out = float32 [B,N,M], the cost tensor d (unfused mode, after forward)
  *   SDTW_EXPORT_R:    out = float64 [B,N,M], the DP table R[1..N,1..M] (after forward)
  *   SDTW_EXPORT_E:    out = float32 [B,N,M], the alignment matrix (after backward; SDTW_ERR_UNSUPPORTED
- *                     where the workspace keeps no E: use sdtw_backward's E_out there)
+ *                     where the workspace keeps E compactly: use sdtw_backward's E_out there)
  * `out` is a device pointer with room for B*N*M elements of that type.
  */
 int sdtw_debug_export(const sdtw_desc *desc, const void *workspace, size_t workspace_bytes,
@@ -251,7 +260,8 @@ int sdtw_debug_export(const sdtw_desc *desc, const void *workspace, size_t works
 int sdtw_debug_lane_shift(int32_t *out, void *stream);
 
 /*
- * The sdtw_debug_set_spin_limit, sdtw_debug_force_workgroup_shape and sdtw_debug_profile hooks below
+ * The sdtw_debug_set_spin_limit, sdtw_debug_force_workgroup_shape, sdtw_debug_set_pool_blocks and
+ * sdtw_debug_profile hooks below
  * set process-wide switches (the only state this library keeps between calls).  They are for tests
  * and benchmarks: call them while no other thread is inside a call of this library, and do not
  * change the forced workgroup shape between sdtw_workspace_bytes, the forward and the backward call
@@ -270,6 +280,13 @@ int sdtw_debug_set_spin_limit(uint32_t polls);
  * set it before sdtw_workspace_bytes.  Process-wide; host only.
  */
 int sdtw_debug_force_workgroup_shape(int bands_per_workgroup);
+
+/*
+ * Test hook: capacity, in 32x32 blocks, of the pool of a compact E for later backward calls (never more
+ * than the workspace was sized for; -1 restores that size).  A small value makes the pool run over,
+ * which sends the backward call down its second, contracting sweep.  Process-wide; host only.
+ */
+int sdtw_debug_set_pool_blocks(long long blocks);
 
 /*
  * Benchmark hook: per-kernel timing.  sdtw_debug_profile(1) makes every later call bracket each

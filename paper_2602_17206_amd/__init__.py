@@ -6,6 +6,7 @@ Importing the package does not load the library; the first call does, and it rai
 the library has not been built.
 """
 from .binding import (  # noqa: F401
+    FLAG_DENSE_E,
     FLAG_MIN_MEMORY,
     FLAG_VALUE_ONLY,
     FUSED,

@@ -16,6 +16,7 @@ UNFUSED = 0
 FUSED = 1
 FLAG_VALUE_ONLY = 1
 FLAG_MIN_MEMORY = 2
+FLAG_DENSE_E = 4
 EXPORT_COST, EXPORT_R, EXPORT_E = 0, 1, 2
 
 STATUS_OK = 0
@@ -58,7 +59,7 @@ EXPORTED_SYMBOLS = (
     "sdtw_forward_ragged", "sdtw_backward_ragged",
     "sdtw_debug_export", "sdtw_debug_lane_shift", "sdtw_debug_set_spin_limit",
     "sdtw_debug_profile", "sdtw_debug_profile_read", "sdtw_debug_force_workgroup_shape",
-    "sdtw_debug_rate_probe", "sdtw_forward_static_scratch",
+    "sdtw_debug_rate_probe", "sdtw_forward_static_scratch", "sdtw_debug_set_pool_blocks",
 )
 
 
@@ -122,6 +123,8 @@ def load_library():
     lib.sdtw_debug_profile_read.restype = i32
     lib.sdtw_debug_profile_read.argtypes = [ctypes.c_char_p, sz, ctypes.POINTER(ctypes.c_float), i32,
                                             ctypes.POINTER(ctypes.c_int)]
+    lib.sdtw_debug_set_pool_blocks.restype = i32
+    lib.sdtw_debug_set_pool_blocks.argtypes = [ctypes.c_longlong]
     lib.sdtw_debug_rate_probe.restype = i32
     lib.sdtw_debug_rate_probe.argtypes = [i32, i32, i32, i32, vp, sz, ctypes.POINTER(ctypes.c_float), vp]
     _lib = lib
@@ -496,3 +499,7 @@ def debug_rate_probe(probe, variant, waves_per_simd, iters, scratch, stream=None
     if rc != 0:
         raise SdtwError(rc, "sdtw_debug_rate_probe")
     return float(ms.value)
+
+
+def debug_set_pool_blocks(blocks):
+    load_library().sdtw_debug_set_pool_blocks(int(blocks))

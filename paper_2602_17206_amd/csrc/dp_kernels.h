@@ -1068,10 +1068,16 @@ __device__ __forceinline__ bool block_in_range(const SweepRange &rg, int rb, int
     return cb + rb >= rg.lo && cb + rb + 1 <= rg.hi_u && cb <= rg.cb_last;
 }
 
+// idxb != nullptr: compact E.  A block that holds a non-zero takes the next free block of the pool
+// (p.pool, handed out by an atomic counter in the workspace header) and leaves its number in the
+// pair's block index idxb, which backward_prep_kernel pre-set to -1 = "all zero" everywhere; a block
+// that finds the pool full raises the overflow flag instead (the backward call then redoes the
+// gradients with the contracting sweep).
 template <int COLS = kRingCols, int STRIDE = kRingStride>
 __device__ __forceinline__ void flush_E_block(const Params &p, const SweepRange &rg, const float *ring,
                                               float *__restrict__ Eb, unsigned char *__restrict__ nzb, int rb, int cb,
-                                              int row0, int lane, bool known_zero = false, int ring_row0 = 0)
+                                              int row0, int lane, bool known_zero = false, int ring_row0 = 0,
+                                              int32_t *__restrict__ idxb = nullptr)
 {
     // ring_row0: the band row that the ring's first row holds (0, or 32 for a ring of the lower block row alone)
     if (cb < 0 || cb >= p.ncb || row0 + 32 * rb >= p.N || !block_in_range(rg, rb, cb)) return;
@@ -1110,7 +1116,29 @@ __device__ __forceinline__ void flush_E_block(const Params &p, const SweepRange 
         }
     }
     const bool blk_any = __any(any);
-    if (lane == 0) nzb[(size_t)(row0 / kBlk + rb) * p.ncb + cb] = blk_any ? 1 : 0;
+    const size_t blk_id = (size_t)(row0 / kBlk + rb) * p.ncb + cb;
+    if (idxb != nullptr) {
+        unsigned slot = 0;
+        if (blk_any && lane == 0) slot = atomicAdd(&p.hdr->pool_count, 1u);
+        slot = (unsigned)__builtin_amdgcn_readfirstlane((int)slot);
+        const bool fits = blk_any && (long long)slot < p.pool_blocks;
+        if (lane == 0) {
+            nzb[blk_id] = fits ? 1 : 0;
+            if (fits) idxb[blk_id] = (int32_t)slot;
+            if (blk_any && !fits) p.hdr->pool_overflow = 1;
+        }
+        if (!fits) return;
+        // the whole 32 x 32 block, row-major (entries outside the grid are never read)
+        float *dst = p.pool + (size_t)slot * (kBlk * kBlk);
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            float v[4];
+            read4(it, v);
+            *reinterpret_cast<float4 *>(dst + ((lane >> 3) + 8 * it) * kBlk + c4) = make_float4(v[0], v[1], v[2], v[3]);
+        }
+        return;
+    }
+    if (lane == 0) nzb[blk_id] = blk_any ? 1 : 0;
     if (!blk_any) return;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
@@ -1335,6 +1363,9 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
     constexpr bool TSWEEP = (SLOTS == 1 || SLOTS == 2);
     const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (p.hdr->abort_backward) return;
+    if constexpr (GRAD) {
+        if (p.hdr->pool_overflow == 0) return;  // the pool held every block: the gradients are done
+    }
 
     if (threadIdx.x == 0) ticket_s = atomicAdd(&p.hdr->bwd_ticket, 1u);
     for (int e = threadIdx.x; e < SLOTS * kRingFloats; e += kThreads) (&sh.ring[0][0])[e] = kBigCost;
@@ -1402,6 +1433,7 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
 
     float *Eb = p.E + (size_t)bb * N * M;
     unsigned char *nzb = p.nz + (size_t)bb * p.nrb * p.ncb;
+    int32_t *idxb = p.idx != nullptr ? p.idx + (size_t)bb * p.nrb * p.ncb : nullptr;  // compact E
     // Who writes the finished E blocks out: the producer, whose loads and stores then wait beside the
     // consumer's chain instead of in it (measured with recomputation at the L = 8192 shape: 6.3 -> 5.3 ms
     // at D = 16, 6.5 -> 6.1 ms at D = 64) - except where the producer has no registers left for it
@@ -1418,8 +1450,8 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
         auto flush = [&](int done, bool upper, bool lower) {
             if constexpr (kProducerFlush) {
                 const bool dead = sh.blk_dead[slot][done & 1] != 0;  // written by the consumer before the last barrier
-                if (upper) flush_E_block(p, rg, ring, Eb, nzb, 0, done, row0, lane, dead);
-                if (lower) flush_E_block(p, rg, ring, Eb, nzb, 1, done - 1, row0, lane, dead);
+                if (upper) flush_E_block(p, rg, ring, Eb, nzb, 0, done, row0, lane, dead, 0, idxb);
+                if (lower) flush_E_block(p, rg, ring, Eb, nzb, 1, done - 1, row0, lane, dead, 0, idxb);
             }
         };
         // blocks the first macro-step reads: (upper rows, sg0-1), (lower rows, sg0-1), (lower rows, sg0-2)
@@ -1715,8 +1747,8 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
                     grad_E_block_any(p, rg, ring, 1, sg - 1, row0, bb, Nl, Ml, lane);
                 }
             } else if constexpr (!kProducerFlush && !TSWEEP) {
-                flush_E_block(p, rg, ring, Eb, nzb, 0, sg, row0, lane, blocks_dead);
-                flush_E_block(p, rg, ring, Eb, nzb, 1, sg - 1, row0, lane, blocks_dead);
+                flush_E_block(p, rg, ring, Eb, nzb, 0, sg, row0, lane, blocks_dead, 0, idxb);
+                flush_E_block(p, rg, ring, Eb, nzb, 1, sg - 1, row0, lane, blocks_dead, 0, idxb);
             } else if constexpr (!TSWEEP) {
                 if (lane == 0) sh.blk_dead[slot][sg & 1] = blocks_dead ? 1 : 0;
             }

@@ -238,6 +238,8 @@ __global__ __launch_bounds__(256) void backward_prep_kernel(Params p)
         Header *h = p.hdr;
         const bool ok = workspace_matches(p);
         h->bwd_ticket = 0;
+        h->pool_count = 0;
+        h->pool_overflow = 0;
         if (ok) {
             h->abort_backward = 0;
         } else {
@@ -248,23 +250,11 @@ __global__ __launch_bounds__(256) void backward_prep_kernel(Params p)
         }
     }
     fill_boundary_rows(p, p.brow_b, true, blockIdx.x, gridDim.x);
-    // a sweep that contracts E into the gradients itself adds to these: they start at zero
-    if (p.rsum != nullptr) {
-        const size_t stride = (size_t)gridDim.x * blockDim.x, first = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-        const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
-        auto clear = [&](float *dst, size_t n) {  // dst is 16-byte aligned (caller's tensors, workspace regions)
-            if (dst == nullptr) return;
-            for (size_t i = first; i < n / 4; i += stride) reinterpret_cast<float4 *>(dst)[i] = z4;
-            for (size_t i = (n / 4) * 4 + first; i < n; i += stride) dst[i] = 0.f;
-        };
-        clear(p.gdx, (size_t)p.B * p.N * p.D);
-        clear(p.rsum, (size_t)p.B * p.N);
-        if (p.gdy != nullptr) {  // (integer words: all bits zero, like 0.f)
-            clear(p.gdy, (size_t)p.B * p.M * p.D);
-            clear(reinterpret_cast<float *>(p.gdy_hi), (size_t)p.B * p.M * p.D);
-            clear(reinterpret_cast<float *>(p.csum_lo), (size_t)p.B * p.M);
-            clear(reinterpret_cast<float *>(p.csum_hi), (size_t)p.B * p.M);
-        }
+    // compact E: every block starts as "all zero"
+    if (p.idx != nullptr) {
+        const size_t n = (size_t)p.B * p.nrb * p.ncb;
+        const size_t stride = (size_t)gridDim.x * blockDim.x;
+        for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p.idx[i] = -1;
     }
     // with a band constraint the sweep never visits the blocks of E outside the window: their
     // "any non-zero" flags are cleared here
@@ -496,6 +486,7 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
     __shared__ __attribute__((aligned(16))) _Float16 Bh[2][2][64 * kGradHalfRow];  // [buffer][piece][n][k]
     __shared__ float msum_part[4][64];
     __shared__ int live_list[kLiveCap];          // first reduced position of every chunk that has a non-zero
+    __shared__ int live_slot[2][kLiveCap];       // compact E: where the chunk's two blocks lie in the pool (-1: all zero)
     __shared__ unsigned long long wave_mask[2][4];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -519,6 +510,11 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
     // (the header is asked for now and looked at below, once the first flags and the output side's
     // own values have been asked for as well: one wait for all three)
     const bool refused = backward_refused(p);
+    // compact E: the blocks lie in the pool (32 x 32 row-major each, found through the index); if the pool
+    // ran over, the gradients come from the second sweep instead and this kernel has nothing to do
+    const bool pooled = p.idx != nullptr;
+    const int32_t *idxb = pooled ? p.idx + (size_t)b * p.nrb * p.ncb : nullptr;
+    if (pooled && p.hdr->pool_overflow != 0 && !refused) return;
 
     const float sA = 1024.0f;
     // the largest 1/scale among the chunk's 32 rows: one row per lane (mod 32; both halves of the
@@ -555,17 +551,22 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
     const int am = side == 0 ? (tid >> 2) : lane, ak = side == 0 ? (tid & 3) * 8 : w * 8;
     const int bn = lane, bk = w * 8;
     // (a list entry is the chunk's first reduced position with the two block flags in bits 30 and 31)
-    auto fetch = [&](int entry, float (&ea)[8], float (&bv)[8], float &ismax) {
+    auto fetch = [&](int pos, float (&ea)[8], float (&bv)[8], float &ismax) {
+        const int entry = live_list[pos];
         const int q0 = entry & 0x3FFFFFFF;
         const bool blk_live = (((unsigned)entry >> (30 + (am >> 5))) & 1u) != 0;  // the block this thread's output position is in
         ismax = chunk_ismax(q0);
+        // this thread's block of E: rows of M floats in the dense tensor, of 32 in a pool block
+        const float *blk = nullptr;
+        if (pooled && blk_live) blk = p.pool + (size_t)live_slot[am >> 5][pos] * (kBlk * kBlk);
+        const size_t ld = pooled ? (size_t)kBlk : (size_t)p.M;
         if (side == 0) {
             const int i = m0 + am;
 #pragma unroll
             for (int c = 0; c < 8; ++c) ea[c] = 0.f;
             if (i < p.N && blk_live) {
-                const float *q = Eb + (size_t)i * p.M + q0 + ak;
-                if (p.vec_m && q0 + ak + 7 < p.M) {
+                const float *q = pooled ? blk + (size_t)(i & (kBlk - 1)) * kBlk + ak : Eb + (size_t)i * p.M + q0 + ak;
+                if ((pooled || p.vec_m) && q0 + ak + 7 < p.M) {
                     const float4 t0 = *reinterpret_cast<const float4 *>(q), t1 = *reinterpret_cast<const float4 *>(q + 4);
                     ea[0] = t0.x; ea[1] = t0.y; ea[2] = t0.z; ea[3] = t0.w;
                     ea[4] = t1.x; ea[5] = t1.y; ea[6] = t1.z; ea[7] = t1.w;
@@ -576,12 +577,12 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
             }
         } else {
             const int j = m0 + am;
-            const float *e = Eb + (size_t)(q0 + ak) * p.M + j;
+            const float *e = pooled ? blk + (size_t)ak * kBlk + (j & (kBlk - 1)) : Eb + (size_t)(q0 + ak) * p.M + j;
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
                 const int i = q0 + ak + c;
                 ea[c] = (i < p.N && j < p.M && blk_live) ? *e : 0.f;
-                e += p.M;
+                e += ld;
             }
         }
         const int n = n0 + bn;
@@ -678,28 +679,36 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
                 if (ww < w) off += cnt;
                 total += cnt;
             }
-            if (lv) live_list[off + __popcll(m & ((1ull << lane) - 1ull))] = (int)((unsigned)(c * kBlk) | (bits << 30));
+            if (lv) {
+                const int pos = off + __popcll(m & ((1ull << lane) - 1ull));
+                live_list[pos] = (int)((unsigned)(c * kBlk) | (bits << 30));
+                if (pooled) {
+                    const int qb = c, mb = m0 / kBlk;  // as in chunk_flags
+                    live_slot[0][pos] = (bits & 1u) ? (side == 0 ? idxb[(size_t)mb * p.ncb + qb] : idxb[(size_t)qb * p.ncb + mb]) : -1;
+                    live_slot[1][pos] = (bits & 2u) ? (side == 0 ? idxb[(size_t)(mb + 1) * p.ncb + qb] : idxb[(size_t)qb * p.ncb + mb + 1]) : -1;
+                }
+            }
             nlive += total;
         }
         __syncthreads();
 
         int i = 0;
-        if (nlive > 0) fetch(live_list[0], ea0, bv0, is0);
-        if (nlive > 1) fetch(live_list[1], ea1, bv1, is1);
+        if (nlive > 0) fetch(0, ea0, bv0, is0);
+        if (nlive > 1) fetch(1, ea1, bv1, is1);
         // (two LDS buffers, one barrier per chunk: a buffer is written again two chunks later, after
         // the barrier of the chunk in between, by when every wavefront is done reading it)
         while (i < nlive) {
             stash(0, ea0, bv0, is0);
             const float isc0 = is0;
             __syncthreads();
-            if (i + 2 < nlive) fetch(live_list[i + 2], ea0, bv0, is0);
+            if (i + 2 < nlive) fetch(i + 2, ea0, bv0, is0);
             contract(0, isc0);
             if (++i >= nlive) break;
 
             stash(1, ea1, bv1, is1);
             const float isc1 = is1;
             __syncthreads();
-            if (i + 2 < nlive) fetch(live_list[i + 2], ea1, bv1, is1);
+            if (i + 2 < nlive) fetch(i + 2, ea1, bv1, is1);
             contract(1, isc1);
             ++i;
         }
@@ -731,12 +740,39 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
     }
 }
 
+// Compact E whose pool ran over: start of the second reverse sweep, the one that contracts E into the
+// gradients itself.  Does nothing unless the overflow flag is up; otherwise resets the band tickets,
+// marks every boundary value of the reverse sweep "not written yet" again and clears the sums that
+// sweep adds to (they lie where the pool was: nobody reads the pool any more).
+__global__ __launch_bounds__(256) void second_sweep_prep_kernel(Params p)
+{
+    if (p.hdr->pool_overflow == 0 || p.hdr->abort_backward != 0) return;
+    if (threadIdx.x == 0 && blockIdx.x == 0) p.hdr->bwd_ticket = 0;
+    fill_boundary_rows(p, p.brow_b, true, blockIdx.x, gridDim.x);
+    const size_t stride = (size_t)gridDim.x * blockDim.x, first = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    auto clear = [&](float *dst, size_t n) {  // dst is 16-byte aligned (caller's tensors, workspace regions)
+        if (dst == nullptr) return;
+        for (size_t i = first; i < n / 4; i += stride) reinterpret_cast<float4 *>(dst)[i] = z4;
+        for (size_t i = (n / 4) * 4 + first; i < n; i += stride) dst[i] = 0.f;
+    };
+    clear(p.gdx, (size_t)p.B * p.N * p.D);
+    clear(p.rsum, (size_t)p.B * p.N);
+    if (p.gdy != nullptr) {  // (integer words: all bits zero, like 0.f)
+        clear(p.gdy, (size_t)p.B * p.M * p.D);
+        clear(reinterpret_cast<float *>(p.gdy_hi), (size_t)p.B * p.M * p.D);
+        clear(reinterpret_cast<float *>(p.csum_lo), (size_t)p.B * p.M);
+        clear(reinterpret_cast<float *>(p.csum_hi), (size_t)p.B * p.M);
+    }
+}
+
 // Exponent bound of every pair's x for the fixed-point sums of the y side (Params::gdy_hi):
 // pair_exp[b] = e with |x_b[i][k]| < 2^e for all rows of the pair, read off the per-row scales
 // 2^(e_row - 14) that the forward call stored with the split copies.  One workgroup per pair.
 __global__ __launch_bounds__(256) void pair_exponent_kernel(Params p, int32_t *__restrict__ pair_exp)
 {
     __shared__ unsigned part[4];
+    if (p.hdr->pool_overflow == 0) return;
     const int b = blockIdx.x;
     const int Nl = pair_len(p.x_len, b, p.N);
     const unsigned *is = reinterpret_cast<const unsigned *>(p.xis + b * p.xn_stride);
@@ -751,7 +787,8 @@ __global__ __launch_bounds__(256) void pair_exponent_kernel(Params p, int32_t *_
     }
 }
 
-// After a reverse sweep that contracted E into the gradients itself: gdx holds sum_j E_ij y_j, rsum
+// After the second reverse sweep of a compact layout (the one that contracts E into the gradients
+// itself; it only ran if the pool overflowed, and this kernel only acts then): gdx holds sum_j E_ij y_j, rsum
 // sum_j E_ij; gdy / gdy_hi and csum_lo / csum_hi hold sum_i E_ij x_i and sum_i E_ij in fixed point
 // (see Params).  The formulas of Sec. 4.3 are completed in place,
 //   dx_i = 2 g (x_i sum_j E_ij - sum_j E_ij y_j),   dy_j = 2 g (y_j sum_i E_ij - sum_i E_ij x_i),
@@ -762,6 +799,7 @@ template <int W>
 __global__ __launch_bounds__(256) void gradient_finish_kernel(Params p, const float *__restrict__ grad_value)
 {
     const bool bad = backward_refused(p);
+    if (p.hdr->pool_overflow == 0 && !bad) return;  // input_grad_half_kernel wrote the gradients from the pool
     const float qnan = __builtin_nanf("");
     const size_t nx = (size_t)p.B * p.N * p.D, ny = (size_t)p.B * p.M * p.D;
     const size_t stride = (size_t)gridDim.x * blockDim.x * W;

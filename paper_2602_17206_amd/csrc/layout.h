@@ -31,7 +31,9 @@ struct Header {
     int32_t two_sweep;     // the forward call also ran the reverse sweep
     int32_t window;        // band constraint |i-j| <= window the forward was run with (kNoWindow: none)
     uint64_t x_len_ptr, y_len_ptr;  // the length vectors the forward was run with (0: none)
-    uint32_t pad[46];
+    uint32_t pool_count;   // compact E: 32x32 blocks handed out so far (may run past the capacity)
+    int32_t pool_overflow; // compact E: a block did not fit; the backward call redoes the gradients the slow way
+    uint32_t pad[44];
 };
 static_assert(sizeof(Header) == 256, "header is 256 bytes");
 
@@ -45,9 +47,10 @@ struct Layout {
     int32_t Dp;                  // D rounded up to 16, 32, 64 or 128: row length of the split-half operand copies (0: none)
     int32_t recompute;           // 1: checkpoints instead of the R table (large problems)
     int32_t two_sweep;           // 1: the forward call also runs the reverse sweep and stores its table Q
-    int32_t sweep_grad;          // 1: the reverse sweep contracts E into the gradients itself, E is not stored (see make_layout)
+    int32_t compact_E;           // 1: E is kept as a pool of its non-zero 32x32 blocks, not as a dense tensor (see make_layout)
+    int64_t pool_blocks;         // capacity of that pool
     size_t off_hdr, off_rfinal, off_xn, off_yn, off_xis, off_yis, off_xh, off_yh, off_brow, off_brow_b, off_R,
-        off_Q, off_ckpt, off_cost, off_E, off_nz, off_rsum, off_csum, off_dyhi, off_pexp, total;
+        off_Q, off_ckpt, off_cost, off_E, off_nz, off_idx, off_pool, off_rsum, off_csum, off_dyhi, off_pexp, total;
 };
 
 // With D <= 128 the workspace keeps a copy of x and y split into two float16 pieces per element
@@ -71,8 +74,13 @@ inline int32_t table_macro_steps(int32_t nmacro, int32_t window)
     return need < nmacro ? (int32_t)need : nmacro;
 }
 
+// Large problems with long sequences keep the alignment matrix compactly (see make_layout): from this
+// many cells per pair on, or whenever the caller asks for little memory.
+constexpr int64_t kCompactCells = (int64_t)1 << 22;
+
 inline Layout make_layout(int32_t B, int32_t N, int32_t M, int32_t D, int32_t mode, bool x_shared,
-                          bool y_shared, bool recompute, bool two_sweep, int32_t window = kNoWindow)
+                          bool y_shared, bool recompute, bool two_sweep, int32_t window = kNoWindow,
+                          int compact = 0 /* -1: never, 0: by size, 1: always (where the regime allows) */)
 {
     Layout L{};
     L.B = B; L.N = N; L.M = M; L.D = D; L.mode = mode;
@@ -117,23 +125,39 @@ inline Layout make_layout(int32_t B, int32_t N, int32_t M, int32_t D, int32_t mo
     L.off_cost = o;
     if (mode == 0) o = align_up(o + (size_t)B * N * (size_t)M * sizeof(float), 256);
     o += kGuardBytes;
-    // The alignment matrix E [B,N,M] float32 - unless the reverse sweep contracts every finished block
-    // of it into the gradients on the spot (large problems with split operand copies, i.e. D <= 128):
-    // then E exists only block by block in LDS, the workspace holds the marginal sums of E instead,
-    // and a caller who wants E itself supplies the memory for it (the E_out argument).
-    L.sweep_grad = (recompute && L.Dp > 0) ? 1 : 0;
+    // The alignment matrix E.  Dense, [B,N,M] float32 - or, for large problems with long sequences
+    // (and split operand copies, D <= 128), compact: the reverse sweep stores only the 32x32 blocks that
+    // hold a non-zero, into a pool of blocks handed out by an atomic counter, with an index
+    // [B, N/32, M/32] that says where each block went (-1: all zero).  For the small gamma that long
+    // alignments are run with, E is a few blocks wide around the alignment path: the pool has room for
+    // 1/64 of all blocks, at least 2 (N/32 + M/32) per pair (a path crosses N/32 + M/32 - 1 of them).  When
+    // the pool runs over, the backward call forms the gradients once more with a reverse sweep that
+    // contracts every block of E into them on the spot (slow: that work then sits in the chain of
+    // dependent steps; callers with long sequences AND dense E ask for the dense layout).  The sums of
+    // that second sweep live where the pool was.
+    const bool long_pairs = (int64_t)N * M >= kCompactCells;
+    L.compact_E = (recompute && L.Dp > 0 && (compact > 0 || (compact == 0 && long_pairs))) ? 1 : 0;
     L.off_E = o;
-    if (!L.sweep_grad) o = align_up(o + (size_t)B * N * (size_t)M * sizeof(float), 256);
+    if (!L.compact_E) o = align_up(o + (size_t)B * N * (size_t)M * sizeof(float), 256);
     o += kGuardBytes;
     L.off_nz = o;       o = align_up(o + (size_t)B * L.nrb * (size_t)L.ncb, 256);
-    L.off_rsum = o;
-    if (L.sweep_grad) o = align_up(o + (size_t)B * N * sizeof(float), 256);
-    L.off_csum = o;  // two 32-bit words per column (see Params::gdy_hi)
-    if (L.sweep_grad) o += 2 * align_up((size_t)B * M * sizeof(uint32_t), 256);
-    L.off_dyhi = o;
-    if (L.sweep_grad) o = align_up(o + (size_t)B * M * (size_t)D * sizeof(int32_t), 256);
-    L.off_pexp = o;
-    if (L.sweep_grad) o = align_up(o + (size_t)B * sizeof(int32_t), 256);
+    L.off_idx = L.off_pool = L.off_rsum = L.off_csum = L.off_dyhi = L.off_pexp = o;
+    L.pool_blocks = 0;
+    if (L.compact_E) {
+        const int64_t all = (int64_t)B * L.nrb * L.ncb;
+        L.pool_blocks = all / 64 > 2 * (int64_t)B * (L.nrb + L.ncb) ? all / 64 : 2 * (int64_t)B * (L.nrb + L.ncb);
+        if (L.pool_blocks > all) L.pool_blocks = all;
+        L.off_idx = o;  o = align_up(o + (size_t)all * sizeof(int32_t), 256);
+        L.off_pool = o;
+        const size_t pool_bytes = (size_t)L.pool_blocks * kBlk * kBlk * sizeof(float);
+        // the second sweep's sums, in the same place: rsum [B,N], csum 2 x [B,M] words, gdy_hi [B,M,D], pair_exp [B]
+        size_t q = o;
+        L.off_rsum = q;  q = align_up(q + (size_t)B * N * sizeof(float), 256);
+        L.off_csum = q;  q += 2 * align_up((size_t)B * M * sizeof(uint32_t), 256);
+        L.off_dyhi = q;  q = align_up(q + (size_t)B * M * (size_t)D * sizeof(int32_t), 256);
+        L.off_pexp = q;  q = align_up(q + (size_t)B * sizeof(int32_t), 256);
+        o = align_up(o + (pool_bytes > q - o ? pool_bytes : q - o), 256);
+    }
     L.total = o;
     return L;
 }
@@ -169,9 +193,14 @@ struct Params {
     double *ckpt;                  // large problems: forward lane state per macro-step instead of R
     int32_t two_sweep;
     float *cost;
-    float *E;                      // alignment matrix: in the workspace, or the caller's E_out where the workspace has none
+    float *E;                      // alignment matrix, dense: in the workspace, or the caller's E_out where the workspace has none
     unsigned char *nz;
-    // Reverse sweep that contracts E into the gradients itself (Layout::sweep_grad, no E_out wanted):
+    // compact E (Layout::compact_E, no E_out wanted): block (rb, cb) of pair b is pool + 1024 * idx[...] floats,
+    // row-major 32 x 32, if idx >= 0; pool_blocks = capacity
+    float *pool;
+    int32_t *idx;
+    int64_t pool_blocks;
+    // Reverse sweep that contracts E into the gradients itself (second sweep of a compact layout whose pool ran over):
     // gdx [B,N,D] / gdy [B,M,D] accumulate sum_j E_ij y_j / sum_i E_ij x_i (the caller's dx, dy buffers,
     // either may be null), rsum [B,N] / csum [B,M] the marginal sums of E; gradient_finish_kernel
     // turns them into dx, dy.

@@ -26,6 +26,7 @@ using namespace sdtw;
 // by part of that call only: set them between calls).
 std::atomic<uint32_t> g_spin_limit{1u << 23};  // ~10 s of polling before a band gives up
 std::atomic<int> g_force_slots{0};             // 0 = choose by problem size, 1, 2 or 4 = force that workgroup shape
+std::atomic<long long> g_pool_blocks{-1};      // >= 0: capacity of the compact-E block pool (at most the layout's), to force an overflow
 
 // Optional per-kernel timing (test/benchmark hook): when switched on, every kernel launch of the
 // library is bracketed by two HIP events on the caller's stream.
@@ -55,7 +56,8 @@ bool desc_ok(const sdtw_desc *d, int *why)
     if (d->B > 32767) return false;
     if (!(d->gamma > 0.0f) || !std::isfinite(d->gamma)) return false;
     if (d->mode != SDTW_UNFUSED && d->mode != SDTW_FUSED) return false;
-    if ((d->flags & ~(uint32_t)(SDTW_FLAG_VALUE_ONLY | SDTW_FLAG_MIN_MEMORY)) != 0) return false;
+    if ((d->flags & ~(uint32_t)(SDTW_FLAG_VALUE_ONLY | SDTW_FLAG_MIN_MEMORY | SDTW_FLAG_DENSE_E)) != 0) return false;
+    if ((d->flags & SDTW_FLAG_MIN_MEMORY) && (d->flags & SDTW_FLAG_DENSE_E)) return false;
     if (d->x_batch_stride != 0 && d->x_batch_stride != (int64_t)d->N * d->D) return false;
     if (d->y_batch_stride != 0 && d->y_batch_stride != (int64_t)d->M * d->D) return false;
     if ((int64_t)d->M + 128 > 0x3FFFFFFF || (int64_t)d->N + 128 > 0x3FFFFFFF) return false;
@@ -100,8 +102,9 @@ Layout layout_of(const sdtw_desc *d)
     const bool small = small_problem(d);
     const bool recompute = !small;  // the 4-band workgroups keep checkpoints instead of R (dp_recompute)
     const bool two_sweep = small && !(d->flags & SDTW_FLAG_VALUE_ONLY);
+    const int compact = (d->flags & SDTW_FLAG_DENSE_E) ? -1 : ((d->flags & SDTW_FLAG_MIN_MEMORY) ? 1 : 0);
     return make_layout(d->B, d->N, d->M, d->D, d->mode, d->x_batch_stride == 0, d->y_batch_stride == 0, recompute,
-                       two_sweep, effective_window(d));
+                       two_sweep, effective_window(d), compact);
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -148,8 +151,11 @@ Params make_params(const sdtw_desc *d, const Layout &L, const float *x, const fl
     p.two_sweep = L.two_sweep;
     p.ckpt = reinterpret_cast<double *>(base + L.off_ckpt);
     p.cost = reinterpret_cast<float *>(base + L.off_cost);
-    p.E = L.sweep_grad ? nullptr : reinterpret_cast<float *>(base + L.off_E);  // (sweep_grad: the caller's E_out, if any)
+    p.E = L.compact_E ? nullptr : reinterpret_cast<float *>(base + L.off_E);  // (compact: the caller's E_out, if any)
     p.nz = reinterpret_cast<unsigned char *>(base + L.off_nz);
+    p.pool = nullptr;  // (compact E: set by the backward call that uses the pool)
+    p.idx = nullptr;
+    p.pool_blocks = 0;
     // (the accumulators of a reverse sweep that forms the gradients itself: set by that backward call)
     p.gdx = p.gdy = p.rsum = nullptr;
     p.csum_lo = nullptr;
@@ -176,10 +182,10 @@ int fused_variant(int D)
 // only the value is wanted); its backward call launches no DP kernel.  Larger problems use 4-band
 // workgroups in which the producer and the consumer of a band share a SIMD, forward sweep in the
 // forward call, reverse sweep in the backward call.
+// grad: the reverse sweep that contracts E into the gradients itself (second sweep of a compact layout)
 template <bool FWD, int KCH>
-void launch_dp_kch(const sdtw_desc *d, const Layout &L, const Params &p, float *value, hipStream_t st)
+void launch_dp_kch(const sdtw_desc *d, const Layout &L, const Params &p, float *value, hipStream_t st, [[maybe_unused]] bool grad)
 {
-    [[maybe_unused]] const bool grad = p.rsum != nullptr;  // the reverse sweep contracts E into the gradients itself
     constexpr int NP = KCH > 0 ? 2 : 1;
     if (small_problem(d)) {
         // Pairs of consecutive bands share a workgroup (the hand-over between them stays in LDS)
@@ -231,15 +237,15 @@ void launch_dp_kch(const sdtw_desc *d, const Layout &L, const Params &p, float *
 }
 
 template <bool FWD>
-void launch_dp(const sdtw_desc *d, const Layout &L, const Params &p, float *value, hipStream_t st)
+void launch_dp(const sdtw_desc *d, const Layout &L, const Params &p, float *value, hipStream_t st, bool grad = false)
 {
-    if (d->mode == SDTW_UNFUSED) return launch_dp_kch<FWD, -1>(d, L, p, value, st);
+    if (d->mode == SDTW_UNFUSED) return launch_dp_kch<FWD, -1>(d, L, p, value, st, grad);
     switch (fused_variant(d->D)) {
-        case 1: return launch_dp_kch<FWD, 1>(d, L, p, value, st);
-        case 2: return launch_dp_kch<FWD, 2>(d, L, p, value, st);
-        case 4: return launch_dp_kch<FWD, 4>(d, L, p, value, st);
-        case 8: return launch_dp_kch<FWD, 8>(d, L, p, value, st);
-        default: return launch_dp_kch<FWD, 0>(d, L, p, value, st);
+        case 1: return launch_dp_kch<FWD, 1>(d, L, p, value, st, grad);
+        case 2: return launch_dp_kch<FWD, 2>(d, L, p, value, st, grad);
+        case 4: return launch_dp_kch<FWD, 4>(d, L, p, value, st, grad);
+        case 8: return launch_dp_kch<FWD, 8>(d, L, p, value, st, grad);
+        default: return launch_dp_kch<FWD, 0>(d, L, p, value, st, grad);
     }
 }
 
@@ -322,14 +328,19 @@ int backward_impl(const sdtw_desc *d, const float *x, const float *y, const floa
     (void)hipGetLastError();  // see forward_impl
     const Layout L = layout_of(d);
     Params p = make_params(d, L, x, y, ws, x_len, y_len);
-    // Large problems with D <= 128 keep no E in the workspace.  Without E_out the reverse sweep contracts
-    // every finished block of E into the gradients where it stands (dx, dy serve as accumulators); with
-    // E_out the blocks go to the caller's memory and the gradients are formed from there, as for small
-    // problems.
-    const bool sweep_grad = L.sweep_grad && E_out == nullptr;
-    if (L.sweep_grad && E_out != nullptr) p.E = E_out;
-    if (sweep_grad) {
+    // Compact E (large problems with long sequences, or on request): the reverse sweep leaves only the
+    // non-zero 32x32 blocks of E, in a pool, and the gradient kernel reads them through the block index.
+    // If the pool was too small (device-side flag) the kernels after it - otherwise no-ops - form the
+    // gradients once more with a reverse sweep that contracts E into them on the spot.  With E_out the
+    // blocks go to the caller's dense memory instead and everything is as for the dense layout.
+    const bool compact = L.compact_E && E_out == nullptr;
+    if (L.compact_E && E_out != nullptr) p.E = E_out;
+    if (compact) {
         char *base = static_cast<char *>(ws);
+        p.pool = reinterpret_cast<float *>(base + L.off_pool);
+        p.idx = reinterpret_cast<int32_t *>(base + L.off_idx);
+        const long long forced = g_pool_blocks;
+        p.pool_blocks = forced >= 0 ? std::min<long long>(forced, L.pool_blocks) : L.pool_blocks;
         p.gdx = dx;
         p.gdy = dy;
         p.rsum = reinterpret_cast<float *>(base + L.off_rsum);
@@ -337,10 +348,10 @@ int backward_impl(const sdtw_desc *d, const float *x, const float *y, const floa
         p.csum_hi = reinterpret_cast<int32_t *>(base + L.off_csum + align_up((size_t)d->B * d->M * sizeof(uint32_t), 256));
         p.gdy_hi = reinterpret_cast<int32_t *>(base + L.off_dyhi);
         p.pair_exp = reinterpret_cast<const int32_t *>(base + L.off_pexp);
-        // Fixed-point format of the y-side sums: a column receives at most two terms per band (one per
-        // 32-row block), each below 2^(prec + 6) units.  With nb bits for their number, the low word
-        // takes lo_bits = 32 - nb bits of every term and the high word the other prec + 6 - lo_bits,
-        // which have to fit 31 bits nb times over: prec <= 57 - 2 nb (26 is plenty).
+        // Fixed-point format of the second sweep's y-side sums: a column receives at most two terms per
+        // band (one per 32-row block), each below 2^(prec + 6) units.  With nb bits for their number, the
+        // low word takes lo_bits = 32 - nb bits of every term and the high word the other
+        // prec + 6 - lo_bits, which have to fit 31 bits nb times over: prec <= 57 - 2 nb (26 is plenty).
         int nb = 1;
         while ((1ll << nb) < 2ll * L.nbands + 1) ++nb;
         p.fx_lo_bits = 32 - nb;
@@ -364,26 +375,12 @@ int backward_impl(const sdtw_desc *d, const float *x, const float *y, const floa
     } else {
         {
             ProfScope ps("backward_prep", st);
-            if (sweep_grad && dy)
-                pair_exponent_kernel<<<d->B, 256, 0, st>>>(p, reinterpret_cast<int32_t *>(static_cast<char *>(ws) + L.off_pexp));
             backward_prep_kernel<<<prep_grid(p, 0), 256, 0, st>>>(p);
         }
         {
             ProfScope ps(d->mode == SDTW_UNFUSED ? "backward_dp_unfused" : "backward_dp_fused", st);
             launch_dp<false>(d, L, p, nullptr, st);
         }
-    }
-    if (sweep_grad) {
-        if (dx || dy) {
-            const bool vec = (d->D % 4 == 0) && aligned16(x) && aligned16(y) && (!dx || aligned16(dx)) && (!dy || aligned16(dy));
-            const size_t n = (size_t)d->B * ((size_t)d->N + d->M) * d->D / (vec ? 4 : 1);
-            ProfScope ps("gradient_finish", st);
-            if (vec)
-                gradient_finish_kernel<4><<<fill_grid(n), 256, 0, st>>>(p, grad_value);
-            else
-                gradient_finish_kernel<1><<<fill_grid(n), 256, 0, st>>>(p, grad_value);
-        }
-        return hip_ok();
     }
     if (dx || dy) {
         const int P = std::max(dx ? d->N : 0, dy ? d->M : 0);
@@ -396,10 +393,23 @@ int backward_impl(const sdtw_desc *d, const float *x, const float *y, const floa
     }
     if (E_out) {
         const size_t n = (size_t)d->B * d->N * d->M;
-        if (L.sweep_grad)
+        if (L.compact_E)
             complete_E_kernel<<<fill_grid(n), 256, 0, st>>>(p);  // the sweep wrote the non-zero blocks into E_out itself
         else
             export_E_kernel<<<fill_grid(n), 256, 0, st>>>(p, E_out);
+    }
+    if (compact && (dx || dy)) {
+        // only if the pool ran over (each of these kernels looks at the flag first)
+        ProfScope ps("second_sweep", st);
+        if (dy) pair_exponent_kernel<<<d->B, 256, 0, st>>>(p, reinterpret_cast<int32_t *>(static_cast<char *>(ws) + L.off_pexp));
+        second_sweep_prep_kernel<<<prep_grid(p, 0), 256, 0, st>>>(p);
+        launch_dp<false>(d, L, p, nullptr, st, true);
+        const bool vec = (d->D % 4 == 0) && aligned16(x) && aligned16(y) && (!dx || aligned16(dx)) && (!dy || aligned16(dy));
+        const size_t n = (size_t)d->B * ((size_t)d->N + d->M) * d->D / (vec ? 4 : 1);
+        if (vec)
+            gradient_finish_kernel<4><<<fill_grid(n), 256, 0, st>>>(p, grad_value);
+        else
+            gradient_finish_kernel<1><<<fill_grid(n), 256, 0, st>>>(p, grad_value);
     }
     return hip_ok();
 }
@@ -759,7 +769,7 @@ int sdtw_debug_export(const sdtw_desc *desc, const void *workspace, size_t works
             export_R_kernel<<<fill_grid(n), 256, 0, st>>>(p, static_cast<double *>(out));
             return hip_ok();
         case SDTW_EXPORT_E:
-            if (L.sweep_grad) return SDTW_ERR_UNSUPPORTED;  // no E in this workspace: ask sdtw_backward for E_out
+            if (L.compact_E) return SDTW_ERR_UNSUPPORTED;  // no dense E in this workspace: ask sdtw_backward for E_out
             export_E_kernel<<<fill_grid(n), 256, 0, st>>>(p, static_cast<float *>(out));
             return hip_ok();
         default:
@@ -815,6 +825,12 @@ int sdtw_debug_rate_probe(int probe, int variant, int waves_per_simd, int iters,
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     return rc;
+}
+
+int sdtw_debug_set_pool_blocks(long long blocks)
+{
+    g_pool_blocks = blocks;
+    return SDTW_OK;
 }
 
 int sdtw_debug_profile(int enable)

@@ -70,6 +70,12 @@ def test_workspace_sizes():
     # ... and so do small ones on request
     d_m = binding.make_desc(32, 1024, 1024, 128, 0.1, pkg.FUSED, flags=pkg.FLAG_MIN_MEMORY)
     assert pkg.sdtw_workspace_bytes(d_m) < 2.5 * 32 * 1024 * 1024
+    # long sequences with a dense E on request: 4 bytes per cell more
+    d_d = binding.make_desc(32, 8192, 8192, 128, 0.01, pkg.FUSED, flags=pkg.FLAG_DENSE_E)
+    assert 4.5 * 32 * 8192 * 8192 < pkg.sdtw_workspace_bytes(d_d) < 5.0 * 32 * 8192 * 8192
+    # large problems of short pairs keep the dense E
+    d_s = binding.make_desc(2048, 256, 256, 16, 1.0, pkg.FUSED)
+    assert pkg.sdtw_workspace_bytes(d_s) > 4.0 * 2048 * 256 * 256
     assert pkg.sdtw_workspace_bytes(binding.make_desc(1, 1, 1, 1, 1.0, pkg.FUSED)) > 0
     # under a band constraint the tables follow the band, not M: E (4 B per cell of the full grid)
     # is what remains
@@ -82,7 +88,7 @@ def test_workspace_sizes():
 
 @pytest.mark.parametrize("kw", [
     dict(B=0), dict(N=0), dict(M=-3), dict(D=0), dict(gamma=0.0), dict(gamma=-1.0), dict(gamma=float("nan")),
-    dict(gamma=float("inf")), dict(mode=2), dict(mode=-1), dict(flags=4), dict(bandwidth=-1),
+    dict(gamma=float("inf")), dict(mode=2), dict(mode=-1), dict(flags=8), dict(flags=6), dict(bandwidth=-1),
     dict(N=8, M=20, bandwidth=11),  # the last cell (N-1, M-1) would lie outside the band |i-j| <= 11
 ])
 def test_invalid_descriptors_need_zero_bytes_and_are_refused(kw):

@@ -206,14 +206,21 @@ def test_alignment_only_looks_where_E_can_be_non_zero(shape, mode, gamma, kind):
 @pytest.mark.parametrize("B,N,M,D,gamma", [(5, 200, 150, 16, 0.1), (2, 130, 257, 128, 0.05), (3, 64, 64, 8, 1.0),
                                            (2, 100, 90, 200, 0.5), (4, 300, 333, 33, 20.0), (1, 1, 1, 1, 1.0),
                                            (3, 31, 700, 64, 0.01)])
-def test_min_memory_flag(mode, B, N, M, D, gamma):
-    # SDTW_FLAG_MIN_MEMORY: small problems on the route of large ones - checkpoints instead of tables, and
-    # (D <= 128) no stored E: the reverse sweep contracts every block of E into dx, dy where it stands.
-    # Sparse to dense E, D that is no multiple of 32, D above 128 (E stays in the workspace there).
-    say("min memory %s B=%d N=%d M=%d D=%d gamma=%g" % (mode, B, N, M, D, gamma))
+@pytest.mark.parametrize("pool", [-1, 0, 7])
+def test_min_memory_flag(pool, mode, B, N, M, D, gamma):
+    # SDTW_FLAG_MIN_MEMORY: small problems on the route of large ones with long sequences - checkpoints
+    # instead of tables and (D <= 128) a compact E: only the non-zero 32x32 blocks, in a pool.  pool = 0 / 7:
+    # a pool of that many blocks, which runs over, so that the backward call takes its second sweep, the
+    # one that contracts every block of E into dx, dy where it stands.
+    # Sparse to dense E, D that is no multiple of 32, D above 128 (a dense E stays in the workspace there).
+    say("min memory %s B=%d N=%d M=%d D=%d gamma=%g pool=%d" % (mode, B, N, M, D, gamma, pool))
     x, y = workloads.normal_pairs(300 + N + D, B, N, M, D)
     ref = oracle.batch(x, y, gamma, want_E=True)
-    got = run_gpu(x, y, gamma, MODES[mode], min_memory=True)
+    binding.debug_set_pool_blocks(pool)
+    try:
+        got = run_gpu(x, y, gamma, MODES[mode], min_memory=True)
+    finally:
+        binding.debug_set_pool_blocks(-1)
     check_against(ref, got, what="min memory %s %dx%d" % (mode, N, M))
     plain = binding.make_desc(B, N, M, D, gamma, MODES[mode])
     assert pkg.sdtw_workspace_bytes(got["desc"]) < pkg.sdtw_workspace_bytes(plain) or N * M < 4096
