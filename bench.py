@@ -305,6 +305,20 @@ def bench_barycenter(with_cpu):
     u, f = out["modes"]["unfused"], out["modes"]["fused"]
     out["peak_memory"] = {"unfused_bytes": u["peak_bytes"], "fused_bytes": f["peak_bytes"],
                           "fused_saving": 1.0 - f["peak_bytes"] / u["peak_bytes"]}
+    # fused with SDTW_FLAG_MIN_MEMORY: 20 steps
+    z = torch.from_numpy(bw.z0.copy()).cuda()
+    m, v, ws = torch.zeros_like(z), torch.zeros_like(z), None
+    loss = torch.empty(1, dtype=torch.float32, device="cuda")
+    for step in range(1, 4):
+        _, _, ws = pkg.sdtw_barycenter_step(z, X, m, v, bw.gamma, step, bw.lr, mode=pkg.FUSED, workspace=ws, loss=loss, min_memory=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for step in range(4, 24):
+        pkg.sdtw_barycenter_step(z, X, m, v, bw.gamma, step, bw.lr, mode=pkg.FUSED, workspace=ws, loss=loss, min_memory=True)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    out["min_memory"] = {"flag": "SDTW_FLAG_MIN_MEMORY", "mode": "fused", "ms_per_step": dt / 20 * 1e3,
+                         "workspace_bytes": ws.nbytes, "peak_bytes": ws.nbytes + (X.numel() + 3 * z.numel() + 1) * 4}
     if with_cpu:
         import oracle
 
@@ -377,7 +391,7 @@ def cpu_baseline(wl, max_pairs=None, target_wall_s=2.0):
             "sample_one_core": "%d repetitions of %d pairs of the same batch on one thread, %.1f s" % (reps1, nb, dt1)}
 
 
-def pair_record(name, steps, warmup, with_cpu, mode_ids, extra_modes=()):
+def pair_record(name, steps, warmup, with_cpu, mode_ids, extra_modes=(), min_memory=False):
     """Everything reported for one pair configuration: per-mode timings and bytes, roofline of the
     slowest kernel, CPU baseline.  extra_modes: modes that are not part of the configuration's step
     but are measured beside it for the memory comparison (fewer steps)."""
@@ -402,6 +416,14 @@ def pair_record(name, steps, warmup, with_cpu, mode_ids, extra_modes=()):
     pm = peak_memory(rec["modes"])
     if pm:
         rec["peak_memory"] = pm
+    if min_memory:
+        # the same configuration with SDTW_FLAG_MIN_MEMORY (checkpoints and a compact E instead of both
+        # tables and a dense E): what the smaller workspace costs in time
+        from paper_2602_17206_amd import binding
+
+        torch.cuda.empty_cache()
+        r3 = bench_pairs(wl, modes, max(5, steps // 2), 2, with_kernels=False, flags=binding.FLAG_MIN_MEMORY)
+        rec["min_memory"] = {"flag": "SDTW_FLAG_MIN_MEMORY", "modes": r3["per_mode"], "peak_memory": peak_memory(r3["per_mode"])}
     if with_cpu:
         rec["cpu_baseline"] = cpu_baseline(wl, max_pairs=8 if wl.N * wl.M >= 4096 * 4096 else None)
     return rec, r
@@ -594,7 +616,7 @@ def main():
             if name == args.workload:
                 continue
             torch.cuda.empty_cache()
-            others[name], _ = pair_record(name, steps, 3, with_cpu, mode_ids)
+            others[name], _ = pair_record(name, steps, 3, with_cpu, mode_ids, min_memory=True)
         torch.cuda.empty_cache()
         others["c5_barycenter"] = bench_barycenter(with_cpu)
         line["other_workloads"] = others

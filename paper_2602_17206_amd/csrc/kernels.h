@@ -465,7 +465,7 @@ __global__ __launch_bounds__(256) void input_grad_kernel(Params p, const float *
 // input_grad_kernel; the pieces sit in LDS as [row][32 reduced positions] with 80-byte rows, so that
 // a lane's 8 consecutive reduced positions are one 16-byte read.
 // ---------------------------------------------------------------------------------------------
-constexpr int kLiveCap = 2048;     // chunks listed at a time
+constexpr int kLiveCap = 1024;     // chunks listed at a time (with the pool positions: 12 KB of LDS)
 constexpr int kGradHalfRow = 40;  // float16 per LDS row: 32 used, padded to 80 bytes against bank conflicts
 
 __device__ __forceinline__ void split8(const float (&v)[8], float scale, half8 &h1, half8 &h2)
