@@ -391,6 +391,36 @@ def cpu_baseline(wl, max_pairs=None, target_wall_s=2.0):
             "sample_one_core": "%d repetitions of %d pairs of the same batch on one thread, %.1f s" % (reps1, nb, dt1)}
 
 
+def bench_half_inputs(wl, steps, warmup):
+    """The workload's shape with float16 sequences (sdtw_forward_half / sdtw_backward_half), fused."""
+    import torch
+
+    import paper_2602_17206_amd as pkg
+    from paper_2602_17206_amd import binding
+
+    xh, yh = torch.from_numpy(wl.x).cuda().half(), torch.from_numpy(wl.y).cuda().half()
+    value, desc, ws = pkg.sdtw_forward_half(xh, yh, wl.gamma, pkg.FUSED)
+
+    def step():
+        pkg.sdtw_forward_half(xh, yh, wl.gamma, pkg.FUSED, workspace=ws, value=value)
+        return pkg.sdtw_backward_half(desc, ws)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        out = step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    del out
+    assert binding.workspace_status(ws) == 0, "device reported an error"
+    cells = wl.B * wl.N * wl.M
+    return {"input_dtype": "f16", "mode": "fused", "contraction": "f16x1 (one fp16 MFMA product per 16 features, float32 accumulate)",
+            "fwd_bwd_ms": dt * 1e3, "fwd_bwd_cells_per_s": cells / dt, "workspace_bytes": ws.nbytes,
+            "note": "values and gradients of the sequences rounded to float16; includes allocating dx, dy per step"}
+
+
 def pair_record(name, steps, warmup, with_cpu, mode_ids, extra_modes=(), min_memory=False):
     """Everything reported for one pair configuration: per-mode timings and bytes, roofline of the
     slowest kernel, CPU baseline.  extra_modes: modes that are not part of the configuration's step
@@ -424,6 +454,9 @@ def pair_record(name, steps, warmup, with_cpu, mode_ids, extra_modes=(), min_mem
         torch.cuda.empty_cache()
         r3 = bench_pairs(wl, modes, max(5, steps // 2), 2, with_kernels=False, flags=binding.FLAG_MIN_MEMORY)
         rec["min_memory"] = {"flag": "SDTW_FLAG_MIN_MEMORY", "modes": r3["per_mode"], "peak_memory": peak_memory(r3["per_mode"])}
+    if name == HEADLINE:
+        torch.cuda.empty_cache()
+        rec["half_inputs"] = bench_half_inputs(wl, max(3, steps // 2), 2)
     if with_cpu:
         rec["cpu_baseline"] = cpu_baseline(wl, max_pairs=8 if wl.N * wl.M >= 4096 * 4096 else None)
     return rec, r
@@ -607,7 +640,7 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
     }
     line.update({k: rec[k] for k in ("config", "modes", "roofline") if k in rec})
-    for k in ("torch_peak_bytes", "peak_memory", "cpu_baseline"):
+    for k in ("torch_peak_bytes", "peak_memory", "half_inputs", "cpu_baseline"):
         if k in rec:
             line[k] = rec[k]
     if not args.headline_only and not args.modes:

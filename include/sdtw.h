@@ -193,6 +193,29 @@ int sdtw_backward_ragged(const sdtw_desc *desc, const float *x, const float *y, 
                          const int32_t *y_len, const float *grad_value, float *dx, float *dy,
                          float *E_out, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Reduced-precision inputs (Sec. 6, "Mixed precision"): x and y given as float16 or bfloat16.
+ *   x [B,N,D] (or [N,D] with x_batch_stride 0), y [B,M,D]: device, read only, 16-bit elements of the type
+ *        `input_type` names; strides in the descriptor count elements, as always.
+ *   value, grad_value, dx, dy, E_out: float32, as for sdtw_forward / sdtw_backward.
+ * The forward call widens x and y to float32 copies inside the workspace (exact) and everything else
+ * runs as for float32 inputs - tables in float64, exponentials in float32 - except the inner products of
+ * the cost: a float16 / bfloat16 element is one float16 piece, not two, so the cost takes one matrix-core
+ * product per 16 features instead of three.  The results are those of the rounded sequences to float32
+ * accuracy (same bars as sdtw_forward against the oracle run on the rounded values).  What the rounding
+ * itself does to the cost is the caller's to weigh against gamma: with relative rounding eps (2^-11 for
+ * float16, 2^-8 for bfloat16), |d~ - d| <= 2 eps sqrt(d) sqrt(2 (||x_i||^2 + ||y_j||^2)), which has to stay
+ * well below gamma for the alignment to be the one of the unrounded sequences.
+ * The backward call reads the copies the forward call left in the workspace; it takes no x, y.
+ * Workspace: sdtw_half_workspace_bytes (the plain workspace plus the two copies).  No per-pair lengths.
+ */
+enum { SDTW_INPUT_F16 = 1, SDTW_INPUT_BF16 = 2 };
+size_t sdtw_half_workspace_bytes(const sdtw_desc *desc);
+int sdtw_forward_half(const sdtw_desc *desc, const void *x, const void *y, int input_type, float *value,
+                      void *workspace, size_t workspace_bytes, void *stream);
+int sdtw_backward_half(const sdtw_desc *desc, const float *grad_value, float *dx, float *dy, float *E_out,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
 /* Bytes of workspace for sdtw_barycenter_step; 0 if the descriptor is invalid.  Host only. */
 size_t sdtw_barycenter_workspace_bytes(const sdtw_bary_desc *desc);
 

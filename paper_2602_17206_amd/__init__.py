@@ -16,10 +16,12 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     sdtw_backward,
+    sdtw_backward_half,
     sdtw_backward_ragged,
     sdtw_barycenter_step,
     sdtw_barycenter_workspace_bytes,
     sdtw_forward,
+    sdtw_forward_half,
     sdtw_forward_ragged,
     sdtw_normalized_backward,
     sdtw_normalized_forward,

@@ -60,6 +60,7 @@ EXPORTED_SYMBOLS = (
     "sdtw_debug_export", "sdtw_debug_lane_shift", "sdtw_debug_set_spin_limit",
     "sdtw_debug_profile", "sdtw_debug_profile_read", "sdtw_debug_force_workgroup_shape",
     "sdtw_debug_rate_probe", "sdtw_forward_static_scratch", "sdtw_debug_set_pool_blocks",
+    "sdtw_half_workspace_bytes", "sdtw_forward_half", "sdtw_backward_half",
 )
 
 
@@ -123,6 +124,12 @@ def load_library():
     lib.sdtw_debug_profile_read.restype = i32
     lib.sdtw_debug_profile_read.argtypes = [ctypes.c_char_p, sz, ctypes.POINTER(ctypes.c_float), i32,
                                             ctypes.POINTER(ctypes.c_int)]
+    lib.sdtw_half_workspace_bytes.restype = sz
+    lib.sdtw_half_workspace_bytes.argtypes = [ctypes.POINTER(Desc)]
+    lib.sdtw_forward_half.restype = i32
+    lib.sdtw_forward_half.argtypes = [ctypes.POINTER(Desc), vp, vp, i32, vp, vp, sz, vp]
+    lib.sdtw_backward_half.restype = i32
+    lib.sdtw_backward_half.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, vp, vp, sz, vp]
     lib.sdtw_debug_set_pool_blocks.restype = i32
     lib.sdtw_debug_set_pool_blocks.argtypes = [ctypes.c_longlong]
     lib.sdtw_debug_rate_probe.restype = i32
@@ -189,7 +196,7 @@ class Workspace:
         return ctypes.c_void_p(self.buffer.data_ptr())
 
 
-def _desc_for(x, y, gamma, mode):
+def _desc_for(x, y, gamma, mode, check_dtype=True):
     import torch
 
     if x.dim() == 2:
@@ -212,7 +219,7 @@ def _desc_for(x, y, gamma, mode):
         raise ValueError("x and y must have the same feature dimension")
     if not x_shared and not y_shared and x.shape[0] != y.shape[0]:
         raise ValueError("x and y must have the same batch size")
-    assert x.dtype == torch.float32 and y.dtype == torch.float32
+    assert not check_dtype or (x.dtype == torch.float32 and y.dtype == torch.float32)
     return make_desc(B, N, M, D, gamma, mode, x_shared, y_shared)
 
 
@@ -503,3 +510,49 @@ def debug_rate_probe(probe, variant, waves_per_simd, iters, scratch, stream=None
 
 def debug_set_pool_blocks(blocks):
     load_library().sdtw_debug_set_pool_blocks(int(blocks))
+
+
+INPUT_F16, INPUT_BF16 = 1, 2
+
+
+def sdtw_forward_half(x, y, gamma, mode=FUSED, workspace=None, value=None, stream=None, min_memory=False):
+    """sdtw_forward for float16 or bfloat16 device tensors x [B,N,D] / [N,D], y [B,M,D] / [M,D] (same dtype).
+    Returns (value float32 [B], desc, workspace); keep the last two for :func:`sdtw_backward_half`."""
+    import torch
+
+    lib = load_library()
+    if x.dtype != y.dtype or x.dtype not in (torch.float16, torch.bfloat16):
+        raise ValueError("x and y must both be float16 or both bfloat16")
+    desc = _desc_for(x, y, gamma, mode, check_dtype=False)
+    if min_memory:
+        desc.flags |= FLAG_MIN_MEMORY
+    if workspace is None:
+        nbytes = int(lib.sdtw_half_workspace_bytes(ctypes.byref(desc)))
+        if nbytes == 0:
+            raise SdtwError(STATUS_INVALID_ARG, "sdtw_half_workspace_bytes")
+        workspace = Workspace(nbytes, x.device)
+    if value is None:
+        value = torch.empty(desc.B, dtype=torch.float32, device=x.device)
+    kind = INPUT_F16 if x.dtype == torch.float16 else INPUT_BF16
+    rc = lib.sdtw_forward_half(ctypes.byref(desc), _ptr(x, name="x"), _ptr(y, name="y"), kind,
+                               _ptr(value, torch.float32, (desc.B,), "value"), workspace.ptr, workspace.nbytes,
+                               _stream_ptr(stream))
+    if rc != 0:
+        raise SdtwError(rc, "sdtw_forward_half")
+    return value, desc, workspace
+
+
+def sdtw_backward_half(desc, workspace, grad_value=None, want_dx=True, want_dy=True, want_E=False, stream=None):
+    """Gradients (float32) of the values :func:`sdtw_forward_half` produced.  Returns (dx, dy, E or None)."""
+    import torch
+
+    lib = load_library()
+    dev = workspace.buffer.device
+    dx = torch.empty((desc.B, desc.N, desc.D), dtype=torch.float32, device=dev) if want_dx else None
+    dy = torch.empty((desc.B, desc.M, desc.D), dtype=torch.float32, device=dev) if want_dy else None
+    E = torch.empty((desc.B, desc.N, desc.M), dtype=torch.float32, device=dev) if want_E else None
+    rc = lib.sdtw_backward_half(ctypes.byref(desc), _ptr(grad_value, torch.float32, (desc.B,), "grad_value"),
+                                _ptr(dx), _ptr(dy), _ptr(E), workspace.ptr, workspace.nbytes, _stream_ptr(stream))
+    if rc != 0:
+        raise SdtwError(rc, "sdtw_backward_half")
+    return dx, dy, E

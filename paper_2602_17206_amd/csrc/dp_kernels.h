@@ -292,6 +292,7 @@ template <int KG, int DIR, int W0, int NW> struct HalfProducer {
     half8 xa[2][2][KG];     // [row block][piece][group]
     half8 ybuf[NBUF][2];    // [stage][piece]
     float yn_c[2], yis_c[2];  // ||y_c||^2 and 1/scale of this lane's column, for the blocks of the macro-step
+    bool one_piece;         // the operands are float16 / bfloat16 values: their first piece is all of them (Params::pieces)
 
     __device__ __forceinline__ int ycol(const Params &p, int cb, int lane) const
     {
@@ -302,12 +303,13 @@ template <int KG, int DIR, int W0, int NW> struct HalfProducer {
     {
         const uint16_t *r = yh + (size_t)ycol(p, cb, lane) * (2 * p.Dp) + 8 * (lane >> 5) + 32 * g;
         ybuf[buf][0] = *reinterpret_cast<const half8 *>(r);
-        ybuf[buf][1] = *reinterpret_cast<const half8 *>(r + 16);
+        if (!one_piece) ybuf[buf][1] = *reinterpret_cast<const half8 *>(r + 16);
     }
     // x pieces of the band, and the per-row table (||x_r||^2, -2/scale_r) in LDS
     __device__ __forceinline__ void init(const Params &p, const uint16_t *xh, const float *xnb, const float *xisb,
                                          float2 *rowtab, int row0, int lane)
     {
+        one_piece = p.pieces == 1;
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
             if (!owns_rb(rb)) continue;
@@ -324,8 +326,10 @@ template <int KG, int DIR, int W0, int NW> struct HalfProducer {
     __device__ __forceinline__ floatx16 mfma3(floatx16 acc, int rb, int g, const half8 &k1, const half8 &k2) const
     {
         acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[rb][0][g], k1, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[rb][0][g], k2, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[rb][1][g], k1, acc, 0, 0, 0);
+        if (!one_piece) {
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[rb][0][g], k2, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[rb][1][g], k1, acc, 0, 0, 0);
+        }
         return acc;
     }
     // acc (scaled inner products) -> cost block in the ring:  d = ||x||^2 + ||y||^2 - 2 <x,y>, clamped at 0
@@ -458,8 +462,10 @@ __device__ __forceinline__ void cost_tile_finish(const Params &p, const half8 (&
                 const half8 k1 = *reinterpret_cast<const half8 *>(yc + 32 * g);
                 const half8 k2 = *reinterpret_cast<const half8 *>(yc + 32 * g + 16);
                 acc[cbk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0][g], k1, acc[cbk], 0, 0, 0);
-                acc[cbk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0][g], k2, acc[cbk], 0, 0, 0);
-                acc[cbk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[1][g], k1, acc[cbk], 0, 0, 0);
+                if (p.pieces != 1) {  // (float16 / bfloat16 inputs: the first piece is the whole element)
+                    acc[cbk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0][g], k2, acc[cbk], 0, 0, 0);
+                    acc[cbk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[1][g], k1, acc[cbk], 0, 0, 0);
+                }
             }
             const float2 yt = ytab[cbk * 32 + (lane & 31)];
 #pragma unroll

@@ -50,6 +50,7 @@ __device__ __forceinline__ void stamp_header(const Params &p)
     h->forward_done = 1;
     h->two_sweep = p.two_sweep;
     h->window = p.window;
+    h->pieces = p.pieces;
     h->x_len_ptr = reinterpret_cast<uint64_t>(p.x_len);
     h->y_len_ptr = reinterpret_cast<uint64_t>(p.y_len);
     h->status = 0;
@@ -211,11 +212,11 @@ __device__ __forceinline__ bool workspace_matches(const Params &p)
     const Header *h = p.hdr;
     const uint32_t magic = h->magic, gamma_bits = h->gamma_bits;
     const int32_t B = h->B, N = h->N, M = h->M, D = h->D, mode = h->mode, done = h->forward_done;
-    const int32_t two_sweep = h->two_sweep, window = h->window;
+    const int32_t two_sweep = h->two_sweep, window = h->window, pieces = h->pieces;
     const uint64_t xl = h->x_len_ptr, yl = h->y_len_ptr;
     const uint32_t diff = (magic ^ kMagic) | (uint32_t)(done ^ 1) | (uint32_t)(B ^ p.B) | (uint32_t)(N ^ p.N) |
                           (uint32_t)(M ^ p.M) | (uint32_t)(D ^ p.D) | (uint32_t)(mode ^ p.mode) |
-                          (uint32_t)(two_sweep ^ p.two_sweep) | (uint32_t)(window ^ p.window) |
+                          (uint32_t)(two_sweep ^ p.two_sweep) | (uint32_t)(window ^ p.window) | (uint32_t)(pieces ^ p.pieces) |
                           (gamma_bits ^ __float_as_uint(p.gamma));
     const uint64_t diff_ptr = (xl ^ reinterpret_cast<uint64_t>(p.x_len)) | (yl ^ reinterpret_cast<uint64_t>(p.y_len));
     return (diff == 0) & (diff_ptr == 0);
@@ -982,6 +983,19 @@ __global__ void merge_status_kernel(Header *xy, const Header *xx, const Header *
         if (xx->magic == kMagic) st = max(st, xx->status);
         if (yy->magic == kMagic) st = max(st, yy->status);
         xy->status = st;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Reduced-precision inputs (Sec. 6, "Mixed precision"): float16 or bfloat16 sequences are widened to
+// float32 copies in the workspace (exact), which the other kernels then read like any float32 input.
+// ---------------------------------------------------------------------------------------------
+__global__ void widen_half_kernel(const uint16_t *__restrict__ src, float *__restrict__ dst, size_t n, int bf16)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const uint16_t h = src[i];
+        dst[i] = bf16 ? __uint_as_float((unsigned)h << 16) : (float)__builtin_bit_cast(_Float16, h);
     }
 }
 

@@ -33,7 +33,8 @@ struct Header {
     uint64_t x_len_ptr, y_len_ptr;  // the length vectors the forward was run with (0: none)
     uint32_t pool_count;   // compact E: 32x32 blocks handed out so far (may run past the capacity)
     int32_t pool_overflow; // compact E: a block did not fit; the backward call redoes the gradients the slow way
-    uint32_t pad[44];
+    int32_t pieces;        // float16 pieces per operand element the forward was run with (Params::pieces)
+    uint32_t pad[43];
 };
 static_assert(sizeof(Header) == 256, "header is 256 bytes");
 
@@ -183,6 +184,9 @@ struct Params {
     double *rfinal;
     float *xn, *yn;
     int32_t Dp;                    // row length (halves) of the split operand copies, 0 if absent
+    int32_t pieces;                // 2: x, y are float32, each element is two float16 pieces (three matrix-core products);
+                                   // 1: x, y hold float16 / bfloat16 values (the *_half entry points): the first piece is
+                                   //    the whole element, one product
     float *xis, *yis;              // per row: 1/scale used for the split copy (a power of two)
     uint16_t *xh, *yh;             // [rows][Dp/16][2 pieces][16] float16 bit patterns
     int64_t xh_stride, yh_stride;  // batch strides of the split copies (0 when shared)

@@ -110,9 +110,10 @@ Layout layout_of(const sdtw_desc *d)
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 Params make_params(const sdtw_desc *d, const Layout &L, const float *x, const float *y, void *ws,
-                   const int32_t *x_len = nullptr, const int32_t *y_len = nullptr)
+                   const int32_t *x_len = nullptr, const int32_t *y_len = nullptr, int pieces = 2)
 {
     Params p{};
+    p.pieces = pieces;
     p.x_len = x_len;
     p.y_len = y_len;
     p.window = effective_window(d);
@@ -270,11 +271,11 @@ unsigned prep_grid(const Params &p, int64_t norm_rows)
 }
 
 int forward_impl(const sdtw_desc *d, const float *x, const float *y, float *value, void *ws, hipStream_t st,
-                 const int32_t *x_len = nullptr, const int32_t *y_len = nullptr)
+                 const int32_t *x_len = nullptr, const int32_t *y_len = nullptr, int pieces = 2)
 {
     (void)hipGetLastError();  // what an earlier, unrelated call left behind is not this call's error
     const Layout L = layout_of(d);
-    const Params p = make_params(d, L, x, y, ws, x_len, y_len);
+    const Params p = make_params(d, L, x, y, ws, x_len, y_len, pieces);
     // Unfused mode, small problems: the start of the call is folded into the cost-tensor kernel (one
     // launch instead of two).  Not with a band constraint or length vectors (tiles outside them are
     // skipped), not without 16-byte rows, and only where the tiles are few (fewer than 512 of 128 x 128):
@@ -323,11 +324,11 @@ int forward_impl(const sdtw_desc *d, const float *x, const float *y, float *valu
 
 int backward_impl(const sdtw_desc *d, const float *x, const float *y, const float *grad_value, float *dx,
                   float *dy, float *E_out, void *ws, hipStream_t st, const int32_t *x_len = nullptr,
-                  const int32_t *y_len = nullptr)
+                  const int32_t *y_len = nullptr, int pieces = 2)
 {
     (void)hipGetLastError();  // see forward_impl
     const Layout L = layout_of(d);
-    Params p = make_params(d, L, x, y, ws, x_len, y_len);
+    Params p = make_params(d, L, x, y, ws, x_len, y_len, pieces);
     // Compact E (large problems with long sequences, or on request): the reverse sweep leaves only the
     // non-zero 32x32 blocks of E, in a pool, and the gradient kernel reads them through the block index.
     // If the pool was too small (device-side flag) the kernels after it - otherwise no-ops - form the
@@ -618,6 +619,65 @@ int sdtw_backward_ragged(const sdtw_desc *desc, const float *x, const float *y, 
     if (int rc = check_ws(workspace, workspace_bytes, layout_of(desc).total)) return rc;
     return backward_impl(desc, x, y, grad_value, dx, dy, E_out, workspace, static_cast<hipStream_t>(stream), x_len,
                          y_len);
+}
+
+// Reduced-precision inputs: the plain workspace first (its header carries the status word), then the
+// float32 copies of x and y.
+struct HalfLayout { size_t off_x, off_y, total; int64_t nx, ny; };
+
+static HalfLayout half_layout(const sdtw_desc *d)
+{
+    HalfLayout H{};
+    H.nx = (int64_t)(d->x_batch_stride == 0 ? 1 : d->B) * d->N * d->D;
+    H.ny = (int64_t)(d->y_batch_stride == 0 ? 1 : d->B) * d->M * d->D;
+    size_t o = align_up(layout_of(d).total, 256);
+    H.off_x = o; o = align_up(o + (size_t)H.nx * sizeof(float), 256);
+    H.off_y = o; o = align_up(o + (size_t)H.ny * sizeof(float), 256);
+    H.total = o;
+    return H;
+}
+
+size_t sdtw_half_workspace_bytes(const sdtw_desc *desc)
+{
+    int why;
+    if (!desc_ok(desc, &why)) return 0;
+    return half_layout(desc).total;
+}
+
+int sdtw_forward_half(const sdtw_desc *desc, const void *x, const void *y, int input_type, float *value,
+                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    int why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!x || !y || !value) return SDTW_ERR_INVALID_ARG;
+    if (input_type != SDTW_INPUT_F16 && input_type != SDTW_INPUT_BF16) return SDTW_ERR_INVALID_ARG;
+    const HalfLayout H = half_layout(desc);
+    if (int rc = check_ws(workspace, workspace_bytes, H.total)) return rc;
+    (void)hipGetLastError();
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *base = static_cast<char *>(workspace);
+    float *x32 = reinterpret_cast<float *>(base + H.off_x), *y32 = reinterpret_cast<float *>(base + H.off_y);
+    {
+        ProfScope ps("widen_inputs", st);
+        const int bf = input_type == SDTW_INPUT_BF16;
+        widen_half_kernel<<<fill_grid((size_t)H.nx), 256, 0, st>>>(static_cast<const uint16_t *>(x), x32, (size_t)H.nx, bf);
+        widen_half_kernel<<<fill_grid((size_t)H.ny), 256, 0, st>>>(static_cast<const uint16_t *>(y), y32, (size_t)H.ny, bf);
+    }
+    return forward_impl(desc, x32, y32, value, workspace, st, nullptr, nullptr, 1);
+}
+
+int sdtw_backward_half(const sdtw_desc *desc, const float *grad_value, float *dx, float *dy, float *E_out,
+                       void *workspace, size_t workspace_bytes, void *stream)
+{
+    int why;
+    if (!desc_ok(desc, &why)) return why;
+    if (desc->flags & SDTW_FLAG_VALUE_ONLY) return SDTW_ERR_STATE;
+    const HalfLayout H = half_layout(desc);
+    if (int rc = check_ws(workspace, workspace_bytes, H.total)) return rc;
+    char *base = static_cast<char *>(workspace);
+    const float *x32 = reinterpret_cast<const float *>(base + H.off_x), *y32 = reinterpret_cast<const float *>(base + H.off_y);
+    return backward_impl(desc, x32, y32, grad_value, dx, dy, E_out, workspace, static_cast<hipStream_t>(stream), nullptr,
+                         nullptr, 1);
 }
 
 size_t sdtw_barycenter_workspace_bytes(const sdtw_bary_desc *desc)

@@ -226,6 +226,41 @@ def test_min_memory_flag(pool, mode, B, N, M, D, gamma):
     assert pkg.sdtw_workspace_bytes(got["desc"]) < pkg.sdtw_workspace_bytes(plain) or N * M < 4096
 
 
+@pytest.mark.parametrize("dtype", ["float16", "bfloat16"])
+@pytest.mark.parametrize("mode", ["unfused", "fused"])
+@pytest.mark.parametrize("B,N,M,D,gamma,shape,min_memory", [
+    (3, 200, 150, 16, 0.5, 0, False), (2, 130, 257, 128, 1.0, 0, False), (2, 100, 90, 200, 1.0, 0, False),
+    (4, 300, 333, 33, 5.0, 0, True), (5, 96, 70, 64, 0.3, 1, False), (3, 260, 200, 128, 2.0, 4, False)])
+def test_half_precision_inputs(dtype, mode, B, N, M, D, gamma, shape, min_memory):
+    # float16 / bfloat16 sequences (Sec. 6, "Mixed precision"): the library's results are those of the
+    # ROUNDED sequences, to the bars of the float32 entry points - the oracle gets the rounded values as
+    # float32.  (The cost then takes one matrix-core product per 16 features instead of three.)
+    import torch
+
+    say("half inputs %s %s B=%d N=%d M=%d D=%d gamma=%g shape=%d min_memory=%s" % (dtype, mode, B, N, M, D, gamma, shape, min_memory))
+    x, y = workloads.normal_pairs(700 + N + D, B, N, M, D)
+    td = getattr(torch, dtype)
+    xh, yh = torch.from_numpy(x).to(td).cuda(), torch.from_numpy(y).to(td).cuda()
+    xr, yr = xh.float().cpu().numpy(), yh.float().cpu().numpy()
+    ref = oracle.batch(xr, yr, gamma, want_E=True)
+    binding.debug_force_workgroup_shape(shape)
+    try:
+        value, desc, ws = pkg.sdtw_forward_half(xh, yh, gamma, MODES[mode], min_memory=min_memory)
+        dx, dy, _ = pkg.sdtw_backward_half(desc, ws)
+        dx2, dy2, E = pkg.sdtw_backward_half(desc, ws, want_E=True)
+        torch.cuda.synchronize()
+    finally:
+        binding.debug_force_workgroup_shape(0)
+    assert binding.workspace_status(ws) == 0
+    got = {"value": value.cpu().numpy().astype(np.float64), "dx": dx.cpu().numpy().astype(np.float64),
+           "dy": dy.cpu().numpy().astype(np.float64), "E": E.cpu().numpy().astype(np.float64)}
+    check_against(ref, got, what="half inputs %s %s" % (dtype, mode))
+    assert_same_gradients(dx, dx2, dy, dy2, xh.float(), yh.float())
+    # a workspace filled by the half entry point is not one of the float32 entry point
+    with pytest.raises(pkg.SdtwError):
+        pkg.sdtw_backward(desc, xh.float(), yh.float(), binding.Workspace(16))
+
+
 def test_config1_tiny_oracle_case():
     wl = workloads.pair_workload("c1_tiny")
     say("config 1")
