@@ -1198,7 +1198,7 @@ __device__ __forceinline__ void fixed_point_add(unsigned *lo_word, int *hi_word,
 }
 
 template <int NFT, int COLS = kRingCols, int STRIDE = kRingStride>
-__device__ __attribute__((noinline)) void grad_E_block(const Params &p, const SweepRange &rg, const float *ring, int rb, int cb,
+__device__ __attribute__((noinline)) void grad_E_block(const Params &p, SweepRange rg, const float *ring, int rb, int cb,
                                                        int row0, int b, int Nl, int Ml, int lane)
 {
     if (cb < 0 || cb >= p.ncb || row0 + 32 * rb >= p.N || !block_in_range(rg, rb, cb)) return;
@@ -1748,9 +1748,11 @@ __device__ __forceinline__ void reverse_dp_body(const Params &p, WgShared<SLOTS>
             dead_prev = dead;
             if constexpr (GRAD) {
                 // into the gradients, once the band above has what it waits for
+                // (the routine is out of line and takes the parameters by reference: from the copy in the
+                // workspace, or the kernel would have to hold one in scratch memory)
                 if (!blocks_dead) {
-                    grad_E_block_any(p, rg, ring, 0, sg, row0, bb, Nl, Ml, lane);
-                    grad_E_block_any(p, rg, ring, 1, sg - 1, row0, bb, Nl, Ml, lane);
+                    grad_E_block_any(*p.self, rg, ring, 0, sg, row0, bb, Nl, Ml, lane);
+                    grad_E_block_any(*p.self, rg, ring, 1, sg - 1, row0, bb, Nl, Ml, lane);
                 }
             } else if constexpr (!kProducerFlush && !TSWEEP) {
                 flush_E_block(p, rg, ring, Eb, nzb, 0, sg, row0, lane, blocks_dead, 0, idxb);

@@ -747,7 +747,9 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
 // sweep adds to (they lie where the pool was: nobody reads the pool any more).
 __global__ __launch_bounds__(256) void second_sweep_prep_kernel(Params p)
 {
+    static_assert(sizeof(Params) <= 1024, "room for the parameter block in the workspace");
     if (p.hdr->pool_overflow == 0 || p.hdr->abort_backward != 0) return;
+    if (threadIdx.x == 0 && blockIdx.x == 0) *const_cast<Params *>(p.self) = p;
     if (threadIdx.x == 0 && blockIdx.x == 0) p.hdr->bwd_ticket = 0;
     fill_boundary_rows(p, p.brow_b, true, blockIdx.x, gridDim.x);
     const size_t stride = (size_t)gridDim.x * blockDim.x, first = (size_t)blockIdx.x * blockDim.x + threadIdx.x;

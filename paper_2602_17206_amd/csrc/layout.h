@@ -38,6 +38,8 @@ struct Header {
 };
 static_assert(sizeof(Header) == 256, "header is 256 bytes");
 
+struct Params;
+
 struct Layout {
     int32_t B, N, M, D, mode;
     int32_t nbands;   // ceil(N/64)
@@ -51,7 +53,7 @@ struct Layout {
     int32_t compact_E;           // 1: E is kept as a pool of its non-zero 32x32 blocks, not as a dense tensor (see make_layout)
     int64_t pool_blocks;         // capacity of that pool
     size_t off_hdr, off_rfinal, off_xn, off_yn, off_xis, off_yis, off_xh, off_yh, off_brow, off_brow_b, off_R,
-        off_Q, off_ckpt, off_cost, off_E, off_nz, off_idx, off_pool, off_rsum, off_csum, off_dyhi, off_pexp, total;
+        off_Q, off_ckpt, off_cost, off_E, off_nz, off_idx, off_pool, off_rsum, off_csum, off_dyhi, off_pexp, off_self, total;
 };
 
 // With D <= 128 the workspace keeps a copy of x and y split into two float16 pieces per element
@@ -142,9 +144,10 @@ inline Layout make_layout(int32_t B, int32_t N, int32_t M, int32_t D, int32_t mo
     if (!L.compact_E) o = align_up(o + (size_t)B * N * (size_t)M * sizeof(float), 256);
     o += kGuardBytes;
     L.off_nz = o;       o = align_up(o + (size_t)B * L.nrb * (size_t)L.ncb, 256);
-    L.off_idx = L.off_pool = L.off_rsum = L.off_csum = L.off_dyhi = L.off_pexp = o;
+    L.off_idx = L.off_pool = L.off_rsum = L.off_csum = L.off_dyhi = L.off_pexp = L.off_self = o;
     L.pool_blocks = 0;
     if (L.compact_E) {
+        L.off_self = o;  o += 1024;  // a copy of the kernel parameter block (Params::self)
         const int64_t all = (int64_t)B * L.nrb * L.ncb;
         L.pool_blocks = all / 64 > 2 * (int64_t)B * (L.nrb + L.ncb) ? all / 64 : 2 * (int64_t)B * (L.nrb + L.ncb);
         if (L.pool_blocks > all) L.pool_blocks = all;
@@ -217,6 +220,9 @@ struct Params {
     int32_t *csum_hi, *gdy_hi;
     const int32_t *pair_exp;       // [B]: |x_b| < 2^pair_exp[b] (from the per-row scales of the split copies)
     int32_t fx_prec, fx_lo_bits;
+    // This very block in device memory (written by second_sweep_prep_kernel): what the second sweep hands to
+    // its out-of-line contraction routine by reference, so that the kernel need not keep a private copy.
+    const Params *self;
 };
 
 }  // namespace sdtw

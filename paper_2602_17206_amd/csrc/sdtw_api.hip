@@ -163,6 +163,7 @@ Params make_params(const sdtw_desc *d, const Layout &L, const float *x, const fl
     p.csum_hi = p.gdy_hi = nullptr;
     p.pair_exp = nullptr;
     p.fx_prec = p.fx_lo_bits = 0;
+    p.self = nullptr;
     return p;
 }
 
@@ -349,6 +350,7 @@ int backward_impl(const sdtw_desc *d, const float *x, const float *y, const floa
         p.csum_hi = reinterpret_cast<int32_t *>(base + L.off_csum + align_up((size_t)d->B * d->M * sizeof(uint32_t), 256));
         p.gdy_hi = reinterpret_cast<int32_t *>(base + L.off_dyhi);
         p.pair_exp = reinterpret_cast<const int32_t *>(base + L.off_pexp);
+        p.self = reinterpret_cast<const Params *>(base + L.off_self);
         // Fixed-point format of the second sweep's y-side sums: a column receives at most two terms per
         // band (one per 32-row block), each below 2^(prec + 6) units.  With nb bits for their number, the
         // low word takes lo_bits = 32 - nb bits of every term and the high word the other
