@@ -515,7 +515,7 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
     // ran over, the gradients come from the second sweep instead and this kernel has nothing to do
     const bool pooled = p.idx != nullptr;
     const int32_t *idxb = pooled ? p.idx + (size_t)b * p.nrb * p.ncb : nullptr;
-    if (pooled && p.hdr->pool_overflow != 0 && !refused) return;
+    const int32_t overflow = pooled ? p.hdr->pool_overflow : 0;  // (looked at below, with the rest of the header)
 
     const float sA = 1024.0f;
     // the largest 1/scale among the chunk's 32 rows: one row per lane (mod 32; both halves of the
@@ -542,6 +542,20 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
             if (mb + 1 < p.ncb && nzb[(size_t)qb * p.ncb + mb + 1] != 0) bits |= 2u;
         }
         return bits;
+    };
+    // compact E: the same from the block index (a block is live where it has a pool position), which is
+    // what the list needs anyway: one memory round trip instead of flags first and positions after
+    auto chunk_slots = [&](int q0, int &s0, int &s1) {
+        const int qb = q0 / kBlk, mb = m0 / kBlk;
+        s1 = -1;
+        if (side == 0) {
+            s0 = idxb[(size_t)mb * p.ncb + qb];
+            if (mb + 1 < p.nrb) s1 = idxb[(size_t)(mb + 1) * p.ncb + qb];
+        } else {
+            s0 = idxb[(size_t)qb * p.ncb + mb];
+            if (mb + 1 < p.ncb) s1 = idxb[(size_t)qb * p.ncb + mb + 1];
+        }
+        return (s0 >= 0 ? 1u : 0u) | (s1 >= 0 ? 2u : 0u);
     };
 
     // Per thread and chunk: 8 values of E and 8 of the reduced sequence, each run along the reduced
@@ -653,7 +667,9 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
             og += 8 * (size_t)p.D;
         }
     }
-    const unsigned first_bits = tid < min(nchunk, kLiveCap) ? chunk_flags(tid * kBlk) : 0u;
+    int first_s0 = -1, first_s1 = -1;
+    unsigned first_bits = 0u;
+    if (tid < min(nchunk, kLiveCap)) first_bits = pooled ? chunk_slots(tid * kBlk, first_s0, first_s1) : chunk_flags(tid * kBlk);
     if (refused) {
         const float qnan = __builtin_nanf("");
         for (int e = tid; e < 64 * 64; e += 256) {
@@ -662,13 +678,19 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
         }
         return;
     }
+    if (overflow != 0) return;
     float ea0[8], bv0[8], ea1[8], bv1[8], is0 = 1.f, is1 = 1.f;
     for (int base = 0; base < nchunk; base += kLiveCap) {
         const int lim = min(nchunk, base + kLiveCap);
         int nlive = 0;
         for (int g = base, round = 0; g < lim; g += 256, ++round) {
             const int c = g + tid;
-            const unsigned bits = g == 0 ? first_bits : (c < lim ? chunk_flags(c * kBlk) : 0u);
+            int s0 = first_s0, s1 = first_s1;
+            unsigned bits = first_bits;
+            if (g != 0) {
+                s0 = s1 = -1;
+                bits = c < lim ? (pooled ? chunk_slots(c * kBlk, s0, s1) : chunk_flags(c * kBlk)) : 0u;
+            }
             const bool lv = bits != 0;
             const unsigned long long m = __ballot(lv);
             if (lane == 0) wave_mask[round & 1][w] = m;
@@ -684,9 +706,8 @@ __global__ __launch_bounds__(256) void input_grad_half_kernel(Params p, const fl
                 const int pos = off + __popcll(m & ((1ull << lane) - 1ull));
                 live_list[pos] = (int)((unsigned)(c * kBlk) | (bits << 30));
                 if (pooled) {
-                    const int qb = c, mb = m0 / kBlk;  // as in chunk_flags
-                    live_slot[0][pos] = (bits & 1u) ? (side == 0 ? idxb[(size_t)mb * p.ncb + qb] : idxb[(size_t)qb * p.ncb + mb]) : -1;
-                    live_slot[1][pos] = (bits & 2u) ? (side == 0 ? idxb[(size_t)(mb + 1) * p.ncb + qb] : idxb[(size_t)qb * p.ncb + mb + 1]) : -1;
+                    live_slot[0][pos] = s0;
+                    live_slot[1][pos] = s1;
                 }
             }
             nlive += total;
