@@ -58,7 +58,7 @@ def run_gpu(x, y, gamma, mode, grad_value=None, want_E=True, min_memory=False):
 def assert_same_gradients(dx, dx2, dy, dy2, xd, yd):
     """Two routes to the same gradients agree to rounding.  Each is 2 g (x_i sum E - sum E y_j) in float32,
     so besides a relative part the difference has a floor of a few ulps of the terms that cancel."""
-    floor = 4e-6 * max(xd.abs().max().item(), yd.abs().max().item())
+    floor = 4e-6 * max(xd.nan_to_num().abs().max().item(), yd.nan_to_num().abs().max().item())  # (padding may hold NaN)
     for a, b2, name in ((dx, dx2, "dx"), (dy, dy2, "dy")):
         for b in range(a.shape[0]):
             err = (a[b] - b2[b]).abs().max().item()
@@ -495,13 +495,13 @@ def test_alignment_at_the_row_length_limits(N, M, ragged):
 
 
 # ------------------------------------------------------------------------------- ragged batches
-def run_gpu_ragged(x, y, xl, yl, gamma, mode, grad_value=None, want_E=True):
+def run_gpu_ragged(x, y, xl, yl, gamma, mode, grad_value=None, want_E=True, min_memory=False):
     import torch
 
     xd, yd = to_dev(x), to_dev(y)
     xld = to_dev(xl) if xl is not None else None
     yld = to_dev(yl) if yl is not None else None
-    value, desc, ws = pkg.sdtw_forward_ragged(xd, yd, xld, yld, gamma, mode)
+    value, desc, ws = pkg.sdtw_forward_ragged(xd, yd, xld, yld, gamma, mode, min_memory=min_memory)
     gv = to_dev(grad_value.astype(np.float32)) if grad_value is not None else None
     return ragged_backward_both_routes(value, desc, ws, xd, yd, xld, yld, gv, want_E)
 
@@ -546,6 +546,38 @@ def test_ragged_batches(shape, mode, B, N, M, D, gamma):
     check_against(ref, got, what="ragged shape %d %s" % (shape, mode))
     for b in range(B):
         assert not got["E"][b, xl[b]:].any() and not got["E"][b, :, yl[b]:].any()
+        assert not got["dx"][b, xl[b]:].any() and not got["dy"][b, yl[b]:].any()
+
+
+@pytest.mark.parametrize("pool", [-1, 3])
+@pytest.mark.parametrize("mode", ["unfused", "fused"])
+@pytest.mark.parametrize("w", [0, 70])
+def test_compact_E_with_lengths_and_band(w, mode, pool):
+    # per-pair lengths (NaN in the padding) and a band constraint on the compact layout, through the pool
+    # and - pool of 3 blocks - through the second, contracting sweep, which masks by the lengths itself
+    B, N, M, D, gamma = 5, 260, 230, 24, 0.2
+    say("compact E ragged w=%d %s pool=%d" % (w, mode, pool))
+    x, y = workloads.normal_pairs(911, B, N, M, D)
+    xl = workloads.ragged_lengths(41, B, N, shortest=200)
+    yl = workloads.ragged_lengths(42, B, M, shortest=200)[::-1].copy()
+    for b in range(B):
+        x[b, xl[b]:] = np.nan
+        y[b, yl[b]:] = np.nan
+    gv = np.linspace(0.5, 2.0, B)
+    ref = oracle.ragged_batch(np.nan_to_num(x), np.nan_to_num(y), xl, yl, gamma, grad_value=gv, want_E=True,
+                              bandwidth=w if w else None)
+    binding.debug_set_pool_blocks(pool)
+    try:
+        if w:
+            got = run_gpu_band(x, y, gamma, MODES[mode], w, xl=xl, yl=yl, min_memory=True)
+        else:
+            got = run_gpu_ragged(x, y, xl, yl, gamma, MODES[mode], grad_value=gv, min_memory=True)
+    finally:
+        binding.debug_set_pool_blocks(-1)
+    if w:  # (the band helper takes no upstream gradient)
+        ref = oracle.ragged_batch(np.nan_to_num(x), np.nan_to_num(y), xl, yl, gamma, want_E=True, bandwidth=w)
+    check_against(ref, got, what="compact E ragged w=%d %s pool=%d" % (w, mode, pool))
+    for b in range(B):
         assert not got["dx"][b, xl[b]:].any() and not got["dy"][b, yl[b]:].any()
 
 
@@ -606,13 +638,13 @@ def test_ragged_large_regime_and_state_check():
 
 
 # ------------------------------------------------------------------------------- band constraint |i-j| <= w
-def run_gpu_band(x, y, gamma, mode, w, want_E=True, xl=None, yl=None):
+def run_gpu_band(x, y, gamma, mode, w, want_E=True, xl=None, yl=None, min_memory=False):
     import torch
 
     xd, yd = to_dev(x), to_dev(y)
     xld = to_dev(xl) if xl is not None else None
     yld = to_dev(yl) if yl is not None else None
-    value, desc, ws = pkg.sdtw_forward_ragged(xd, yd, xld, yld, gamma, mode, bandwidth=w)
+    value, desc, ws = pkg.sdtw_forward_ragged(xd, yd, xld, yld, gamma, mode, bandwidth=w, min_memory=min_memory)
     return ragged_backward_both_routes(value, desc, ws, xd, yd, xld, yld, None, want_E)
 
 
