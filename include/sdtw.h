@@ -67,8 +67,8 @@ enum { SDTW_UNFUSED = 0, SDTW_FUSED = 1 };
  * How the alignment matrix E is kept between the reverse sweep and the gradient kernel.
  *   Problems too small to fill the chip keep both DP tables (16 bytes per cell) and a dense E.
  *   Large problems keep checkpoints of the forward sweep (0.5 bytes per cell) and
- *     - with fewer than 2^22 cells per pair: a dense float32 E [B,N,M] (4 bytes per cell);
- *     - with 2^22 cells per pair or more, D <= 128: a COMPACT E - only the 32x32 blocks that hold a
+ *     - with fewer than 2^24 cells per pair (4096 x 4096): a dense float32 E [B,N,M] (4 bytes per cell);
+ *     - with 2^24 cells per pair or more, D <= 128: a COMPACT E - only the 32x32 blocks that hold a
  *       non-zero, in a pool with room for 1/64 of all blocks (at least 2 (N/32 + M/32) per pair).  For
  *       the small gamma long alignments are run with, E is a few blocks wide around the alignment
  *       path and fits many times over.  If it does not fit, the backward call notices on the device

@@ -79,7 +79,7 @@ inline int32_t table_macro_steps(int32_t nmacro, int32_t window)
 
 // Large problems with long sequences keep the alignment matrix compactly (see make_layout): from this
 // many cells per pair on, or whenever the caller asks for little memory.
-constexpr int64_t kCompactCells = (int64_t)1 << 22;
+constexpr int64_t kCompactCells = (int64_t)1 << 24;
 
 inline Layout make_layout(int32_t B, int32_t N, int32_t M, int32_t D, int32_t mode, bool x_shared,
                           bool y_shared, bool recompute, bool two_sweep, int32_t window = kNoWindow,
