@@ -361,12 +361,14 @@ def sdtw_normalized_workspace_bytes(desc):
     return int(load_library().sdtw_normalized_workspace_bytes(ctypes.byref(desc)))
 
 
-def sdtw_normalized_forward(x, y, gamma, mode=FUSED, workspace=None, value=None, stream=None):
+def sdtw_normalized_forward(x, y, gamma, mode=FUSED, workspace=None, value=None, stream=None, min_memory=False):
     """value[b] = sdtw(x_b,y_b) - (sdtw(x_b,x_b) + sdtw(y_b,y_b)) / 2.  Returns (value, desc, workspace)."""
     import torch
 
     lib = load_library()
     desc = _desc_for(x, y, gamma, mode)
+    if min_memory:
+        desc.flags |= FLAG_MIN_MEMORY
     if workspace is None:
         nbytes = sdtw_normalized_workspace_bytes(desc)
         if nbytes == 0:

@@ -769,10 +769,11 @@ def test_random_configurations(seed):
                                                   (2, 1, 1, 4, 1.0, False), (3, 2, 2, 3, 0.5, False),
                                                   # equal lengths but a shared x: three passes
                                                   (3, 96, 96, 8, 0.5, True)])
-def test_normalized_value_and_gradients(mode, B, N, M, D, gamma, shared):
+@pytest.mark.parametrize("min_memory", [False, True])
+def test_normalized_value_and_gradients(min_memory, mode, B, N, M, D, gamma, shared):
     import torch
 
-    say("normalised %s B=%d N=%d M=%d D=%d gamma=%g shared_x=%s" % (mode, B, N, M, D, gamma, shared))
+    say("normalised %s B=%d N=%d M=%d D=%d gamma=%g shared_x=%s min_memory=%s" % (mode, B, N, M, D, gamma, shared, min_memory))
     x, y = workloads.normal_pairs(700 + N, B, N, M, D)
     if shared:
         x = x[0]
@@ -780,7 +781,7 @@ def test_normalized_value_and_gradients(mode, B, N, M, D, gamma, shared):
     ref = oracle.normalized(np.broadcast_to(x, (B, N, D)) if shared else x, y, gamma, grad_value=gv)
     plain = oracle.batch(x, y, gamma, grad_value=gv)  # scale of the terms that cancel
     xd, yd = to_dev(x), to_dev(y)
-    value, desc, ws = pkg.sdtw_normalized_forward(xd, yd, gamma, MODES[mode])
+    value, desc, ws = pkg.sdtw_normalized_forward(xd, yd, gamma, MODES[mode], min_memory=min_memory)
     dx, dy = pkg.sdtw_normalized_backward(desc, xd, yd, ws, grad_value=to_dev(gv.astype(np.float32)))
     torch.cuda.synchronize()
     assert binding.workspace_status(ws) == 0
