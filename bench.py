@@ -9,7 +9,9 @@ configuration lists).  The value is DP cells per second for forward+backward, ce
 
 The same JSON line carries, under `other_workloads`, the B = 32 configurations with N = M = 256 and
 1024 (both modes each) and the barycenter configuration, every one with its own timings, peak
-bytes, `roofline` and `cpu_baseline`; `--headline-only` leaves them out (used for profiling runs).
+bytes, `roofline` and `cpu_baseline`; `--headline-only` leaves them out, and with them the two extra legs
+of the headline shape (its unfused mode, for the memory comparison, and float16 inputs): a profiling run
+then sees the kernels of the configuration's own step alone.
 
 `roofline` describes the kernel that took the most time in the step, timed with HIP events on the
 launch stream (per-kernel events are recorded in a second, identical loop so that they do not
@@ -421,7 +423,7 @@ def bench_half_inputs(wl, steps, warmup):
             "note": "values and gradients of the sequences rounded to float16; includes allocating dx, dy per step"}
 
 
-def pair_record(name, steps, warmup, with_cpu, mode_ids, extra_modes=(), min_memory=False):
+def pair_record(name, steps, warmup, with_cpu, mode_ids, extra_modes=(), min_memory=False, half_inputs=False):
     """Everything reported for one pair configuration: per-mode timings and bytes, roofline of the
     slowest kernel, CPU baseline.  extra_modes: modes that are not part of the configuration's step
     but are measured beside it for the memory comparison (fewer steps)."""
@@ -454,7 +456,7 @@ def pair_record(name, steps, warmup, with_cpu, mode_ids, extra_modes=(), min_mem
         torch.cuda.empty_cache()
         r3 = bench_pairs(wl, modes, max(5, steps // 2), 2, with_kernels=False, flags=binding.FLAG_MIN_MEMORY)
         rec["min_memory"] = {"flag": "SDTW_FLAG_MIN_MEMORY", "modes": r3["per_mode"], "peak_memory": peak_memory(r3["per_mode"])}
-    if name == HEADLINE:
+    if half_inputs:
         torch.cuda.empty_cache()
         rec["half_inputs"] = bench_half_inputs(wl, max(3, steps // 2), 2)
     if with_cpu:
@@ -630,8 +632,11 @@ def main():
                "ms_per_step": r["sec_step"] * 1e3, "modes": r["per_mode"],
                "roofline": dominant_roofline(r["kernels"], wl.B * wl.N * wl.M, wl.D, wl.name)}
     else:
-        extra = ("unfused",) if args.workload == HEADLINE else ()
-        rec, r = pair_record(args.workload, args.steps, args.warmup, with_cpu, mode_ids, extra_modes=extra)
+        # beside the configuration's own step: the unfused mode of the same shape (memory comparison) and
+        # float16 inputs - not in a --headline-only run, whose kernel statistics are then the step's alone
+        full = args.workload == HEADLINE and not args.headline_only
+        rec, r = pair_record(args.workload, args.steps, args.warmup, with_cpu, mode_ids,
+                             extra_modes=("unfused",) if full else (), half_inputs=full)
 
     line = {
         "metric": "Soft-DTW fwd+bwd DP cells/sec (B*N*M/s) at B=32",
