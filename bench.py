@@ -527,7 +527,8 @@ def ingest_pmc(base, workload):
         k = max((k for k in agg if len(agg[k]) >= 10), key=lambda k: sum(agg[k]) / len(agg[k]))
         return k, sorted(agg[k])[len(agg[k]) // 2]
 
-    labels = [("both_sweeps_kernel<-1", "both_sweeps_unfused"), ("both_sweeps_kernel<", "both_sweeps_fused"),
+    labels = [(", true>", "second_sweep_dp"),  # backward_dp_kernel<..., true>: the contracting sweep (a no-op unless the pool overflowed)
+              ("both_sweeps_kernel<-1", "both_sweeps_unfused"), ("both_sweeps_kernel<", "both_sweeps_fused"),
               ("forward_dp_kernel<-1", "forward_dp_unfused"), ("backward_dp_kernel<-1", "backward_dp_unfused"),
               ("forward_dp_kernel<", "forward_dp_fused"), ("backward_dp_kernel<", "backward_dp_fused"),
               ("cost_tensor", "cost_tensor"), ("input_grad", "input_grad"), ("alignment", "alignment"),
