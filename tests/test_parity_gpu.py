@@ -930,6 +930,20 @@ def test_rectangular_large_regime():
                 assert (got["E"][b][ref["E"][r] > 1e-36] > 0).all()
 
 
+@pytest.mark.parametrize("mode", ["unfused", "fused"])
+def test_many_bands_few_pairs(mode):
+    # 512 bands per pair and a batch that does not fill the last 4-band workgroup (B = 5: one workgroup
+    # in two runs with three idle slots); every band after the first hangs on a chain of 511 hand-overs
+    B, N, M, D, gamma = 5, 32768, 600, 8, 0.5
+    say("many bands %s B=%d N=%d M=%d" % (mode, B, N, M))
+    x, y = workloads.walk_pairs(73, B, N, M, D)
+    pairs = [0, 4]
+    ref = oracle.batch(x[pairs], y[pairs], gamma, nthreads=2)
+    got = run_gpu(x, y, gamma, MODES[mode], want_E=False)
+    check_against(ref, got, pairs=pairs, what="many bands " + mode)
+    assert np.all(np.isfinite(got["dx"])) and np.all(np.isfinite(got["dy"]))
+
+
 # ------------------------------------------------------------------------------- benchmark configurations
 @pytest.mark.parametrize("mode", ["unfused", "fused"])
 def test_config2_full(mode):
